@@ -1,0 +1,28 @@
+"""Compile the CPU oracle (test infrastructure) into oracle/liboracle.so with g++.
+
+Flags: -O2, no fast-math, -ffp-contract=off (the Pong comparison is bit for bit, so no fused
+multiply-add may be formed).  Run as `python oracle/build_oracle.py`.
+"""
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+SOURCES = ["philox.cpp", "pong.cpp", "body.cpp"]
+LIB = os.path.join(HERE, "liboracle.so")
+
+
+def build(force=True):
+    srcs = [os.path.join(HERE, s) for s in SOURCES if os.path.exists(os.path.join(HERE, s))]
+    if not force and os.path.exists(LIB) and all(
+            os.path.getmtime(LIB) >= os.path.getmtime(s) for s in srcs):
+        return LIB
+    cmd = ["g++", "-std=c++17", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
+           "-pthread", "-Wall", "-Wextra", "-o", LIB] + srcs + ["-lm"]
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(force=True))
+    sys.exit(0)
