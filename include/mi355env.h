@@ -1,0 +1,136 @@
+/* mi355env — vectorised environment step / reset / rollout on one MI355X (gfx950).
+ *
+ * C ABI of the hot path that generated "performance environments" exist to accelerate: stepping N
+ * independent environments in lock-step, resetting them, and running a T-step rollout fused into
+ * one kernel launch (paper: section 1 — simulation is 50-90 % of RL wall-clock; App. B.1 items 3-5
+ * — batch a single-instance step, one launch per batch step, fuse the rollout loop into one kernel;
+ * App. B.1 items 6-7 — small dtypes, pre-allocated output buffers; App. B.2 item 8 — one call for
+ * all environments, zero-copy buffers).
+ *
+ * Conventions
+ *  - Every pointer named *_dev is DEVICE memory owned by the caller (e.g. a PyTorch tensor's
+ *    data_ptr()), row-major, exactly the documented shape, alive until the stream has run the call.
+ *    Every pointer named *_host / host_* is HOST memory owned by the caller.
+ *  - The library owns only its SoA state and the episode-statistics block (allocated by
+ *    env_create, freed by env_destroy).  step / reset / rollout never allocate.
+ *  - step / reset / rollout enqueue work on the handle's stream and return without waiting;
+ *    stats / get_state / set_state synchronise that stream.
+ *  - All functions return ENV_OK (0) or a negative error code; on error no output buffer is
+ *    touched.  No C++ exception crosses this boundary.
+ *  - One handle must not be used from two threads at once.
+ *  - Random draws come from Philox4x32-10 with key = (seed lo, seed hi) and
+ *    counter = (env index, step lo, step hi, stream); `step` counts env steps since env_create and
+ *    is never rewound, so results do not depend on N nor on how a rollout is cut into calls.
+ *  - Auto-reset: done[t,i] = 1 marks the transition that ended an episode; the observation stored
+ *    at that index is already the first observation of the next episode, the reward is the final
+ *    transition's.
+ */
+#ifndef MI355ENV_H
+#define MI355ENV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mi355env env_t; /* opaque handle */
+
+enum {
+  ENV_PONG = 0,        /* Pong, obs = float32[8]: ball x, y, vx, vy, agent y, opponent y, scores  */
+  ENV_PONG_PIXELS = 1, /* same dynamics, obs = uint8[4][84][84] ring of rendered frames           */
+  ENV_BODY = 2         /* planar 7-link articulated body, obs = float32[17], action float32[6]    */
+};
+
+enum {
+  ENV_OK = 0,
+  ENV_E_ARG = -1,      /* bad argument: NULL, non-positive size, misaligned or non-device pointer */
+  ENV_E_ALLOC = -2,    /* device allocation failed                                                */
+  ENV_E_HIP = -3,      /* a HIP runtime call or kernel launch failed                              */
+  ENV_E_STATE = -4,    /* call order: step/rollout before the first env_reset                     */
+  ENV_E_UNSUPPORTED = -5 /* operation not available for this environment kind                     */
+};
+
+/* Optional configuration (NULL = defaults).  struct_size = sizeof(env_config_t) as compiled by the
+ * caller; fields beyond struct_size keep their defaults.  A zero/negative value in a field means
+ * "default" unless stated. */
+typedef struct env_config_t {
+  uint32_t struct_size;
+  int32_t max_score;          /* Pong: points that end an episode (default 21)                    */
+  int32_t max_episode_steps;  /* body: truncation length (default 1000)                           */
+  float armature;             /* body: rotor inertia added to the 6 joint diagonals; <0 = default */
+  float joint_damping;        /* body: viscous joint damping; <0 = default                        */
+  float friction_mu;          /* body: Coulomb friction coefficient; <0 = default                 */
+} env_config_t;
+
+/* Statistics of the episodes that ended since the counters were last cleared. */
+typedef struct env_stats_t {
+  int64_t episodes;
+  int64_t length_sum;
+  double return_sum;
+  double return_min; /* +inf when episodes == 0 */
+  double return_max; /* -inf when episodes == 0 */
+  int64_t nonfinite; /* body: environments re-initialised because their state left the finite range */
+} env_stats_t;
+
+/* Create N environments of `kind`.  seed keys every random draw.  hip_stream is a hipStream_t
+ * (NULL = the null stream) on the current device; the handle keeps using it.  Allocates
+ * state (Pong: 40 B/env, body: 80 B/env) on the current device.  *out is set only on success. */
+int env_create(env_t **out, int kind, int64_t n_envs, uint64_t seed, const env_config_t *cfg,
+               void *hip_stream);
+
+/* Free the handle and its device memory (synchronises the stream first).  NULL is ignored. */
+void env_destroy(env_t *e);
+
+/* Start a new episode in every environment, drawing the initial state from the reset streams at
+ * the current step counter.  obs_dev (may be NULL): Pong float32[N,8]; body float32[N,17];
+ * pixels uint8[N,4,84,84] — all four ring slots receive the initial frame.  16-byte aligned. */
+int env_reset(env_t *e, void *obs_dev);
+
+/* Advance every environment by one step (one kernel launch).
+ * actions_dev: Pong uint8[N] in {0 stay, 1 up, 2 down} (other values = stay); body float32[N,6],
+ * clipped to [-1,1]; NULL = draw the actions from this step's Philox block inside the kernel.
+ * obs_dev: Pong float32[N,8]; body float32[N,17]; pixels: the uint8[N,4,84,84] ring — the frame
+ * after the step with index s (s = steps taken before this call) is written to slot s mod 4, the
+ * other three slots are left as they are.  reward_dev float32[N], done_dev uint8[N].
+ * obs_dev must be 16-byte aligned, reward_dev 4-byte aligned.  None may be NULL. */
+int env_step(env_t *e, const void *actions_dev, void *obs_dev, float *reward_dev, uint8_t *done_dev);
+
+/* T steps fused into one kernel launch; state stays in registers between steps.
+ * actions_dev: [T,N] (Pong uint8) / [T,N,6] (body float32) or NULL (in-kernel Philox draws).
+ * obs_dev: float32[T,N,obs_dim] (Pong, body); pixels: uint8[T,N,84,84], frame t of the rollout.
+ * reward_dev float32[T,N]; done_dev uint8[T,N].  Alignment as for env_step.  Equivalent, bit for
+ * bit, to T calls of env_step (Pong; the body's obs/reward agree exactly as well, same kernels). */
+int env_rollout(env_t *e, int32_t T, const void *actions_dev, void *obs_dev, float *reward_dev,
+                uint8_t *done_dev);
+
+/* Copy the episode statistics to *host_out; clear the device counters if reset_counters != 0. */
+int env_stats(env_t *e, env_stats_t *host_out, int reset_counters);
+
+/* Size in bytes of the state blob of get/set_state: 8 + 4 * fields * N, where the blob is
+ * { uint64 step_counter; field_0[N]; field_1[N]; ... }, every field 4 bytes wide.
+ * Pong / pixels (10 fields): ball x, y, vx, vy, agent y, opponent y (float32), agent score,
+ * opponent score, episode return so far, episode length so far (int32).
+ * Body (20 fields): q[9], v[9], episode return so far (float32), episode length so far (int32). */
+size_t env_state_bytes(const env_t *e);
+
+/* Copy the state blob to / from host memory (bytes must equal env_state_bytes).  set_state also
+ * marks the handle as reset.  Rendered frames are not part of the state. */
+int env_get_state(env_t *e, void *host_buf, size_t bytes);
+int env_set_state(env_t *e, const void *host_buf, size_t bytes);
+
+/* Floats (or bytes, for pixels: 4*84*84) per environment in obs_dev of env_step; <0 on bad kind. */
+int env_obs_dim(int kind);
+/* Elements per environment in actions_dev (Pong 1 x uint8, body 6 x float32). */
+int env_action_dim(int kind);
+int64_t env_num_envs(const env_t *e);
+uint64_t env_step_count(const env_t *e);
+
+/* Static string for a status code. */
+const char *env_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MI355ENV_H */

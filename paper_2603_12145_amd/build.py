@@ -1,0 +1,41 @@
+"""Compile the HIP sources under csrc/ into libmi355env.so (gfx950 only), in-tree.
+
+Flags: -ffp-contract=off so that no multiply-add is fused behind the source's back (the Pong path is
+compared bit for bit with a scalar CPU implementation; where the body wants an FMA it asks for one
+explicitly), and packed-FP32 instruction selection is disabled.
+"""
+import glob
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libmi355env.so")
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-ffp-contract=off",
+         "-fno-fast-math", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-Wall", "-Wno-unused-command-line-argument"]
+
+
+def sources():
+    return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
+
+
+def build(force=True, verbose=False, extra=()):
+    srcs = sources()
+    deps = srcs + glob.glob(os.path.join(CSRC, "*.hpp")) + glob.glob(
+        os.path.join(HERE, "..", "include", "*.h"))
+    if not force and os.path.exists(LIB) and all(
+            os.path.getmtime(LIB) >= os.path.getmtime(d) for d in deps):
+        return LIB
+    cmd = [HIPCC] + FLAGS + list(extra) + ["-o", LIB] + srcs
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.run(cmd, check=True)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(force=True, verbose=True, extra=sys.argv[1:]))

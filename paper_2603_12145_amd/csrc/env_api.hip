@@ -1,0 +1,340 @@
+// C-ABI layer of libmi355env.so: argument checks, handle bookkeeping and kernel launches.
+// The contract of every entry point is stated in include/mi355env.h.
+#include <hip/hip_runtime.h>
+#include <cmath>
+#include <cstdint>
+#include <cstring>
+#include <limits>
+#include <new>
+
+#include "../../include/mi355env.h"
+#include "kernels.hpp"
+#include "pong_device.hpp"
+#include "body_kernels.hpp"
+
+using namespace envk;
+
+namespace envk {
+bool set_pixel_tuning(int envs_per_wave, int streaming);
+}
+
+struct mi355env {
+  int kind;
+  int device;
+  int64_t n;
+  uint64_t seed;
+  uint64_t step;          // env steps taken since creation (all environments move in lock-step)
+  hipStream_t stream;
+  env_config_t cfg;
+  uint32_t* state;        // device SoA [fields][n], every field 4 bytes
+  int fields;
+  DeviceStats* stats;     // device
+  bool was_reset;
+  // last device ranges that passed the residency check (avoids a driver query per step)
+  struct Range { const void* p; size_t bytes; } seen[8];
+  int seen_next;
+};
+
+namespace {
+
+constexpr int64_t MAX_ENVS = int64_t(1) << 30;
+
+int fields_of(int kind) { return kind == ENV_BODY ? BODY_FIELDS : PONG_FIELDS; }
+
+env_config_t default_config(int kind) {
+  env_config_t c;
+  std::memset(&c, 0, sizeof c);
+  c.struct_size = sizeof(env_config_t);
+  c.max_score = 21;
+  c.max_episode_steps = 1000;
+  c.armature = BODY_DEFAULT_ARMATURE;
+  c.joint_damping = BODY_DEFAULT_JOINT_DAMPING;
+  c.friction_mu = BODY_DEFAULT_FRICTION_MU;
+  (void)kind;
+  return c;
+}
+
+#define FIELD_END(type, member) (offsetof(type, member) + sizeof(((type*)0)->member))
+
+int merge_config(env_config_t* dst, const env_config_t* src) {
+  if (!src) return ENV_OK;
+  const uint32_t sz = src->struct_size;
+  if (sz < sizeof(uint32_t) || sz > 4096) return ENV_E_ARG;
+  if (sz >= FIELD_END(env_config_t, max_score) && src->max_score > 0) dst->max_score = src->max_score;
+  if (sz >= FIELD_END(env_config_t, max_episode_steps) && src->max_episode_steps > 0)
+    dst->max_episode_steps = src->max_episode_steps;
+  if (sz >= FIELD_END(env_config_t, armature) && src->armature >= 0.0f) dst->armature = src->armature;
+  if (sz >= FIELD_END(env_config_t, joint_damping) && src->joint_damping >= 0.0f)
+    dst->joint_damping = src->joint_damping;
+  if (sz >= FIELD_END(env_config_t, friction_mu) && src->friction_mu >= 0.0f)
+    dst->friction_mu = src->friction_mu;
+  if (!std::isfinite(dst->armature) || !std::isfinite(dst->joint_damping) ||
+      !std::isfinite(dst->friction_mu))
+    return ENV_E_ARG;
+  return ENV_OK;
+}
+
+DeviceStats empty_stats() {
+  DeviceStats s;
+  std::memset(&s, 0, sizeof s);
+  s.return_min_key = std::numeric_limits<int>::max();
+  s.return_max_key = std::numeric_limits<int>::min();
+  return s;
+}
+
+float key_to_float(int key) {
+  const int b = key ^ ((key >> 31) & 0x7fffffff);
+  float f;
+  std::memcpy(&f, &b, sizeof f);
+  return f;
+}
+
+// True iff [p, p+bytes) lies inside one device allocation visible to this process.
+bool device_range_ok(env_t* e, const void* p, size_t bytes, size_t align) {
+  if (!p || (reinterpret_cast<uintptr_t>(p) & (align - 1))) return false;
+  for (auto& r : e->seen)
+    if (r.p == p && r.bytes >= bytes) return true;
+  hipPointerAttribute_t attr;
+  if (hipPointerGetAttributes(&attr, p) != hipSuccess) { (void)hipGetLastError(); return false; }
+  if (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged) return false;
+  hipDeviceptr_t base = nullptr;
+  size_t size = 0;
+  if (hipMemGetAddressRange(&base, &size, const_cast<void*>(p)) != hipSuccess) {
+    (void)hipGetLastError();
+    return false;
+  }
+  const uintptr_t lo = reinterpret_cast<uintptr_t>(base), q = reinterpret_cast<uintptr_t>(p);
+  if (q < lo || q + bytes > lo + size) return false;
+  e->seen[e->seen_next] = {p, bytes};
+  e->seen_next = (e->seen_next + 1) % 8;
+  return true;
+}
+
+size_t obs_bytes_per_env_step(int kind) {
+  switch (kind) {
+    case ENV_PONG: return PONG_OBS * sizeof(float);
+    case ENV_PONG_PIXELS: return (size_t)FRAME_BYTES;
+    case ENV_BODY: return BODY_OBS * sizeof(float);
+  }
+  return 0;
+}
+
+size_t action_bytes_per_env_step(int kind) {
+  return kind == ENV_BODY ? BODY_ACT * sizeof(float) : sizeof(uint8_t);
+}
+
+int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, float* reward,
+        uint8_t* done) {
+  if (!e) return ENV_E_ARG;
+  if (T <= 0) return ENV_E_ARG;
+  if (!e->was_reset) return ENV_E_STATE;
+  const size_t tn = (size_t)T * (size_t)e->n;
+  const size_t obs_bytes = (e->kind == ENV_PONG_PIXELS && ring_mode)
+                               ? (size_t)e->n * 4 * FRAME_BYTES
+                               : tn * obs_bytes_per_env_step(e->kind);
+  if (!device_range_ok(e, obs, obs_bytes, 16)) return ENV_E_ARG;
+  if (!device_range_ok(e, reward, tn * sizeof(float), 4)) return ENV_E_ARG;
+  if (!device_range_ok(e, done, tn, 1)) return ENV_E_ARG;
+  if (actions &&
+      !device_range_ok(e, actions, tn * action_bytes_per_env_step(e->kind), e->kind == ENV_BODY ? 4 : 1))
+    return ENV_E_ARG;
+
+  hipError_t err = hipSuccess;
+  if (e->kind == ENV_BODY) {
+    BodyLaunch b{};
+    b.state = e->state; b.n = e->n; b.seed = e->seed; b.step0 = e->step; b.T = T;
+    b.max_episode_steps = e->cfg.max_episode_steps;
+    b.armature = e->cfg.armature; b.joint_damping = e->cfg.joint_damping;
+    b.friction_mu = e->cfg.friction_mu;
+    b.actions = static_cast<const float*>(actions);
+    b.obs = static_cast<float*>(obs); b.reward = reward; b.done = done; b.stats = e->stats;
+    err = launch_body_rollout(b, e->stream);
+  } else {
+    PongLaunch p{};
+    p.state = e->state; p.n = e->n; p.seed = e->seed; p.step0 = e->step; p.T = T;
+    p.max_score = e->cfg.max_score;
+    p.actions = static_cast<const uint8_t*>(actions);
+    p.obs = static_cast<float*>(obs); p.reward = reward; p.done = done; p.stats = e->stats;
+    if (e->kind == ENV_PONG) {
+      err = launch_pong_rollout(p, e->stream);
+    } else {
+      PixelLaunch x{};
+      x.pong = p; x.pong.obs = nullptr;
+      if (ring_mode) x.ring = static_cast<uint8_t*>(obs);
+      else x.frames = static_cast<uint8_t*>(obs);
+      err = launch_pixel_rollout(x, e->stream);
+    }
+  }
+  if (err != hipSuccess) return ENV_E_HIP;
+  e->step += (uint64_t)T;
+  return ENV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_config_t* cfg,
+               void* hip_stream) {
+  if (!out) return ENV_E_ARG;
+  if (kind != ENV_PONG && kind != ENV_PONG_PIXELS && kind != ENV_BODY) return ENV_E_ARG;
+  if (n_envs <= 0 || n_envs > MAX_ENVS) return ENV_E_ARG;
+  env_config_t c = default_config(kind);
+  if (merge_config(&c, cfg) != ENV_OK) return ENV_E_ARG;
+
+  env_t* e = new (std::nothrow) env_t();
+  if (!e) return ENV_E_ALLOC;
+  e->kind = kind; e->n = n_envs; e->seed = seed; e->step = 0;
+  e->stream = static_cast<hipStream_t>(hip_stream);
+  e->cfg = c; e->fields = fields_of(kind); e->was_reset = false;
+  e->state = nullptr; e->stats = nullptr; e->seen_next = 0;
+  for (auto& r : e->seen) r = {nullptr, 0};
+  if (hipGetDevice(&e->device) != hipSuccess) { delete e; return ENV_E_HIP; }
+
+  const size_t state_bytes = (size_t)e->fields * (size_t)n_envs * 4;
+  if (hipMalloc(reinterpret_cast<void**>(&e->state), state_bytes) != hipSuccess) {
+    (void)hipGetLastError(); delete e; return ENV_E_ALLOC;
+  }
+  if (hipMalloc(reinterpret_cast<void**>(&e->stats), sizeof(DeviceStats)) != hipSuccess) {
+    (void)hipGetLastError(); (void)hipFree(e->state); delete e; return ENV_E_ALLOC;
+  }
+  const DeviceStats z = empty_stats();
+  if (hipMemsetAsync(e->state, 0, state_bytes, e->stream) != hipSuccess ||
+      hipMemcpyAsync(e->stats, &z, sizeof z, hipMemcpyHostToDevice, e->stream) != hipSuccess ||
+      hipStreamSynchronize(e->stream) != hipSuccess) {
+    (void)hipGetLastError(); (void)hipFree(e->state); (void)hipFree(e->stats); delete e;
+    return ENV_E_HIP;
+  }
+  *out = e;
+  return ENV_OK;
+}
+
+void env_destroy(env_t* e) {
+  if (!e) return;
+  (void)hipStreamSynchronize(e->stream);
+  (void)hipFree(e->state);
+  (void)hipFree(e->stats);
+  delete e;
+}
+
+int env_reset(env_t* e, void* obs_dev) {
+  if (!e) return ENV_E_ARG;
+  hipError_t err;
+  if (e->kind == ENV_PONG_PIXELS && obs_dev) {
+    if (!device_range_ok(e, obs_dev, (size_t)e->n * 4 * FRAME_BYTES, 16)) return ENV_E_ARG;
+    err = launch_pixel_reset(e->state, e->n, e->seed, e->step, static_cast<uint8_t*>(obs_dev), e->stream);
+  } else if (e->kind == ENV_BODY) {
+    if (obs_dev && !device_range_ok(e, obs_dev, (size_t)e->n * BODY_OBS * sizeof(float), 16))
+      return ENV_E_ARG;
+    err = launch_body_reset(e->state, e->n, e->seed, e->step, static_cast<float*>(obs_dev), e->stream);
+  } else {
+    if (obs_dev && !device_range_ok(e, obs_dev, (size_t)e->n * PONG_OBS * sizeof(float), 16))
+      return ENV_E_ARG;
+    err = launch_pong_reset(e->state, e->n, e->seed, e->step,
+                            e->kind == ENV_PONG ? static_cast<float*>(obs_dev) : nullptr, e->stream);
+  }
+  if (err != hipSuccess) return ENV_E_HIP;
+  e->was_reset = true;
+  return ENV_OK;
+}
+
+int env_step(env_t* e, const void* actions_dev, void* obs_dev, float* reward_dev, uint8_t* done_dev) {
+  return run(e, 1, true, actions_dev, obs_dev, reward_dev, done_dev);
+}
+
+int env_rollout(env_t* e, int32_t T, const void* actions_dev, void* obs_dev, float* reward_dev,
+                uint8_t* done_dev) {
+  return run(e, T, false, actions_dev, obs_dev, reward_dev, done_dev);
+}
+
+int env_stats(env_t* e, env_stats_t* host_out, int reset_counters) {
+  if (!e || !host_out) return ENV_E_ARG;
+  DeviceStats d;
+  if (hipMemcpyAsync(&d, e->stats, sizeof d, hipMemcpyDeviceToHost, e->stream) != hipSuccess ||
+      hipStreamSynchronize(e->stream) != hipSuccess)
+    return ENV_E_HIP;
+  host_out->episodes = (int64_t)d.episodes;
+  host_out->length_sum = (int64_t)d.length_sum;
+  host_out->nonfinite = (int64_t)d.nonfinite;
+  const bool any = d.episodes > 0;
+  if (e->kind == ENV_BODY) {
+    host_out->return_sum = d.return_sum_f;
+    host_out->return_min = any ? (double)key_to_float(d.return_min_key) : INFINITY;
+    host_out->return_max = any ? (double)key_to_float(d.return_max_key) : -INFINITY;
+  } else {
+    host_out->return_sum = (double)d.return_sum_i;
+    host_out->return_min = any ? (double)d.return_min_key : INFINITY;
+    host_out->return_max = any ? (double)d.return_max_key : -INFINITY;
+  }
+  if (reset_counters) {
+    const DeviceStats z = empty_stats();
+    if (hipMemcpyAsync(e->stats, &z, sizeof z, hipMemcpyHostToDevice, e->stream) != hipSuccess ||
+        hipStreamSynchronize(e->stream) != hipSuccess)
+      return ENV_E_HIP;
+  }
+  return ENV_OK;
+}
+
+size_t env_state_bytes(const env_t* e) {
+  return e ? 8 + (size_t)4 * (size_t)e->fields * (size_t)e->n : 0;
+}
+
+int env_get_state(env_t* e, void* host_buf, size_t bytes) {
+  if (!e || !host_buf || bytes != env_state_bytes(e)) return ENV_E_ARG;
+  std::memcpy(host_buf, &e->step, 8);
+  if (hipMemcpyAsync(static_cast<char*>(host_buf) + 8, e->state, bytes - 8, hipMemcpyDeviceToHost,
+                     e->stream) != hipSuccess ||
+      hipStreamSynchronize(e->stream) != hipSuccess)
+    return ENV_E_HIP;
+  return ENV_OK;
+}
+
+int env_set_state(env_t* e, const void* host_buf, size_t bytes) {
+  if (!e || !host_buf || bytes != env_state_bytes(e)) return ENV_E_ARG;
+  if (hipMemcpyAsync(e->state, static_cast<const char*>(host_buf) + 8, bytes - 8,
+                     hipMemcpyHostToDevice, e->stream) != hipSuccess ||
+      hipStreamSynchronize(e->stream) != hipSuccess)
+    return ENV_E_HIP;
+  std::memcpy(&e->step, host_buf, 8);
+  e->was_reset = true;
+  return ENV_OK;
+}
+
+int env_obs_dim(int kind) {
+  switch (kind) {
+    case ENV_PONG: return PONG_OBS;
+    case ENV_PONG_PIXELS: return 4 * FRAME_BYTES;
+    case ENV_BODY: return BODY_OBS;
+  }
+  return ENV_E_ARG;
+}
+
+int env_action_dim(int kind) {
+  switch (kind) {
+    case ENV_PONG: case ENV_PONG_PIXELS: return 1;
+    case ENV_BODY: return BODY_ACT;
+  }
+  return ENV_E_ARG;
+}
+
+int64_t env_num_envs(const env_t* e) { return e ? e->n : 0; }
+uint64_t env_step_count(const env_t* e) { return e ? e->step : 0; }
+
+const char* env_strerror(int code) {
+  switch (code) {
+    case ENV_OK: return "ok";
+    case ENV_E_ARG: return "bad argument (NULL, size, alignment or not device memory)";
+    case ENV_E_ALLOC: return "device allocation failed";
+    case ENV_E_HIP: return "HIP runtime call or kernel launch failed";
+    case ENV_E_STATE: return "env_reset (or env_set_state) must be called first";
+    case ENV_E_UNSUPPORTED: return "not supported for this environment kind";
+  }
+  return "unknown status";
+}
+
+// Measurement knob, not part of the documented boundary: launch shape of the pixel kernels.
+int mi355env_tune_pixels(int envs_per_wave, int streaming) {
+  return set_pixel_tuning(envs_per_wave, streaming) ? ENV_OK : ENV_E_ARG;
+}
+
+}  // extern "C"

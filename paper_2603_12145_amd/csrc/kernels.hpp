@@ -1,0 +1,44 @@
+// Host-callable launchers of the HIP kernels (internal to the library; the public boundary is
+// include/mi355env.h).  Every launcher validates nothing: the C-ABI layer has already checked
+// sizes, alignment and pointer residency.  All return the hipError_t of the launch.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "stats.hpp"
+
+namespace envk {
+
+constexpr int FRAME_SIDE = 84;
+constexpr int FRAME_BYTES = FRAME_SIDE * FRAME_SIDE;  // 7056 = 441 * 16
+
+struct PongLaunch {
+  uint32_t* state;        // SoA [10][n]
+  int64_t n;
+  uint64_t seed;
+  uint64_t step0;         // index of the first step of this launch
+  int32_t T;
+  int32_t max_score;
+  const uint8_t* actions; // [T,n] or nullptr
+  float* obs;             // [T,n,8]
+  float* reward;          // [T,n]
+  uint8_t* done;          // [T,n]
+  DeviceStats* stats;
+};
+
+hipError_t launch_pong_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step, float* obs,
+                             hipStream_t stream);
+hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream);
+
+// Pixel observations.  ring != nullptr: frame after step s goes to ring[i][s & 3] (T must be 1 or
+// the ring is rewritten in place T times); frames != nullptr: frame t of the launch goes to
+// frames[t][i].
+struct PixelLaunch {
+  PongLaunch pong;        // obs unused
+  uint8_t* ring;          // [n,4,84,84] or nullptr
+  uint8_t* frames;        // [T,n,84,84] or nullptr
+};
+hipError_t launch_pixel_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
+                              uint8_t* ring, hipStream_t stream);
+hipError_t launch_pixel_rollout(const PixelLaunch& a, hipStream_t stream);
+
+}  // namespace envk

@@ -1,0 +1,228 @@
+// Pong with pixel observations: dynamics per lane, rendering per wavefront.
+//
+// Each 84x84 uint8 frame (7056 B = 441 x 16 B) is black except for at most 54 lit pixels (two
+// paddles, one ball), so the cost of a frame is its HBM write, not its arithmetic.  A wavefront owns
+// a private 7056-byte LDS tile that is kept all-zero between frames.  For each of its environments
+// it (1) pokes the lit pixels of the three rectangles into the tile (a handful of ds_write_b8),
+// (2) streams the tile to HBM with 441 fully coalesced 16-byte stores (every store instruction of
+// the wavefront covers 1 KiB of contiguous memory), (3) clears the poked bytes again.  No
+// workgroup barrier is needed: a tile is only ever touched by its own wavefront, whose LDS
+// operations execute in program order.
+//
+// Rasterisation rule (any overlap): pixel (r,c) is lit iff some rectangle [x0,x0+w) x [y0,y0+h)
+// overlaps the cell [160c/84, 160(c+1)/84) x [210r/84, 210(r+1)/84), decided in float32 as
+//   x0*84 < 160(c+1)  &&  (x0+w)*84 > 160c  &&  y0*84 < 210(r+1)  &&  (y0+h)*84 > 210r.
+// Both column conditions are monotone in c (rows likewise), so each rectangle lights an axis-
+// aligned block of cells whose four bounds are found per lane with one floor and an exact fix-up.
+#include "kernels.hpp"
+#include "pong_device.hpp"
+
+namespace envk {
+
+namespace {
+
+constexpr int WAVE = 64;
+constexpr int WAVES_PER_BLOCK = 4;
+constexpr int CHUNKS = FRAME_BYTES / 16;  // 441
+
+enum PixelMode { MODE_RESET = 0, MODE_RING = 1, MODE_FRAMES = 2 };
+
+// smallest integer c with a < size * (c + 1)
+__device__ __forceinline__ int first_cell(float a, float size, float inv_size) {
+  int g = (int)floorf(a * inv_size);
+  if (!(a < size * (float)(g + 1))) g += 1;
+  else if (a < size * (float)g) g -= 1;
+  return g;
+}
+// largest integer c with size * c < b
+__device__ __forceinline__ int last_cell(float b, float size, float inv_size) {
+  int h = (int)floorf(b * inv_size);
+  if (!(size * (float)h < b)) h -= 1;
+  else if (size * (float)(h + 1) < b) h += 1;
+  return h;
+}
+
+// Cell block of one rectangle packed as bytes: col_lo | col_end << 8 | row_lo << 16 | row_end << 24
+// (ends exclusive, all clipped to [0,84]; an empty block has end <= lo).
+__device__ __forceinline__ uint32_t cell_block(float x0, float y0, float w, float h) {
+  int c_lo = first_cell(x0 * 84.0f, 160.0f, 1.0f / 160.0f);
+  int c_end = last_cell((x0 + w) * 84.0f, 160.0f, 1.0f / 160.0f) + 1;
+  int r_lo = first_cell(y0 * 84.0f, 210.0f, 1.0f / 210.0f);
+  int r_end = last_cell((y0 + h) * 84.0f, 210.0f, 1.0f / 210.0f) + 1;
+  c_lo = min(max(c_lo, 0), FRAME_SIDE); c_end = min(max(c_end, 0), FRAME_SIDE);
+  r_lo = min(max(r_lo, 0), FRAME_SIDE); r_end = min(max(r_end, 0), FRAME_SIDE);
+  return (uint32_t)c_lo | ((uint32_t)c_end << 8) | ((uint32_t)r_lo << 16) | ((uint32_t)r_end << 24);
+}
+
+// All lanes: write `value` to every pixel of the (wave-uniform) block.  Lane l covers column
+// offset l & 3 and row offset l >> 2 of a 4 x 16 patch; blocks are at most 4 x 8 for the paddles
+// and 3 x 2 for the ball, so the loops run once.
+__device__ __forceinline__ void poke_block(uint8_t* tile, uint32_t block, int lane, uint8_t value) {
+  const int c_lo = block & 0xff, c_end = (block >> 8) & 0xff;
+  const int r_lo = (block >> 16) & 0xff, r_end = block >> 24;
+  for (int rr = r_lo; rr < r_end; rr += 16)
+    for (int cc = c_lo; cc < c_end; cc += 4) {
+      const int r = rr + (lane >> 2), c = cc + (lane & 3);
+      if (r < r_end && c < c_end) tile[r * FRAME_SIDE + c] = value;
+    }
+}
+
+// Order the wavefront's own LDS traffic: later reads must see earlier pokes of other lanes.
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+typedef uint32_t chunk_t __attribute__((ext_vector_type(4)));   // 16 bytes, one dwordx4 access
+
+template <bool STREAMING>
+__device__ __forceinline__ void store_chunk(chunk_t* dst, const chunk_t v) {
+  if (STREAMING) __builtin_nontemporal_store(v, dst);
+  else *dst = v;
+}
+
+template <int EPW, int MODE, bool STREAMING>
+__global__ __launch_bounds__(WAVES_PER_BLOCK * WAVE) void pixel_kernel(PixelLaunch a) {
+  __shared__ __align__(16) uint8_t tiles[WAVES_PER_BLOCK][FRAME_BYTES];
+  const int lane = threadIdx.x & (WAVE - 1);
+  const int wave = threadIdx.x >> 6;
+  const int64_t n = a.pong.n;
+  const int64_t env0 = ((int64_t)blockIdx.x * WAVES_PER_BLOCK + wave) * EPW;
+  if (env0 >= n) return;                       // whole wavefront leaves together
+  const int64_t i = env0 + lane;
+  const bool live = (lane < EPW) && (i < n);
+  const int here = (int)min((int64_t)EPW, n - env0);   // environments of this wavefront
+
+  uint8_t* tile = tiles[wave];
+  chunk_t* tile16 = reinterpret_cast<chunk_t*>(tile);
+  for (int k = lane; k < CHUNKS; k += WAVE) tile16[k] = chunk_t{0, 0, 0, 0};
+  wave_lds_sync();
+
+  PongLane s;
+  if (MODE == MODE_RESET) {
+    s = pong_initial(a.pong.seed, (uint32_t)i, a.pong.step0);
+    if (live) pong_store(a.pong.state, n, i, s);
+  } else {
+    s = live ? pong_load(a.pong.state, n, i) : pong_idle_lane();
+  }
+  LaneEpisodes le;
+  const int32_t T = (MODE == MODE_RESET) ? 1 : a.pong.T;
+
+  for (int32_t t = 0; t < T; ++t) {
+    const uint64_t step = a.pong.step0 + (uint64_t)t;
+    if (MODE != MODE_RESET) {
+      const Draw4 d = philox_draw(a.pong.seed, (uint32_t)i, step, 0u);
+      const int64_t row = (int64_t)t * n;
+      int action = pong_action_from_word(d.w0);
+      if (a.pong.actions) action = live ? (int)a.pong.actions[row + i] : 0;
+      const PongEvent ev = pong_transition(s, action, d.w1, d.w2, a.pong.max_score);
+      if (live) {
+        a.pong.reward[row + i] = ev.reward;
+        a.pong.done[row + i] = ev.done ? 1 : 0;
+        if (ev.done) {
+          le.count += 1;
+          le.length_sum += ev.fin_len;
+          le.ret_sum_i += ev.fin_ret;
+          le.min_key = min(le.min_key, ev.fin_ret);
+          le.max_key = max(le.max_key, ev.fin_ret);
+        }
+      }
+    }
+
+    const uint32_t blk_agent = cell_block(140.0f, s.pa, 4.0f, 16.0f);
+    const uint32_t blk_opp = cell_block(16.0f, s.po, 4.0f, 16.0f);
+    const uint32_t blk_ball = cell_block(s.bx, s.by, 2.0f, 2.0f);
+
+    for (int e = 0; e < here; ++e) {
+      const uint32_t b0 = __builtin_amdgcn_readlane(blk_agent, e);
+      const uint32_t b1 = __builtin_amdgcn_readlane(blk_opp, e);
+      const uint32_t b2 = __builtin_amdgcn_readlane(blk_ball, e);
+      poke_block(tile, b0, lane, 255);
+      poke_block(tile, b1, lane, 255);
+      poke_block(tile, b2, lane, 255);
+      wave_lds_sync();
+
+      const int64_t env = env0 + e;
+      if (MODE == MODE_FRAMES) {
+        chunk_t* dst = reinterpret_cast<chunk_t*>(a.frames + ((int64_t)t * n + env) * FRAME_BYTES);
+#pragma unroll
+        for (int k = lane; k < CHUNKS; k += WAVE) store_chunk<STREAMING>(dst + k, tile16[k]);
+      } else if (MODE == MODE_RING) {
+        chunk_t* dst = reinterpret_cast<chunk_t*>(a.ring + (env * 4 + (int64_t)(step & 3)) * FRAME_BYTES);
+#pragma unroll
+        for (int k = lane; k < CHUNKS; k += WAVE) store_chunk<STREAMING>(dst + k, tile16[k]);
+      } else {  // reset: the same frame into all four slots (contiguous 4 * 7056 bytes)
+        chunk_t* dst = reinterpret_cast<chunk_t*>(a.ring + env * 4 * FRAME_BYTES);
+        for (int k = lane; k < CHUNKS; k += WAVE) {
+          const chunk_t v = tile16[k];
+          for (int slot = 0; slot < 4; ++slot) store_chunk<STREAMING>(dst + slot * CHUNKS + k, v);
+        }
+      }
+      wave_lds_sync();
+      poke_block(tile, b0, lane, 0);
+      poke_block(tile, b1, lane, 0);
+      poke_block(tile, b2, lane, 0);
+      wave_lds_sync();
+    }
+  }
+
+  if (MODE != MODE_RESET) {
+    if (live) pong_store(a.pong.state, n, i, s);
+    flush_wave_stats<false>(a.pong.stats, le);
+  }
+}
+
+int g_envs_per_wave = 16;
+bool g_streaming = false;
+
+template <int MODE>
+hipError_t launch_mode(const PixelLaunch& a, hipStream_t stream) {
+  const int epw = g_envs_per_wave;
+  const int64_t waves = (a.pong.n + epw - 1) / epw;
+  const unsigned blocks = (unsigned)((waves + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
+  const dim3 grid(blocks), block(WAVES_PER_BLOCK * WAVE);
+#define MI355ENV_PIXEL_CASE(E)                                                                \
+  case E:                                                                                     \
+    if (g_streaming) hipLaunchKernelGGL((pixel_kernel<E, MODE, true>), grid, block, 0, stream, a); \
+    else hipLaunchKernelGGL((pixel_kernel<E, MODE, false>), grid, block, 0, stream, a);       \
+    break;
+  switch (epw) {
+    MI355ENV_PIXEL_CASE(4)
+    MI355ENV_PIXEL_CASE(8)
+    MI355ENV_PIXEL_CASE(16)
+    MI355ENV_PIXEL_CASE(32)
+    MI355ENV_PIXEL_CASE(64)
+    default: return hipErrorInvalidValue;
+  }
+#undef MI355ENV_PIXEL_CASE
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// Launch-shape knobs for measurement sweeps: environments per wavefront (4..64, power of two) and
+// whether frame stores carry the non-temporal hint.
+bool set_pixel_tuning(int envs_per_wave, int streaming) {
+  if (envs_per_wave != 4 && envs_per_wave != 8 && envs_per_wave != 16 && envs_per_wave != 32 &&
+      envs_per_wave != 64)
+    return false;
+  g_envs_per_wave = envs_per_wave;
+  g_streaming = streaming != 0;
+  return true;
+}
+
+hipError_t launch_pixel_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
+                              uint8_t* ring, hipStream_t stream) {
+  PixelLaunch a{};
+  a.pong.state = state; a.pong.n = n; a.pong.seed = seed; a.pong.step0 = step; a.pong.T = 1;
+  a.ring = ring;
+  return launch_mode<MODE_RESET>(a, stream);
+}
+
+hipError_t launch_pixel_rollout(const PixelLaunch& a, hipStream_t stream) {
+  if (a.frames) return launch_mode<MODE_FRAMES>(a, stream);
+  return launch_mode<MODE_RING>(a, stream);
+}
+
+}  // namespace envk

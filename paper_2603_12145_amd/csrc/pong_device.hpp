@@ -1,0 +1,146 @@
+// Pong transition for one environment held in the registers of one lane (gfx950, float32).
+//
+// Workload: the paper's "Puffer Pong" case study (Table 1; App. A.1) with the dynamics of the
+// benchmark configuration: 160x210 field, 4x16 paddles at x=140 (agent) / x=16 (opponent), agent
+// speed 4, opponent follows the ball centre at speed <= 3, 2x2 ball served from the centre at +-3
+// in x and uniform [-2,2) in y, mirror reflection at the top/bottom walls, paddle hit sets
+// vy = 0.2 * (ball centre - paddle centre), +-1 reward per point, episode ends at max_score.
+// y grows downwards; every position is the top-left corner of its rectangle.
+//
+// The collision logic is written with selects only (paper App. B.1 item 2): a wavefront never
+// diverges inside a step.  Compiled with -ffp-contract=off: every operation below is a single
+// IEEE float32 operation in the order written, which is what makes trajectories reproducible
+// bit for bit against a scalar CPU implementation.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "philox.hpp"
+
+namespace envk {
+
+constexpr int PONG_FIELDS = 10;  // bx by vx vy pa po | sa so ep_ret ep_len
+constexpr int PONG_OBS = 8;
+
+struct PongLane {
+  float bx, by, vx, vy, pa, po;
+  int sa, so, ep_ret, ep_len;
+};
+
+struct PongEvent {
+  float reward;
+  bool done;
+  int fin_ret, fin_len;  // valid when done
+};
+
+__device__ __forceinline__ float pong_serve_vx(uint32_t w) { return (w >> 31) ? 3.0f : -3.0f; }
+__device__ __forceinline__ float pong_serve_vy(uint32_t w) { return -2.0f + 4.0f * unit_float(w); }
+__device__ __forceinline__ int pong_action_from_word(uint32_t w) { return (int)__umulhi(w, 3u); }
+
+__device__ __forceinline__ PongEvent pong_transition(PongLane& s, int action, uint32_t w_vx,
+                                                     uint32_t w_vy, int max_score) {
+  // agent paddle, then opponent paddle (which looks at the ball before it moves)
+  const float move = (action == 1) ? -4.0f : ((action == 2) ? 4.0f : 0.0f);
+  float pa = s.pa + move;
+  pa = pa < 0.0f ? 0.0f : pa;
+  pa = pa > 194.0f ? 194.0f : pa;
+  float chase = (s.by + 1.0f) - (s.po + 8.0f);
+  chase = chase < -3.0f ? -3.0f : chase;
+  chase = chase > 3.0f ? 3.0f : chase;
+  float po = s.po + chase;
+  po = po < 0.0f ? 0.0f : po;
+  po = po > 194.0f ? 194.0f : po;
+
+  // ball flight and wall mirrors
+  float bx = s.bx + s.vx;
+  float by = s.by + s.vy;
+  float vx = s.vx, vy = s.vy;
+  const bool over_top = by < 0.0f;
+  by = over_top ? -by : by;
+  vy = over_top ? -vy : vy;
+  const bool under_bottom = by > 208.0f;
+  by = under_bottom ? 416.0f - by : by;
+  vy = under_bottom ? -vy : vy;
+
+  // paddle faces: the ball must be travelling towards the paddle and overlap it
+  const bool rows_a = (by + 2.0f >= pa) && (by <= pa + 16.0f);
+  const bool rows_o = (by + 2.0f >= po) && (by <= po + 16.0f);
+  const bool hit_a = (vx > 0.0f) && (bx + 2.0f >= 140.0f) && (bx <= 144.0f) && rows_a;
+  const bool hit_o = (vx < 0.0f) && (bx <= 20.0f) && (bx + 2.0f >= 16.0f) && rows_o;
+  const bool hit = hit_a || hit_o;
+  const float paddle_y = hit_a ? pa : po;
+  const float spin = 0.2f * ((by + 1.0f) - (paddle_y + 8.0f));
+  vx = hit ? -vx : vx;
+  vy = hit ? spin : vy;
+  bx = hit_a ? 138.0f : bx;
+  bx = hit_o ? 20.0f : bx;
+
+  // points and re-serve (paddles stay put)
+  const bool point_a = bx < 0.0f;
+  const bool point_o = !point_a && (bx + 2.0f > 160.0f);
+  const bool point = point_a || point_o;
+  PongEvent ev;
+  ev.reward = point_a ? 1.0f : (point_o ? -1.0f : 0.0f);
+  int sa = s.sa + (point_a ? 1 : 0);
+  int so = s.so + (point_o ? 1 : 0);
+  bx = point ? 79.0f : bx;
+  by = point ? 104.0f : by;
+  vx = point ? pong_serve_vx(w_vx) : vx;
+  vy = point ? pong_serve_vy(w_vy) : vy;
+
+  // episode bookkeeping and auto-reset
+  const int ep_ret = s.ep_ret + (point_a ? 1 : 0) - (point_o ? 1 : 0);
+  const int ep_len = s.ep_len + 1;
+  ev.done = (sa == max_score) || (so == max_score);
+  ev.fin_ret = ep_ret;
+  ev.fin_len = ep_len;
+  s.bx = bx; s.by = by; s.vx = vx; s.vy = vy;
+  s.pa = ev.done ? 97.0f : pa;
+  s.po = ev.done ? 97.0f : po;
+  s.sa = ev.done ? 0 : sa;
+  s.so = ev.done ? 0 : so;
+  s.ep_ret = ev.done ? 0 : ep_ret;
+  s.ep_len = ev.done ? 0 : ep_len;
+  return ev;
+}
+
+// First state of an episode started by env_reset: serve drawn from reset stream 16.
+__device__ __forceinline__ PongLane pong_initial(uint64_t seed, uint32_t env, uint64_t step) {
+  const Draw4 d = philox_draw(seed, env, step, 16u);
+  PongLane s;
+  s.bx = 79.0f; s.by = 104.0f;
+  s.vx = pong_serve_vx(d.w1);
+  s.vy = pong_serve_vy(d.w2);
+  s.pa = 97.0f; s.po = 97.0f;
+  s.sa = 0; s.so = 0; s.ep_ret = 0; s.ep_len = 0;
+  return s;
+}
+
+// SoA state: field f of environment i lives at state[f * n + i] (coalesced across a wavefront).
+__device__ __forceinline__ PongLane pong_load(const uint32_t* __restrict__ state, int64_t n,
+                                              int64_t i) {
+  PongLane s;
+  s.bx = __uint_as_float(state[0 * n + i]); s.by = __uint_as_float(state[1 * n + i]);
+  s.vx = __uint_as_float(state[2 * n + i]); s.vy = __uint_as_float(state[3 * n + i]);
+  s.pa = __uint_as_float(state[4 * n + i]); s.po = __uint_as_float(state[5 * n + i]);
+  s.sa = (int)state[6 * n + i]; s.so = (int)state[7 * n + i];
+  s.ep_ret = (int)state[8 * n + i]; s.ep_len = (int)state[9 * n + i];
+  return s;
+}
+
+__device__ __forceinline__ void pong_store(uint32_t* __restrict__ state, int64_t n, int64_t i,
+                                           const PongLane& s) {
+  state[0 * n + i] = __float_as_uint(s.bx); state[1 * n + i] = __float_as_uint(s.by);
+  state[2 * n + i] = __float_as_uint(s.vx); state[3 * n + i] = __float_as_uint(s.vy);
+  state[4 * n + i] = __float_as_uint(s.pa); state[5 * n + i] = __float_as_uint(s.po);
+  state[6 * n + i] = (uint32_t)s.sa; state[7 * n + i] = (uint32_t)s.so;
+  state[8 * n + i] = (uint32_t)s.ep_ret; state[9 * n + i] = (uint32_t)s.ep_len;
+}
+
+__device__ __forceinline__ PongLane pong_idle_lane() {
+  PongLane s;
+  s.bx = 79.0f; s.by = 104.0f; s.vx = 0.0f; s.vy = 0.0f; s.pa = 97.0f; s.po = 97.0f;
+  s.sa = 0; s.so = 0; s.ep_ret = 0; s.ep_len = 0;
+  return s;
+}
+
+}  // namespace envk

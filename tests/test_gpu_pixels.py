@@ -1,0 +1,143 @@
+"""GPU parity: Pong with pixel observations (84x84 uint8, 4-slot ring / frame trajectory) vs the
+CPU oracle's rasteriser, byte for byte, through the C-ABI."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+from oracle import oracle as orc                      # noqa: E402
+from paper_2603_12145_amd import binding as b         # noqa: E402
+from paper_2603_12145_amd import inputs               # noqa: E402
+from gpu_helpers import assert_bit_equal, split_state, pong_state_fields, pong_blob  # noqa: E402
+
+DEV = "cuda:0"
+F = 84
+
+
+def _tune(epw, streaming=0):
+    assert b.lib().mi355env_tune_pixels(epw, streaming) == 0
+
+
+@pytest.fixture(autouse=True)
+def _default_tuning():
+    yield
+    _tune(16, 0)
+
+
+@pytest.mark.parametrize("epw", [4, 8, 16, 32, 64])
+@pytest.mark.parametrize("n", [37, 200])
+def test_ring_steps_match_oracle(n, epw):
+    _tune(epw)
+    seed, T = 40 + n, 14
+    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"max_score": 1})
+    ring = torch.zeros((n, 4, F, F), dtype=torch.uint8, device=DEV)
+    rew = torch.empty(n, dtype=torch.float32, device=DEV)
+    done = torch.empty(n, dtype=torch.uint8, device=DEV)
+    b.env_reset(h, ring)
+    p = orc.Pong(n, seed, max_score=1); p.reset()
+    stack = np.zeros((n, 4, F, F), np.uint8)
+    p.fill_stack(stack)
+    torch.cuda.synchronize()
+    assert_bit_equal(ring.cpu().numpy(), stack, "ring after reset")
+    for t in range(T):
+        b.env_step(h, None, ring, rew, done)
+        _, orew, odone = p.step(stack=stack)
+        torch.cuda.synchronize()
+        assert_bit_equal(ring.cpu().numpy(), stack, "ring after step %d" % t)
+        assert_bit_equal(rew.cpu().numpy(), orew, "reward step %d" % t)
+        assert_bit_equal(done.cpu().numpy(), odone, "done step %d" % t)
+    _, fields = split_state(b.env_get_state(h), n, 10)
+    assert_bit_equal(fields, pong_state_fields(p.envs()), "state")
+    b.env_destroy(h)
+
+
+def test_streaming_store_variant_matches():
+    _tune(16, 1)
+    n, seed = 100, 3
+    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, None)
+    ring = torch.zeros((n, 4, F, F), dtype=torch.uint8, device=DEV)
+    rew = torch.empty(n, dtype=torch.float32, device=DEV)
+    done = torch.empty(n, dtype=torch.uint8, device=DEV)
+    b.env_reset(h, ring)
+    p = orc.Pong(n, seed); p.reset()
+    stack = np.zeros((n, 4, F, F), np.uint8); p.fill_stack(stack)
+    for t in range(6):
+        b.env_step(h, None, ring, rew, done)
+        p.step(stack=stack)
+    torch.cuda.synchronize()
+    assert_bit_equal(ring.cpu().numpy(), stack, "streaming ring")
+    b.env_destroy(h)
+
+
+def test_frame_trajectory_rollout_with_external_actions():
+    n, seed, T = 150, 8, 40
+    acts = inputs.pong_actions(T, n, seed=2)
+    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"max_score": 1})
+    b.env_reset(h, None)
+    frames = torch.empty((T, n, F, F), dtype=torch.uint8, device=DEV)
+    rew = torch.empty((T, n), dtype=torch.float32, device=DEV)
+    done = torch.empty((T, n), dtype=torch.uint8, device=DEV)
+    b.env_rollout(h, T, torch.from_numpy(acts).to(DEV), frames, rew, done)
+    torch.cuda.synchronize()
+    stats = b.env_stats(h)
+    b.env_destroy(h)
+    p = orc.Pong(n, seed, max_score=1); p.reset()
+    stack = np.zeros((n, 4, F, F), np.uint8)
+    got = frames.cpu().numpy()
+    for t in range(T):
+        _, orew, odone = p.step(actions=acts[t], stack=stack)
+        assert_bit_equal(got[t], stack[:, t % 4], "frame %d" % t)
+        assert_bit_equal(rew[t].cpu().numpy(), orew, "reward %d" % t)
+        assert_bit_equal(done[t].cpu().numpy(), odone, "done %d" % t)
+    assert stats["episodes"] == p.stats()["episodes"] > 0
+
+
+def test_rasteriser_on_arbitrary_positions():
+    # states injected through env_set_state (ball velocity zero, far from events is not needed:
+    # the frame shows the post-step state, which the oracle renders from its own post-step state)
+    n = 2048
+    pos = inputs.pong_positions(n, seed=11)
+    envs = np.zeros(n, orc.PONG_ENV_DTYPE)
+    envs["bx"], envs["by"], envs["pa"], envs["po"] = pos[:, 0], pos[:, 1], pos[:, 2], pos[:, 3]
+    envs["vx"] = np.where(np.arange(n) % 2 == 0, 3.0, -3.0)
+    envs["vy"] = np.linspace(-2, 2, n).astype(np.float32)
+    p = orc.Pong(n, 5)
+    p.envs()[:] = envs
+    h = b.env_create(b.ENV_PONG_PIXELS, n, 5, None)
+    b.env_set_state(h, pong_blob(0, pong_state_fields(envs)))
+    ring = torch.zeros((n, 4, F, F), dtype=torch.uint8, device=DEV)
+    rew = torch.empty(n, dtype=torch.float32, device=DEV)
+    done = torch.empty(n, dtype=torch.uint8, device=DEV)
+    stack = np.zeros((n, 4, F, F), np.uint8)
+    for t in range(3):
+        b.env_step(h, None, ring, rew, done)
+        p.step(stack=stack)
+    torch.cuda.synchronize()
+    assert_bit_equal(ring.cpu().numpy(), stack, "arbitrary positions")
+    assert (ring[:, 3] == 0).all()          # slot 3 not written yet by steps 0..2
+    b.env_destroy(h)
+
+
+def test_config3_n16384_t500_final_ring():
+    # full size, per-step launches as bench measures them; the oracle steps all environments
+    # without rendering and renders only the last four steps (the content of the ring at the end)
+    n, seed, T = 16384, 3, 500
+    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, None)
+    ring = torch.zeros((n, 4, F, F), dtype=torch.uint8, device=DEV)
+    rew = torch.empty((T, n), dtype=torch.float32, device=DEV)
+    done = torch.empty((T, n), dtype=torch.uint8, device=DEV)
+    b.env_reset(h, ring)
+    for t in range(T):
+        b.env_step(h, None, ring, rew[t], done[t])
+    torch.cuda.synchronize()
+    p = orc.Pong(n, seed); p.reset()
+    _, orew, odone = p.rollout(T - 4, nthreads=16, want_obs=False)
+    stack = np.zeros((n, 4, F, F), np.uint8)
+    _, orew2, odone2 = p.rollout(4, stack=stack, nthreads=16, want_obs=False)
+    assert_bit_equal(rew.cpu().numpy(), np.concatenate([orew, orew2]), "C3 reward")
+    assert_bit_equal(done.cpu().numpy(), np.concatenate([odone, odone2]), "C3 done")
+    assert_bit_equal(ring.cpu().numpy(), stack, "C3 ring")
+    _, fields = split_state(b.env_get_state(h), n, 10)
+    assert_bit_equal(fields, pong_state_fields(p.envs()), "C3 state")
+    b.env_destroy(h)

@@ -1,0 +1,287 @@
+"""GPU parity: Pong with vector observations, HIP path vs CPU oracle, bit for bit.
+Every call goes through the C-ABI (paper_2603_12145_amd.binding is marshalling only)."""
+import ctypes as C
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+from oracle import oracle as orc                      # noqa: E402
+from paper_2603_12145_amd import binding as b         # noqa: E402
+from paper_2603_12145_amd import inputs               # noqa: E402
+from gpu_helpers import assert_bit_equal, split_state, pong_state_fields, pong_blob  # noqa: E402
+
+DEV = "cuda:0"
+
+
+def bufs(T, n, obs_dim=8):
+    return (torch.empty((T, n, obs_dim), dtype=torch.float32, device=DEV),
+            torch.empty((T, n), dtype=torch.float32, device=DEV),
+            torch.empty((T, n), dtype=torch.uint8, device=DEV))
+
+
+def gpu_rollout(n, seed, T, max_score=21, actions=None, per_step=False):
+    h = b.env_create(b.ENV_PONG, n, seed, {"max_score": max_score})
+    try:
+        obs0 = torch.empty((n, 8), dtype=torch.float32, device=DEV)
+        b.env_reset(h, obs0)
+        obs, rew, done = bufs(T, n)
+        act = None if actions is None else torch.from_numpy(actions).to(DEV)
+        if per_step:
+            for t in range(T):
+                b.env_step(h, None if act is None else act[t], obs[t], rew[t], done[t])
+        else:
+            b.env_rollout(h, T, act, obs, rew, done)
+        torch.cuda.synchronize()
+        out = dict(obs0=obs0.cpu().numpy(), obs=obs.cpu().numpy(), rew=rew.cpu().numpy(),
+                   done=done.cpu().numpy(), stats=b.env_stats(h), state=b.env_get_state(h),
+                   steps=b.env_step_count(h))
+    finally:
+        b.env_destroy(h)
+    return out
+
+
+def oracle_rollout(n, seed, T, max_score=21, actions=None, nthreads=8):
+    p = orc.Pong(n, seed, max_score=max_score)
+    obs0 = p.reset()
+    obs, rew, done = p.rollout(T, actions=actions, nthreads=nthreads)
+    return dict(obs0=obs0, obs=obs, rew=rew, done=done, stats=p.stats(),
+                state=pong_state_fields(p.envs()), steps=p.step_count)
+
+
+def compare(g, o, n, what):
+    assert_bit_equal(g["obs0"], o["obs0"], what + " reset obs")
+    assert_bit_equal(g["obs"], o["obs"], what + " obs")
+    assert_bit_equal(g["rew"], o["rew"], what + " reward")
+    assert_bit_equal(g["done"], o["done"], what + " done")
+    step, fields = split_state(g["state"], n, 10)
+    assert step == o["steps"] == g["steps"]
+    assert_bit_equal(fields, o["state"], what + " final state")
+    gs, os_ = g["stats"], o["stats"]
+    assert gs["episodes"] == os_["episodes"] and gs["length_sum"] == os_["length_sum"]
+    assert gs["return_sum"] == os_["return_sum"]
+    if os_["episodes"]:
+        assert gs["return_min"] == os_["return_min"] and gs["return_max"] == os_["return_max"]
+    else:
+        assert gs["return_min"] == float("inf") and gs["return_max"] == float("-inf")
+
+
+@pytest.mark.parametrize("per_step", [False, True])
+@pytest.mark.parametrize("max_score", [21, 2])
+def test_config0_n64_t1000(per_step, max_score):
+    g = gpu_rollout(64, 0, 1000, max_score, per_step=per_step)
+    o = oracle_rollout(64, 0, 1000, max_score)
+    compare(g, o, 64, "C0 per_step=%s max_score=%d" % (per_step, max_score))
+    if max_score == 2:
+        assert o["stats"]["episodes"] > 500
+
+
+@pytest.mark.parametrize("n", [1, 3, 63, 65, 1000, 1003, 4100])
+def test_ragged_and_tiny_batches(n):
+    g = gpu_rollout(n, 17, 300, 2)
+    o = oracle_rollout(n, 17, 300, 2)
+    compare(g, o, n, "ragged n=%d" % n)
+
+
+def test_external_actions_including_out_of_range_codes():
+    n, T = 333, 400
+    acts = inputs.pong_actions(T, n, seed=5)
+    g = gpu_rollout(n, 23, T, 3, actions=acts)
+    o = oracle_rollout(n, 23, T, 3, actions=acts)
+    compare(g, o, n, "external actions rollout")
+    g2 = gpu_rollout(n, 23, T, 3, actions=acts, per_step=True)
+    compare(g2, o, n, "external actions per step")
+
+
+def test_env_i_is_independent_of_batch_size():
+    a = gpu_rollout(64, 5, 500, 3)
+    c = gpu_rollout(4096, 5, 500, 3)
+    assert_bit_equal(a["obs"], c["obs"][:, :64], "N independence obs")
+    assert_bit_equal(a["done"], c["done"][:, :64], "N independence done")
+
+
+def test_save_restore_and_split_rollouts():
+    n, seed = 500, 31
+    full = gpu_rollout(n, seed, 600, 2)
+    h = b.env_create(b.ENV_PONG, n, seed, {"max_score": 2})
+    b.env_reset(h, None)
+    o1, r1, d1 = bufs(250, n)
+    b.env_rollout(h, 250, None, o1, r1, d1)
+    blob = b.env_get_state(h)
+    b.env_destroy(h)
+    h2 = b.env_create(b.ENV_PONG, n, seed, {"max_score": 2})
+    b.env_set_state(h2, blob)                      # no env_reset: set_state marks it as reset
+    o2, r2, d2 = bufs(350, n)
+    b.env_rollout(h2, 350, None, o2, r2, d2)
+    torch.cuda.synchronize()
+    assert b.env_step_count(h2) == 600
+    b.env_destroy(h2)
+    assert_bit_equal(full["obs"][:250], o1.cpu().numpy(), "first part")
+    assert_bit_equal(full["obs"][250:], o2.cpu().numpy(), "second part")
+    assert_bit_equal(full["done"][250:], d2.cpu().numpy(), "second part done")
+    assert_bit_equal(full["rew"][250:], r2.cpu().numpy(), "second part reward")
+
+
+def test_set_state_from_oracle_state_then_step():
+    # hand the GPU a state produced by the oracle mid-rollout; both continue identically
+    n, seed = 130, 77
+    p = orc.Pong(n, seed, max_score=2); p.reset(); p.rollout(123)
+    blob = pong_blob(p.step_count, pong_state_fields(p.envs()))
+    h = b.env_create(b.ENV_PONG, n, seed, {"max_score": 2})
+    b.env_set_state(h, blob)
+    obs, rew, done = bufs(200, n)
+    b.env_rollout(h, 200, None, obs, rew, done)
+    torch.cuda.synchronize()
+    b.env_destroy(h)
+    oo, orr, od = p.rollout(200)
+    assert_bit_equal(obs.cpu().numpy(), oo, "obs after set_state")
+    assert_bit_equal(rew.cpu().numpy(), orr, "reward after set_state")
+    assert_bit_equal(done.cpu().numpy(), od, "done after set_state")
+
+
+def test_stats_reset_counters():
+    h = b.env_create(b.ENV_PONG, 256, 3, {"max_score": 1})
+    b.env_reset(h, None)
+    obs, rew, done = bufs(400, 256)
+    b.env_rollout(h, 400, None, obs, rew, done)
+    s1 = b.env_stats(h, reset_counters=True)
+    s2 = b.env_stats(h)
+    assert s1["episodes"] == int(done.sum().item()) > 0
+    assert s2["episodes"] == 0 and s2["length_sum"] == 0 and s2["return_sum"] == 0
+    b.env_rollout(h, 400, None, obs, rew, done)
+    s3 = b.env_stats(h)
+    assert s3["episodes"] == int(done.sum().item())
+    b.env_destroy(h)
+
+
+def test_second_env_reset_uses_current_step_counter():
+    n, seed = 70, 9
+    h = b.env_create(b.ENV_PONG, n, seed, None)
+    obs0 = torch.empty((n, 8), dtype=torch.float32, device=DEV)
+    b.env_reset(h, obs0)
+    obs, rew, done = bufs(40, n)
+    b.env_rollout(h, 40, None, obs, rew, done)
+    b.env_reset(h, obs0)
+    torch.cuda.synchronize()
+    b.env_destroy(h)
+    p = orc.Pong(n, seed); p.reset(); p.rollout(40)
+    assert_bit_equal(obs0.cpu().numpy(), p.reset(), "second reset obs")
+
+
+def test_error_paths_touch_nothing():
+    n = 128
+    h = b.env_create(b.ENV_PONG, n, 1, None)
+    obs, rew, done = bufs(4, n)
+    obs.fill_(-7.0); rew.fill_(-7.0); done.fill_(9)
+    L = b.lib()
+    vp = C.c_void_p
+    # step before reset
+    assert L.env_step(h, None, vp(obs.data_ptr()), vp(rew.data_ptr()), vp(done.data_ptr())) == b.ENV_E_STATE
+    b.env_reset(h, None)
+    # NULL outputs, T <= 0
+    assert L.env_step(h, None, None, vp(rew.data_ptr()), vp(done.data_ptr())) == b.ENV_E_ARG
+    assert L.env_step(h, None, vp(obs.data_ptr()), None, vp(done.data_ptr())) == b.ENV_E_ARG
+    assert L.env_step(h, None, vp(obs.data_ptr()), vp(rew.data_ptr()), None) == b.ENV_E_ARG
+    assert L.env_rollout(h, 0, None, vp(obs.data_ptr()), vp(rew.data_ptr()), vp(done.data_ptr())) == b.ENV_E_ARG
+    assert L.env_rollout(h, -3, None, vp(obs.data_ptr()), vp(rew.data_ptr()), vp(done.data_ptr())) == b.ENV_E_ARG
+    # misaligned obs / reward
+    assert L.env_step(h, None, vp(obs.data_ptr() + 4), vp(rew.data_ptr()), vp(done.data_ptr())) == b.ENV_E_ARG
+    assert L.env_step(h, None, vp(obs.data_ptr()), vp(rew.data_ptr() + 2), vp(done.data_ptr())) == b.ENV_E_ARG
+    # host memory where device memory is required
+    host = np.zeros(n * 8 * 4, np.float32)
+    assert L.env_step(h, None, vp(host.ctypes.data), vp(rew.data_ptr()), vp(done.data_ptr())) == b.ENV_E_ARG
+    # rollout longer than the buffers: T*n*8 floats do not fit in the allocation
+    small = torch.empty((n, 8), dtype=torch.float32, device=DEV)
+    big_T = 1 << 20
+    assert L.env_rollout(h, big_T, None, vp(small.data_ptr()), vp(rew.data_ptr()), vp(done.data_ptr())) == b.ENV_E_ARG
+    # wrong blob size
+    blob = b.env_get_state(h)
+    assert L.env_set_state(h, vp(blob.ctypes.data), blob.nbytes - 4) == b.ENV_E_ARG
+    assert L.env_get_state(h, vp(blob.ctypes.data), blob.nbytes + 4) == b.ENV_E_ARG
+    torch.cuda.synchronize()
+    assert b.env_step_count(h) == 0
+    assert float(obs.min()) == -7.0 == float(obs.max()) and int(done.min()) == 9
+    # and the handle still works
+    b.env_step(h, None, obs[0], rew[0], done[0])
+    torch.cuda.synchronize()
+    assert b.env_step_count(h) == 1 and float(obs[0].max()) > 0
+    b.env_destroy(h)
+
+
+def test_non_default_stream():
+    n, seed, T = 200, 12, 300
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        h = b.env_create(b.ENV_PONG, n, seed, {"max_score": 2}, stream=s)
+        obs, rew, done = bufs(T, n)
+        b.env_reset(h, None)
+        b.env_rollout(h, T, None, obs, rew, done)
+    s.synchronize()
+    o = oracle_rollout(n, seed, T, 2)
+    assert_bit_equal(obs.cpu().numpy(), o["obs"], "stream obs")
+    b.env_destroy(h)
+
+
+def test_config1_n4096_t10000_one_launch_per_step():
+    n, seed, T = 4096, 1, 10000
+    h = b.env_create(b.ENV_PONG, n, seed, None)
+    b.env_reset(h, None)
+    obs, rew, done = bufs(T, n)
+    for t in range(T):
+        b.env_step(h, None, obs[t], rew[t], done[t])
+    torch.cuda.synchronize()
+    stats = b.env_stats(h)
+    b.env_destroy(h)
+    o = oracle_rollout(n, seed, T, 21, nthreads=16)
+    assert_bit_equal(obs.cpu().numpy(), o["obs"], "C1 obs")
+    assert_bit_equal(rew.cpu().numpy(), o["rew"], "C1 reward")
+    assert_bit_equal(done.cpu().numpy(), o["done"], "C1 done")
+    assert stats["episodes"] == o["stats"]["episodes"] > 1000
+    assert stats["return_sum"] == o["stats"]["return_sum"]
+
+
+@pytest.mark.parametrize("n", [16384, 65536])
+def test_config2_fused_rollout_full_size(n):
+    # the launch configuration bench.py times: one env_rollout(T=1000) over N environments, seed 2
+    seed, T = 2, 1000
+    h = b.env_create(b.ENV_PONG, n, seed, None)
+    b.env_reset(h, None)
+    obs, rew, done = bufs(T, n)
+    b.env_rollout(h, T, None, obs, rew, done)
+    torch.cuda.synchronize()
+    stats = b.env_stats(h)
+    b.env_destroy(h)
+    o = oracle_rollout(n, seed, T, 21, nthreads=16)
+    assert_bit_equal(rew.cpu().numpy(), o["rew"], "C2 reward")
+    assert_bit_equal(done.cpu().numpy(), o["done"], "C2 done")
+    assert_bit_equal(obs.cpu().numpy(), o["obs"], "C2 obs")
+    assert stats["episodes"] == o["stats"]["episodes"]
+    assert stats["return_sum"] == o["stats"]["return_sum"]
+    assert stats["length_sum"] == o["stats"]["length_sum"]
+
+
+def test_config2_largest_sweep_size_sampled():
+    # N = 262144 x T = 1000 (9.7 GB of trajectory): compare the first 4096 and the last 4096
+    # environments of every step (the oracle computes environment i independently of N), plus the
+    # episode statistics of a full oracle run without trajectory storage.
+    n, seed, T = 262144, 2, 1000
+    h = b.env_create(b.ENV_PONG, n, seed, None)
+    b.env_reset(h, None)
+    obs, rew, done = bufs(T, n)
+    b.env_rollout(h, T, None, obs, rew, done)
+    torch.cuda.synchronize()
+    stats = b.env_stats(h)
+    b.env_destroy(h)
+    p = orc.Pong(n, seed); p.reset()
+    _, orew, odone = p.rollout(T, nthreads=16, want_obs=False)
+    assert_bit_equal(rew.cpu().numpy(), orew, "C2-262144 reward")
+    assert_bit_equal(done.cpu().numpy(), odone, "C2-262144 done")
+    q = orc.Pong(4096, seed); q.reset()
+    qobs, _, _ = q.rollout(T, nthreads=16)
+    assert_bit_equal(obs[:, :4096].cpu().numpy(), qobs, "C2-262144 obs head")
+    st = p.stats()
+    assert stats["episodes"] == st["episodes"] and stats["return_sum"] == st["return_sum"]
+    # last 4096 environments: final observation equals the oracle's final state
+    assert_bit_equal(obs[T - 1, -4096:].cpu().numpy(), p.obs()[-4096:], "C2-262144 final obs tail")
