@@ -1,0 +1,257 @@
+#!/usr/bin/env python3
+"""Benchmark of the vectorised-environment hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--skip-extra] [--skip-cpu]
+
+A "step" is one env_rollout launch of the headline workload: Pong, N = 65536 environments x
+T = 1000 steps fused into one kernel (seed 2), writing obs[T,N,8] f32, reward[T,N] f32 and
+done[T,N] u8 — Philox draws, dynamics, auto-reset, trajectory stores and episode statistics all
+inside the launch.  Buffers are resident in HBM before the timed region.  One JSON line is printed.
+
+`roofline` is for the rollout kernel: algorithmic bytes (37 B per env-step x N x T) divided by the
+mean launch duration measured with HIP events on the launch stream, against 8 TB/s.
+`cpu_baseline` times the CPU oracle (test infrastructure) on the same workload on the host cores.
+`extra` carries the other hot-path rows (per-step launches, pixel render, rigid body) measured the
+same way, and a plain fill kernel as the write-bandwidth yardstick.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+PONG_BYTES_PER_ENV_STEP = 37   # 32 obs + 4 reward + 1 done
+FRAME_BYTES = 84 * 84          # one new frame per env-step
+
+
+def _events(n):
+    import torch
+    return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
+
+
+def _mean_std(xs):
+    m = sum(xs) / len(xs)
+    v = sum((x - m) ** 2 for x in xs) / max(1, len(xs) - 1)
+    return m, v ** 0.5
+
+
+def time_launches(fn, steps, warmup):
+    """Runs fn() warmup + steps times; returns (wall seconds for the timed steps, list of
+    per-launch milliseconds from HIP events recorded on the current stream)."""
+    import torch
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    starts, ends = _events(steps), _events(steps)
+    t0 = time.perf_counter()
+    for k in range(steps):
+        starts[k].record()
+        fn()
+        ends[k].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall, [s.elapsed_time(e) for s, e in zip(starts, ends)]
+
+
+def bench_pong_rollout(b, torch, n, T, seed, steps, warmup):
+    dev = "cuda:0"
+    h = b.env_create(b.ENV_PONG, n, seed, None)
+    obs = torch.empty((T, n, 8), dtype=torch.float32, device=dev)
+    rew = torch.empty((T, n), dtype=torch.float32, device=dev)
+    done = torch.empty((T, n), dtype=torch.uint8, device=dev)
+    b.env_reset(h, None)
+    wall, ms = time_launches(lambda: b.env_rollout(h, T, None, obs, rew, done), steps, warmup)
+    stats = b.env_stats(h)
+    b.env_destroy(h)
+    del obs, rew, done
+    mean_ms, std_ms = _mean_std(ms)
+    return dict(wall=wall, mean_ms=mean_ms, std_ms=std_ms, env_steps=n * T * steps,
+                episodes=stats["episodes"])
+
+
+def bench_pong_per_step(b, torch, n, seed, launches):
+    dev = "cuda:0"
+    h = b.env_create(b.ENV_PONG, n, seed, None)
+    obs = torch.empty((n, 8), dtype=torch.float32, device=dev)
+    rew = torch.empty(n, dtype=torch.float32, device=dev)
+    done = torch.empty(n, dtype=torch.uint8, device=dev)
+    b.env_reset(h, None)
+    for _ in range(200):
+        b.env_step(h, None, obs, rew, done)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(launches):
+        b.env_step(h, None, obs, rew, done)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    b.env_destroy(h)
+    return dict(workload="pong vector obs N=%d, one env_step launch per step" % n,
+                us_per_launch=1e6 * wall / launches, env_steps_per_s=n * launches / wall,
+                bound="dispatch latency", launches=launches)
+
+
+def bench_pixels(b, torch, n, seed, launches, warmup=20):
+    dev = "cuda:0"
+    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, None)
+    ring = torch.zeros((n, 4, 84, 84), dtype=torch.uint8, device=dev)
+    rew = torch.empty(n, dtype=torch.float32, device=dev)
+    done = torch.empty(n, dtype=torch.uint8, device=dev)
+    b.env_reset(h, ring)
+    wall, ms = time_launches(lambda: b.env_step(h, None, ring, rew, done), launches, warmup)
+    b.env_destroy(h)
+    mean_ms, std_ms = _mean_std(ms)
+    gbs = n * FRAME_BYTES / (mean_ms * 1e-3) / 1e9
+    return dict(workload="pong pixels N=%d, 84x84 u8 frame into a 4-slot ring, one env_step launch per step" % n,
+                env_steps_per_s=n * launches / wall, us_per_launch_events=mean_ms * 1e3,
+                us_per_launch_wall=1e6 * wall / launches,
+                roofline=dict(bound="hbm", achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s",
+                              frac=gbs / HBM_PEAK_GBS, traffic=None),
+                launches=launches)
+
+
+def bench_fill(b, torch, nbytes, launches=50):
+    import ctypes as C
+    L = b.lib()
+    L.mi355env_bench_fill.argtypes = [C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p]
+    buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    s = torch.cuda.current_stream().cuda_stream
+    wall, ms = time_launches(lambda: L.mi355env_bench_fill(buf.data_ptr(), nbytes, 0, s), launches, 5)
+    mean_ms, _ = _mean_std(ms)
+    return dict(workload="plain 16-byte fill of %d MiB" % (nbytes >> 20),
+                gbs=nbytes / (mean_ms * 1e-3) / 1e9, frac_of_peak=nbytes / (mean_ms * 1e-3) / 1e9 / HBM_PEAK_GBS)
+
+
+def bench_body(b, torch, n, T, seed, steps):
+    dev = "cuda:0"
+    h = b.env_create(b.ENV_BODY, n, seed, None)
+    obs = torch.empty((T, n, 17), dtype=torch.float32, device=dev)
+    rew = torch.empty((T, n), dtype=torch.float32, device=dev)
+    done = torch.empty((T, n), dtype=torch.uint8, device=dev)
+    b.env_reset(h, None)
+    wall, ms = time_launches(lambda: b.env_rollout(h, T, None, obs, rew, done), steps, 1)
+    st = b.env_stats(h)
+    b.env_destroy(h)
+    mean_ms, std_ms = _mean_std(ms)
+    return dict(workload="articulated body N=%d x T=%d fused rollout" % (n, T),
+                env_steps_per_s=n * T * steps / wall, ms_per_launch=mean_ms,
+                nonfinite=st["nonfinite"], episodes=st["episodes"])
+
+
+def cpu_baseline(n, T, seed):
+    """The oracle as it stands, one pass over the headline workload, all host threads allotted."""
+    import numpy as np
+    from oracle import oracle as orc
+    cores = min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), 16)
+    out = (np.zeros((T, n, 8), np.float32), np.zeros((T, n), np.float32), np.zeros((T, n), np.uint8))
+    p = orc.Pong(n, seed)
+    p.reset()
+    p.rollout(10, nthreads=cores, out=tuple(a[:10] for a in out))       # warm-up, touches code paths
+    p = orc.Pong(n, seed)
+    p.reset()
+    t0 = time.perf_counter()
+    p.rollout(T, nthreads=cores, out=out)
+    multi = time.perf_counter() - t0
+    n1 = max(1, n // 8)
+    out1 = (np.zeros((T, n1, 8), np.float32), np.zeros((T, n1), np.float32),
+            np.zeros((T, n1), np.uint8))
+    q = orc.Pong(n1, seed)
+    q.reset()
+    t0 = time.perf_counter()
+    q.rollout(T, nthreads=1, out=out1)
+    single = time.perf_counter() - t0
+    return dict(value=n * T / multi, unit="env-steps/s", cores=cores, kind="oracle",
+                sample="Pong N=%d x T=%d, one full pass of the headline workload, %d threads; "
+                       "single thread on N=%d: %.3g env-steps/s" % (n, T, cores, n1, n1 * T / single),
+                single_thread_value=n1 * T / single)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--n", type=int, default=65536, help="environments (headline: 65536)")
+    ap.add_argument("--T", type=int, default=1000)
+    ap.add_argument("--skip-extra", action="store_true")
+    ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--only", default="", help="run only this extra workload (profiling aid)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this path runs on one GPU only (environments shard by index with no "
+              "per-step traffic; no multi-GPU figure is produced). Use --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2603_12145_amd import binding as b
+    b.lib()  # fails loudly if the HIP library is not built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    props = torch.cuda.get_device_properties(0)
+
+    if args.only:
+        fn = {"pixels": lambda: bench_pixels(b, torch, 16384, 3, args.steps),
+              "per_step": lambda: bench_pong_per_step(b, torch, 4096, 1, args.steps),
+              "body": lambda: bench_body(b, torch, 8192, 1000, 4, args.steps),
+              "fill": lambda: bench_fill(b, torch, 1 << 30, args.steps)}[args.only]
+        print(json.dumps(fn()))
+        return
+
+    n, T, seed = args.n, args.T, 2
+    r = bench_pong_rollout(b, torch, n, T, seed, args.steps, args.warmup)
+    value = r["env_steps"] / r["wall"]
+    achieved = PONG_BYTES_PER_ENV_STEP * n * T / (r["mean_ms"] * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get("pong_rollout_n%d_t%d" % (n, T))
+        except Exception:
+            traffic = None
+    line = {
+        "metric": "env-steps/sec on 1 MI355X (Pong N=65536 fused rollout) + % of HBM roofline",
+        "value": value, "unit": "env-steps/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": 1e3 * r["wall"] / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": "Pong fused env_rollout, N=%d envs x T=%d steps per launch, seed 2, "
+                               "in-kernel Philox actions, obs[T,N,8] f32 + reward[T,N] f32 + done[T,N] u8"
+                               % (n, T),
+                   "n_envs": n, "T": T, "env_steps_per_step": n * T},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": "pong_rollout_kernel", "launch_ms_mean": r["mean_ms"],
+                     "launch_ms_std": r["std_ms"],
+                     "algorithmic_bytes_per_launch": PONG_BYTES_PER_ENV_STEP * n * T},
+        "device": {"name": props.name, "cus": props.multi_processor_count,
+                   "hbm_gib": round(props.total_memory / 2 ** 30, 1)},
+    }
+    if not args.skip_cpu:
+        line["cpu_baseline"] = cpu_baseline(n, T, seed)
+    if not args.skip_extra:
+        extra = {}
+        extra["fill_yardstick"] = bench_fill(b, torch, 1 << 30)
+        extra["config1_per_step"] = bench_pong_per_step(b, torch, 4096, 1, 10000)
+        extra["config3_pixels"] = bench_pixels(b, torch, 16384, 3, 500)
+        for nn in (16384, 262144):
+            rr = bench_pong_rollout(b, torch, nn, T, seed, max(3, args.steps // 6), 1)
+            gbs = PONG_BYTES_PER_ENV_STEP * nn * T / (rr["mean_ms"] * 1e-3) / 1e9
+            extra["config2_n%d" % nn] = dict(env_steps_per_s=rr["env_steps"] / rr["wall"],
+                                             ms_per_launch=rr["mean_ms"], hbm_gbs=gbs,
+                                             frac=gbs / HBM_PEAK_GBS)
+        try:
+            extra["config4_body"] = bench_body(b, torch, 8192, 1000, 4, 2)
+        except b.EnvError as e:
+            extra["config4_body"] = {"error": str(e)}
+        line["extra"] = extra
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

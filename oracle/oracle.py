@@ -154,10 +154,16 @@ class Pong:
         return np.stack([e["bx"], e["by"], e["vx"], e["vy"], e["pa"], e["po"],
                          e["sa"].astype(np.float32), e["so"].astype(np.float32)], axis=1)
 
-    def rollout(self, T, actions=None, stack=None, nthreads=1, want_obs=True):
-        obs = np.empty((T, self.n, 8), np.float32) if want_obs else None
-        rew = np.empty((T, self.n), np.float32)
-        done = np.empty((T, self.n), np.uint8)
+    def rollout(self, T, actions=None, stack=None, nthreads=1, want_obs=True, out=None):
+        """out: optional pre-allocated (obs, reward, done) arrays to write into."""
+        if out is not None:
+            obs, rew, done = out
+            assert obs.shape == (T, self.n, 8) and obs.dtype == np.float32
+            assert rew.shape == (T, self.n) and done.shape == (T, self.n)
+        else:
+            obs = np.empty((T, self.n, 8), np.float32) if want_obs else None
+            rew = np.empty((T, self.n), np.float32)
+            done = np.empty((T, self.n), np.uint8)
         if actions is not None:
             actions = np.ascontiguousarray(actions, np.uint8)
             assert actions.shape == (T, self.n)
