@@ -23,19 +23,28 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
-def build(force=True, verbose=False, extra=()):
+def build(force=True, verbose=False, extra=(), out=None):
+    """extra: additional hipcc flags (e.g. -D switches for measurement variants); out: alternative
+    output path (the default in-tree library is what the binding loads)."""
     srcs = sources()
     deps = srcs + glob.glob(os.path.join(CSRC, "*.hpp")) + glob.glob(
         os.path.join(HERE, "..", "include", "*.h"))
-    if not force and os.path.exists(LIB) and all(
-            os.path.getmtime(LIB) >= os.path.getmtime(d) for d in deps):
-        return LIB
-    cmd = [HIPCC] + FLAGS + list(extra) + ["-o", LIB] + srcs
+    lib = out or LIB
+    if not force and os.path.exists(lib) and all(
+            os.path.getmtime(lib) >= os.path.getmtime(d) for d in deps):
+        return lib
+    cmd = [HIPCC] + FLAGS + list(extra) + ["-o", lib] + srcs
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":
-    print(build(force=True, verbose=True, extra=sys.argv[1:]))
+    args = sys.argv[1:]
+    out = None
+    if "--out" in args:
+        k = args.index("--out")
+        out = os.path.abspath(args[k + 1])
+        del args[k:k + 2]
+    print(build(force=True, verbose=True, extra=args, out=out))

@@ -14,7 +14,10 @@ namespace envk {
 namespace {
 
 constexpr int WAVE = 64;
-constexpr int ROLLOUT_BLOCK = 64;   // one wavefront per workgroup: spreads small N over many CUs
+#ifndef MI355ENV_ROLLOUT_BLOCK
+#define MI355ENV_ROLLOUT_BLOCK 64
+#endif
+constexpr int ROLLOUT_BLOCK = MI355ENV_ROLLOUT_BLOCK;   // threads per workgroup of the rollout kernel
 
 __global__ __launch_bounds__(256) void pong_reset_kernel(uint32_t* __restrict__ state, int64_t n,
                                                          uint64_t seed, uint64_t step,
@@ -63,7 +66,11 @@ __global__ __launch_bounds__(ROLLOUT_BLOCK) void pong_rollout_kernel(PongLaunch 
       le.max_key = max(le.max_key, ev.fin_ret);
     }
 
+#ifdef MI355ENV_EXPERIMENT_NO_STORES
+    if (live && a.T < 0) {
+#else
     if (live) {
+#endif
       float4* o = reinterpret_cast<float4*>(a.obs + (row + i) * PONG_OBS);
       o[0] = make_float4(s.bx, s.by, s.vx, s.vy);
       o[1] = make_float4(s.pa, s.po, (float)s.sa, (float)s.so);
