@@ -16,6 +16,7 @@ using namespace envk;
 
 namespace envk {
 bool set_pixel_tuning(int envs_per_wave, int streaming);
+bool set_rollout_block(int threads, int xcd_remap);
 }
 
 struct mi355env {
@@ -335,6 +336,10 @@ const char* env_strerror(int code) {
 // Measurement knob, not part of the documented boundary: launch shape of the pixel kernels.
 int mi355env_tune_pixels(int envs_per_wave, int streaming) {
   return set_pixel_tuning(envs_per_wave, streaming) ? ENV_OK : ENV_E_ARG;
+}
+
+int mi355env_tune_rollout(int threads_per_block, int xcd_remap) {
+  return set_rollout_block(threads_per_block, xcd_remap) ? ENV_OK : ENV_E_ARG;
 }
 
 }  // extern "C"

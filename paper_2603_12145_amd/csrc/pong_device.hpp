@@ -36,37 +36,45 @@ __device__ __forceinline__ float pong_serve_vx(uint32_t w) { return (w >> 31) ? 
 __device__ __forceinline__ float pong_serve_vy(uint32_t w) { return -2.0f + 4.0f * unit_float(w); }
 __device__ __forceinline__ int pong_action_from_word(uint32_t w) { return (int)__umulhi(w, 3u); }
 
+// Bit-exactness notes for the branch-free forms below (all values are finite, never NaN):
+//  * clamp(x, lo, hi) as min(max(x, lo), hi) equals the compare-and-assign form except for the
+//    sign of a zero; a negative zero cannot reach a clamp (paddle positions are sums of
+//    non-negative-zero terms, and x + (-x) rounds to +0).
+//  * the top-wall mirror "if (by < 0) { by = -by; vy = -vy; }" is done on the sign bit: by is a sum
+//    whose operands are never -0, so "sign bit set" and "by < 0" coincide.
+//  * the bottom-wall mirror by = min(by, 416 - by): for by <= 208 the rounded 416 - by is >= 208,
+//    for by > 208 it is < 208, so the minimum picks exactly what the comparison would.
+__device__ __forceinline__ float clampf(float x, float lo, float hi) {
+  return __builtin_fminf(__builtin_fmaxf(x, lo), hi);
+}
+
 __device__ __forceinline__ PongEvent pong_transition(PongLane& s, int action, uint32_t w_vx,
                                                      uint32_t w_vy, int max_score) {
   // agent paddle, then opponent paddle (which looks at the ball before it moves)
   const float move = (action == 1) ? -4.0f : ((action == 2) ? 4.0f : 0.0f);
-  float pa = s.pa + move;
-  pa = pa < 0.0f ? 0.0f : pa;
-  pa = pa > 194.0f ? 194.0f : pa;
-  float chase = (s.by + 1.0f) - (s.po + 8.0f);
-  chase = chase < -3.0f ? -3.0f : chase;
-  chase = chase > 3.0f ? 3.0f : chase;
-  float po = s.po + chase;
-  po = po < 0.0f ? 0.0f : po;
-  po = po > 194.0f ? 194.0f : po;
+  const float pa = clampf(s.pa + move, 0.0f, 194.0f);
+  const float chase = clampf((s.by + 1.0f) - (s.po + 8.0f), -3.0f, 3.0f);
+  const float po = clampf(s.po + chase, 0.0f, 194.0f);
 
   // ball flight and wall mirrors
   float bx = s.bx + s.vx;
-  float by = s.by + s.vy;
-  float vx = s.vx, vy = s.vy;
-  const bool over_top = by < 0.0f;
-  by = over_top ? -by : by;
-  vy = over_top ? -vy : vy;
-  const bool under_bottom = by > 208.0f;
-  by = under_bottom ? 416.0f - by : by;
+  const float by_raw = s.by + s.vy;
+  const uint32_t top_sign = __float_as_uint(by_raw) & 0x80000000u;
+  const float by_top = __uint_as_float(__float_as_uint(by_raw) ^ top_sign);
+  float vy = __uint_as_float(__float_as_uint(s.vy) ^ top_sign);
+  const bool under_bottom = by_top > 208.0f;
+  float by = __builtin_fminf(by_top, 416.0f - by_top);
   vy = under_bottom ? -vy : vy;
+  float vx = s.vx;
 
   // paddle faces: the ball must be travelling towards the paddle and overlap it
-  const bool rows_a = (by + 2.0f >= pa) && (by <= pa + 16.0f);
-  const bool rows_o = (by + 2.0f >= po) && (by <= po + 16.0f);
-  const bool hit_a = (vx > 0.0f) && (bx + 2.0f >= 140.0f) && (bx <= 144.0f) && rows_a;
-  const bool hit_o = (vx < 0.0f) && (bx <= 20.0f) && (bx + 2.0f >= 16.0f) && rows_o;
-  const bool hit = hit_a || hit_o;
+  // (bitwise & on purpose: no short-circuit branches inside the step)
+  const float by_bottom = by + 2.0f, bx_right = bx + 2.0f;
+  const bool rows_a = (by_bottom >= pa) & (by <= pa + 16.0f);
+  const bool rows_o = (by_bottom >= po) & (by <= po + 16.0f);
+  const bool hit_a = (vx > 0.0f) & (bx_right >= 140.0f) & (bx <= 144.0f) & rows_a;
+  const bool hit_o = (vx < 0.0f) & (bx <= 20.0f) & (bx_right >= 16.0f) & rows_o;
+  const bool hit = hit_a | hit_o;
   const float paddle_y = hit_a ? pa : po;
   const float spin = 0.2f * ((by + 1.0f) - (paddle_y + 8.0f));
   vx = hit ? -vx : vx;
@@ -76,12 +84,12 @@ __device__ __forceinline__ PongEvent pong_transition(PongLane& s, int action, ui
 
   // points and re-serve (paddles stay put)
   const bool point_a = bx < 0.0f;
-  const bool point_o = !point_a && (bx + 2.0f > 160.0f);
-  const bool point = point_a || point_o;
+  const bool point_o = (!point_a) & (bx + 2.0f > 160.0f);
+  const bool point = point_a | point_o;
   PongEvent ev;
   ev.reward = point_a ? 1.0f : (point_o ? -1.0f : 0.0f);
-  int sa = s.sa + (point_a ? 1 : 0);
-  int so = s.so + (point_o ? 1 : 0);
+  const int sa = s.sa + (point_a ? 1 : 0);
+  const int so = s.so + (point_o ? 1 : 0);
   bx = point ? 79.0f : bx;
   by = point ? 104.0f : by;
   vx = point ? pong_serve_vx(w_vx) : vx;
@@ -90,7 +98,7 @@ __device__ __forceinline__ PongEvent pong_transition(PongLane& s, int action, ui
   // episode bookkeeping and auto-reset
   const int ep_ret = s.ep_ret + (point_a ? 1 : 0) - (point_o ? 1 : 0);
   const int ep_len = s.ep_len + 1;
-  ev.done = (sa == max_score) || (so == max_score);
+  ev.done = (sa == max_score) | (so == max_score);
   ev.fin_ret = ep_ret;
   ev.fin_len = ep_len;
   s.bx = bx; s.by = by; s.vx = vx; s.vy = vy;

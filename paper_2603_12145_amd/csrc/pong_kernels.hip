@@ -38,23 +38,29 @@ __device__ __forceinline__ uint32_t spread_nibble(uint32_t nibble) {
   return (nibble & 1u) | ((nibble & 2u) << 7) | ((nibble & 4u) << 14) | ((nibble & 8u) << 21);
 }
 
-template <bool PACK_DONE>
-__global__ __launch_bounds__(ROLLOUT_BLOCK) void pong_rollout_kernel(PongLaunch a) {
-  const int lane = threadIdx.x & (WAVE - 1);
-  const int64_t i = (int64_t)blockIdx.x * ROLLOUT_BLOCK + threadIdx.x;
-  const int64_t wave_base = i - lane;
-  const bool live = i < a.n;
+// One wavefront's T-step loop.  FULL: all 64 lanes own an environment (no per-lane predication in
+// the loop).  Row pointers are wave-uniform (scalar) and advance by one row per step; the per-lane
+// part of every address is a constant 32-bit offset, so the stores need no vector address math.
+template <bool PACK_DONE, bool FULL, bool EXTERNAL_ACTIONS>
+__device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, LaneEpisodes& le,
+                                             const int lane, const int64_t wave_base) {
   const int64_t n = a.n;
+  const uint32_t env = (uint32_t)(wave_base + lane);
+  const bool live = FULL || (wave_base + lane < n);
+  float* obs_row = a.obs + wave_base * PONG_OBS;
+  float* rew_row = a.reward + wave_base;
+  uint8_t* done_row = a.done + wave_base;
+  const uint8_t* act_row = EXTERNAL_ACTIONS ? a.actions + wave_base : nullptr;
+  const bool done_lane = (lane < 16) && (FULL || (wave_base + 4 * lane < n));
 
-  PongLane s = live ? pong_load(a.state, n, i) : pong_idle_lane();
-  LaneEpisodes le;
-
+  Draw4 d = philox_draw(a.seed, env, a.step0, 0u);
   for (int32_t t = 0; t < a.T; ++t) {
-    const uint64_t step = a.step0 + (uint64_t)t;
-    const Draw4 d = philox_draw(a.seed, (uint32_t)i, step, 0u);
-    const int64_t row = (int64_t)t * n;
-    int action = pong_action_from_word(d.w0);
-    if (a.actions) action = live ? (int)a.actions[row + i] : 0;
+    // draw of the next step first: it does not depend on the state, so its multiply chain
+    // overlaps the compare/select chain of this step's transition
+    const Draw4 d_next = philox_draw(a.seed, env, a.step0 + (uint64_t)t + 1u, 0u);
+    int action;
+    if (EXTERNAL_ACTIONS) action = live ? (int)act_row[lane] : 0;
+    else action = pong_action_from_word(d.w0);
 
     const PongEvent ev = pong_transition(s, action, d.w1, d.w2, a.max_score);
     const bool done = live && ev.done;
@@ -71,27 +77,62 @@ __global__ __launch_bounds__(ROLLOUT_BLOCK) void pong_rollout_kernel(PongLaunch 
 #else
     if (live) {
 #endif
-      float4* o = reinterpret_cast<float4*>(a.obs + (row + i) * PONG_OBS);
+      float4* o = reinterpret_cast<float4*>(obs_row + lane * PONG_OBS);
       o[0] = make_float4(s.bx, s.by, s.vx, s.vy);
       o[1] = make_float4(s.pa, s.po, (float)s.sa, (float)s.so);
-      a.reward[row + i] = ev.reward;
+      rew_row[lane] = ev.reward;
     }
     if (PACK_DONE) {
       // n % 4 == 0 and done 4-byte aligned: every dword is entirely inside or outside the row
       const unsigned long long mask = __ballot(done);
-      const int64_t first = wave_base + 4 * lane;
-      if (lane < 16 && first < n) {
+      if (done_lane) {
         const uint32_t nibble = (uint32_t)(mask >> (4 * lane)) & 0xFu;
-        *reinterpret_cast<uint32_t*>(a.done + row + first) = spread_nibble(nibble);
+        reinterpret_cast<uint32_t*>(done_row)[lane] = spread_nibble(nibble);
       }
     } else if (live) {
-      a.done[row + i] = done ? 1 : 0;
+      done_row[lane] = done ? 1 : 0;
     }
+    obs_row += n * PONG_OBS;
+    rew_row += n;
+    done_row += n;
+    if (EXTERNAL_ACTIONS) act_row += n;
+    d = d_next;
   }
+}
 
+template <bool PACK_DONE, bool XCD_REMAP>
+__global__ __launch_bounds__(256) void pong_rollout_kernel(PongLaunch a) {
+  const int lane = threadIdx.x & (WAVE - 1);
+  // wave-uniform by construction; readfirstlane tells the compiler so (scalar address math)
+  const int wave_in_block = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  // Workgroups are handed to the 8 XCDs round-robin by blockIdx.  Give XCD x the x-th contiguous
+  // eighth of the environments (gridDim.x is a multiple of 8), so that every row of obs / reward /
+  // done is written as 8 contiguous slices, each through a single L2, instead of being
+  // interleaved across all eight at workgroup granularity.
+  const unsigned per_xcd = gridDim.x >> 3;
+  const unsigned logical_block = XCD_REMAP ? (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3) : blockIdx.x;
+  const int64_t wave_base = ((int64_t)logical_block * (blockDim.x >> 6) + wave_in_block) * WAVE;
+  const int64_t n = a.n;
+  if (wave_base >= n) return;
+  const int64_t i = wave_base + lane;
+  const bool live = i < n;
+  const bool full = wave_base + WAVE <= n;
+
+  PongLane s = live ? pong_load(a.state, n, i) : pong_idle_lane();
+  LaneEpisodes le;
+  if (a.actions) {
+    if (full) rollout_wave<PACK_DONE, true, true>(a, s, le, lane, wave_base);
+    else rollout_wave<PACK_DONE, false, true>(a, s, le, lane, wave_base);
+  } else {
+    if (full) rollout_wave<PACK_DONE, true, false>(a, s, le, lane, wave_base);
+    else rollout_wave<PACK_DONE, false, false>(a, s, le, lane, wave_base);
+  }
   if (live) pong_store(a.state, n, i, s);
   flush_wave_stats<false>(a.stats, le);
 }
+
+int g_rollout_block = 0;   // 0 = choose from N
+int g_xcd_remap = 1;
 
 }  // namespace
 
@@ -102,13 +143,27 @@ hipError_t launch_pong_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t
   return hipGetLastError();
 }
 
+// Measurement knob: threads per workgroup of the rollout kernel (64, 128, 256; 0 = automatic).
+bool set_rollout_block(int threads, int xcd_remap) {
+  if (threads != 0 && threads != 64 && threads != 128 && threads != 256) return false;
+  g_rollout_block = threads;
+  g_xcd_remap = xcd_remap;
+  return true;
+}
+
 hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream) {
-  const unsigned blocks = (unsigned)((a.n + ROLLOUT_BLOCK - 1) / ROLLOUT_BLOCK);
+  const int block = g_rollout_block ? g_rollout_block : ROLLOUT_BLOCK;
+  unsigned blocks = (unsigned)((a.n + block - 1) / block);
+  blocks = (blocks + 7u) & ~7u;   // multiple of the XCD count; surplus workgroups exit at once
   const bool pack = (a.n % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.done) & 3u) == 0);
-  if (pack)
-    hipLaunchKernelGGL(pong_rollout_kernel<true>, dim3(blocks), dim3(ROLLOUT_BLOCK), 0, stream, a);
-  else
-    hipLaunchKernelGGL(pong_rollout_kernel<false>, dim3(blocks), dim3(ROLLOUT_BLOCK), 0, stream, a);
+  const dim3 g(blocks), b(block);
+  if (pack) {
+    if (g_xcd_remap) hipLaunchKernelGGL((pong_rollout_kernel<true, true>), g, b, 0, stream, a);
+    else hipLaunchKernelGGL((pong_rollout_kernel<true, false>), g, b, 0, stream, a);
+  } else {
+    if (g_xcd_remap) hipLaunchKernelGGL((pong_rollout_kernel<false, true>), g, b, 0, stream, a);
+    else hipLaunchKernelGGL((pong_rollout_kernel<false, false>), g, b, 0, stream, a);
+  }
   return hipGetLastError();
 }
 
