@@ -3,9 +3,9 @@
 // One lane per environment, one wavefront per 64 consecutive environments.  The state is read from
 // the SoA arrays once, lives in VGPRs for all T steps (paper App. B.1 item 5: the rollout loop is
 // fused into the kernel, no per-step dispatch), and is written back once.  Per step a wavefront
-// emits: two 16-byte stores per lane for obs[t, i, 0:8], one dword per lane for reward[t, i], and
-// the 64 done flags of the wavefront packed into 16 dwords (ballot -> byte spread), 37 bytes per
-// environment step in total.  The kernel is a pure write stream; nothing is re-read.
+// emits: two 16-byte stores per lane for obs[t, i, 0:8], one dword per lane for reward[t, i] and
+// one byte per lane for done[t, i], 37 bytes per environment step in total.  The kernel is a pure
+// write stream; nothing is re-read.
 #include "kernels.hpp"
 #include "pong_device.hpp"
 
@@ -14,10 +14,7 @@ namespace envk {
 namespace {
 
 constexpr int WAVE = 64;
-#ifndef MI355ENV_ROLLOUT_BLOCK
-#define MI355ENV_ROLLOUT_BLOCK 64
-#endif
-constexpr int ROLLOUT_BLOCK = MI355ENV_ROLLOUT_BLOCK;   // threads per workgroup of the rollout kernel
+constexpr int ROLLOUT_BLOCK = 256;   // default threads per workgroup of the rollout kernel
 
 __global__ __launch_bounds__(256) void pong_reset_kernel(uint32_t* __restrict__ state, int64_t n,
                                                          uint64_t seed, uint64_t step,
@@ -33,15 +30,12 @@ __global__ __launch_bounds__(256) void pong_reset_kernel(uint32_t* __restrict__ 
   }
 }
 
-// bit k of `nibble` -> byte k of the result (0 or 1)
-__device__ __forceinline__ uint32_t spread_nibble(uint32_t nibble) {
-  return (nibble & 1u) | ((nibble & 2u) << 7) | ((nibble & 4u) << 14) | ((nibble & 8u) << 21);
-}
-
 // One wavefront's T-step loop.  FULL: all 64 lanes own an environment (no per-lane predication in
-// the loop).  Row pointers are wave-uniform (scalar) and advance by one row per step; the per-lane
-// part of every address is a constant 32-bit offset, so the stores need no vector address math.
-template <bool PACK_DONE, bool FULL, bool EXTERNAL_ACTIONS>
+// the loop).  Row pointers are wave-uniform and advance by one row per step.  The done flags go
+// out as one byte per lane: the 64 bytes of a wavefront are contiguous, so the memory pipeline
+// sees a single 64-byte write either way, and packing them by hand (ballot, shift, spread) only
+// added ~25 instructions per step.
+template <bool FULL, bool EXTERNAL_ACTIONS>
 __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, LaneEpisodes& le,
                                              const int lane, const int64_t wave_base) {
   const int64_t n = a.n;
@@ -51,7 +45,6 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
   float* rew_row = a.reward + wave_base;
   uint8_t* done_row = a.done + wave_base;
   const uint8_t* act_row = EXTERNAL_ACTIONS ? a.actions + wave_base : nullptr;
-  const bool done_lane = (lane < 16) && (FULL || (wave_base + 4 * lane < n));
 
   Draw4 d = philox_draw(a.seed, env, a.step0, 0u);
   for (int32_t t = 0; t < a.T; ++t) {
@@ -64,32 +57,19 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
 
     const PongEvent ev = pong_transition(s, action, d.w1, d.w2, a.max_score);
     const bool done = live && ev.done;
-    if (done) {
-      le.count += 1;
-      le.length_sum += ev.fin_len;
-      le.ret_sum_i += ev.fin_ret;
-      le.min_key = min(le.min_key, ev.fin_ret);
-      le.max_key = max(le.max_key, ev.fin_ret);
-    }
+    // selects, not a branch: the loop body stays one basic block, which lets the scheduler
+    // interleave the next step's Philox rounds with this step's transition
+    le.count += done ? 1 : 0;
+    le.length_sum += done ? ev.fin_len : 0;
+    le.ret_sum_i += done ? ev.fin_ret : 0;
+    le.min_key = done ? min(le.min_key, ev.fin_ret) : le.min_key;
+    le.max_key = done ? max(le.max_key, ev.fin_ret) : le.max_key;
 
-#ifdef MI355ENV_EXPERIMENT_NO_STORES
-    if (live && a.T < 0) {
-#else
     if (live) {
-#endif
       float4* o = reinterpret_cast<float4*>(obs_row + lane * PONG_OBS);
       o[0] = make_float4(s.bx, s.by, s.vx, s.vy);
       o[1] = make_float4(s.pa, s.po, (float)s.sa, (float)s.so);
       rew_row[lane] = ev.reward;
-    }
-    if (PACK_DONE) {
-      // n % 4 == 0 and done 4-byte aligned: every dword is entirely inside or outside the row
-      const unsigned long long mask = __ballot(done);
-      if (done_lane) {
-        const uint32_t nibble = (uint32_t)(mask >> (4 * lane)) & 0xFu;
-        reinterpret_cast<uint32_t*>(done_row)[lane] = spread_nibble(nibble);
-      }
-    } else if (live) {
       done_row[lane] = done ? 1 : 0;
     }
     obs_row += n * PONG_OBS;
@@ -100,7 +80,7 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
   }
 }
 
-template <bool PACK_DONE, bool XCD_REMAP>
+template <bool XCD_REMAP>
 __global__ __launch_bounds__(256) void pong_rollout_kernel(PongLaunch a) {
   const int lane = threadIdx.x & (WAVE - 1);
   // wave-uniform by construction; readfirstlane tells the compiler so (scalar address math)
@@ -121,11 +101,11 @@ __global__ __launch_bounds__(256) void pong_rollout_kernel(PongLaunch a) {
   PongLane s = live ? pong_load(a.state, n, i) : pong_idle_lane();
   LaneEpisodes le;
   if (a.actions) {
-    if (full) rollout_wave<PACK_DONE, true, true>(a, s, le, lane, wave_base);
-    else rollout_wave<PACK_DONE, false, true>(a, s, le, lane, wave_base);
+    if (full) rollout_wave<true, true>(a, s, le, lane, wave_base);
+    else rollout_wave<false, true>(a, s, le, lane, wave_base);
   } else {
-    if (full) rollout_wave<PACK_DONE, true, false>(a, s, le, lane, wave_base);
-    else rollout_wave<PACK_DONE, false, false>(a, s, le, lane, wave_base);
+    if (full) rollout_wave<true, false>(a, s, le, lane, wave_base);
+    else rollout_wave<false, false>(a, s, le, lane, wave_base);
   }
   if (live) pong_store(a.state, n, i, s);
   flush_wave_stats<false>(a.stats, le);
@@ -155,15 +135,9 @@ hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream) {
   const int block = g_rollout_block ? g_rollout_block : ROLLOUT_BLOCK;
   unsigned blocks = (unsigned)((a.n + block - 1) / block);
   blocks = (blocks + 7u) & ~7u;   // multiple of the XCD count; surplus workgroups exit at once
-  const bool pack = (a.n % 4 == 0) && ((reinterpret_cast<uintptr_t>(a.done) & 3u) == 0);
   const dim3 g(blocks), b(block);
-  if (pack) {
-    if (g_xcd_remap) hipLaunchKernelGGL((pong_rollout_kernel<true, true>), g, b, 0, stream, a);
-    else hipLaunchKernelGGL((pong_rollout_kernel<true, false>), g, b, 0, stream, a);
-  } else {
-    if (g_xcd_remap) hipLaunchKernelGGL((pong_rollout_kernel<false, true>), g, b, 0, stream, a);
-    else hipLaunchKernelGGL((pong_rollout_kernel<false, false>), g, b, 0, stream, a);
-  }
+  if (g_xcd_remap) hipLaunchKernelGGL(pong_rollout_kernel<true>, g, b, 0, stream, a);
+  else hipLaunchKernelGGL(pong_rollout_kernel<false>, g, b, 0, stream, a);
   return hipGetLastError();
 }
 
