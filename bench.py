@@ -95,10 +95,12 @@ def bench_pong_per_step(b, torch, n, seed, launches):
                 bound="dispatch latency", launches=launches)
 
 
-def bench_pixels(b, torch, n, seed, launches, warmup=20):
+def bench_pixels(b, torch, n, seed, launches, warmup=20, layout="slot_major"):
     dev = "cuda:0"
-    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, None)
-    ring = torch.zeros((n, 4, 84, 84), dtype=torch.uint8, device=dev)
+    code = b.ENV_PIXELS_SLOT_MAJOR if layout == "slot_major" else b.ENV_PIXELS_ENV_MAJOR
+    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"pixel_layout": code})
+    ring = torch.zeros((4, n, 84, 84) if layout == "slot_major" else (n, 4, 84, 84),
+                       dtype=torch.uint8, device=dev)
     rew = torch.empty(n, dtype=torch.float32, device=dev)
     done = torch.empty(n, dtype=torch.uint8, device=dev)
     b.env_reset(h, ring)
@@ -106,7 +108,8 @@ def bench_pixels(b, torch, n, seed, launches, warmup=20):
     b.env_destroy(h)
     mean_ms, std_ms = _mean_std(ms)
     gbs = n * FRAME_BYTES / (mean_ms * 1e-3) / 1e9
-    return dict(workload="pong pixels N=%d, 84x84 u8 frame into a 4-slot ring, one env_step launch per step" % n,
+    return dict(workload="pong pixels N=%d, 84x84 u8 frame into a 4-slot ring (%s), one env_step "
+                         "launch per step" % (n, "u8[4,N,84,84]" if layout == "slot_major" else "u8[N,4,84,84]"),
                 env_steps_per_s=n * launches / wall, us_per_launch_events=mean_ms * 1e3,
                 us_per_launch_wall=1e6 * wall / launches,
                 roofline=dict(bound="hbm", achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s",
@@ -239,6 +242,7 @@ def main():
         extra["fill_yardstick"] = bench_fill(b, torch, 1 << 30)
         extra["config1_per_step"] = bench_pong_per_step(b, torch, 4096, 1, 10000)
         extra["config3_pixels"] = bench_pixels(b, torch, 16384, 3, 500)
+        extra["config3_pixels_env_major"] = bench_pixels(b, torch, 16384, 3, 500, layout="env_major")
         for nn in (16384, 262144):
             rr = bench_pong_rollout(b, torch, nn, T, seed, max(3, args.steps // 6), 1)
             gbs = PONG_BYTES_PER_ENV_STEP * nn * T / (rr["mean_ms"] * 1e-3) / 1e9

@@ -39,7 +39,7 @@ typedef struct mi355env env_t; /* opaque handle */
 
 enum {
   ENV_PONG = 0,        /* Pong, obs = float32[8]: ball x, y, vx, vy, agent y, opponent y, scores  */
-  ENV_PONG_PIXELS = 1, /* same dynamics, obs = uint8[4][84][84] ring of rendered frames           */
+  ENV_PONG_PIXELS = 1, /* same dynamics, obs = ring of four rendered 84x84 uint8 frames per env   */
   ENV_BODY = 2         /* planar 7-link articulated body, obs = float32[17], action float32[6]    */
 };
 
@@ -62,7 +62,15 @@ typedef struct env_config_t {
   float armature;             /* body: rotor inertia added to the 6 joint diagonals; <0 = default */
   float joint_damping;        /* body: viscous joint damping; <0 = default                        */
   float friction_mu;          /* body: Coulomb friction coefficient; <0 = default                 */
+  int32_t pixel_layout;       /* pixels: ENV_PIXELS_* below; 0 = default (slot-major)             */
 } env_config_t;
+
+/* Layout of the 4-frame ring of ENV_PONG_PIXELS in obs_dev of env_reset / env_step:
+ *   slot-major  uint8[4][N][84][84]  frame of slot k of environment i at ((k*N + i) * 7056);
+ *               one step writes one contiguous plane of N frames (the dense stream HBM likes);
+ *   env-major   uint8[N][4][84][84]  frame at ((i*4 + k) * 7056): each environment's four frames
+ *               are adjacent (NCHW order), at the price of a 25 %-dense write stream per step. */
+enum { ENV_PIXELS_SLOT_MAJOR = 1, ENV_PIXELS_ENV_MAJOR = 2 };
 
 /* Statistics of the episodes that ended since the counters were last cleared. */
 typedef struct env_stats_t {
@@ -85,15 +93,16 @@ void env_destroy(env_t *e);
 
 /* Start a new episode in every environment, drawing the initial state from the reset streams at
  * the current step counter.  obs_dev (may be NULL): Pong float32[N,8]; body float32[N,17];
- * pixels uint8[N,4,84,84] — all four ring slots receive the initial frame.  16-byte aligned. */
+ * pixels: the ring (4*N*7056 bytes, layout per cfg.pixel_layout) — all four slots of every
+ * environment receive the initial frame.  16-byte aligned. */
 int env_reset(env_t *e, void *obs_dev);
 
 /* Advance every environment by one step (one kernel launch).
  * actions_dev: Pong uint8[N] in {0 stay, 1 up, 2 down} (other values = stay); body float32[N,6],
  * clipped to [-1,1]; NULL = draw the actions from this step's Philox block inside the kernel.
- * obs_dev: Pong float32[N,8]; body float32[N,17]; pixels: the uint8[N,4,84,84] ring — the frame
- * after the step with index s (s = steps taken before this call) is written to slot s mod 4, the
- * other three slots are left as they are.  reward_dev float32[N], done_dev uint8[N].
+ * obs_dev: Pong float32[N,8]; body float32[N,17]; pixels: the ring — the frame after the step
+ * with index s (s = steps taken before this call) is written to slot s mod 4, the other three
+ * slots are left as they are.  reward_dev float32[N], done_dev uint8[N].
  * obs_dev must be 16-byte aligned, reward_dev 4-byte aligned.  None may be NULL. */
 int env_step(env_t *e, const void *actions_dev, void *obs_dev, float *reward_dev, uint8_t *done_dev);
 

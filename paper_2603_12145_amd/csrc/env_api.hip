@@ -51,6 +51,7 @@ env_config_t default_config(int kind) {
   c.armature = BODY_DEFAULT_ARMATURE;
   c.joint_damping = BODY_DEFAULT_JOINT_DAMPING;
   c.friction_mu = BODY_DEFAULT_FRICTION_MU;
+  c.pixel_layout = ENV_PIXELS_SLOT_MAJOR;
   (void)kind;
   return c;
 }
@@ -69,6 +70,11 @@ int merge_config(env_config_t* dst, const env_config_t* src) {
     dst->joint_damping = src->joint_damping;
   if (sz >= FIELD_END(env_config_t, friction_mu) && src->friction_mu >= 0.0f)
     dst->friction_mu = src->friction_mu;
+  if (sz >= FIELD_END(env_config_t, pixel_layout) && src->pixel_layout != 0) {
+    if (src->pixel_layout != ENV_PIXELS_SLOT_MAJOR && src->pixel_layout != ENV_PIXELS_ENV_MAJOR)
+      return ENV_E_ARG;
+    dst->pixel_layout = src->pixel_layout;
+  }
   if (!std::isfinite(dst->armature) || !std::isfinite(dst->joint_damping) ||
       !std::isfinite(dst->friction_mu))
     return ENV_E_ARG;
@@ -161,6 +167,7 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
     } else {
       PixelLaunch x{};
       x.pong = p; x.pong.obs = nullptr;
+      x.slot_major = e->cfg.pixel_layout == ENV_PIXELS_SLOT_MAJOR;
       if (ring_mode) x.ring = static_cast<uint8_t*>(obs);
       else x.frames = static_cast<uint8_t*>(obs);
       err = launch_pixel_rollout(x, e->stream);
@@ -223,7 +230,8 @@ int env_reset(env_t* e, void* obs_dev) {
   hipError_t err;
   if (e->kind == ENV_PONG_PIXELS && obs_dev) {
     if (!device_range_ok(e, obs_dev, (size_t)e->n * 4 * FRAME_BYTES, 16)) return ENV_E_ARG;
-    err = launch_pixel_reset(e->state, e->n, e->seed, e->step, static_cast<uint8_t*>(obs_dev), e->stream);
+    err = launch_pixel_reset(e->state, e->n, e->seed, e->step, static_cast<uint8_t*>(obs_dev),
+                             e->cfg.pixel_layout == ENV_PIXELS_SLOT_MAJOR, e->stream);
   } else if (e->kind == ENV_BODY) {
     if (obs_dev && !device_range_ok(e, obs_dev, (size_t)e->n * BODY_OBS * sizeof(float), 16))
       return ENV_E_ARG;

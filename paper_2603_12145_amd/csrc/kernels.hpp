@@ -34,11 +34,12 @@ hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream);
 // frames[t][i].
 struct PixelLaunch {
   PongLaunch pong;        // obs unused
-  uint8_t* ring;          // [n,4,84,84] or nullptr
+  uint8_t* ring;          // 4-slot ring or nullptr
   uint8_t* frames;        // [T,n,84,84] or nullptr
+  bool slot_major;        // ring layout: [4,n,84,84] (true) or [n,4,84,84] (false)
 };
 hipError_t launch_pixel_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
-                              uint8_t* ring, hipStream_t stream);
+                              uint8_t* ring, bool slot_major, hipStream_t stream);
 hipError_t launch_pixel_rollout(const PixelLaunch& a, hipStream_t stream);
 
 }  // namespace envk

@@ -149,14 +149,18 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * WAVE) void pixel_kernel(PixelLaun
 #pragma unroll
         for (int k = lane; k < CHUNKS; k += WAVE) store_chunk<STREAMING>(dst + k, tile16[k]);
       } else if (MODE == MODE_RING) {
-        chunk_t* dst = reinterpret_cast<chunk_t*>(a.ring + (env * 4 + (int64_t)(step & 3)) * FRAME_BYTES);
+        const int64_t slot = (int64_t)(step & 3);
+        const int64_t frame = a.slot_major ? slot * n + env : env * 4 + slot;
+        chunk_t* dst = reinterpret_cast<chunk_t*>(a.ring + frame * FRAME_BYTES);
 #pragma unroll
         for (int k = lane; k < CHUNKS; k += WAVE) store_chunk<STREAMING>(dst + k, tile16[k]);
-      } else {  // reset: the same frame into all four slots (contiguous 4 * 7056 bytes)
-        chunk_t* dst = reinterpret_cast<chunk_t*>(a.ring + env * 4 * FRAME_BYTES);
+      } else {  // reset: the same frame into all four slots
+        const int64_t first = a.slot_major ? env : env * 4;
+        const int64_t pitch = a.slot_major ? n : 1;            // frames between slots
+        chunk_t* dst = reinterpret_cast<chunk_t*>(a.ring + first * FRAME_BYTES);
         for (int k = lane; k < CHUNKS; k += WAVE) {
           const chunk_t v = tile16[k];
-          for (int slot = 0; slot < 4; ++slot) store_chunk<STREAMING>(dst + slot * CHUNKS + k, v);
+          for (int slot = 0; slot < 4; ++slot) store_chunk<STREAMING>(dst + slot * pitch * CHUNKS + k, v);
         }
       }
       wave_lds_sync();
@@ -213,8 +217,9 @@ bool set_pixel_tuning(int envs_per_wave, int streaming) {
 }
 
 hipError_t launch_pixel_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
-                              uint8_t* ring, hipStream_t stream) {
+                              uint8_t* ring, bool slot_major, hipStream_t stream) {
   PixelLaunch a{};
+  a.slot_major = slot_major;
   a.pong.state = state; a.pong.n = n; a.pong.seed = seed; a.pong.step0 = step; a.pong.T = 1;
   a.ring = ring;
   return launch_mode<MODE_RESET>(a, stream);

@@ -15,6 +15,20 @@ DEV = "cuda:0"
 F = 84
 
 
+LAYOUTS = {"slot_major": b.ENV_PIXELS_SLOT_MAJOR, "env_major": b.ENV_PIXELS_ENV_MAJOR}
+
+
+def new_ring(n, layout):
+    shape = (4, n, F, F) if layout == "slot_major" else (n, 4, F, F)
+    return torch.zeros(shape, dtype=torch.uint8, device=DEV)
+
+
+def ring_as_env_major(ring, layout):
+    """numpy [n,4,84,84] view of the ring's content, whatever its layout."""
+    a = ring.cpu().numpy()
+    return np.ascontiguousarray(a.transpose(1, 0, 2, 3)) if layout == "slot_major" else a
+
+
 def _tune(epw, streaming=0):
     assert b.lib().mi355env_tune_pixels(epw, streaming) == 0
 
@@ -25,13 +39,14 @@ def _default_tuning():
     _tune(16, 0)
 
 
+@pytest.mark.parametrize("layout", ["slot_major", "env_major"])
 @pytest.mark.parametrize("epw", [4, 8, 16, 32, 64])
 @pytest.mark.parametrize("n", [37, 200])
-def test_ring_steps_match_oracle(n, epw):
+def test_ring_steps_match_oracle(n, epw, layout):
     _tune(epw)
     seed, T = 40 + n, 14
-    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"max_score": 1})
-    ring = torch.zeros((n, 4, F, F), dtype=torch.uint8, device=DEV)
+    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"max_score": 1, "pixel_layout": LAYOUTS[layout]})
+    ring = new_ring(n, layout)
     rew = torch.empty(n, dtype=torch.float32, device=DEV)
     done = torch.empty(n, dtype=torch.uint8, device=DEV)
     b.env_reset(h, ring)
@@ -39,12 +54,12 @@ def test_ring_steps_match_oracle(n, epw):
     stack = np.zeros((n, 4, F, F), np.uint8)
     p.fill_stack(stack)
     torch.cuda.synchronize()
-    assert_bit_equal(ring.cpu().numpy(), stack, "ring after reset")
+    assert_bit_equal(ring_as_env_major(ring, layout), stack, "ring after reset")
     for t in range(T):
         b.env_step(h, None, ring, rew, done)
         _, orew, odone = p.step(stack=stack)
         torch.cuda.synchronize()
-        assert_bit_equal(ring.cpu().numpy(), stack, "ring after step %d" % t)
+        assert_bit_equal(ring_as_env_major(ring, layout), stack, "ring after step %d" % t)
         assert_bit_equal(rew.cpu().numpy(), orew, "reward step %d" % t)
         assert_bit_equal(done.cpu().numpy(), odone, "done step %d" % t)
     _, fields = split_state(b.env_get_state(h), n, 10)
@@ -55,8 +70,8 @@ def test_ring_steps_match_oracle(n, epw):
 def test_streaming_store_variant_matches():
     _tune(16, 1)
     n, seed = 100, 3
-    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, None)
-    ring = torch.zeros((n, 4, F, F), dtype=torch.uint8, device=DEV)
+    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, None)          # default layout: slot-major
+    ring = new_ring(n, "slot_major")
     rew = torch.empty(n, dtype=torch.float32, device=DEV)
     done = torch.empty(n, dtype=torch.uint8, device=DEV)
     b.env_reset(h, ring)
@@ -66,7 +81,7 @@ def test_streaming_store_variant_matches():
         b.env_step(h, None, ring, rew, done)
         p.step(stack=stack)
     torch.cuda.synchronize()
-    assert_bit_equal(ring.cpu().numpy(), stack, "streaming ring")
+    assert_bit_equal(ring_as_env_major(ring, "slot_major"), stack, "streaming ring")
     b.env_destroy(h)
 
 
@@ -104,7 +119,7 @@ def test_rasteriser_on_arbitrary_positions():
     envs["vy"] = np.linspace(-2, 2, n).astype(np.float32)
     p = orc.Pong(n, 5)
     p.envs()[:] = envs
-    h = b.env_create(b.ENV_PONG_PIXELS, n, 5, None)
+    h = b.env_create(b.ENV_PONG_PIXELS, n, 5, {"pixel_layout": b.ENV_PIXELS_ENV_MAJOR})
     b.env_set_state(h, pong_blob(0, pong_state_fields(envs)))
     ring = torch.zeros((n, 4, F, F), dtype=torch.uint8, device=DEV)
     rew = torch.empty(n, dtype=torch.float32, device=DEV)
@@ -119,12 +134,13 @@ def test_rasteriser_on_arbitrary_positions():
     b.env_destroy(h)
 
 
-def test_config3_n16384_t500_final_ring():
+@pytest.mark.parametrize("layout", ["slot_major", "env_major"])
+def test_config3_n16384_t500_final_ring(layout):
     # full size, per-step launches as bench measures them; the oracle steps all environments
     # without rendering and renders only the last four steps (the content of the ring at the end)
     n, seed, T = 16384, 3, 500
-    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, None)
-    ring = torch.zeros((n, 4, F, F), dtype=torch.uint8, device=DEV)
+    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"pixel_layout": LAYOUTS[layout]})
+    ring = new_ring(n, layout)
     rew = torch.empty((T, n), dtype=torch.float32, device=DEV)
     done = torch.empty((T, n), dtype=torch.uint8, device=DEV)
     b.env_reset(h, ring)
@@ -137,7 +153,7 @@ def test_config3_n16384_t500_final_ring():
     _, orew2, odone2 = p.rollout(4, stack=stack, nthreads=16, want_obs=False)
     assert_bit_equal(rew.cpu().numpy(), np.concatenate([orew, orew2]), "C3 reward")
     assert_bit_equal(done.cpu().numpy(), np.concatenate([odone, odone2]), "C3 done")
-    assert_bit_equal(ring.cpu().numpy(), stack, "C3 ring")
+    assert_bit_equal(ring_as_env_major(ring, layout), stack, "C3 ring")
     _, fields = split_state(b.env_get_state(h), n, 10)
     assert_bit_equal(fields, pong_state_fields(p.envs()), "C3 state")
     b.env_destroy(h)
