@@ -17,6 +17,7 @@ using namespace envk;
 namespace envk {
 bool set_pixel_tuning(int envs_per_wave, int streaming);
 bool set_rollout_block(int threads, int xcd_remap);
+bool set_plane_path(int on);
 }
 
 struct mi355env {
@@ -30,6 +31,7 @@ struct mi355env {
   uint32_t* state;        // device SoA [fields][n], every field 4 bytes
   int fields;
   DeviceStats* stats;     // device
+  uint32_t* blocks;       // device scratch [3][n], pixels only: cell blocks of the newest frame
   bool was_reset;
   // last device ranges that passed the residency check (avoids a driver query per step)
   struct Range { const void* p; size_t bytes; } seen[8];
@@ -168,6 +170,7 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
       PixelLaunch x{};
       x.pong = p; x.pong.obs = nullptr;
       x.slot_major = e->cfg.pixel_layout == ENV_PIXELS_SLOT_MAJOR;
+      x.blocks = e->blocks;
       if (ring_mode) x.ring = static_cast<uint8_t*>(obs);
       else x.frames = static_cast<uint8_t*>(obs);
       err = launch_pixel_rollout(x, e->stream);
@@ -195,7 +198,7 @@ int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_c
   e->kind = kind; e->n = n_envs; e->seed = seed; e->step = 0;
   e->stream = static_cast<hipStream_t>(hip_stream);
   e->cfg = c; e->fields = fields_of(kind); e->was_reset = false;
-  e->state = nullptr; e->stats = nullptr; e->seen_next = 0;
+  e->state = nullptr; e->stats = nullptr; e->blocks = nullptr; e->seen_next = 0;
   for (auto& r : e->seen) r = {nullptr, 0};
   if (hipGetDevice(&e->device) != hipSuccess) { delete e; return ENV_E_HIP; }
 
@@ -206,11 +209,17 @@ int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_c
   if (hipMalloc(reinterpret_cast<void**>(&e->stats), sizeof(DeviceStats)) != hipSuccess) {
     (void)hipGetLastError(); (void)hipFree(e->state); delete e; return ENV_E_ALLOC;
   }
+  if (kind == ENV_PONG_PIXELS &&
+      hipMalloc(reinterpret_cast<void**>(&e->blocks), (size_t)3 * (size_t)n_envs * 4) != hipSuccess) {
+    (void)hipGetLastError(); (void)hipFree(e->state); (void)hipFree(e->stats); delete e;
+    return ENV_E_ALLOC;
+  }
   const DeviceStats z = empty_stats();
   if (hipMemsetAsync(e->state, 0, state_bytes, e->stream) != hipSuccess ||
       hipMemcpyAsync(e->stats, &z, sizeof z, hipMemcpyHostToDevice, e->stream) != hipSuccess ||
       hipStreamSynchronize(e->stream) != hipSuccess) {
-    (void)hipGetLastError(); (void)hipFree(e->state); (void)hipFree(e->stats); delete e;
+    (void)hipGetLastError(); (void)hipFree(e->state); (void)hipFree(e->stats);
+    (void)hipFree(e->blocks); delete e;
     return ENV_E_HIP;
   }
   *out = e;
@@ -222,6 +231,7 @@ void env_destroy(env_t* e) {
   (void)hipStreamSynchronize(e->stream);
   (void)hipFree(e->state);
   (void)hipFree(e->stats);
+  (void)hipFree(e->blocks);
   delete e;
 }
 
@@ -231,7 +241,7 @@ int env_reset(env_t* e, void* obs_dev) {
   if (e->kind == ENV_PONG_PIXELS && obs_dev) {
     if (!device_range_ok(e, obs_dev, (size_t)e->n * 4 * FRAME_BYTES, 16)) return ENV_E_ARG;
     err = launch_pixel_reset(e->state, e->n, e->seed, e->step, static_cast<uint8_t*>(obs_dev),
-                             e->cfg.pixel_layout == ENV_PIXELS_SLOT_MAJOR, e->stream);
+                             e->cfg.pixel_layout == ENV_PIXELS_SLOT_MAJOR, e->blocks, e->stream);
   } else if (e->kind == ENV_BODY) {
     if (obs_dev && !device_range_ok(e, obs_dev, (size_t)e->n * BODY_OBS * sizeof(float), 16))
       return ENV_E_ARG;
@@ -345,6 +355,8 @@ const char* env_strerror(int code) {
 int mi355env_tune_pixels(int envs_per_wave, int streaming) {
   return set_pixel_tuning(envs_per_wave, streaming) ? ENV_OK : ENV_E_ARG;
 }
+
+int mi355env_tune_plane_path(int on) { return set_plane_path(on) ? ENV_OK : ENV_E_ARG; }
 
 int mi355env_tune_rollout(int threads_per_block, int xcd_remap) {
   return set_rollout_block(threads_per_block, xcd_remap) ? ENV_OK : ENV_E_ARG;

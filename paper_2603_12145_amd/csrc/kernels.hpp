@@ -37,9 +37,10 @@ struct PixelLaunch {
   uint8_t* ring;          // 4-slot ring or nullptr
   uint8_t* frames;        // [T,n,84,84] or nullptr
   bool slot_major;        // ring layout: [4,n,84,84] (true) or [n,4,84,84] (false)
+  uint32_t* blocks;       // library scratch [3][n]: packed cell blocks of the newest frame
 };
 hipError_t launch_pixel_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
-                              uint8_t* ring, bool slot_major, hipStream_t stream);
+                              uint8_t* ring, bool slot_major, uint32_t* blocks, hipStream_t stream);
 hipError_t launch_pixel_rollout(const PixelLaunch& a, hipStream_t stream);
 
 }  // namespace envk

@@ -177,6 +177,95 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * WAVE) void pixel_kernel(PixelLaun
   }
 }
 
+// ---------------------------------------------------------------------------------------------
+// Slot-major ring: one step rewrites one whole plane of N frames, a single dense N*7056-byte
+// stream.  Measured on MI355X, the write pattern that gets closest to HBM peak is "one workgroup
+// writes one 4 KiB-aligned page with one 16-byte store per thread, workgroups dispatched in address
+// order" (about 6.8 TB/s for a plain fill against about 5.3 TB/s for any scheme in which a
+// wavefront streams several KiB on its own).  The plane is therefore rendered by two launches:
+//   1. pixel_dynamics_kernel: one lane per environment; transition, state / reward / done stores,
+//      and the three cell blocks of the new frame (12 bytes per environment) into `blocks`;
+//   2. plane_render_kernel: one workgroup per 4 KiB page of the plane.  A page overlaps at most two
+//      frames; their six cell blocks arrive by scalar loads, the lit pixels that fall inside the
+//      page are poked into a zeroed 4 KiB LDS page, and every thread stores its 16 bytes.
+// ---------------------------------------------------------------------------------------------
+template <bool RESET>
+__global__ __launch_bounds__(256) void pixel_dynamics_kernel(PongLaunch a, uint32_t* __restrict__ blocks) {
+  const int64_t n = a.n;
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const bool live = i < n;
+  PongLane s;
+  LaneEpisodes le;
+  if (RESET) {
+    s = pong_initial(a.seed, (uint32_t)i, a.step0);
+  } else {
+    s = live ? pong_load(a.state, n, i) : pong_idle_lane();
+    const Draw4 d = philox_draw(a.seed, (uint32_t)i, a.step0, 0u);
+    int action = pong_action_from_word(d.w0);
+    if (a.actions) action = live ? (int)a.actions[i] : 0;
+    const PongEvent ev = pong_transition(s, action, d.w1, d.w2, a.max_score);
+    if (live) {
+      a.reward[i] = ev.reward;
+      a.done[i] = ev.done ? 1 : 0;
+      if (ev.done) {
+        le.count = 1; le.length_sum = ev.fin_len; le.ret_sum_i = ev.fin_ret;
+        le.min_key = ev.fin_ret; le.max_key = ev.fin_ret;
+      }
+    }
+  }
+  if (live) {
+    pong_store(a.state, n, i, s);
+    blocks[0 * n + i] = cell_block(140.0f, s.pa, 4.0f, 16.0f);
+    blocks[1 * n + i] = cell_block(16.0f, s.po, 4.0f, 16.0f);
+    blocks[2 * n + i] = cell_block(s.bx, s.by, 2.0f, 2.0f);
+  }
+  if (!RESET) flush_wave_stats<false>(a.stats, le);
+}
+
+constexpr int PAGE = 4096;
+
+// plane: first byte of the plane (16-byte aligned), n frames long.  Workgroup b handles the b-th
+// 4 KiB-aligned page that intersects it.
+__global__ __launch_bounds__(256) void plane_render_kernel(const uint32_t* __restrict__ blocks, int64_t n,
+                                                           uint8_t* __restrict__ plane) {
+  __shared__ __align__(16) uint8_t page[PAGE];
+  const int tid = threadIdx.x;
+  const uintptr_t base = reinterpret_cast<uintptr_t>(plane);
+  const int64_t total = n * FRAME_BYTES;
+  // byte offsets relative to the start of the plane; the first page may begin before it
+  const int64_t page_off = (int64_t)blockIdx.x * PAGE - (int64_t)(base & (PAGE - 1));
+  const int64_t lo = page_off < 0 ? 0 : page_off;
+  const int64_t hi = page_off + PAGE < total ? page_off + PAGE : total;
+  const int64_t f_first = lo / FRAME_BYTES;
+  const int64_t f_last = (hi - 1) / FRAME_BYTES;      // f_first or f_first + 1
+
+  // threads 0..191: (frame, rectangle) pair tid / 32, pixel tid % 32 of a 4-column x 8-row patch
+  // (a paddle covers at most 4 x 8 cells, the ball at most 3 x 2).  The cell block is loaded
+  // before the page is zeroed so that its latency overlaps the zeroing and the barrier.
+  const int pair = tid >> 5;
+  const bool from_last = pair >= 3;
+  const bool candidate = pair < 6 && !(from_last && f_last == f_first);
+  const int64_t f = from_last ? f_last : f_first;
+  uint32_t blk = 0;
+  if (candidate) blk = blocks[(int64_t)(from_last ? pair - 3 : pair) * n + f];
+
+  chunk_t* page16 = reinterpret_cast<chunk_t*>(page);
+  page16[tid] = chunk_t{0, 0, 0, 0};
+  __syncthreads();
+
+  if (candidate) {
+    const int c_lo = blk & 0xff, c_end = (blk >> 8) & 0xff;
+    const int r_lo = (blk >> 16) & 0xff, r_end = blk >> 24;
+    const int c = c_lo + (tid & 3), r = r_lo + ((tid >> 2) & 7);
+    const int64_t off = f * FRAME_BYTES + r * FRAME_SIDE + c - page_off;
+    if (c < c_end && r < r_end && off >= 0 && off < PAGE) page[off] = 255;
+  }
+  __syncthreads();
+
+  const int64_t mine = page_off + 16 * tid;
+  if (mine >= lo && mine < hi) *reinterpret_cast<chunk_t*>(plane + mine) = page16[tid];
+}
+
 int g_envs_per_wave = 16;
 bool g_streaming = false;
 
@@ -216,8 +305,34 @@ bool set_pixel_tuning(int envs_per_wave, int streaming) {
   return true;
 }
 
+namespace {
+
+bool g_plane_path = true;   // slot-major ring steps go through the two-launch plane renderer
+
+hipError_t launch_plane(const uint32_t* blocks, int64_t n, uint8_t* plane, hipStream_t stream) {
+  const uintptr_t base = reinterpret_cast<uintptr_t>(plane);
+  const uintptr_t end = base + (uintptr_t)n * FRAME_BYTES;
+  const unsigned pages = (unsigned)(((end + PAGE - 1) >> 12) - (base >> 12));
+  hipLaunchKernelGGL(plane_render_kernel, dim3(pages), dim3(256), 0, stream, blocks, n, plane);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+bool set_plane_path(int on) { g_plane_path = on != 0; return true; }
+
 hipError_t launch_pixel_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
-                              uint8_t* ring, bool slot_major, hipStream_t stream) {
+                              uint8_t* ring, bool slot_major, uint32_t* blocks, hipStream_t stream) {
+  if (slot_major && g_plane_path && blocks) {
+    PongLaunch p{};
+    p.state = state; p.n = n; p.seed = seed; p.step0 = step; p.T = 1;
+    hipLaunchKernelGGL(pixel_dynamics_kernel<true>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
+                       stream, p, blocks);
+    hipError_t err = hipGetLastError();
+    for (int slot = 0; slot < 4 && err == hipSuccess; ++slot)
+      err = launch_plane(blocks, n, ring + (int64_t)slot * n * FRAME_BYTES, stream);
+    return err;
+  }
   PixelLaunch a{};
   a.slot_major = slot_major;
   a.pong.state = state; a.pong.n = n; a.pong.seed = seed; a.pong.step0 = step; a.pong.T = 1;
@@ -226,6 +341,14 @@ hipError_t launch_pixel_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_
 }
 
 hipError_t launch_pixel_rollout(const PixelLaunch& a, hipStream_t stream) {
+  if (a.ring && a.slot_major && g_plane_path && a.blocks && a.pong.T == 1) {
+    hipLaunchKernelGGL(pixel_dynamics_kernel<false>, dim3((unsigned)((a.pong.n + 255) / 256)), dim3(256),
+                       0, stream, a.pong, a.blocks);
+    const hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    const int64_t slot = (int64_t)(a.pong.step0 & 3);
+    return launch_plane(a.blocks, a.pong.n, a.ring + slot * a.pong.n * FRAME_BYTES, stream);
+  }
   if (a.frames) return launch_mode<MODE_FRAMES>(a, stream);
   return launch_mode<MODE_RING>(a, stream);
 }

@@ -37,6 +37,7 @@ def _tune(epw, streaming=0):
 def _default_tuning():
     yield
     _tune(16, 0)
+    assert b.lib().mi355env_tune_plane_path(1) == 0
 
 
 @pytest.mark.parametrize("layout", ["slot_major", "env_major"])
@@ -65,6 +66,36 @@ def test_ring_steps_match_oracle(n, epw, layout):
     _, fields = split_state(b.env_get_state(h), n, 10)
     assert_bit_equal(fields, pong_state_fields(p.envs()), "state")
     b.env_destroy(h)
+
+
+@pytest.mark.parametrize("n", [1, 7, 255, 256, 257, 1000])
+def test_plane_renderer_and_wave_renderer_agree_with_oracle(n):
+    # slot-major steps normally take the two-launch page renderer; with it switched off the
+    # per-wavefront tile renderer writes the same ring.  Plane starts are 4 KiB-aligned only when
+    # n is a multiple of 256: the other sizes exercise the partial first and last pages.
+    seed, T = 90 + n, 9
+    p = orc.Pong(n, seed, max_score=1); p.reset()
+    stack = np.zeros((n, 4, F, F), np.uint8); p.fill_stack(stack)
+    rings = []
+    for plane_path in (1, 0):
+        assert b.lib().mi355env_tune_plane_path(plane_path) == 0
+        h = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"max_score": 1})
+        ring = new_ring(n, "slot_major")
+        ring.fill_(77)                       # stale content must be overwritten, not OR-ed into
+        rew = torch.empty(n, dtype=torch.float32, device=DEV)
+        done = torch.empty(n, dtype=torch.uint8, device=DEV)
+        b.env_reset(h, ring)
+        for t in range(T):
+            b.env_step(h, None, ring, rew, done)
+        torch.cuda.synchronize()
+        rings.append(ring_as_env_major(ring, "slot_major"))
+        stats = b.env_stats(h)
+        b.env_destroy(h)
+    for t in range(T):
+        p.step(stack=stack)
+    assert_bit_equal(rings[0], stack, "plane renderer")
+    assert_bit_equal(rings[1], stack, "wave renderer")
+    assert stats["episodes"] == p.stats()["episodes"]
 
 
 def test_streaming_store_variant_matches():
