@@ -77,7 +77,7 @@ def lib():
 
 def _bind_body(L):
     """Rigid-body entry points (present once body.cpp is part of the build)."""
-    if not hasattr(L, "oracle_body_create"):
+    if not hasattr(L, "oracle_body_create_f32"):
         return
     from oracle import body_binding
     body_binding.bind(L)
