@@ -129,6 +129,21 @@ def bench_fill(b, torch, nbytes, launches=50):
                 gbs=nbytes / (mean_ms * 1e-3) / 1e9, frac_of_peak=nbytes / (mean_ms * 1e-3) / 1e9 / HBM_PEAK_GBS)
 
 
+def bench_copy(b, torch, nbytes, launches=20):
+    """Plain device-to-device copy of known size: calibrates the HBM byte counters."""
+    import ctypes as C
+    L = b.lib()
+    L.mi355env_bench_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    src = torch.ones(nbytes, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    s = torch.cuda.current_stream().cuda_stream
+    wall, ms = time_launches(lambda: L.mi355env_bench_copy(dst.data_ptr(), src.data_ptr(), nbytes, s),
+                             launches, 3)
+    mean_ms, _ = _mean_std(ms)
+    return dict(workload="plain 16-byte copy of %d MiB (reads and writes that many bytes)" % (nbytes >> 20),
+                gbs_each_way=nbytes / (mean_ms * 1e-3) / 1e9)
+
+
 def bench_body(b, torch, n, T, seed, steps):
     dev = "cuda:0"
     h = b.env_create(b.ENV_BODY, n, seed, None)
@@ -202,7 +217,8 @@ def main():
         fn = {"pixels": lambda: bench_pixels(b, torch, 16384, 3, args.steps),
               "per_step": lambda: bench_pong_per_step(b, torch, 4096, 1, args.steps),
               "body": lambda: bench_body(b, torch, 8192, 1000, 4, args.steps),
-              "fill": lambda: bench_fill(b, torch, 1 << 30, args.steps)}[args.only]
+              "fill": lambda: bench_fill(b, torch, 1 << 30, args.steps),
+              "copy": lambda: bench_copy(b, torch, 1 << 30, args.steps)}[args.only]
         print(json.dumps(fn()))
         return
 
