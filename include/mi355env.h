@@ -94,7 +94,7 @@ void env_destroy(env_t *e);
 /* Start a new episode in every environment, drawing the initial state from the reset streams at
  * the current step counter.  obs_dev (may be NULL): Pong float32[N,8]; body float32[N,17];
  * pixels: the ring (4*N*7056 bytes, layout per cfg.pixel_layout) — all four slots of every
- * environment receive the initial frame.  16-byte aligned. */
+ * environment receive the initial frame.  16-byte aligned (body: 4-byte). */
 int env_reset(env_t *e, void *obs_dev);
 
 /* Advance every environment by one step (one kernel launch).
@@ -103,7 +103,7 @@ int env_reset(env_t *e, void *obs_dev);
  * obs_dev: Pong float32[N,8]; body float32[N,17]; pixels: the ring — the frame after the step
  * with index s (s = steps taken before this call) is written to slot s mod 4, the other three
  * slots are left as they are.  reward_dev float32[N], done_dev uint8[N].
- * obs_dev must be 16-byte aligned, reward_dev 4-byte aligned.  None may be NULL. */
+ * obs_dev must be 16-byte aligned (body: 4-byte), reward_dev 4-byte aligned.  None may be NULL. */
 int env_step(env_t *e, const void *actions_dev, void *obs_dev, float *reward_dev, uint8_t *done_dev);
 
 /* T steps fused into one kernel launch; state stays in registers between steps.

@@ -69,6 +69,7 @@ struct Params {
   R armature, joint_damping, friction_mu;
   R gravity, contact_k, contact_c, h, gear, z0;
   int substeps, max_episode_steps;
+  int round_state_f32;   // round q, v, episode return to float32 after every step (the storage format)
 };
 
 template <class R>
@@ -352,6 +353,11 @@ R env_step(const Params<R>& P, Env<R>* e, const R a_in[NACT], uint64_t seed, uin
   }
   e->ep_ret += reward;
   e->ep_len += 1;
+  if (P.round_state_f32) {
+    for (int j = 0; j < NQ; ++j) { e->q[j] = (R)(float)e->q[j]; e->v[j] = (R)(float)e->v[j]; }
+    e->ep_ret = (R)(float)e->ep_ret;
+    reward = (R)(float)reward;
+  }
   if (e->ep_len >= P.max_episode_steps) {
     info->done = 1;
     info->fin_ret = (double)e->ep_ret; info->fin_len = e->ep_len;
@@ -390,7 +396,7 @@ Params<R> default_params() {
   Params<R> P;
   P.armature = (R)0.1; P.joint_damping = (R)3.0; P.friction_mu = (R)0.4;
   P.gravity = (R)9.81; P.contact_k = (R)1e4; P.contact_c = (R)100; P.h = (R)0.01; P.gear = (R)120;
-  P.z0 = (R)0.8; P.substeps = 5; P.max_episode_steps = 1000;
+  P.z0 = (R)0.8; P.substeps = 5; P.max_episode_steps = 1000; P.round_state_f32 = 0;
   return P;
 }
 
@@ -467,11 +473,11 @@ Batch<R>* create(int64_t n, uint64_t seed, const double* cfg /* armature, dampin
     return create<R>(n, seed, cfg);                                                               \
   }                                                                                               \
   void oracle_body_destroy##SFX(void* h) { delete (Batch<R>*)h; }                                 \
-  void oracle_body_set_params##SFX(void* h, const double* p /* 9: armature damping mu g k c h gear substeps */) { \
+  void oracle_body_set_params##SFX(void* h, const double* p /* 10: armature damping mu g k c h gear substeps round_state_f32 */) { \
     Batch<R>* B = (Batch<R>*)h;                                                                   \
     B->P.armature = (R)p[0]; B->P.joint_damping = (R)p[1]; B->P.friction_mu = (R)p[2];            \
     B->P.gravity = (R)p[3]; B->P.contact_k = (R)p[4]; B->P.contact_c = (R)p[5]; B->P.h = (R)p[6]; \
-    B->P.gear = (R)p[7]; B->P.substeps = (int)p[8];                                               \
+    B->P.gear = (R)p[7]; B->P.substeps = (int)p[8]; B->P.round_state_f32 = (int)p[9];             \
   }                                                                                               \
   void oracle_body_reset##SFX(void* h, R* obs) {                                                  \
     Batch<R>* B = (Batch<R>*)h;                                                                   \

@@ -44,7 +44,7 @@ class Body:
     """Batch of N oracle bodies in float32 (dtype=np.float32) or float64."""
 
     DEFAULTS = dict(armature=0.1, joint_damping=3.0, friction_mu=0.4, gravity=9.81, contact_k=1e4,
-                    contact_c=100.0, h=0.01, gear=120.0, substeps=5)
+                    contact_c=100.0, h=0.01, gear=120.0, substeps=5, round_state_f32=0)
 
     def __init__(self, n, seed, dtype=np.float32, max_episode_steps=1000, **params):
         from oracle import oracle as orc
@@ -65,7 +65,8 @@ class Body:
     def _push_params(self):
         p = self.params
         arr = np.array([p["armature"], p["joint_damping"], p["friction_mu"], p["gravity"],
-                        p["contact_k"], p["contact_c"], p["h"], p["gear"], p["substeps"]], np.float64)
+                        p["contact_k"], p["contact_c"], p["h"], p["gear"], p["substeps"],
+                        p["round_state_f32"]], np.float64)
         self._f("set_params")(self.h, _p(arr))
 
     def set_params(self, **kw):

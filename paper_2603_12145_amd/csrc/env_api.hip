@@ -141,7 +141,7 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
   const size_t obs_bytes = (e->kind == ENV_PONG_PIXELS && ring_mode)
                                ? (size_t)e->n * 4 * FRAME_BYTES
                                : tn * obs_bytes_per_env_step(e->kind);
-  if (!device_range_ok(e, obs, obs_bytes, 16)) return ENV_E_ARG;
+  if (!device_range_ok(e, obs, obs_bytes, e->kind == ENV_BODY ? 4 : 16)) return ENV_E_ARG;
   if (!device_range_ok(e, reward, tn * sizeof(float), 4)) return ENV_E_ARG;
   if (!device_range_ok(e, done, tn, 1)) return ENV_E_ARG;
   if (actions &&
@@ -243,7 +243,7 @@ int env_reset(env_t* e, void* obs_dev) {
     err = launch_pixel_reset(e->state, e->n, e->seed, e->step, static_cast<uint8_t*>(obs_dev),
                              e->cfg.pixel_layout == ENV_PIXELS_SLOT_MAJOR, e->blocks, e->stream);
   } else if (e->kind == ENV_BODY) {
-    if (obs_dev && !device_range_ok(e, obs_dev, (size_t)e->n * BODY_OBS * sizeof(float), 16))
+    if (obs_dev && !device_range_ok(e, obs_dev, (size_t)e->n * BODY_OBS * sizeof(float), 4))
       return ENV_E_ARG;
     err = launch_body_reset(e->state, e->n, e->seed, e->step, static_cast<float*>(obs_dev), e->stream);
   } else {
