@@ -27,8 +27,10 @@
 //   3. joint limits +-1 rad: S = joints sitting at a limit and still moving outwards under v*;
 //      v+ = M-orthogonal projection of v* onto {v_S = 0}: solve M_FF v_F = (M v + h rhs)_F;
 //   4. q+ = q + h v+, joint angles clipped to [-1, 1].
-// Everything is templated on the scalar type: float32 is the parity target, float64 serves the
-// invariants.  Build with -ffp-contract=off.
+// Everything is templated on the scalar type.  float64 serves the invariants and is the parity
+// target of the single-step comparison (stepping from a float32 state; `round_state_f32` rounds the
+// state back to the storage format after every step); float32 serves the long-rollout statistics
+// and shows what float32 arithmetic alone would cost.  Build with -ffp-contract=off.
 #include <cmath>
 #include <cstdint>
 #include <cstdlib>
