@@ -28,10 +28,11 @@ struct mi355env {
   uint64_t step;          // env steps taken since creation (all environments move in lock-step)
   hipStream_t stream;
   env_config_t cfg;
-  uint32_t* state;        // device SoA [fields][n], every field 4 bytes
+  uint32_t* state;        // device SoA [fields][n], every field 4 bytes (pixels: may point into pipe)
+  uint32_t* state_alloc;  // the allocation made for it by env_create
   int fields;
   DeviceStats* stats;     // device
-  uint32_t* blocks;       // device scratch [3][n], pixels only: cell blocks of the newest frame
+  PixelPipe pipe;         // pixels only: second state buffer and the staging buffers of the lookahead
   bool was_reset;
   // last device ranges that passed the residency check (avoids a driver query per step)
   struct Range { const void* p; size_t bytes; } seen[8];
@@ -170,10 +171,15 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
       PixelLaunch x{};
       x.pong = p; x.pong.obs = nullptr;
       x.slot_major = e->cfg.pixel_layout == ENV_PIXELS_SLOT_MAJOR;
-      x.blocks = e->blocks;
+      x.blocks = e->pipe.blocks[0];
       if (ring_mode) x.ring = static_cast<uint8_t*>(obs);
       else x.frames = static_cast<uint8_t*>(obs);
-      err = launch_pixel_rollout(x, e->stream);
+      if (ring_mode && x.slot_major && T == 1 && pixel_plane_mode() != 0) {
+        err = pixel_pipe_step(e->pipe, e->state, x, pixel_plane_mode() == 2, e->stream);
+      } else {
+        pixel_pipe_invalidate(e->pipe);      // the state moves without the lookahead knowing
+        err = launch_pixel_rollout(x, e->stream);
+      }
     }
   }
   if (err != hipSuccess) return ENV_E_HIP;
@@ -198,7 +204,7 @@ int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_c
   e->kind = kind; e->n = n_envs; e->seed = seed; e->step = 0;
   e->stream = static_cast<hipStream_t>(hip_stream);
   e->cfg = c; e->fields = fields_of(kind); e->was_reset = false;
-  e->state = nullptr; e->stats = nullptr; e->blocks = nullptr; e->seen_next = 0;
+  e->state = nullptr; e->stats = nullptr; e->seen_next = 0;
   for (auto& r : e->seen) r = {nullptr, 0};
   if (hipGetDevice(&e->device) != hipSuccess) { delete e; return ENV_E_HIP; }
 
@@ -206,11 +212,11 @@ int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_c
   if (hipMalloc(reinterpret_cast<void**>(&e->state), state_bytes) != hipSuccess) {
     (void)hipGetLastError(); delete e; return ENV_E_ALLOC;
   }
+  e->state_alloc = e->state;
   if (hipMalloc(reinterpret_cast<void**>(&e->stats), sizeof(DeviceStats)) != hipSuccess) {
     (void)hipGetLastError(); (void)hipFree(e->state); delete e; return ENV_E_ALLOC;
   }
-  if (kind == ENV_PONG_PIXELS &&
-      hipMalloc(reinterpret_cast<void**>(&e->blocks), (size_t)3 * (size_t)n_envs * 4) != hipSuccess) {
+  if (kind == ENV_PONG_PIXELS && pixel_pipe_create(e->pipe, n_envs) != hipSuccess) {
     (void)hipGetLastError(); (void)hipFree(e->state); (void)hipFree(e->stats); delete e;
     return ENV_E_ALLOC;
   }
@@ -219,7 +225,7 @@ int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_c
       hipMemcpyAsync(e->stats, &z, sizeof z, hipMemcpyHostToDevice, e->stream) != hipSuccess ||
       hipStreamSynchronize(e->stream) != hipSuccess) {
     (void)hipGetLastError(); (void)hipFree(e->state); (void)hipFree(e->stats);
-    (void)hipFree(e->blocks); delete e;
+    pixel_pipe_destroy(e->pipe); delete e;
     return ENV_E_HIP;
   }
   *out = e;
@@ -229,9 +235,9 @@ int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_c
 void env_destroy(env_t* e) {
   if (!e) return;
   (void)hipStreamSynchronize(e->stream);
-  (void)hipFree(e->state);
+  (void)hipFree(e->state_alloc);
   (void)hipFree(e->stats);
-  (void)hipFree(e->blocks);
+  pixel_pipe_destroy(e->pipe);
   delete e;
 }
 
@@ -241,7 +247,8 @@ int env_reset(env_t* e, void* obs_dev) {
   if (e->kind == ENV_PONG_PIXELS && obs_dev) {
     if (!device_range_ok(e, obs_dev, (size_t)e->n * 4 * FRAME_BYTES, 16)) return ENV_E_ARG;
     err = launch_pixel_reset(e->state, e->n, e->seed, e->step, static_cast<uint8_t*>(obs_dev),
-                             e->cfg.pixel_layout == ENV_PIXELS_SLOT_MAJOR, e->blocks, e->stream);
+                             e->cfg.pixel_layout == ENV_PIXELS_SLOT_MAJOR, e->pipe.blocks[0], e->stream);
+    pixel_pipe_invalidate(e->pipe);
   } else if (e->kind == ENV_BODY) {
     if (obs_dev && !device_range_ok(e, obs_dev, (size_t)e->n * BODY_OBS * sizeof(float), 4))
       return ENV_E_ARG;
@@ -251,6 +258,7 @@ int env_reset(env_t* e, void* obs_dev) {
       return ENV_E_ARG;
     err = launch_pong_reset(e->state, e->n, e->seed, e->step,
                             e->kind == ENV_PONG ? static_cast<float*>(obs_dev) : nullptr, e->stream);
+    if (e->kind == ENV_PONG_PIXELS) pixel_pipe_invalidate(e->pipe);
   }
   if (err != hipSuccess) return ENV_E_HIP;
   e->was_reset = true;
@@ -316,6 +324,7 @@ int env_set_state(env_t* e, const void* host_buf, size_t bytes) {
     return ENV_E_HIP;
   std::memcpy(&e->step, host_buf, 8);
   e->was_reset = true;
+  if (e->kind == ENV_PONG_PIXELS) pixel_pipe_invalidate(e->pipe);
   return ENV_OK;
 }
 

@@ -43,4 +43,29 @@ hipError_t launch_pixel_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_
                               uint8_t* ring, bool slot_major, uint32_t* blocks, hipStream_t stream);
 hipError_t launch_pixel_rollout(const PixelLaunch& a, hipStream_t stream);
 
+// Slot-major pixel step with one-step lookahead.  Every step is the launch F(t) = { hand step t's
+// staged reward / done to the caller and flush its episode statistics; render step t's plane;
+// compute step t+1 (in-kernel actions) from the state after t into the staging buffers of the other
+// parity }.  The three parts are independent, so the dynamics of the next step hide under the
+// render of this one inside a single launch.  If the staged step is not the one asked for (first
+// step, external actions, state restored), the dynamics launch D(t) runs first.
+struct PixelPipe {
+  void* slab = nullptr;                            // one allocation holding everything below
+  uint32_t* state_alt = nullptr;                   // second state buffer [10][n] (ping-pong)
+  uint32_t* blocks[2] = {nullptr, nullptr};        // [3][n] cell blocks of the staged frame
+  float* reward[2] = {nullptr, nullptr};           // [n]
+  uint8_t* done[2] = {nullptr, nullptr};           // [n]
+  int32_t* fin_ret[2] = {nullptr, nullptr};        // [n] return / length of an episode that ended
+  int32_t* fin_len[2] = {nullptr, nullptr};
+  bool staged = false;                             // staging buffers of parity (step & 1) hold `step`
+};
+hipError_t pixel_pipe_create(PixelPipe& p, int64_t n);
+void pixel_pipe_destroy(PixelPipe& p);
+// One slot-major ring step.  `state` is the handle's committed-state pointer and is swapped with
+// p.state_alt.  a.pong.actions may be null (staged lookahead usable) or external.
+hipError_t pixel_pipe_step(PixelPipe& p, uint32_t*& state, const PixelLaunch& a, bool lookahead,
+                           hipStream_t stream);
+inline void pixel_pipe_invalidate(PixelPipe& p) { p.staged = false; }
+int pixel_plane_mode();
+
 }  // namespace envk

@@ -182,58 +182,63 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * WAVE) void pixel_kernel(PixelLaun
 // stream.  Measured on MI355X, the write pattern that gets closest to HBM peak is "one workgroup
 // writes one 4 KiB-aligned page with one 16-byte store per thread, workgroups dispatched in address
 // order" (about 6.8 TB/s for a plain fill against about 5.3 TB/s for any scheme in which a
-// wavefront streams several KiB on its own).  The plane is therefore rendered by two launches:
-//   1. pixel_dynamics_kernel: one lane per environment; transition, state / reward / done stores,
-//      and the three cell blocks of the new frame (12 bytes per environment) into `blocks`;
-//   2. plane_render_kernel: one workgroup per 4 KiB page of the plane.  A page overlaps at most two
-//      frames; their six cell blocks arrive by scalar loads, the lit pixels that fall inside the
-//      page are poked into a zeroed 4 KiB LDS page, and every thread stores its 16 bytes.
+// wavefront streams several KiB on its own).  The plane is therefore rendered page by page from
+// 12 bytes per environment (the three rectangles' cell blocks), which a lane-per-environment
+// dynamics pass stages in library scratch one step ahead of the renderer.
 // ---------------------------------------------------------------------------------------------
+// Staging buffers of one step (library scratch): what the dynamics produce for the renderer and for
+// the caller.
+struct Staged {
+  uint32_t* blocks;     // [3][n]
+  float* reward;        // [n]
+  uint8_t* done;        // [n]
+  int32_t* fin_ret;     // [n], valid where done
+  int32_t* fin_len;
+};
+
+// Dynamics of one step for environment i: state_in -> state_out and the staging buffers.
+// RESET: draw the initial state instead (state_in unused, only state_out and blocks written).
 template <bool RESET>
-__global__ __launch_bounds__(256) void pixel_dynamics_kernel(PongLaunch a, uint32_t* __restrict__ blocks) {
+__device__ __forceinline__ void stage_step(const PongLaunch& a, const uint32_t* __restrict__ state_in,
+                                           uint32_t* __restrict__ state_out, const Staged& st, int64_t i) {
   const int64_t n = a.n;
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const bool live = i < n;
+  if (i >= n) return;
   PongLane s;
-  LaneEpisodes le;
   if (RESET) {
     s = pong_initial(a.seed, (uint32_t)i, a.step0);
   } else {
-    s = live ? pong_load(a.state, n, i) : pong_idle_lane();
+    s = pong_load(state_in, n, i);
     const Draw4 d = philox_draw(a.seed, (uint32_t)i, a.step0, 0u);
-    int action = pong_action_from_word(d.w0);
-    if (a.actions) action = live ? (int)a.actions[i] : 0;
+    const int action = a.actions ? (int)a.actions[i] : pong_action_from_word(d.w0);
     const PongEvent ev = pong_transition(s, action, d.w1, d.w2, a.max_score);
-    if (live) {
-      a.reward[i] = ev.reward;
-      a.done[i] = ev.done ? 1 : 0;
-      if (ev.done) {
-        le.count = 1; le.length_sum = ev.fin_len; le.ret_sum_i = ev.fin_ret;
-        le.min_key = ev.fin_ret; le.max_key = ev.fin_ret;
-      }
-    }
+    st.reward[i] = ev.reward;
+    st.done[i] = ev.done ? 1 : 0;
+    st.fin_ret[i] = ev.fin_ret;
+    st.fin_len[i] = ev.fin_len;
   }
-  if (live) {
-    pong_store(a.state, n, i, s);
-    blocks[0 * n + i] = cell_block(140.0f, s.pa, 4.0f, 16.0f);
-    blocks[1 * n + i] = cell_block(16.0f, s.po, 4.0f, 16.0f);
-    blocks[2 * n + i] = cell_block(s.bx, s.by, 2.0f, 2.0f);
-  }
-  if (!RESET) flush_wave_stats<false>(a.stats, le);
+  pong_store(state_out, n, i, s);
+  st.blocks[0 * n + i] = cell_block(140.0f, s.pa, 4.0f, 16.0f);
+  st.blocks[1 * n + i] = cell_block(16.0f, s.po, 4.0f, 16.0f);
+  st.blocks[2 * n + i] = cell_block(s.bx, s.by, 2.0f, 2.0f);
+}
+
+template <bool RESET>
+__global__ __launch_bounds__(256) void pixel_dynamics_kernel(PongLaunch a, const uint32_t* state_in,
+                                                             uint32_t* state_out, Staged st) {
+  stage_step<RESET>(a, state_in, state_out, st, (int64_t)blockIdx.x * 256 + threadIdx.x);
 }
 
 constexpr int PAGE = 4096;
 
-// plane: first byte of the plane (16-byte aligned), n frames long.  Workgroup b handles the b-th
-// 4 KiB-aligned page that intersects it.
-__global__ __launch_bounds__(256) void plane_render_kernel(const uint32_t* __restrict__ blocks, int64_t n,
-                                                           uint8_t* __restrict__ plane) {
-  __shared__ __align__(16) uint8_t page[PAGE];
+// One 4 KiB-aligned page of a plane: zero an LDS page, poke the lit pixels of the (at most two)
+// frames overlapping it -- 192 candidate pixels, one per thread -- store 16 bytes per thread.
+__device__ __forceinline__ void render_page(const uint32_t* __restrict__ blocks, int64_t n,
+                                            uint8_t* __restrict__ plane, unsigned page_index, uint8_t* page) {
   const int tid = threadIdx.x;
   const uintptr_t base = reinterpret_cast<uintptr_t>(plane);
   const int64_t total = n * FRAME_BYTES;
   // byte offsets relative to the start of the plane; the first page may begin before it
-  const int64_t page_off = (int64_t)blockIdx.x * PAGE - (int64_t)(base & (PAGE - 1));
+  const int64_t page_off = (int64_t)page_index * PAGE - (int64_t)(base & (PAGE - 1));
   const int64_t lo = page_off < 0 ? 0 : page_off;
   const int64_t hi = page_off + PAGE < total ? page_off + PAGE : total;
   const int64_t f_first = lo / FRAME_BYTES;
@@ -264,6 +269,53 @@ __global__ __launch_bounds__(256) void plane_render_kernel(const uint32_t* __res
 
   const int64_t mine = page_off + 16 * tid;
   if (mine >= lo && mine < hi) *reinterpret_cast<chunk_t*>(plane + mine) = page16[tid];
+}
+
+__global__ __launch_bounds__(256) void plane_render_kernel(const uint32_t* __restrict__ blocks, int64_t n,
+                                                           uint8_t* __restrict__ plane) {
+  __shared__ __align__(16) uint8_t page[PAGE];
+  render_page(blocks, n, plane, blockIdx.x, page);
+}
+
+// F(t): the first ceil(n / 256) workgroups commit step t (reward / done to the caller, episode
+// statistics) and, if `ahead`, stage step t+1; the remaining workgroups render step t's plane.
+struct FusedStep {
+  PongLaunch next;              // step0 = t + 1, actions = nullptr; reward / done = the CALLER's for step t
+  const uint32_t* state_now;    // state after step t
+  uint32_t* state_next;         // receives the state after step t + 1
+  Staged now, ahead_to;         // staged step t (read), staging buffers for step t + 1 (written)
+  uint8_t* plane;
+  unsigned commit_blocks;       // ceil(n / 256)
+  int commit_first;             // commit workgroups before (1) or after (0) the render pages
+  int ahead;
+};
+
+__global__ __launch_bounds__(256) void pixel_fused_step_kernel(FusedStep a) {
+  __shared__ __align__(16) uint8_t page[PAGE];
+  // The commit / lookahead workgroups sit either before or after the render pages in the grid.
+  // In front their latency hides completely under the render (best for small batches, where it is
+  // a sizeable part of the step); for large batches a few hundred workgroups in front of the page
+  // stream cost more than they hide (measured), so they go last.
+  const unsigned pages = gridDim.x - a.commit_blocks;
+  const unsigned first_commit = a.commit_first ? 0u : pages;
+  if (blockIdx.x < first_commit || blockIdx.x >= first_commit + a.commit_blocks) {
+    render_page(a.now.blocks, a.next.n, a.plane, a.commit_first ? blockIdx.x - a.commit_blocks : blockIdx.x, page);
+    return;
+  }
+  const int64_t n = a.next.n;
+  const int64_t i = (int64_t)(blockIdx.x - first_commit) * 256 + threadIdx.x;
+  LaneEpisodes le;
+  if (i < n) {
+    const uint8_t d = a.now.done[i];
+    a.next.reward[i] = a.now.reward[i];
+    a.next.done[i] = d;
+    if (d) {
+      const int r = a.now.fin_ret[i];
+      le.count = 1; le.length_sum = a.now.fin_len[i]; le.ret_sum_i = r; le.min_key = r; le.max_key = r;
+    }
+  }
+  flush_wave_stats<false>(a.next.stats, le);
+  if (a.ahead) stage_step<false>(a.next, a.state_now, a.state_next, a.ahead_to, i);
 }
 
 int g_envs_per_wave = 16;
@@ -307,30 +359,100 @@ bool set_pixel_tuning(int envs_per_wave, int streaming) {
 
 namespace {
 
-bool g_plane_path = true;   // slot-major ring steps go through the two-launch plane renderer
+int g_plane_path = 2;   // slot-major ring steps: 0 wave renderer, 1 page renderer without lookahead, 2 with
 
-hipError_t launch_plane(const uint32_t* blocks, int64_t n, uint8_t* plane, hipStream_t stream) {
+unsigned plane_pages(const uint8_t* plane, int64_t n) {
   const uintptr_t base = reinterpret_cast<uintptr_t>(plane);
   const uintptr_t end = base + (uintptr_t)n * FRAME_BYTES;
-  const unsigned pages = (unsigned)(((end + PAGE - 1) >> 12) - (base >> 12));
-  hipLaunchKernelGGL(plane_render_kernel, dim3(pages), dim3(256), 0, stream, blocks, n, plane);
-  return hipGetLastError();
+  return (unsigned)(((end + PAGE - 1) >> 12) - (base >> 12));
+}
+
+Staged staged_of(const PixelPipe& p, int k) {
+  return Staged{p.blocks[k], p.reward[k], p.done[k], p.fin_ret[k], p.fin_len[k]};
 }
 
 }  // namespace
 
-bool set_plane_path(int on) { g_plane_path = on != 0; return true; }
+bool set_plane_path(int mode) {
+  if (mode < 0 || mode > 2) return false;
+  g_plane_path = mode;
+  return true;
+}
+int pixel_plane_mode() { return g_plane_path; }
+
+hipError_t pixel_pipe_create(PixelPipe& p, int64_t n) {
+  auto up = [](size_t b) { return (b + 255) & ~(size_t)255; };
+  const size_t state_b = up((size_t)PONG_FIELDS * n * 4), blocks_b = up((size_t)3 * n * 4);
+  const size_t word_b = up((size_t)n * 4), done_b = up((size_t)n);
+  const hipError_t err = hipMalloc(&p.slab, state_b + 2 * (blocks_b + 3 * word_b + done_b));
+  if (err != hipSuccess) return err;
+  char* at = static_cast<char*>(p.slab);
+  p.state_alt = reinterpret_cast<uint32_t*>(at); at += state_b;
+  for (int k = 0; k < 2; ++k) {
+    p.blocks[k] = reinterpret_cast<uint32_t*>(at); at += blocks_b;
+    p.reward[k] = reinterpret_cast<float*>(at); at += word_b;
+    p.fin_ret[k] = reinterpret_cast<int32_t*>(at); at += word_b;
+    p.fin_len[k] = reinterpret_cast<int32_t*>(at); at += word_b;
+    p.done[k] = reinterpret_cast<uint8_t*>(at); at += done_b;
+  }
+  p.staged = false;
+  return hipSuccess;
+}
+
+void pixel_pipe_destroy(PixelPipe& p) {
+  if (p.slab) { (void)hipFree(p.slab); p.slab = nullptr; }
+  p.staged = false;
+}
+
+hipError_t pixel_pipe_step(PixelPipe& p, uint32_t*& state, const PixelLaunch& a, bool lookahead,
+                           hipStream_t stream) {
+  const int64_t n = a.pong.n;
+  const int k = (int)(a.pong.step0 & 1);
+  const unsigned commit_blocks = (unsigned)((n + 255) / 256);
+  if (!(p.staged && a.pong.actions == nullptr)) {
+    // D(t): stage this step from the committed state into the other state buffer
+    hipLaunchKernelGGL(pixel_dynamics_kernel<false>, dim3(commit_blocks), dim3(256), 0, stream, a.pong,
+                       state, p.state_alt, staged_of(p, k));
+    const hipError_t err = hipGetLastError();
+    if (err != hipSuccess) return err;
+  }
+  // whichever launch staged step t wrote its state into state_alt: that is the committed state now
+  uint32_t* const after_t = p.state_alt;
+  p.state_alt = state;
+  state = after_t;
+
+  FusedStep f{};
+  f.next = a.pong;
+  f.next.step0 = a.pong.step0 + 1;
+  f.next.actions = nullptr;
+  f.state_now = state;
+  f.state_next = p.state_alt;
+  f.now = staged_of(p, k);
+  f.ahead_to = staged_of(p, k ^ 1);
+  f.plane = a.ring + (int64_t)(a.pong.step0 & 3) * n * FRAME_BYTES;
+  f.commit_blocks = commit_blocks;
+  f.commit_first = n <= 24576 ? 1 : 0;
+  f.ahead = lookahead ? 1 : 0;
+  hipLaunchKernelGGL(pixel_fused_step_kernel, dim3(f.commit_blocks + plane_pages(f.plane, n)), dim3(256), 0,
+                     stream, f);
+  p.staged = lookahead;
+  return hipGetLastError();
+}
 
 hipError_t launch_pixel_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
                               uint8_t* ring, bool slot_major, uint32_t* blocks, hipStream_t stream) {
-  if (slot_major && g_plane_path && blocks) {
+  if (slot_major && g_plane_path != 0 && blocks) {
     PongLaunch p{};
     p.state = state; p.n = n; p.seed = seed; p.step0 = step; p.T = 1;
+    const Staged st{blocks, nullptr, nullptr, nullptr, nullptr};
     hipLaunchKernelGGL(pixel_dynamics_kernel<true>, dim3((unsigned)((n + 255) / 256)), dim3(256), 0,
-                       stream, p, blocks);
+                       stream, p, static_cast<const uint32_t*>(nullptr), state, st);
     hipError_t err = hipGetLastError();
-    for (int slot = 0; slot < 4 && err == hipSuccess; ++slot)
-      err = launch_plane(blocks, n, ring + (int64_t)slot * n * FRAME_BYTES, stream);
+    for (int slot = 0; slot < 4 && err == hipSuccess; ++slot) {
+      uint8_t* plane = ring + (int64_t)slot * n * FRAME_BYTES;
+      hipLaunchKernelGGL(plane_render_kernel, dim3(plane_pages(plane, n)), dim3(256), 0, stream, blocks, n, plane);
+      err = hipGetLastError();
+    }
     return err;
   }
   PixelLaunch a{};
@@ -341,14 +463,6 @@ hipError_t launch_pixel_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_
 }
 
 hipError_t launch_pixel_rollout(const PixelLaunch& a, hipStream_t stream) {
-  if (a.ring && a.slot_major && g_plane_path && a.blocks && a.pong.T == 1) {
-    hipLaunchKernelGGL(pixel_dynamics_kernel<false>, dim3((unsigned)((a.pong.n + 255) / 256)), dim3(256),
-                       0, stream, a.pong, a.blocks);
-    const hipError_t err = hipGetLastError();
-    if (err != hipSuccess) return err;
-    const int64_t slot = (int64_t)(a.pong.step0 & 3);
-    return launch_plane(a.blocks, a.pong.n, a.ring + slot * a.pong.n * FRAME_BYTES, stream);
-  }
   if (a.frames) return launch_mode<MODE_FRAMES>(a, stream);
   return launch_mode<MODE_RING>(a, stream);
 }

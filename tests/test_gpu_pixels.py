@@ -37,7 +37,7 @@ def _tune(epw, streaming=0):
 def _default_tuning():
     yield
     _tune(16, 0)
-    assert b.lib().mi355env_tune_plane_path(1) == 0
+    assert b.lib().mi355env_tune_plane_path(2) == 0
 
 
 @pytest.mark.parametrize("layout", ["slot_major", "env_major"])
@@ -70,14 +70,15 @@ def test_ring_steps_match_oracle(n, epw, layout):
 
 @pytest.mark.parametrize("n", [1, 7, 255, 256, 257, 1000])
 def test_plane_renderer_and_wave_renderer_agree_with_oracle(n):
-    # slot-major steps normally take the two-launch page renderer; with it switched off the
-    # per-wavefront tile renderer writes the same ring.  Plane starts are 4 KiB-aligned only when
+    # slot-major steps normally take the page renderer with the dynamics launch overlapped on a
+    # second stream (2); the same two launches in series (1) and the per-wavefront tile renderer (0)
+    # write the same ring.  Plane starts are 4 KiB-aligned only when
     # n is a multiple of 256: the other sizes exercise the partial first and last pages.
     seed, T = 90 + n, 9
     p = orc.Pong(n, seed, max_score=1); p.reset()
     stack = np.zeros((n, 4, F, F), np.uint8); p.fill_stack(stack)
     rings = []
-    for plane_path in (1, 0):
+    for plane_path in (2, 1, 0):
         assert b.lib().mi355env_tune_plane_path(plane_path) == 0
         h = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"max_score": 1})
         ring = new_ring(n, "slot_major")
@@ -93,9 +94,44 @@ def test_plane_renderer_and_wave_renderer_agree_with_oracle(n):
         b.env_destroy(h)
     for t in range(T):
         p.step(stack=stack)
-    assert_bit_equal(rings[0], stack, "plane renderer")
-    assert_bit_equal(rings[1], stack, "wave renderer")
+    assert_bit_equal(rings[0], stack, "overlapped plane renderer")
+    assert_bit_equal(rings[1], stack, "serial plane renderer")
+    assert_bit_equal(rings[2], stack, "wave renderer")
     assert stats["episodes"] == p.stats()["episodes"]
+
+
+def test_overlapped_and_serial_steps_interleave_correctly():
+    # in-kernel actions take the two-stream pipeline, external actions the serial path; switching
+    # between them, resetting and restoring state in between must not reorder anything
+    n, seed, T = 700, 13, 60
+    rng = np.random.default_rng(1)
+    acts = inputs.pong_actions(T, n, seed=9)
+    use_ext = rng.random(T) < 0.4
+    L = b.lib()
+    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"max_score": 1})
+    ring = new_ring(n, "slot_major")
+    rew = torch.empty((T, n), dtype=torch.float32, device=DEV)
+    done = torch.empty((T, n), dtype=torch.uint8, device=DEV)
+    dacts = torch.from_numpy(acts).to(DEV)
+    b.env_reset(h, ring)
+    p = orc.Pong(n, seed, max_score=1); p.reset()
+    stack = np.zeros((n, 4, F, F), np.uint8); p.fill_stack(stack)
+    orew = np.zeros((T, n), np.float32); odone = np.zeros((T, n), np.uint8)
+    for t in range(T):
+        b.env_step(h, dacts[t] if use_ext[t] else None, ring, rew[t], done[t])
+        _, orew[t], odone[t] = p.step(actions=acts[t] if use_ext[t] else None, stack=stack)
+        if t == 20:                         # save / restore in the middle of the pipeline
+            blob = b.env_get_state(h)
+            b.env_set_state(h, blob)
+        if t == 40:                         # second reset: all four slots rewritten
+            b.env_reset(h, ring)
+            p.reset(); p.fill_stack(stack)
+    torch.cuda.synchronize()
+    assert_bit_equal(ring_as_env_major(ring, "slot_major"), stack, "ring")
+    assert_bit_equal(rew.cpu().numpy(), orew, "reward")
+    assert_bit_equal(done.cpu().numpy(), odone, "done")
+    assert b.env_stats(h)["episodes"] == p.stats()["episodes"] > 0
+    b.env_destroy(h)
 
 
 def test_streaming_store_variant_matches():
