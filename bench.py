@@ -29,6 +29,15 @@ PONG_BYTES_PER_ENV_STEP = 37   # 32 obs + 4 reward + 1 done
 FRAME_BYTES = 84 * 84          # one new frame per env-step
 
 
+def _traffic(key):
+    """Measured HBM bytes per launch (rocprofv3 --pmc, see profiles/), or None."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        return json.load(open(path)).get(key)
+    except (OSError, ValueError):
+        return None
+
+
 def _events(n):
     import torch
     return [torch.cuda.Event(enable_timing=True) for _ in range(n)]
@@ -131,7 +140,8 @@ def bench_pixels(b, torch, n, seed, launches, warmup=20, layout="slot_major"):
                 env_steps_per_s=n * launches / wall, us_per_step_events=mean_ms * 1e3,
                 us_per_step_wall=1e6 * wall / launches,
                 roofline=dict(bound="hbm", achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s",
-                              frac=gbs / HBM_PEAK_GBS, traffic=None),
+                              frac=gbs / HBM_PEAK_GBS,
+                              traffic=_traffic("pixel_fused_step_n%d" % n) if layout == "slot_major" else None),
                 launches=launches)
 
 
@@ -244,13 +254,7 @@ def main():
     r = bench_pong_rollout(b, torch, n, T, seed, args.steps, args.warmup)
     value = r["env_steps"] / r["wall"]
     achieved = PONG_BYTES_PER_ENV_STEP * n * T / (r["mean_ms"] * 1e-3) / 1e9
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        try:
-            traffic = json.load(open(tpath)).get("pong_rollout_n%d_t%d" % (n, T))
-        except Exception:
-            traffic = None
+    traffic = _traffic("pong_rollout_n%d_t%d" % (n, T))
     line = {
         "metric": "env-steps/sec on 1 MI355X (Pong N=65536 fused rollout) + % of HBM roofline",
         "value": value, "unit": "env-steps/s", "n_gpus": 1, "steps": args.steps,
