@@ -27,6 +27,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 PONG_BYTES_PER_ENV_STEP = 37   # 32 obs + 4 reward + 1 done
 FRAME_BYTES = 84 * 84          # one new frame per env-step
+FP64_PEAK_TFLOPS = 78.6        # MI355X vector float64 (256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz)
+BODY_FLOP_PER_ENV_STEP = 9400   # 5 substeps x 1876 float64 flops (FMA = 2), counted in the substep loop of the kernel ISA
 
 
 def _traffic(key):
@@ -99,9 +101,24 @@ def bench_pong_per_step(b, torch, n, seed, launches):
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     b.env_destroy(h)
+    # the same loop with an empty kernel: what a launch costs from this process on this stream
+    import ctypes as C
+    L = b.lib()
+    L.mi355env_bench_empty.argtypes = [C.c_void_p]
+    s = torch.cuda.current_stream().cuda_stream
+    for _ in range(200):
+        L.mi355env_bench_empty(s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(launches):
+        L.mi355env_bench_empty(s)
+    torch.cuda.synchronize()
+    empty = time.perf_counter() - t0
     return dict(workload="pong vector obs N=%d, one env_step launch per step" % n,
                 us_per_launch=1e6 * wall / launches, env_steps_per_s=n * launches / wall,
-                bound="dispatch latency", launches=launches)
+                bound="dispatch latency", launches=launches,
+                empty_kernel_us_per_launch=1e6 * empty / launches, ratio_to_empty_launch=wall / empty,
+                hbm_gbs=n * 101 / (wall / launches) / 1e9)
 
 
 def bench_pixels(b, torch, n, seed, launches, warmup=20, layout="slot_major"):
@@ -183,9 +200,12 @@ def bench_body(b, torch, n, T, seed, steps):
     st = b.env_stats(h)
     b.env_destroy(h)
     mean_ms, std_ms = _mean_std(ms)
+    flops = BODY_FLOP_PER_ENV_STEP * n * T / (mean_ms * 1e-3) / 1e12
     return dict(workload="articulated body N=%d x T=%d fused rollout" % (n, T), dtype="f64 in-step arithmetic, f32 state and I/O",
                 env_steps_per_s=n * T * steps / wall, ms_per_launch=mean_ms,
-                nonfinite=st["nonfinite"], episodes=st["episodes"])
+                nonfinite=st["nonfinite"], episodes=st["episodes"],
+                roofline=dict(bound="alu", achieved=flops, peak=FP64_PEAK_TFLOPS, unit="TFLOP/s",
+                              frac=flops / FP64_PEAK_TFLOPS, traffic=None))
 
 
 def cpu_baseline(n, T, seed):
@@ -287,10 +307,8 @@ def main():
             extra["config2_n%d" % nn] = dict(env_steps_per_s=rr["env_steps"] / rr["wall"],
                                              ms_per_launch=rr["mean_ms"], hbm_gbs=gbs,
                                              frac=gbs / HBM_PEAK_GBS)
-        try:
-            extra["config4_body"] = bench_body(b, torch, 8192, 1000, 4, 2)
-        except b.EnvError as e:
-            extra["config4_body"] = {"error": str(e)}
+        extra["config4_body"] = bench_body(b, torch, 8192, 1000, 4, 2)
+        extra["config4_body_n262144_t100"] = bench_body(b, torch, 262144, 100, 4, 2)
         line["extra"] = extra
     print(json.dumps(line))
 

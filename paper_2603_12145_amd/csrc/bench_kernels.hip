@@ -20,6 +20,8 @@ __global__ __launch_bounds__(256) void copy16_kernel(vec16* __restrict__ dst, co
   for (size_t k = (size_t)blockIdx.x * blockDim.x + threadIdx.x; k < chunks; k += stride) dst[k] = src[k];
 }
 
+__global__ void empty_kernel() {}
+
 unsigned grid_for(size_t chunks) {
   const size_t want = (chunks + 255) / 256;
   const size_t cap = 256 * 32;   // 32 workgroups per CU
@@ -36,6 +38,12 @@ int mi355env_bench_fill(void* dst_dev, size_t bytes, uint32_t value, void* hip_s
   const size_t chunks = bytes / 16;
   hipLaunchKernelGGL(fill16_kernel, dim3(grid_for(chunks)), dim3(256), 0,
                      static_cast<hipStream_t>(hip_stream), static_cast<vec16*>(dst_dev), chunks, value);
+  return hipGetLastError() == hipSuccess ? 0 : -3;
+}
+
+// One workgroup that does nothing: the floor of what a launch costs on this stream.
+int mi355env_bench_empty(void* hip_stream) {
+  hipLaunchKernelGGL(empty_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream));
   return hipGetLastError() == hipSuccess ? 0 : -3;
 }
 

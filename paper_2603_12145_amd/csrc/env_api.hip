@@ -174,7 +174,7 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
       x.blocks = e->pipe.blocks[0];
       if (ring_mode) x.ring = static_cast<uint8_t*>(obs);
       else x.frames = static_cast<uint8_t*>(obs);
-      if (ring_mode && x.slot_major && T == 1 && pixel_plane_mode() != 0) {
+      if (ring_mode && x.slot_major && T == 1 && pixel_plane_mode() != 0 && e->n < (int64_t)4000000) {
         err = pixel_pipe_step(e->pipe, e->state, x, pixel_plane_mode() == 2, e->stream);
       } else {
         pixel_pipe_invalidate(e->pipe);      // the state moves without the lookahead knowing

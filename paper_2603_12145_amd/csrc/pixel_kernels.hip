@@ -232,17 +232,19 @@ constexpr int PAGE = 4096;
 
 // One 4 KiB-aligned page of a plane: zero an LDS page, poke the lit pixels of the (at most two)
 // frames overlapping it -- 192 candidate pixels, one per thread -- store 16 bytes per thread.
+// Offsets are counted in 16-byte chunks (441 per frame, 256 per page) and fit 32 bits: the host
+// only takes this path for n * 441 < 2^31.
 __device__ __forceinline__ void render_page(const uint32_t* __restrict__ blocks, int64_t n,
                                             uint8_t* __restrict__ plane, unsigned page_index, uint8_t* page) {
   const int tid = threadIdx.x;
-  const uintptr_t base = reinterpret_cast<uintptr_t>(plane);
-  const int64_t total = n * FRAME_BYTES;
-  // byte offsets relative to the start of the plane; the first page may begin before it
-  const int64_t page_off = (int64_t)page_index * PAGE - (int64_t)(base & (PAGE - 1));
-  const int64_t lo = page_off < 0 ? 0 : page_off;
-  const int64_t hi = page_off + PAGE < total ? page_off + PAGE : total;
-  const int64_t f_first = lo / FRAME_BYTES;
-  const int64_t f_last = (hi - 1) / FRAME_BYTES;      // f_first or f_first + 1
+  const int total = (int)n * CHUNKS;                                  // chunks in the plane
+  // chunk offsets relative to the start of the plane; the first page may begin before it
+  const int lead = (int)((reinterpret_cast<uintptr_t>(plane) & (PAGE - 1)) >> 4);
+  const int page_off = (int)page_index * (PAGE / 16) - lead;
+  const int lo = page_off < 0 ? 0 : page_off;
+  const int hi = page_off + PAGE / 16 < total ? page_off + PAGE / 16 : total;
+  const int f_first = (int)((unsigned)lo / (unsigned)CHUNKS);
+  const int f_last = (int)((unsigned)(hi - 1) / (unsigned)CHUNKS);     // f_first or f_first + 1
 
   // threads 0..191: (frame, rectangle) pair tid / 32, pixel tid % 32 of a 4-column x 8-row patch
   // (a paddle covers at most 4 x 8 cells, the ball at most 3 x 2).  The cell block is loaded
@@ -250,7 +252,7 @@ __device__ __forceinline__ void render_page(const uint32_t* __restrict__ blocks,
   const int pair = tid >> 5;
   const bool from_last = pair >= 3;
   const bool candidate = pair < 6 && !(from_last && f_last == f_first);
-  const int64_t f = from_last ? f_last : f_first;
+  const int f = from_last ? f_last : f_first;
   uint32_t blk = 0;
   if (candidate) blk = blocks[(int64_t)(from_last ? pair - 3 : pair) * n + f];
 
@@ -262,13 +264,13 @@ __device__ __forceinline__ void render_page(const uint32_t* __restrict__ blocks,
     const int c_lo = blk & 0xff, c_end = (blk >> 8) & 0xff;
     const int r_lo = (blk >> 16) & 0xff, r_end = blk >> 24;
     const int c = c_lo + (tid & 3), r = r_lo + ((tid >> 2) & 7);
-    const int64_t off = f * FRAME_BYTES + r * FRAME_SIDE + c - page_off;
+    const int off = (f * CHUNKS - page_off) * 16 + r * FRAME_SIDE + c;   // byte offset inside the page
     if (c < c_end && r < r_end && off >= 0 && off < PAGE) page[off] = 255;
   }
   __syncthreads();
 
-  const int64_t mine = page_off + 16 * tid;
-  if (mine >= lo && mine < hi) *reinterpret_cast<chunk_t*>(plane + mine) = page16[tid];
+  const int mine = page_off + tid;
+  if (mine >= lo && mine < hi) reinterpret_cast<chunk_t*>(plane)[mine] = page16[tid];
 }
 
 __global__ __launch_bounds__(256) void plane_render_kernel(const uint32_t* __restrict__ blocks, int64_t n,
@@ -441,7 +443,7 @@ hipError_t pixel_pipe_step(PixelPipe& p, uint32_t*& state, const PixelLaunch& a,
 
 hipError_t launch_pixel_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
                               uint8_t* ring, bool slot_major, uint32_t* blocks, hipStream_t stream) {
-  if (slot_major && g_plane_path != 0 && blocks) {
+  if (slot_major && g_plane_path != 0 && blocks && n < (int64_t)4000000) {
     PongLaunch p{};
     p.state = state; p.n = n; p.seed = seed; p.step0 = step; p.T = 1;
     const Staged st{blocks, nullptr, nullptr, nullptr, nullptr};
