@@ -30,7 +30,7 @@ def main():
         d, obs, rew, done, st = digest(ms)
         lines.append("max_score=%d sha256=%s episodes=%d return_sum=%d length_sum=%d" % (
             ms, d, st["episodes"], st["return_sum"], st["length_sum"]))
-        lines.append("max_score=%d obs[999,0]=%s" % (ms, " ".join(x.hex() for x in obs[999, 0])))
+        lines.append("max_score=%d obs[999,0]=%s" % (ms, " ".join(float(x).hex() for x in obs[999, 0])))
         lines.append("max_score=%d reward_sum=%d done_sum=%d" % (ms, int(rew.sum()), int(done.sum())))
     path = os.path.join(ROOT, "tests", "golden", "pong_oracle_digest.txt")
     with open(path, "w") as f:

@@ -333,3 +333,25 @@ def test_opponent_is_beatable_and_agent_random_play_loses():
     assert (rew == 1).sum() > 0 and (rew == -1).sum() > (rew == 1).sum()
     st = p.stats()
     assert st["episodes"] > 100 and st["return_max"] < 0
+
+
+def test_oracle_arithmetic_is_frozen_by_the_committed_digest():
+    # tests/golden/pong_oracle_digest.txt is written by tests/golden/make_pong_digest.py from the
+    # oracle alone; a change to the oracle's arithmetic must regenerate it on purpose
+    import importlib.util
+    import os
+    here = os.path.dirname(os.path.abspath(__file__))
+    spec = importlib.util.spec_from_file_location("make_pong_digest",
+                                                  os.path.join(here, "golden", "make_pong_digest.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    want = {}
+    for line in open(os.path.join(here, "golden", "pong_oracle_digest.txt")):
+        if "sha256=" in line:
+            parts = dict(kv.split("=") for kv in line.split())
+            want[int(parts["max_score"])] = parts
+    for ms in (21, 2):
+        d, obs, rew, done, st = mod.digest(ms)
+        assert d == want[ms]["sha256"]
+        assert st["episodes"] == int(want[ms]["episodes"])
+        assert st["return_sum"] == int(want[ms]["return_sum"])
