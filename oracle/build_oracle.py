@@ -8,7 +8,7 @@ import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SOURCES = ["philox.cpp", "pong.cpp", "body.cpp"]
+SOURCES = ["philox.cpp", "pong.cpp", "body.cpp", "cartpole.cpp"]
 LIB = os.path.join(HERE, "liboracle.so")
 
 
