@@ -40,7 +40,8 @@ typedef struct mi355env env_t; /* opaque handle */
 enum {
   ENV_PONG = 0,        /* Pong, obs = float32[8]: ball x, y, vx, vy, agent y, opponent y, scores  */
   ENV_PONG_PIXELS = 1, /* same dynamics, obs = ring of four rendered 84x84 uint8 frames per env   */
-  ENV_BODY = 2         /* planar 7-link articulated body, obs = float32[17], action float32[6]    */
+  ENV_BODY = 2,        /* planar 7-link articulated body, obs = float32[17], action float32[6]    */
+  ENV_CARTPOLE = 3     /* cart-pole, obs = float32[4]: x, xdot, theta, thetadot; action uint8     */
 };
 
 enum {
@@ -58,7 +59,7 @@ enum {
 typedef struct env_config_t {
   uint32_t struct_size;
   int32_t max_score;          /* Pong: points that end an episode (default 21)                    */
-  int32_t max_episode_steps;  /* body: truncation length (default 1000)                           */
+  int32_t max_episode_steps;  /* truncation length: body (default 1000), cart-pole (default 500)  */
   float armature;             /* body: rotor inertia added to the 6 joint diagonals; <0 = default */
   float joint_damping;        /* body: viscous joint damping; <0 = default                        */
   float friction_mu;          /* body: Coulomb friction coefficient; <0 = default                 */
@@ -84,7 +85,7 @@ typedef struct env_stats_t {
 
 /* Create N environments of `kind`.  seed keys every random draw.  hip_stream is a hipStream_t
  * (NULL = the null stream) on the current device; the handle keeps using it.  Allocates
- * state (Pong: 40 B/env, body: 80 B/env) on the current device.  *out is set only on success. */
+ * state (Pong: 40 B/env, body: 80 B/env, cart-pole: 24 B/env) on the current device.  *out is set only on success. */
 int env_create(env_t **out, int kind, int64_t n_envs, uint64_t seed, const env_config_t *cfg,
                void *hip_stream);
 
@@ -99,8 +100,9 @@ int env_reset(env_t *e, void *obs_dev);
 
 /* Advance every environment by one step (one kernel launch).
  * actions_dev: Pong uint8[N] in {0 stay, 1 up, 2 down} (other values = stay); body float32[N,6],
- * clipped to [-1,1]; NULL = draw the actions from this step's Philox block inside the kernel.
- * obs_dev: Pong float32[N,8]; body float32[N,17]; pixels: the ring — the frame after the step
+ * clipped to [-1,1]; cart-pole uint8[N], 1 = push right, anything else = push left;
+ * NULL = draw the actions from this step's Philox block inside the kernel.
+ * obs_dev: Pong float32[N,8]; body float32[N,17]; cart-pole float32[N,4]; pixels: the ring — the frame after the step
  * with index s (s = steps taken before this call) is written to slot s mod 4, the other three
  * slots are left as they are.  reward_dev float32[N], done_dev uint8[N].
  * obs_dev must be 16-byte aligned (body: 4-byte), reward_dev 4-byte aligned.  None may be NULL. */
@@ -121,7 +123,8 @@ int env_stats(env_t *e, env_stats_t *host_out, int reset_counters);
  * { uint64 step_counter; field_0[N]; field_1[N]; ... }, every field 4 bytes wide.
  * Pong / pixels (10 fields): ball x, y, vx, vy, agent y, opponent y (float32), agent score,
  * opponent score, episode return so far, episode length so far (int32).
- * Body (20 fields): q[9], v[9], episode return so far (float32), episode length so far (int32). */
+ * Body (20 fields): q[9], v[9], episode return so far (float32), episode length so far (int32).
+ * Cart-pole (6 fields): x, xdot, theta, thetadot, return so far (float32), length so far (int32). */
 size_t env_state_bytes(const env_t *e);
 
 /* Copy the state blob to / from host memory (bytes must equal env_state_bytes).  set_state also

@@ -6,7 +6,7 @@ library is missing or a call fails, an exception is raised.
 import ctypes as C
 import os
 
-ENV_PONG, ENV_PONG_PIXELS, ENV_BODY = 0, 1, 2
+ENV_PONG, ENV_PONG_PIXELS, ENV_BODY, ENV_CARTPOLE = 0, 1, 2, 3
 ENV_PIXELS_SLOT_MAJOR, ENV_PIXELS_ENV_MAJOR = 1, 2
 ENV_OK, ENV_E_ARG, ENV_E_ALLOC, ENV_E_HIP, ENV_E_STATE, ENV_E_UNSUPPORTED = 0, -1, -2, -3, -4, -5
 

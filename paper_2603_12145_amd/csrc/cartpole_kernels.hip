@@ -1,0 +1,158 @@
+// CartPole: reset and the fused T-step rollout (T = 1 is env_step), one lane per environment.
+// Third workload of the fused-rollout path (paper Table 8 and App. B.1 item 5 use a CartPole scan).
+// Dynamics: the classic cart-pole (Barto, Sutton, Anderson 1983) in the usual parametrisation:
+// cart 1.0 kg, pole 0.1 kg, half-length 0.5 m, g 9.8, force +-10 N, Euler step 0.02 s, failure at
+// |x| > 2.4 or |theta| > 12 degrees, reward 1 per step, truncation at max_episode_steps.
+// float32, -ffp-contract=off, every operation in the order written; sin / cos are the fixed
+// degree-7 / degree-8 polynomials below (theta stays within +-0.21 rad during an episode), so a
+// scalar CPU implementation of the same polynomials reproduces the trajectories bit for bit.
+// Per step a lane writes one 16-byte obs, one reward dword and one done byte: 21 B per env-step.
+#include "kernels.hpp"
+#include "philox.hpp"
+
+namespace envk {
+
+namespace {
+
+constexpr int WAVE = 64;
+
+struct CartLane { float x, xd, th, thd; int ep_len; };
+
+__device__ __forceinline__ float poly_sin(float x) {
+  const float x2 = x * x;
+  float p = -(1.0f / 5040.0f);
+  p = p * x2; p = p + (1.0f / 120.0f);
+  p = p * x2; p = p - (1.0f / 6.0f);
+  p = p * x2; p = p + 1.0f;
+  return x * p;
+}
+__device__ __forceinline__ float poly_cos(float x) {
+  const float x2 = x * x;
+  float p = 1.0f / 40320.0f;
+  p = p * x2; p = p - (1.0f / 720.0f);
+  p = p * x2; p = p + (1.0f / 24.0f);
+  p = p * x2; p = p - 0.5f;
+  p = p * x2; p = p + 1.0f;
+  return p;
+}
+
+__device__ __forceinline__ CartLane cart_initial(uint64_t seed, uint32_t env, uint64_t step) {
+  const Draw4 d = philox_draw(seed, env, step, 16u);
+  CartLane s;
+  s.x = -0.05f + 0.1f * unit_float(d.w0);
+  s.xd = -0.05f + 0.1f * unit_float(d.w1);
+  s.th = -0.05f + 0.1f * unit_float(d.w2);
+  s.thd = -0.05f + 0.1f * unit_float(d.w3);
+  s.ep_len = 0;
+  return s;
+}
+
+// returns true if the episode ended (fin_len = its length); s is then the next episode's start
+__device__ __forceinline__ bool cart_transition(CartLane& s, int action, int max_steps, uint64_t seed,
+                                                uint32_t env, uint64_t step, int& fin_len) {
+  const float force = (action == 1) ? 10.0f : -10.0f;
+  const float sn = poly_sin(s.th), cs = poly_cos(s.th);
+  const float temp = (force + ((0.05f * s.thd) * s.thd) * sn) / 1.1f;
+  const float denom = 0.5f * ((4.0f / 3.0f) - ((0.1f * cs) * cs) / 1.1f);
+  const float thacc = (9.8f * sn - cs * temp) / denom;
+  const float xacc = temp - ((0.05f * thacc) * cs) / 1.1f;
+  s.x = s.x + 0.02f * s.xd;
+  s.xd = s.xd + 0.02f * xacc;
+  s.th = s.th + 0.02f * s.thd;
+  s.thd = s.thd + 0.02f * thacc;
+  s.ep_len += 1;
+  const bool failed = (s.x < -2.4f) | (s.x > 2.4f) | (s.th < -0.20943951f) | (s.th > 0.20943951f);
+  const bool ended = failed | (s.ep_len >= max_steps);
+  fin_len = s.ep_len;
+  // the reset draw is cheap next to a divergent branch around it: every lane computes it
+  const CartLane fresh = cart_initial(seed, env, step + 1);
+  s.x = ended ? fresh.x : s.x; s.xd = ended ? fresh.xd : s.xd;
+  s.th = ended ? fresh.th : s.th; s.thd = ended ? fresh.thd : s.thd;
+  s.ep_len = ended ? 0 : s.ep_len;
+  return ended;
+}
+
+__device__ __forceinline__ CartLane cart_load(const uint32_t* __restrict__ st, int64_t n, int64_t i) {
+  CartLane s;
+  s.x = __uint_as_float(st[0 * n + i]); s.xd = __uint_as_float(st[1 * n + i]);
+  s.th = __uint_as_float(st[2 * n + i]); s.thd = __uint_as_float(st[3 * n + i]);
+  s.ep_len = (int)st[5 * n + i];
+  return s;
+}
+__device__ __forceinline__ void cart_store(uint32_t* __restrict__ st, int64_t n, int64_t i, const CartLane& s) {
+  st[0 * n + i] = __float_as_uint(s.x); st[1 * n + i] = __float_as_uint(s.xd);
+  st[2 * n + i] = __float_as_uint(s.th); st[3 * n + i] = __float_as_uint(s.thd);
+  st[4 * n + i] = __float_as_uint((float)s.ep_len);      // return so far = steps so far
+  st[5 * n + i] = (uint32_t)s.ep_len;
+}
+
+__global__ __launch_bounds__(256) void cartpole_reset_kernel(uint32_t* __restrict__ state, int64_t n,
+                                                             uint64_t seed, uint64_t step, float* __restrict__ obs) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const CartLane s = cart_initial(seed, (uint32_t)i, step);
+  cart_store(state, n, i, s);
+  if (obs) reinterpret_cast<float4*>(obs)[i] = make_float4(s.x, s.xd, s.th, s.thd);
+}
+
+__global__ __launch_bounds__(256) void cartpole_rollout_kernel(PongLaunch a) {
+  const int lane = threadIdx.x & (WAVE - 1);
+  const int wave_in_block = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  // XCD-aware mapping as in the Pong rollout: each XCD owns a contiguous eighth of the batch
+  const unsigned per_xcd = gridDim.x >> 3;
+  const unsigned logical_block = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+  const int64_t wave_base = ((int64_t)logical_block * (blockDim.x >> 6) + wave_in_block) * WAVE;
+  const int64_t n = a.n;
+  if (wave_base >= n) return;
+  const int64_t i = wave_base + lane;
+  const bool live = i < n;
+  const int64_t ic = live ? i : n - 1;
+  CartLane s = cart_load(a.state, n, ic);
+  LaneEpisodes le;
+  float4* obs_row = reinterpret_cast<float4*>(a.obs) + wave_base;
+  float* rew_row = a.reward + wave_base;
+  uint8_t* done_row = a.done + wave_base;
+  const uint8_t* act_row = a.actions ? a.actions + wave_base : nullptr;
+  for (int32_t t = 0; t < a.T; ++t) {
+    const uint64_t step = a.step0 + (uint64_t)t;
+    int action;
+    if (act_row) action = live ? (int)act_row[lane] : 0;
+    else action = (int)(philox_draw(a.seed, (uint32_t)ic, step, 0u).w0 >> 31);
+    int fin_len;
+    const bool ended = cart_transition(s, action, a.max_score, a.seed, (uint32_t)ic, step, fin_len);
+    const bool done = live && ended;
+    le.count += done ? 1 : 0;
+    le.length_sum += done ? fin_len : 0;
+    le.ret_sum_i += done ? fin_len : 0;
+    le.min_key = done ? min(le.min_key, fin_len) : le.min_key;
+    le.max_key = done ? max(le.max_key, fin_len) : le.max_key;
+    if (live) {
+      obs_row[lane] = make_float4(s.x, s.xd, s.th, s.thd);
+      rew_row[lane] = 1.0f;
+      done_row[lane] = done ? 1 : 0;
+    }
+    obs_row += n; rew_row += n; done_row += n;
+    if (act_row) act_row += n;
+  }
+  if (live) cart_store(a.state, n, i, s);
+  flush_wave_stats<false>(a.stats, le);
+}
+
+}  // namespace
+
+hipError_t launch_cartpole_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step, float* obs,
+                                 hipStream_t stream) {
+  hipLaunchKernelGGL(cartpole_reset_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, state, n,
+                     seed, step, obs);
+  return hipGetLastError();
+}
+
+// a.max_score carries max_episode_steps
+hipError_t launch_cartpole_rollout(const PongLaunch& a, hipStream_t stream) {
+  unsigned blocks = (unsigned)((a.n + 255) / 256);
+  blocks = (blocks + 7u) & ~7u;
+  hipLaunchKernelGGL(cartpole_rollout_kernel, dim3(blocks), dim3(256), 0, stream, a);
+  return hipGetLastError();
+}
+
+}  // namespace envk

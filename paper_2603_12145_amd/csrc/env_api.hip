@@ -43,14 +43,16 @@ namespace {
 
 constexpr int64_t MAX_ENVS = int64_t(1) << 30;
 
-int fields_of(int kind) { return kind == ENV_BODY ? BODY_FIELDS : PONG_FIELDS; }
+int fields_of(int kind) {
+  return kind == ENV_BODY ? BODY_FIELDS : kind == ENV_CARTPOLE ? CARTPOLE_FIELDS : PONG_FIELDS;
+}
 
 env_config_t default_config(int kind) {
   env_config_t c;
   std::memset(&c, 0, sizeof c);
   c.struct_size = sizeof(env_config_t);
   c.max_score = 21;
-  c.max_episode_steps = 1000;
+  c.max_episode_steps = kind == ENV_CARTPOLE ? 500 : 1000;
   c.armature = BODY_DEFAULT_ARMATURE;
   c.joint_damping = BODY_DEFAULT_JOINT_DAMPING;
   c.friction_mu = BODY_DEFAULT_FRICTION_MU;
@@ -125,6 +127,7 @@ size_t obs_bytes_per_env_step(int kind) {
     case ENV_PONG: return PONG_OBS * sizeof(float);
     case ENV_PONG_PIXELS: return (size_t)FRAME_BYTES;
     case ENV_BODY: return BODY_OBS * sizeof(float);
+    case ENV_CARTPOLE: return CARTPOLE_OBS * sizeof(float);
   }
   return 0;
 }
@@ -167,6 +170,9 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
     p.obs = static_cast<float*>(obs); p.reward = reward; p.done = done; p.stats = e->stats;
     if (e->kind == ENV_PONG) {
       err = launch_pong_rollout(p, e->stream);
+    } else if (e->kind == ENV_CARTPOLE) {
+      p.max_score = e->cfg.max_episode_steps;
+      err = launch_cartpole_rollout(p, e->stream);
     } else {
       PixelLaunch x{};
       x.pong = p; x.pong.obs = nullptr;
@@ -194,7 +200,7 @@ extern "C" {
 int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_config_t* cfg,
                void* hip_stream) {
   if (!out) return ENV_E_ARG;
-  if (kind != ENV_PONG && kind != ENV_PONG_PIXELS && kind != ENV_BODY) return ENV_E_ARG;
+  if (kind != ENV_PONG && kind != ENV_PONG_PIXELS && kind != ENV_BODY && kind != ENV_CARTPOLE) return ENV_E_ARG;
   if (n_envs <= 0 || n_envs > MAX_ENVS) return ENV_E_ARG;
   env_config_t c = default_config(kind);
   if (merge_config(&c, cfg) != ENV_OK) return ENV_E_ARG;
@@ -253,6 +259,10 @@ int env_reset(env_t* e, void* obs_dev) {
     if (obs_dev && !device_range_ok(e, obs_dev, (size_t)e->n * BODY_OBS * sizeof(float), 4))
       return ENV_E_ARG;
     err = launch_body_reset(e->state, e->n, e->seed, e->step, static_cast<float*>(obs_dev), e->stream);
+  } else if (e->kind == ENV_CARTPOLE) {
+    if (obs_dev && !device_range_ok(e, obs_dev, (size_t)e->n * CARTPOLE_OBS * sizeof(float), 16))
+      return ENV_E_ARG;
+    err = launch_cartpole_reset(e->state, e->n, e->seed, e->step, static_cast<float*>(obs_dev), e->stream);
   } else {
     if (obs_dev && !device_range_ok(e, obs_dev, (size_t)e->n * PONG_OBS * sizeof(float), 16))
       return ENV_E_ARG;
@@ -333,13 +343,14 @@ int env_obs_dim(int kind) {
     case ENV_PONG: return PONG_OBS;
     case ENV_PONG_PIXELS: return 4 * FRAME_BYTES;
     case ENV_BODY: return BODY_OBS;
+    case ENV_CARTPOLE: return CARTPOLE_OBS;
   }
   return ENV_E_ARG;
 }
 
 int env_action_dim(int kind) {
   switch (kind) {
-    case ENV_PONG: case ENV_PONG_PIXELS: return 1;
+    case ENV_PONG: case ENV_PONG_PIXELS: case ENV_CARTPOLE: return 1;
     case ENV_BODY: return BODY_ACT;
   }
   return ENV_E_ARG;

@@ -29,6 +29,13 @@ hipError_t launch_pong_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t
                              hipStream_t stream);
 hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream);
 
+// CartPole: same launch descriptor (max_score carries max_episode_steps; obs is [T,n,4]).
+constexpr int CARTPOLE_FIELDS = 6;   // x xdot theta thetadot | ep_ret ep_len
+constexpr int CARTPOLE_OBS = 4;
+hipError_t launch_cartpole_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step, float* obs,
+                                 hipStream_t stream);
+hipError_t launch_cartpole_rollout(const PongLaunch& a, hipStream_t stream);
+
 // Pixel observations.  ring != nullptr: frame after step s goes to ring[i][s & 3] (T must be 1 or
 // the ring is rewritten in place T times); frames != nullptr: frame t of the launch goes to
 // frames[t][i].

@@ -28,3 +28,13 @@ def pong_positions(count, seed):
     rng = np.random.default_rng(seed)
     return np.stack([rng.uniform(0, 158, count), rng.uniform(0, 208, count),
                      rng.uniform(0, 194, count), rng.uniform(0, 194, count)], 1).astype(np.float32)
+
+
+def cartpole_actions(T, n, seed):
+    """uint8 [T, n]: uniform over {0 push left, 1 push right}, plus a sprinkle of other codes
+    (which the boundary defines as 'push left')."""
+    rng = np.random.default_rng(seed)
+    a = rng.integers(0, 2, size=(T, n), dtype=np.uint8)
+    odd = rng.random((T, n)) < 0.01
+    a[odd] = rng.integers(2, 256, size=int(odd.sum()), dtype=np.uint8)
+    return a

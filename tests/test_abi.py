@@ -38,6 +38,7 @@ def test_dims_and_strings(L):
     assert b.env_obs_dim(b.ENV_PONG) == 8
     assert b.env_obs_dim(b.ENV_PONG_PIXELS) == 4 * 84 * 84
     assert b.env_obs_dim(b.ENV_BODY) == 17
+    assert b.env_obs_dim(b.ENV_CARTPOLE) == 4 and b.env_action_dim(b.ENV_CARTPOLE) == 1
     assert b.env_obs_dim(99) == b.ENV_E_ARG
     assert b.env_action_dim(b.ENV_PONG) == 1 and b.env_action_dim(b.ENV_BODY) == 6
     for code in (0, -1, -2, -3, -4, -5, -99):
