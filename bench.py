@@ -26,6 +26,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 PONG_BYTES_PER_ENV_STEP = 37   # 32 obs + 4 reward + 1 done
+CARTPOLE_BYTES_PER_ENV_STEP = 21   # 16 obs + 4 reward + 1 done
 FRAME_BYTES = 84 * 84          # one new frame per env-step
 FP64_PEAK_TFLOPS = 78.6        # MI355X vector float64 (256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz)
 BODY_FLOP_PER_ENV_STEP = 9400   # 5 substeps x 1876 float64 flops (FMA = 2), counted in the substep loop of the kernel ISA
@@ -208,6 +209,24 @@ def bench_body(b, torch, n, T, seed, steps):
                               frac=flops / FP64_PEAK_TFLOPS, traffic=None))
 
 
+def bench_cartpole(b, torch, n, T, seed, steps):
+    dev = "cuda:0"
+    h = b.env_create(b.ENV_CARTPOLE, n, seed, None)
+    obs = torch.empty((T, n, 4), dtype=torch.float32, device=dev)
+    rew = torch.empty((T, n), dtype=torch.float32, device=dev)
+    done = torch.empty((T, n), dtype=torch.uint8, device=dev)
+    b.env_reset(h, None)
+    wall, ms = time_launches(lambda: b.env_rollout(h, T, None, obs, rew, done), steps, 2)
+    st = b.env_stats(h)
+    b.env_destroy(h)
+    mean_ms, std_ms = _mean_std(ms)
+    gbs = CARTPOLE_BYTES_PER_ENV_STEP * n * T / (mean_ms * 1e-3) / 1e9
+    return dict(workload="cart-pole N=%d x T=%d fused rollout, in-kernel Philox actions" % (n, T), dtype="f32",
+                env_steps_per_s=n * T * steps / wall, ms_per_launch=mean_ms, episodes=st["episodes"],
+                roofline=dict(bound="hbm", achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s",
+                              frac=gbs / HBM_PEAK_GBS, traffic=None))
+
+
 def cpu_baseline(n, T, seed):
     """The oracle as it stands, one pass over the headline workload, all host threads allotted."""
     import numpy as np
@@ -265,6 +284,7 @@ def main():
         fn = {"pixels": lambda: bench_pixels(b, torch, 16384, 3, args.steps),
               "per_step": lambda: bench_pong_per_step(b, torch, 4096, 1, args.steps),
               "body": lambda: bench_body(b, torch, 8192, 1000, 4, args.steps),
+              "cartpole": lambda: bench_cartpole(b, torch, 65536, 1000, 2, args.steps),
               "fill": lambda: bench_fill(b, torch, 1 << 30, args.steps),
               "copy": lambda: bench_copy(b, torch, 1 << 30, args.steps)}[args.only]
         print(json.dumps(fn()))
@@ -309,6 +329,7 @@ def main():
                                              frac=gbs / HBM_PEAK_GBS)
         extra["config4_body"] = bench_body(b, torch, 8192, 1000, 4, 2)
         extra["config4_body_n262144_t100"] = bench_body(b, torch, 262144, 100, 4, 2)
+        extra["cartpole_n65536_t1000"] = bench_cartpole(b, torch, 65536, 1000, 2, 5)
         line["extra"] = extra
     print(json.dumps(line))
 
