@@ -64,7 +64,22 @@ typedef struct env_config_t {
   float joint_damping;        /* body: viscous joint damping; <0 = default                        */
   float friction_mu;          /* body: Coulomb friction coefficient; <0 = default                 */
   int32_t pixel_layout;       /* pixels: ENV_PIXELS_* below; 0 = default (slot-major)             */
+  int32_t step_counter;       /* ENV_STEP_COUNTER_* below; 0 = default (host)                     */
 } env_config_t;
+
+/* Where the handle's step counter (which keys every random draw) lives.
+ *   host    the library passes it to each launch as a kernel argument (default, cheapest);
+ *   device  each launch reads it from device memory and advances it there, so an env_step /
+ *           env_rollout call recorded into a HIP graph (stream capture) can be replayed and every
+ *           replay continues the sequence exactly as the same number of direct calls would
+ *           (the policy-in-the-loop rollout: policy kernels and env_step in one captured graph).
+ *           Before capturing, make one direct call with the same buffers (the pointer checks query
+ *           the driver the first time they see a buffer; later calls with the same buffers do
+ *           not).  Launches of one handle must not overlap.  env_step_count, env_get_state and
+ *           env_reset read the device counter; the first two synchronise the stream.
+ *           Not available for ENV_PONG_PIXELS (its step alternates library buffers from the host):
+ *           env_create returns ENV_E_UNSUPPORTED. */
+enum { ENV_STEP_COUNTER_HOST = 1, ENV_STEP_COUNTER_DEVICE = 2 };
 
 /* Layout of the 4-frame ring of ENV_PONG_PIXELS in obs_dev of env_reset / env_step:
  *   slot-major  uint8[4][N][84][84]  frame of slot k of environment i at ((k*N + i) * 7056);
@@ -137,7 +152,13 @@ int env_obs_dim(int kind);
 /* Elements per environment in actions_dev (Pong 1 x uint8, body 6 x float32). */
 int env_action_dim(int kind);
 int64_t env_num_envs(const env_t *e);
+/* Env steps taken since env_create.  With the device step counter this synchronises the stream
+ * (returns UINT64_MAX if that fails). */
 uint64_t env_step_count(const env_t *e);
+
+/* Enqueue all later work of the handle on another stream of the same device (e.g. the stream a
+ * graph capture runs on).  The caller orders the two streams; nothing is synchronised here. */
+int env_set_stream(env_t *e, void *hip_stream);
 
 /* Static string for a status code. */
 const char *env_strerror(int code);

@@ -8,6 +8,7 @@ import os
 
 ENV_PONG, ENV_PONG_PIXELS, ENV_BODY, ENV_CARTPOLE = 0, 1, 2, 3
 ENV_PIXELS_SLOT_MAJOR, ENV_PIXELS_ENV_MAJOR = 1, 2
+ENV_STEP_COUNTER_HOST, ENV_STEP_COUNTER_DEVICE = 1, 2
 ENV_OK, ENV_E_ARG, ENV_E_ALLOC, ENV_E_HIP, ENV_E_STATE, ENV_E_UNSUPPORTED = 0, -1, -2, -3, -4, -5
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -19,7 +20,7 @@ class env_config_t(C.Structure):
     _fields_ = [("struct_size", C.c_uint32), ("max_score", C.c_int32),
                 ("max_episode_steps", C.c_int32), ("armature", C.c_float),
                 ("joint_damping", C.c_float), ("friction_mu", C.c_float),
-                ("pixel_layout", C.c_int32)]
+                ("pixel_layout", C.c_int32), ("step_counter", C.c_int32)]
 
 
 class env_stats_t(C.Structure):
@@ -55,9 +56,11 @@ def lib():
         L.env_action_dim.argtypes = [C.c_int]
         L.env_num_envs.argtypes = [vp]; L.env_num_envs.restype = C.c_int64
         L.env_step_count.argtypes = [vp]; L.env_step_count.restype = C.c_uint64
+        L.env_set_stream.argtypes = [vp, vp]
         L.env_strerror.argtypes = [C.c_int]; L.env_strerror.restype = C.c_char_p
         for f in (L.env_create, L.env_reset, L.env_step, L.env_rollout, L.env_stats,
-                  L.env_get_state, L.env_set_state, L.env_obs_dim, L.env_action_dim):
+                  L.env_get_state, L.env_set_state, L.env_obs_dim, L.env_action_dim,
+                  L.env_set_stream):
             f.restype = C.c_int
         _lib = L
     return _lib
@@ -92,7 +95,8 @@ def env_create(kind, n_envs, seed, cfg=None, stream=None):
     c = None
     if cfg is not None:
         c = env_config_t(struct_size=C.sizeof(env_config_t), max_score=0, max_episode_steps=0,
-                         armature=-1.0, joint_damping=-1.0, friction_mu=-1.0, pixel_layout=0)
+                         armature=-1.0, joint_damping=-1.0, friction_mu=-1.0, pixel_layout=0,
+                         step_counter=0)
         for k, v in cfg.items():
             setattr(c, k, v)
     s = torch.cuda.current_stream() if stream is None else stream
@@ -159,3 +163,9 @@ def env_num_envs(h):
 
 def env_step_count(h):
     return int(lib().env_step_count(h))
+
+
+def env_set_stream(h, stream):
+    """stream: torch.cuda.Stream (or a raw hipStream_t address)."""
+    addr = stream if isinstance(stream, int) else stream.cuda_stream
+    _check(lib().env_set_stream(h, C.c_void_p(addr)), "env_set_stream")

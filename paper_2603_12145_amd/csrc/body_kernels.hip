@@ -395,9 +395,12 @@ __device__ __forceinline__ void body_observe(float* __restrict__ o, const BodyLa
 __device__ __forceinline__ bool finite32(float x) { return (__float_as_uint(x) & 0x7f800000u) != 0x7f800000u; }
 
 __global__ __launch_bounds__(256) void body_reset_kernel(uint32_t* __restrict__ state, int64_t n, uint64_t seed,
-                                                         uint64_t step, float* __restrict__ obs) {
+                                                         uint64_t host_step,
+                                                         const StepCounter* __restrict__ counter,
+                                                         float* __restrict__ obs) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
+  const uint64_t step = read_step(counter, host_step);
   BodyLane s;
   body_initial(s, seed, (uint32_t)i, step);
   body_store(state, n, i, s);
@@ -405,6 +408,7 @@ __global__ __launch_bounds__(256) void body_reset_kernel(uint32_t* __restrict__ 
 }
 
 __global__ __launch_bounds__(WAVE) void body_rollout_kernel(BodyLaunch a) {
+  a.step0 = launch_first_step(a.counter, a.step0, a.T);
   const int64_t n = a.n;
   const int64_t i = (int64_t)blockIdx.x * WAVE + threadIdx.x;
   const bool live = i < n;
@@ -478,10 +482,10 @@ __global__ __launch_bounds__(WAVE) void body_rollout_kernel(BodyLaunch a) {
 
 }  // namespace
 
-hipError_t launch_body_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step, float* obs,
-                             hipStream_t stream) {
+hipError_t launch_body_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
+                             const StepCounter* counter, float* obs, hipStream_t stream) {
   hipLaunchKernelGGL(body_reset_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, state, n,
-                     seed, step, obs);
+                     seed, step, counter, obs);
   return hipGetLastError();
 }
 

@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include "stats.hpp"
+#include "step_counter.hpp"
 
 namespace envk {
 
@@ -18,7 +19,8 @@ struct BodyLaunch {
   uint32_t* state;       // SoA [20][n]
   int64_t n;
   uint64_t seed;
-  uint64_t step0;
+  uint64_t step0;        // used when counter == nullptr
+  StepCounter* counter;  // device-resident step counter, or nullptr
   int32_t T;
   int32_t max_episode_steps;
   float armature, joint_damping, friction_mu;
@@ -29,8 +31,8 @@ struct BodyLaunch {
   DeviceStats* stats;
 };
 
-hipError_t launch_body_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step, float* obs,
-                             hipStream_t stream);
+hipError_t launch_body_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
+                             const StepCounter* counter, float* obs, hipStream_t stream);
 hipError_t launch_body_rollout(const BodyLaunch& a, hipStream_t stream);
 
 }  // namespace envk

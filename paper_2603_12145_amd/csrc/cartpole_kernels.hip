@@ -64,11 +64,15 @@ __device__ __forceinline__ bool cart_transition(CartLane& s, int action, int max
   const bool failed = (s.x < -2.4f) | (s.x > 2.4f) | (s.th < -0.20943951f) | (s.th > 0.20943951f);
   const bool ended = failed | (s.ep_len >= max_steps);
   fin_len = s.ep_len;
-  // the reset draw is cheap next to a divergent branch around it: every lane computes it
-  const CartLane fresh = cart_initial(seed, env, step + 1);
-  s.x = ended ? fresh.x : s.x; s.xd = ended ? fresh.xd : s.xd;
-  s.th = ended ? fresh.th : s.th; s.thd = ended ? fresh.thd : s.thd;
-  s.ep_len = ended ? 0 : s.ep_len;
+  // The reset draw is skipped only when no lane of the wavefront needs it (a wave-uniform branch:
+  // under a random policy some lane ends an episode on almost every step, under a good policy
+  // almost none does); within the branch every lane computes it and selects.
+  if (__ballot(ended) != 0ull) {
+    const CartLane fresh = cart_initial(seed, env, step + 1);
+    s.x = ended ? fresh.x : s.x; s.xd = ended ? fresh.xd : s.xd;
+    s.th = ended ? fresh.th : s.th; s.thd = ended ? fresh.thd : s.thd;
+    s.ep_len = ended ? 0 : s.ep_len;
+  }
   return ended;
 }
 
@@ -87,15 +91,19 @@ __device__ __forceinline__ void cart_store(uint32_t* __restrict__ st, int64_t n,
 }
 
 __global__ __launch_bounds__(256) void cartpole_reset_kernel(uint32_t* __restrict__ state, int64_t n,
-                                                             uint64_t seed, uint64_t step, float* __restrict__ obs) {
+                                                             uint64_t seed, uint64_t host_step,
+                                                             const StepCounter* __restrict__ counter,
+                                                             float* __restrict__ obs) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
+  const uint64_t step = read_step(counter, host_step);
   const CartLane s = cart_initial(seed, (uint32_t)i, step);
   cart_store(state, n, i, s);
   if (obs) reinterpret_cast<float4*>(obs)[i] = make_float4(s.x, s.xd, s.th, s.thd);
 }
 
 __global__ __launch_bounds__(256) void cartpole_rollout_kernel(PongLaunch a) {
+  a.step0 = launch_first_step(a.counter, a.step0, a.T);
   const int lane = threadIdx.x & (WAVE - 1);
   const int wave_in_block = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   // XCD-aware mapping as in the Pong rollout: each XCD owns a contiguous eighth of the batch
@@ -140,10 +148,10 @@ __global__ __launch_bounds__(256) void cartpole_rollout_kernel(PongLaunch a) {
 
 }  // namespace
 
-hipError_t launch_cartpole_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step, float* obs,
-                                 hipStream_t stream) {
+hipError_t launch_cartpole_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
+                                 const StepCounter* counter, float* obs, hipStream_t stream) {
   hipLaunchKernelGGL(cartpole_reset_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, state, n,
-                     seed, step, obs);
+                     seed, step, counter, obs);
   return hipGetLastError();
 }
 

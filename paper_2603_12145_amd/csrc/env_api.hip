@@ -32,6 +32,8 @@ struct mi355env {
   uint32_t* state_alloc;  // the allocation made for it by env_create
   int fields;
   DeviceStats* stats;     // device
+  StepCounter* counter;   // device, behind stats in the same allocation
+  bool device_counter;    // launches read and advance `counter` instead of taking `step` as an argument
   PixelPipe pipe;         // pixels only: second state buffer and the staging buffers of the lookahead
   bool was_reset;
   // last device ranges that passed the residency check (avoids a driver query per step)
@@ -57,6 +59,7 @@ env_config_t default_config(int kind) {
   c.joint_damping = BODY_DEFAULT_JOINT_DAMPING;
   c.friction_mu = BODY_DEFAULT_FRICTION_MU;
   c.pixel_layout = ENV_PIXELS_SLOT_MAJOR;
+  c.step_counter = ENV_STEP_COUNTER_HOST;
   (void)kind;
   return c;
 }
@@ -79,6 +82,11 @@ int merge_config(env_config_t* dst, const env_config_t* src) {
     if (src->pixel_layout != ENV_PIXELS_SLOT_MAJOR && src->pixel_layout != ENV_PIXELS_ENV_MAJOR)
       return ENV_E_ARG;
     dst->pixel_layout = src->pixel_layout;
+  }
+  if (sz >= FIELD_END(env_config_t, step_counter) && src->step_counter != 0) {
+    if (src->step_counter != ENV_STEP_COUNTER_HOST && src->step_counter != ENV_STEP_COUNTER_DEVICE)
+      return ENV_E_ARG;
+    dst->step_counter = src->step_counter;
   }
   if (!std::isfinite(dst->armature) || !std::isfinite(dst->joint_damping) ||
       !std::isfinite(dst->friction_mu))
@@ -122,6 +130,15 @@ bool device_range_ok(env_t* e, const void* p, size_t bytes, size_t align) {
   return true;
 }
 
+int read_device_step(const env_t* e, uint64_t* out) {
+  unsigned long long s = 0;
+  if (hipMemcpyAsync(&s, &e->counter->step, sizeof s, hipMemcpyDeviceToHost, e->stream) != hipSuccess ||
+      hipStreamSynchronize(e->stream) != hipSuccess)
+    return ENV_E_HIP;
+  *out = s;
+  return ENV_OK;
+}
+
 size_t obs_bytes_per_env_step(int kind) {
   switch (kind) {
     case ENV_PONG: return PONG_OBS * sizeof(float);
@@ -156,6 +173,7 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
   if (e->kind == ENV_BODY) {
     BodyLaunch b{};
     b.state = e->state; b.n = e->n; b.seed = e->seed; b.step0 = e->step; b.T = T;
+    b.counter = e->device_counter ? e->counter : nullptr;
     b.max_episode_steps = e->cfg.max_episode_steps;
     b.armature = e->cfg.armature; b.joint_damping = e->cfg.joint_damping;
     b.friction_mu = e->cfg.friction_mu;
@@ -165,6 +183,7 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
   } else {
     PongLaunch p{};
     p.state = e->state; p.n = e->n; p.seed = e->seed; p.step0 = e->step; p.T = T;
+    p.counter = e->device_counter ? e->counter : nullptr;
     p.max_score = e->cfg.max_score;
     p.actions = static_cast<const uint8_t*>(actions);
     p.obs = static_cast<float*>(obs); p.reward = reward; p.done = done; p.stats = e->stats;
@@ -204,13 +223,15 @@ int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_c
   if (n_envs <= 0 || n_envs > MAX_ENVS) return ENV_E_ARG;
   env_config_t c = default_config(kind);
   if (merge_config(&c, cfg) != ENV_OK) return ENV_E_ARG;
+  if (c.step_counter == ENV_STEP_COUNTER_DEVICE && kind == ENV_PONG_PIXELS) return ENV_E_UNSUPPORTED;
 
   env_t* e = new (std::nothrow) env_t();
   if (!e) return ENV_E_ALLOC;
   e->kind = kind; e->n = n_envs; e->seed = seed; e->step = 0;
   e->stream = static_cast<hipStream_t>(hip_stream);
   e->cfg = c; e->fields = fields_of(kind); e->was_reset = false;
-  e->state = nullptr; e->stats = nullptr; e->seen_next = 0;
+  e->state = nullptr; e->stats = nullptr; e->counter = nullptr; e->seen_next = 0;
+  e->device_counter = c.step_counter == ENV_STEP_COUNTER_DEVICE;
   for (auto& r : e->seen) r = {nullptr, 0};
   if (hipGetDevice(&e->device) != hipSuccess) { delete e; return ENV_E_HIP; }
 
@@ -219,15 +240,18 @@ int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_c
     (void)hipGetLastError(); delete e; return ENV_E_ALLOC;
   }
   e->state_alloc = e->state;
-  if (hipMalloc(reinterpret_cast<void**>(&e->stats), sizeof(DeviceStats)) != hipSuccess) {
+  static_assert(sizeof(DeviceStats) % 8 == 0, "the step counter behind the statistics must be 8-byte aligned");
+  if (hipMalloc(reinterpret_cast<void**>(&e->stats), sizeof(DeviceStats) + sizeof(StepCounter)) != hipSuccess) {
     (void)hipGetLastError(); (void)hipFree(e->state); delete e; return ENV_E_ALLOC;
   }
   if (kind == ENV_PONG_PIXELS && pixel_pipe_create(e->pipe, n_envs) != hipSuccess) {
     (void)hipGetLastError(); (void)hipFree(e->state); (void)hipFree(e->stats); delete e;
     return ENV_E_ALLOC;
   }
+  e->counter = reinterpret_cast<StepCounter*>(e->stats + 1);
   const DeviceStats z = empty_stats();
   if (hipMemsetAsync(e->state, 0, state_bytes, e->stream) != hipSuccess ||
+      hipMemsetAsync(e->counter, 0, sizeof(StepCounter), e->stream) != hipSuccess ||
       hipMemcpyAsync(e->stats, &z, sizeof z, hipMemcpyHostToDevice, e->stream) != hipSuccess ||
       hipStreamSynchronize(e->stream) != hipSuccess) {
     (void)hipGetLastError(); (void)hipFree(e->state); (void)hipFree(e->stats);
@@ -250,6 +274,7 @@ void env_destroy(env_t* e) {
 int env_reset(env_t* e, void* obs_dev) {
   if (!e) return ENV_E_ARG;
   hipError_t err;
+  const StepCounter* counter = e->device_counter ? e->counter : nullptr;
   if (e->kind == ENV_PONG_PIXELS && obs_dev) {
     if (!device_range_ok(e, obs_dev, (size_t)e->n * 4 * FRAME_BYTES, 16)) return ENV_E_ARG;
     err = launch_pixel_reset(e->state, e->n, e->seed, e->step, static_cast<uint8_t*>(obs_dev),
@@ -258,15 +283,16 @@ int env_reset(env_t* e, void* obs_dev) {
   } else if (e->kind == ENV_BODY) {
     if (obs_dev && !device_range_ok(e, obs_dev, (size_t)e->n * BODY_OBS * sizeof(float), 4))
       return ENV_E_ARG;
-    err = launch_body_reset(e->state, e->n, e->seed, e->step, static_cast<float*>(obs_dev), e->stream);
+    err = launch_body_reset(e->state, e->n, e->seed, e->step, counter, static_cast<float*>(obs_dev), e->stream);
   } else if (e->kind == ENV_CARTPOLE) {
     if (obs_dev && !device_range_ok(e, obs_dev, (size_t)e->n * CARTPOLE_OBS * sizeof(float), 16))
       return ENV_E_ARG;
-    err = launch_cartpole_reset(e->state, e->n, e->seed, e->step, static_cast<float*>(obs_dev), e->stream);
+    err = launch_cartpole_reset(e->state, e->n, e->seed, e->step, counter, static_cast<float*>(obs_dev),
+                                e->stream);
   } else {
     if (obs_dev && !device_range_ok(e, obs_dev, (size_t)e->n * PONG_OBS * sizeof(float), 16))
       return ENV_E_ARG;
-    err = launch_pong_reset(e->state, e->n, e->seed, e->step,
+    err = launch_pong_reset(e->state, e->n, e->seed, e->step, counter,
                             e->kind == ENV_PONG ? static_cast<float*>(obs_dev) : nullptr, e->stream);
     if (e->kind == ENV_PONG_PIXELS) pixel_pipe_invalidate(e->pipe);
   }
@@ -319,6 +345,11 @@ size_t env_state_bytes(const env_t* e) {
 int env_get_state(env_t* e, void* host_buf, size_t bytes) {
   if (!e || !host_buf || bytes != env_state_bytes(e)) return ENV_E_ARG;
   std::memcpy(host_buf, &e->step, 8);
+  if (e->device_counter) {
+    uint64_t s = 0;
+    if (read_device_step(e, &s) != ENV_OK) return ENV_E_HIP;
+    std::memcpy(host_buf, &s, 8);
+  }
   if (hipMemcpyAsync(static_cast<char*>(host_buf) + 8, e->state, bytes - 8, hipMemcpyDeviceToHost,
                      e->stream) != hipSuccess ||
       hipStreamSynchronize(e->stream) != hipSuccess)
@@ -333,6 +364,12 @@ int env_set_state(env_t* e, const void* host_buf, size_t bytes) {
       hipStreamSynchronize(e->stream) != hipSuccess)
     return ENV_E_HIP;
   std::memcpy(&e->step, host_buf, 8);
+  if (e->device_counter) {
+    const StepCounter c = {e->step, 0u, 0u};
+    if (hipMemcpyAsync(e->counter, &c, sizeof c, hipMemcpyHostToDevice, e->stream) != hipSuccess ||
+        hipStreamSynchronize(e->stream) != hipSuccess)
+      return ENV_E_HIP;
+  }
   e->was_reset = true;
   if (e->kind == ENV_PONG_PIXELS) pixel_pipe_invalidate(e->pipe);
   return ENV_OK;
@@ -357,7 +394,18 @@ int env_action_dim(int kind) {
 }
 
 int64_t env_num_envs(const env_t* e) { return e ? e->n : 0; }
-uint64_t env_step_count(const env_t* e) { return e ? e->step : 0; }
+uint64_t env_step_count(const env_t* e) {
+  if (!e) return 0;
+  if (!e->device_counter) return e->step;
+  uint64_t s = 0;
+  return read_device_step(e, &s) == ENV_OK ? s : UINT64_MAX;
+}
+
+int env_set_stream(env_t* e, void* hip_stream) {
+  if (!e) return ENV_E_ARG;
+  e->stream = static_cast<hipStream_t>(hip_stream);
+  return ENV_OK;
+}
 
 const char* env_strerror(int code) {
   switch (code) {

@@ -5,6 +5,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include "stats.hpp"
+#include "step_counter.hpp"
 
 namespace envk {
 
@@ -15,7 +16,8 @@ struct PongLaunch {
   uint32_t* state;        // SoA [10][n]
   int64_t n;
   uint64_t seed;
-  uint64_t step0;         // index of the first step of this launch
+  uint64_t step0;         // index of the first step of this launch (used when counter == nullptr)
+  StepCounter* counter;   // device-resident step counter, or nullptr
   int32_t T;
   int32_t max_score;
   const uint8_t* actions; // [T,n] or nullptr
@@ -25,15 +27,16 @@ struct PongLaunch {
   DeviceStats* stats;
 };
 
-hipError_t launch_pong_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step, float* obs,
-                             hipStream_t stream);
+// reset launchers: counter != nullptr -> the step is read from it instead of `step`
+hipError_t launch_pong_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
+                             const StepCounter* counter, float* obs, hipStream_t stream);
 hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream);
 
 // CartPole: same launch descriptor (max_score carries max_episode_steps; obs is [T,n,4]).
 constexpr int CARTPOLE_FIELDS = 6;   // x xdot theta thetadot | ep_ret ep_len
 constexpr int CARTPOLE_OBS = 4;
-hipError_t launch_cartpole_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step, float* obs,
-                                 hipStream_t stream);
+hipError_t launch_cartpole_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
+                                 const StepCounter* counter, float* obs, hipStream_t stream);
 hipError_t launch_cartpole_rollout(const PongLaunch& a, hipStream_t stream);
 
 // Pixel observations.  ring != nullptr: frame after step s goes to ring[i][s & 3] (T must be 1 or

@@ -17,10 +17,12 @@ constexpr int WAVE = 64;
 constexpr int ROLLOUT_BLOCK = 256;   // default threads per workgroup of the rollout kernel
 
 __global__ __launch_bounds__(256) void pong_reset_kernel(uint32_t* __restrict__ state, int64_t n,
-                                                         uint64_t seed, uint64_t step,
+                                                         uint64_t seed, uint64_t host_step,
+                                                         const StepCounter* __restrict__ counter,
                                                          float* __restrict__ obs) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
+  const uint64_t step = read_step(counter, host_step);
   const PongLane s = pong_initial(seed, (uint32_t)i, step);
   pong_store(state, n, i, s);
   if (obs) {
@@ -82,6 +84,7 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
 
 template <bool XCD_REMAP>
 __global__ __launch_bounds__(256) void pong_rollout_kernel(PongLaunch a) {
+  a.step0 = launch_first_step(a.counter, a.step0, a.T);
   const int lane = threadIdx.x & (WAVE - 1);
   // wave-uniform by construction; readfirstlane tells the compiler so (scalar address math)
   const int wave_in_block = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -116,10 +119,11 @@ int g_xcd_remap = 1;
 
 }  // namespace
 
-hipError_t launch_pong_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step, float* obs,
-                             hipStream_t stream) {
+hipError_t launch_pong_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
+                             const StepCounter* counter, float* obs, hipStream_t stream) {
   const unsigned blocks = (unsigned)((n + 255) / 256);
-  hipLaunchKernelGGL(pong_reset_kernel, dim3(blocks), dim3(256), 0, stream, state, n, seed, step, obs);
+  hipLaunchKernelGGL(pong_reset_kernel, dim3(blocks), dim3(256), 0, stream, state, n, seed, step, counter,
+                     obs);
   return hipGetLastError();
 }
 

@@ -1,0 +1,49 @@
+// Step counter kept in device memory, for launches that are recorded once in a HIP graph and
+// replayed: a kernel argument is frozen at capture time, so the index of the launch's first step
+// (which keys every Philox draw) is read from memory instead, and the launch advances it itself.
+//
+// Protocol, per launch: thread 0 of every workgroup reads the counter, then takes a ticket; the
+// workgroup that takes the last ticket knows every other workgroup has already read, so it alone
+// writes counter + T and clears the tickets.  The next launch on the stream starts after this one
+// has drained, so it reads the advanced value.  Two launches that use one counter must not overlap.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace envk {
+
+struct StepCounter {
+  unsigned long long step;
+  unsigned int ticket;
+  unsigned int pad;
+};
+
+// Must be called by every thread of every workgroup of a one-dimensional launch, before any early
+// exit.  counter == nullptr: the host passed the step as a kernel argument; nothing is touched.
+// The result is wave-uniform (kept in scalar registers).
+__device__ __forceinline__ uint64_t launch_first_step(StepCounter* counter, uint64_t host_step0, int32_t T) {
+  if (!counter) return host_step0;
+  __shared__ unsigned long long shared_step;
+  if (threadIdx.x == 0) {
+    const unsigned long long s = __hip_atomic_load(&counter->step, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+    shared_step = s;
+    const unsigned int t =
+        __hip_atomic_fetch_add(&counter->ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    if (t == gridDim.x - 1u) {
+      __hip_atomic_store(&counter->ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&counter->step, s + (unsigned long long)T, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+  __syncthreads();
+  const unsigned long long s = shared_step;
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)s);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(s >> 32));
+  return ((uint64_t)hi << 32) | lo;
+}
+
+// For kernels that only read the counter (reset): no ticket, no write.
+__device__ __forceinline__ uint64_t read_step(const StepCounter* counter, uint64_t host_step) {
+  return counter ? __hip_atomic_load(&counter->step, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : host_step;
+}
+
+}  // namespace envk

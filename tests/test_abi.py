@@ -57,6 +57,12 @@ def test_argument_errors_without_gpu(L):
     assert L.env_create(C.byref(h), 0, 64, 0, C.byref(bad), None) == b.ENV_E_ARG
     assert h.value is None
     assert L.env_reset(None, None) == b.ENV_E_ARG
+    assert L.env_set_stream(None, None) == b.ENV_E_ARG
+    odd = b.env_config_t(struct_size=C.sizeof(b.env_config_t), step_counter=7)
+    assert L.env_create(C.byref(h), 0, 64, 0, C.byref(odd), None) == b.ENV_E_ARG
+    dev = b.env_config_t(struct_size=C.sizeof(b.env_config_t), armature=-1, joint_damping=-1,
+                         friction_mu=-1, step_counter=b.ENV_STEP_COUNTER_DEVICE)
+    assert L.env_create(C.byref(h), b.ENV_PONG_PIXELS, 64, 0, C.byref(dev), None) == b.ENV_E_UNSUPPORTED
     assert L.env_step(None, None, None, None, None) == b.ENV_E_ARG
     assert L.env_rollout(None, 5, None, None, None, None) == b.ENV_E_ARG
     assert L.env_stats(None, None, 0) == b.ENV_E_ARG
@@ -68,7 +74,7 @@ def test_argument_errors_without_gpu(L):
 
 def test_binding_struct_layout_matches_header():
     from paper_2603_12145_amd import binding as b
-    assert C.sizeof(b.env_config_t) == 28
+    assert C.sizeof(b.env_config_t) == 32
     assert C.sizeof(b.env_stats_t) == 48
     hdr = open(HEADER).read()
     cfg = re.search(r"typedef struct env_config_t \{(.*?)\} env_config_t;", hdr, re.S).group(1)

@@ -1,0 +1,202 @@
+"""GPU: device-resident step counter and HIP-graph replay of env_step (policy-in-the-loop rollout).
+
+A launch recorded in a graph has frozen kernel arguments, so the handle created with
+step_counter = ENV_STEP_COUNTER_DEVICE keeps the step index in device memory.  Checked here:
+direct calls in that mode match the oracle bit for bit; a captured {policy, env_step} graph replayed
+K times matches K direct calls, replay by replay, and (through the recorded actions) the oracle."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+from oracle import oracle as orc                      # noqa: E402
+from oracle.cartpole_binding import CartPole          # noqa: E402
+from oracle.body_binding import Body                  # noqa: E402
+from paper_2603_12145_amd import binding as b         # noqa: E402
+from gpu_helpers import assert_bit_equal              # noqa: E402
+
+DEV = "cuda:0"
+DEVICE_COUNTER = {"step_counter": b.ENV_STEP_COUNTER_DEVICE}
+
+
+def _bufs(kind, n, T=None):
+    d = b.env_obs_dim(kind)
+    lead = (n,) if T is None else (T, n)
+    return (torch.empty(lead + (d,), dtype=torch.float32, device=DEV),
+            torch.empty(lead, dtype=torch.float32, device=DEV),
+            torch.empty(lead, dtype=torch.uint8, device=DEV))
+
+
+@pytest.mark.parametrize("n", [64, 300, 5000])
+def test_device_counter_direct_calls_match_oracle(n):
+    h = b.env_create(b.ENV_PONG, n, 5, dict(DEVICE_COUNTER, max_score=2))
+    try:
+        o0 = torch.empty((n, 8), dtype=torch.float32, device=DEV)
+        b.env_reset(h, o0)
+        T = 260
+        obs, rew, done = _bufs(b.ENV_PONG, n, T)
+        t = 0
+        for c in (1, 1, 58, 100, 1, 99):        # steps and rollouts mixed
+            b.env_rollout(h, c, None, obs[t:t + c], rew[t:t + c], done[t:t + c])
+            t += c
+        assert b.env_step_count(h) == T
+        # a reset in the middle keys its draws with the device counter
+        o1 = torch.empty((n, 8), dtype=torch.float32, device=DEV)
+        b.env_reset(h, o1)
+        obs2, rew2, done2 = _bufs(b.ENV_PONG, n, 40)
+        b.env_rollout(h, 40, None, obs2, rew2, done2)
+        torch.cuda.synchronize()
+        blob = b.env_get_state(h)
+        assert int(np.frombuffer(blob[:8].tobytes(), np.uint64)[0]) == T + 40
+    finally:
+        b.env_destroy(h)
+    p = orc.Pong(n, 5, max_score=2)
+    assert_bit_equal(o0.cpu().numpy(), p.reset(), "reset obs")
+    oo, orr, od = p.rollout(T)
+    assert_bit_equal(obs.cpu().numpy(), oo, "obs")
+    assert_bit_equal(rew.cpu().numpy(), orr, "reward")
+    assert_bit_equal(done.cpu().numpy(), od, "done")
+    assert_bit_equal(o1.cpu().numpy(), p.reset(), "second reset obs")
+    oo, orr, od = p.rollout(40)
+    assert_bit_equal(obs2.cpu().numpy(), oo, "obs after second reset")
+    assert_bit_equal(done2.cpu().numpy(), od, "done after second reset")
+
+
+def test_device_counter_set_state_moves_the_counter():
+    n = 200
+    h = b.env_create(b.ENV_CARTPOLE, n, 8, DEVICE_COUNTER)
+    g = b.env_create(b.ENV_CARTPOLE, n, 8)
+    try:
+        b.env_reset(g)
+        a = _bufs(b.ENV_CARTPOLE, n, 30)
+        b.env_rollout(g, 30, None, *a)
+        b.env_set_state(h, b.env_get_state(g))
+        assert b.env_step_count(h) == 30
+        x, y = _bufs(b.ENV_CARTPOLE, n, 50), _bufs(b.ENV_CARTPOLE, n, 50)
+        b.env_rollout(g, 50, None, *x)
+        b.env_rollout(h, 50, None, *y)
+        torch.cuda.synchronize()
+        for u, v in zip(x, y):
+            assert torch.equal(u, v)
+        assert np.array_equal(b.env_get_state(g), b.env_get_state(h))
+    finally:
+        b.env_destroy(h); b.env_destroy(g)
+
+
+def _pong_policy(obs, act):
+    """Chase the ball: 1 = up when the ball centre is above the paddle centre, 2 = down."""
+    up = (obs[:, 1] + 1.0) < (obs[:, 4] + 8.0)
+    act.copy_(torch.where(up, 1, 2).to(torch.uint8))
+
+
+def _cartpole_policy(obs, act):
+    act.copy_(((obs[:, 2] + 0.5 * obs[:, 3]) > 0).to(torch.uint8))
+
+
+def _body_policy_factory(seed):
+    gen = torch.Generator(device="cpu").manual_seed(seed)
+    W = (0.3 * torch.randn((17, 6), generator=gen)).to(DEV)
+
+    def policy(obs, act):
+        act.copy_(torch.tanh(obs @ W))
+    return policy
+
+
+def _run_graph_vs_direct(kind, n, seed, cfg, policy, K, act_shape, act_dtype):
+    """Returns per-step (actions, obs, reward, done) of the graph-replayed run after checking them
+    against K direct policy+step calls on a second handle."""
+    s = torch.cuda.Stream()
+    outs = {}
+    for mode in ("direct", "graph"):
+        c = dict(cfg)
+        if mode == "graph":
+            c.update(DEVICE_COUNTER)
+        h = b.env_create(kind, n, seed, c, stream=s)
+        try:
+            with torch.cuda.stream(s):
+                obs, rew, done = _bufs(kind, n)
+                act = torch.zeros(act_shape, dtype=act_dtype, device=DEV)
+                b.env_reset(h, obs)
+
+                def one_step():
+                    policy(obs, act)
+                    b.env_step(h, act, obs, rew, done)
+
+                rec = []
+
+                def record():
+                    s.synchronize()
+                    rec.append((act.cpu().numpy().copy(), obs.cpu().numpy().copy(),
+                                rew.cpu().numpy().copy(), done.cpu().numpy().copy()))
+
+                warm = 3                       # direct calls first: they also validate the buffers
+                for _ in range(warm):
+                    one_step(); record()
+                if mode == "direct":
+                    for _ in range(K):
+                        one_step(); record()
+                else:
+                    s.synchronize()
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g, stream=s):
+                        one_step()
+                    # the capture itself ran nothing: the counter still says `warm`
+                    assert b.env_step_count(h) == warm
+                    for k in range(K):
+                        g.replay()
+                        record()
+                        if k % 7 == 3:         # direct work of the program between replays
+                            (obs.sum() + rew.sum()).item()
+                    assert b.env_step_count(h) == warm + K
+                    # direct calls continue where the replays stopped
+                    one_step(); record()
+                    assert b.env_step_count(h) == warm + K + 1
+                stats = b.env_stats(h)
+        finally:
+            b.env_destroy(h)
+        outs[mode] = (rec, stats)
+    d, g = outs["direct"][0], outs["graph"][0]
+    for k in range(len(d)):
+        for name, x, y in zip(("action", "obs", "reward", "done"), d[k], g[k]):
+            assert_bit_equal(y, x, "step %d %s (graph vs direct)" % (k, name))
+    return g, outs["graph"][1]
+
+
+def test_graph_replay_pong_policy_in_the_loop():
+    n, K = 1000, 60
+    rec, stats = _run_graph_vs_direct(b.ENV_PONG, n, 12, {"max_score": 1}, _pong_policy, K, (n,), torch.uint8)
+    T = len(rec)
+    acts = np.stack([r[0] for r in rec])
+    p = orc.Pong(n, 12, max_score=1)
+    p.reset()
+    oo, orr, od = p.rollout(T, actions=acts)
+    assert_bit_equal(np.stack([r[1] for r in rec]), oo, "obs vs oracle")
+    assert_bit_equal(np.stack([r[2] for r in rec]), orr, "reward vs oracle")
+    assert_bit_equal(np.stack([r[3] for r in rec]), od, "done vs oracle")
+    assert stats["episodes"] == p.stats()["episodes"]
+
+
+def test_graph_replay_cartpole_policy_in_the_loop():
+    n, K = 777, 80
+    rec, stats = _run_graph_vs_direct(b.ENV_CARTPOLE, n, 13, {"max_episode_steps": 40}, _cartpole_policy, K,
+                                      (n,), torch.uint8)
+    T = len(rec)
+    acts = np.stack([r[0] for r in rec])
+    p = CartPole(n, 13, max_steps=40)
+    p.reset()
+    oo, _, od = p.rollout(T, actions=acts)
+    assert_bit_equal(np.stack([r[1] for r in rec]), oo, "obs vs oracle")
+    assert_bit_equal(np.stack([r[3] for r in rec]), od, "done vs oracle")
+    assert od.sum() >= 2 * n and stats["episodes"] == int(od.sum())
+
+
+def test_graph_replay_body_policy_in_the_loop():
+    n, K = 256, 30
+    rec, _ = _run_graph_vs_direct(b.ENV_BODY, n, 14, {}, _body_policy_factory(3), K, (n, 6), torch.float32)
+    # single steps against the float64 oracle from the GPU's own pre-step states are covered by the
+    # body parity tests; here the recorded trajectory must be finite and the policy must have acted
+    obs = np.stack([r[1] for r in rec])
+    acts = np.stack([r[0] for r in rec])
+    assert np.isfinite(obs).all() and np.abs(acts).max() > 0.05
+    assert np.abs(obs[-1] - obs[0]).max() > 1e-3
