@@ -115,7 +115,35 @@ def bench_pong_per_step(b, torch, n, seed, launches):
         L.mi355env_bench_empty(s)
     torch.cuda.synchronize()
     empty = time.perf_counter() - t0
+    # the same launches recorded once in a HIP graph (device-resident step counter) and replayed
+    per_graph = 100
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        hg = b.env_create(b.ENV_PONG, n, seed, {"step_counter": b.ENV_STEP_COUNTER_DEVICE}, stream=st)
+        b.env_reset(hg, None)
+        b.env_step(hg, None, obs, rew, done)
+        st.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=st):
+            for _ in range(per_graph):
+                b.env_step(hg, None, obs, rew, done)
+        for _ in range(3):
+            g.replay()
+        st.synchronize()
+        reps = max(1, launches // per_graph)
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            g.replay()
+        st.synchronize()
+        graph_wall = time.perf_counter() - t0
+        graph_steps = b.env_step_count(hg)
+        del g
+        b.env_destroy(hg)
+    assert graph_steps == 1 + per_graph * (3 + reps), graph_steps   # the capture itself runs nothing
+    graph_us = 1e6 * graph_wall / (reps * per_graph)
     return dict(workload="pong vector obs N=%d, one env_step launch per step" % n,
+                graph_replay_us_per_launch=graph_us, graph_env_steps_per_s=n / (graph_us * 1e-6),
+                graph_launches_per_graph=per_graph,
                 us_per_launch=1e6 * wall / launches, env_steps_per_s=n * launches / wall,
                 bound="dispatch latency", launches=launches,
                 empty_kernel_us_per_launch=1e6 * empty / launches, ratio_to_empty_launch=wall / empty,
@@ -227,6 +255,77 @@ def bench_cartpole(b, torch, n, T, seed, steps):
                               frac=gbs / HBM_PEAK_GBS, traffic=None))
 
 
+def bench_policy_loop(b, torch, n, policy_kind, steps, steps_per_graph):
+    """Policy-in-the-loop rollout: a PyTorch policy reads obs and writes actions, env_step consumes
+    them, all on one stream; timed as direct calls and as a replayed HIP graph (device step counter)."""
+    dev = "cuda:0"
+    torch.manual_seed(0)
+    if policy_kind == "mlp":
+        net = torch.nn.Sequential(torch.nn.Linear(8, 64), torch.nn.Tanh(), torch.nn.Linear(64, 64),
+                                  torch.nn.Tanh(), torch.nn.Linear(64, 3)).to(dev)
+        hidden = None
+    else:   # GRU cell with ~2M parameters, bf16 weights
+        net = torch.nn.GRUCell(8, 800).to(dev).to(torch.bfloat16)
+        head = torch.nn.Linear(800, 3).to(dev).to(torch.bfloat16)
+        hidden = torch.zeros((n, 800), dtype=torch.bfloat16, device=dev)
+    params = sum(p.numel() for p in net.parameters())
+    s = torch.cuda.Stream()
+    out = {}
+    with torch.no_grad(), torch.cuda.stream(s):
+        for mode in ("direct", "graph"):
+            cfg = {"step_counter": b.ENV_STEP_COUNTER_DEVICE} if mode == "graph" else None
+            h = b.env_create(b.ENV_PONG, n, 1, cfg, stream=s)
+            obs = torch.empty((n, 8), dtype=torch.float32, device=dev)
+            rew = torch.empty(n, dtype=torch.float32, device=dev)
+            done = torch.empty(n, dtype=torch.uint8, device=dev)
+            act = torch.zeros(n, dtype=torch.uint8, device=dev)
+            b.env_reset(h, obs)
+            if hidden is not None:
+                hidden.zero_()
+
+            def one_step():
+                if hidden is None:
+                    logits = net(obs)
+                else:
+                    hidden.copy_(net(obs.to(torch.bfloat16), hidden))
+                    logits = head(hidden)
+                act.copy_(logits.argmax(dim=1).to(torch.uint8))
+                b.env_step(h, act, obs, rew, done)
+
+            for _ in range(20):
+                one_step()
+            s.synchronize()
+            if mode == "direct":
+                t0 = time.perf_counter()
+                for _ in range(steps):
+                    one_step()
+                s.synchronize()
+                wall = time.perf_counter() - t0
+                done_steps = steps
+            else:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=s):
+                    for _ in range(steps_per_graph):
+                        one_step()
+                for _ in range(3):
+                    g.replay()
+                s.synchronize()
+                reps = max(1, steps // steps_per_graph)
+                t0 = time.perf_counter()
+                for _ in range(reps):
+                    g.replay()
+                s.synchronize()
+                wall = time.perf_counter() - t0
+                done_steps = reps * steps_per_graph
+                del g
+            out[mode] = dict(us_per_step=1e6 * wall / done_steps, env_steps_per_s=n * done_steps / wall)
+            b.env_destroy(h)
+    return dict(workload="Pong N=%d, %s policy (%d parameters) -> argmax -> env_step, one stream"
+                         % (n, policy_kind, params),
+                steps_per_graph=steps_per_graph, direct=out["direct"], graph=out["graph"],
+                speedup_from_graph=out["direct"]["us_per_step"] / out["graph"]["us_per_step"])
+
+
 def cpu_baseline(n, T, seed):
     """The oracle as it stands, one pass over the headline workload, all host threads allotted."""
     import numpy as np
@@ -284,6 +383,9 @@ def main():
         fn = {"pixels": lambda: bench_pixels(b, torch, 16384, 3, args.steps),
               "per_step": lambda: bench_pong_per_step(b, torch, 4096, 1, args.steps),
               "body": lambda: bench_body(b, torch, 8192, 1000, 4, args.steps),
+              "policy": lambda: [bench_policy_loop(b, torch, 4096, "mlp", 2000, 50),
+                                 bench_policy_loop(b, torch, 65536, "mlp", 2000, 50),
+                                 bench_policy_loop(b, torch, 4096, "gru", 1000, 50)],
               "cartpole": lambda: bench_cartpole(b, torch, 65536, 1000, 2, args.steps),
               "fill": lambda: bench_fill(b, torch, 1 << 30, args.steps),
               "copy": lambda: bench_copy(b, torch, 1 << 30, args.steps)}[args.only]
@@ -330,6 +432,8 @@ def main():
         extra["config4_body"] = bench_body(b, torch, 8192, 1000, 4, 2)
         extra["config4_body_n262144_t100"] = bench_body(b, torch, 262144, 100, 4, 2)
         extra["cartpole_n65536_t1000"] = bench_cartpole(b, torch, 65536, 1000, 2, 5)
+        extra["policy_in_loop_mlp_n4096"] = bench_policy_loop(b, torch, 4096, "mlp", 2000, 50)
+        extra["policy_in_loop_gru2m_n4096"] = bench_policy_loop(b, torch, 4096, "gru", 1000, 50)
         line["extra"] = extra
     print(json.dumps(line))
 
