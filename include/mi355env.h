@@ -65,7 +65,15 @@ typedef struct env_config_t {
   float friction_mu;          /* body: Coulomb friction coefficient; <0 = default                 */
   int32_t pixel_layout;       /* pixels: ENV_PIXELS_* below; 0 = default (slot-major)             */
   int32_t step_counter;       /* ENV_STEP_COUNTER_* below; 0 = default (host)                     */
+  int32_t obs_scaling;        /* ENV_OBS_* below; 0 = default (raw)                               */
 } env_config_t;
+
+/* ENV_PONG only (other kinds: ENV_E_UNSUPPORTED).  ENV_OBS_NORMALIZED scales every observation
+ * component inside the step kernel (paper App. B.1 item 8) by one float32 multiplication with the
+ * reciprocal of its range: ball x * (1/158), ball y * (1/208), vx * (1/3), vy * (1/2),
+ * both paddle y * (1/194), both scores * (1/max_score) - positions and scores in [0,1],
+ * velocities in [-1,1].  Dynamics, rewards, done flags and the state blob are unchanged. */
+enum { ENV_OBS_RAW = 1, ENV_OBS_NORMALIZED = 2 };
 
 /* Where the handle's step counter (which keys every random draw) lives.
  *   host    the library passes it to each launch as a kernel argument (default, cheapest);

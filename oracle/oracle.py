@@ -63,6 +63,7 @@ def lib():
         L.oracle_pong_envs.argtypes = [C.c_void_p]; L.oracle_pong_envs.restype = C.c_void_p
         L.oracle_pong_step_count.argtypes = [C.c_void_p]; L.oracle_pong_step_count.restype = C.c_uint64
         L.oracle_pong_set_step_count.argtypes = [C.c_void_p, C.c_uint64]
+        L.oracle_pong_set_normalize.argtypes = [C.c_void_p, C.c_int32]
         L.oracle_pong_get_stats.argtypes = [C.c_void_p, C.POINTER(PongStats), C.c_int32]
         L.oracle_pong_reset.argtypes = [C.c_void_p, C.c_void_p]
         L.oracle_pong_rollout.argtypes = [C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -121,9 +122,10 @@ def pong_render_one(state):
 class Pong:
     """Batch of N oracle Pong environments (host memory)."""
 
-    def __init__(self, n, seed, max_score=21):
+    def __init__(self, n, seed, max_score=21, normalize=False):
         self.n, self.seed, self.max_score = int(n), int(seed), int(max_score)
         self.h = lib().oracle_pong_create(self.n, self.seed, self.max_score)
+        lib().oracle_pong_set_normalize(self.h, int(bool(normalize)))
 
     def __del__(self):
         if getattr(self, "h", None):

@@ -63,6 +63,7 @@ struct oracle_pong {
   uint64_t seed;
   uint64_t step;
   int32_t max_score;
+  int32_t normalize;   // 1: observations are scaled at the source (paper App. B.1 item 8)
   oracle_pong_env* env;
   oracle_pong_stats stats;
 };
@@ -155,6 +156,24 @@ void oracle_pong_obs_one(const oracle_pong_env* e, float obs[8]) {
   obs[4] = e->pa; obs[5] = e->po; obs[6] = (float)e->sa; obs[7] = (float)e->so;
 }
 
+// Observation normalised at the source (paper App. B.1 item 8: constant denominators computed
+// once, the scaling done inside the step).  Each component is one float32 multiplication by the
+// float32 reciprocal of its range: ball x / 158, ball y / 208 and paddle y / 194 land in [0, 1],
+// vx / 3 is +-1, vy / 2 lies in [-1, 1] (serves are within +-2, paddle spin within +-1.8), the
+// scores are divided by max_score.
+void oracle_pong_obs_one_normalized(const oracle_pong_env* e, int32_t max_score, float obs[8]) {
+  const float inv_score = 1.0f / (float)max_score;
+  obs[0] = e->bx * (1.0f / 158.0f); obs[1] = e->by * (1.0f / 208.0f);
+  obs[2] = e->vx * (1.0f / 3.0f); obs[3] = e->vy * 0.5f;
+  obs[4] = e->pa * (1.0f / 194.0f); obs[5] = e->po * (1.0f / 194.0f);
+  obs[6] = (float)e->sa * inv_score; obs[7] = (float)e->so * inv_score;
+}
+
+static void write_obs(const oracle_pong* h, const oracle_pong_env* e, float* obs) {
+  if (h->normalize) oracle_pong_obs_one_normalized(e, h->max_score, obs);
+  else oracle_pong_obs_one(e, obs);
+}
+
 // Initial state of an episode started by env_reset: draws come from reset stream 16.
 void oracle_pong_reset_one(oracle_pong_env* e, uint64_t seed, uint32_t env, uint64_t step) {
   uint32_t w[4];
@@ -203,6 +222,7 @@ void oracle_pong_destroy(oracle_pong* h) { if (h) { free(h->env); free(h); } }
 oracle_pong_env* oracle_pong_envs(oracle_pong* h) { return h->env; }
 uint64_t oracle_pong_step_count(const oracle_pong* h) { return h->step; }
 void oracle_pong_set_step_count(oracle_pong* h, uint64_t step) { h->step = step; }
+void oracle_pong_set_normalize(oracle_pong* h, int32_t on) { h->normalize = on ? 1 : 0; }
 
 void oracle_pong_get_stats(oracle_pong* h, oracle_pong_stats* out, int32_t clear) {
   *out = h->stats;
@@ -213,7 +233,7 @@ void oracle_pong_get_stats(oracle_pong* h, oracle_pong_stats* out, int32_t clear
 void oracle_pong_reset(oracle_pong* h, float* obs) {
   for (int64_t i = 0; i < h->n; ++i) {
     oracle_pong_reset_one(&h->env[i], h->seed, (uint32_t)i, h->step);
-    if (obs) oracle_pong_obs_one(&h->env[i], obs + 8 * i);
+    if (obs) write_obs(h, &h->env[i], obs + 8 * i);
   }
 }
 
@@ -234,7 +254,7 @@ static void run_range(oracle_pong* h, int64_t lo, int64_t hi, int32_t T, const u
       const float r = oracle_pong_step_one(&h->env[i], a, oracle_pong_serve_vx(w[1]),
                                            oracle_pong_serve_vy(w[2]), h->max_score, &dn, &fr, &fl);
       if (dn) stats_add_episode(st, fr, fl);
-      if (obs) oracle_pong_obs_one(&h->env[i], obs + ((int64_t)t * n + i) * 8);
+      if (obs) write_obs(h, &h->env[i], obs + ((int64_t)t * n + i) * 8);
       if (reward) reward[(int64_t)t * n + i] = r;
       if (done) done[(int64_t)t * n + i] = dn;
       if (stack) oracle_pong_render_one(&h->env[i], stack + ((size_t)i * 4 + (size_t)(s & 3)) * FRAME * FRAME);

@@ -60,6 +60,7 @@ env_config_t default_config(int kind) {
   c.friction_mu = BODY_DEFAULT_FRICTION_MU;
   c.pixel_layout = ENV_PIXELS_SLOT_MAJOR;
   c.step_counter = ENV_STEP_COUNTER_HOST;
+  c.obs_scaling = ENV_OBS_RAW;
   (void)kind;
   return c;
 }
@@ -87,6 +88,10 @@ int merge_config(env_config_t* dst, const env_config_t* src) {
     if (src->step_counter != ENV_STEP_COUNTER_HOST && src->step_counter != ENV_STEP_COUNTER_DEVICE)
       return ENV_E_ARG;
     dst->step_counter = src->step_counter;
+  }
+  if (sz >= FIELD_END(env_config_t, obs_scaling) && src->obs_scaling != 0) {
+    if (src->obs_scaling != ENV_OBS_RAW && src->obs_scaling != ENV_OBS_NORMALIZED) return ENV_E_ARG;
+    dst->obs_scaling = src->obs_scaling;
   }
   if (!std::isfinite(dst->armature) || !std::isfinite(dst->joint_damping) ||
       !std::isfinite(dst->friction_mu))
@@ -184,6 +189,8 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
     PongLaunch p{};
     p.state = e->state; p.n = e->n; p.seed = e->seed; p.step0 = e->step; p.T = T;
     p.counter = e->device_counter ? e->counter : nullptr;
+    p.normalize = e->cfg.obs_scaling == ENV_OBS_NORMALIZED;
+    p.inv_score = 1.0f / (float)e->cfg.max_score;
     p.max_score = e->cfg.max_score;
     p.actions = static_cast<const uint8_t*>(actions);
     p.obs = static_cast<float*>(obs); p.reward = reward; p.done = done; p.stats = e->stats;
@@ -224,6 +231,7 @@ int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_c
   env_config_t c = default_config(kind);
   if (merge_config(&c, cfg) != ENV_OK) return ENV_E_ARG;
   if (c.step_counter == ENV_STEP_COUNTER_DEVICE && kind == ENV_PONG_PIXELS) return ENV_E_UNSUPPORTED;
+  if (c.obs_scaling == ENV_OBS_NORMALIZED && kind != ENV_PONG) return ENV_E_UNSUPPORTED;
 
   env_t* e = new (std::nothrow) env_t();
   if (!e) return ENV_E_ALLOC;
@@ -293,7 +301,8 @@ int env_reset(env_t* e, void* obs_dev) {
     if (obs_dev && !device_range_ok(e, obs_dev, (size_t)e->n * PONG_OBS * sizeof(float), 16))
       return ENV_E_ARG;
     err = launch_pong_reset(e->state, e->n, e->seed, e->step, counter,
-                            e->kind == ENV_PONG ? static_cast<float*>(obs_dev) : nullptr, e->stream);
+                            e->kind == ENV_PONG ? static_cast<float*>(obs_dev) : nullptr,
+                            e->cfg.obs_scaling == ENV_OBS_NORMALIZED, e->stream);
     if (e->kind == ENV_PONG_PIXELS) pixel_pipe_invalidate(e->pipe);
   }
   if (err != hipSuccess) return ENV_E_HIP;

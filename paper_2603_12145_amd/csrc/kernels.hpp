@@ -25,11 +25,13 @@ struct PongLaunch {
   float* reward;          // [T,n]
   uint8_t* done;          // [T,n]
   DeviceStats* stats;
+  int32_t normalize;      // Pong vector obs only: 1 = scale every component at the source
+  float inv_score;        // 1 / max_score in float32 (used when normalize)
 };
 
 // reset launchers: counter != nullptr -> the step is read from it instead of `step`
 hipError_t launch_pong_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
-                             const StepCounter* counter, float* obs, hipStream_t stream);
+                             const StepCounter* counter, float* obs, bool normalize, hipStream_t stream);
 hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream);
 
 // CartPole: same launch descriptor (max_score carries max_episode_steps; obs is [T,n,4]).

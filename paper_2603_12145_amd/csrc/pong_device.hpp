@@ -123,6 +123,21 @@ __device__ __forceinline__ PongLane pong_initial(uint64_t seed, uint32_t env, ui
   return s;
 }
 
+// The 8-float observation as two 16-byte halves.  NORMALIZE: scaled at the source (paper App. B.1
+// item 8) by one float32 multiplication per component with the reciprocal of its range
+// (ball x 158, ball y 208, vx 3, vy 2, paddles 194, scores max_score).
+template <bool NORMALIZE>
+__device__ __forceinline__ void pong_observe(const PongLane& s, float inv_score, float4& lo, float4& hi) {
+  if (NORMALIZE) {
+    lo = make_float4(s.bx * (1.0f / 158.0f), s.by * (1.0f / 208.0f), s.vx * (1.0f / 3.0f), s.vy * 0.5f);
+    hi = make_float4(s.pa * (1.0f / 194.0f), s.po * (1.0f / 194.0f), (float)s.sa * inv_score,
+                     (float)s.so * inv_score);
+  } else {
+    lo = make_float4(s.bx, s.by, s.vx, s.vy);
+    hi = make_float4(s.pa, s.po, (float)s.sa, (float)s.so);
+  }
+}
+
 // SoA state: field f of environment i lives at state[f * n + i] (coalesced across a wavefront).
 __device__ __forceinline__ PongLane pong_load(const uint32_t* __restrict__ state, int64_t n,
                                               int64_t i) {

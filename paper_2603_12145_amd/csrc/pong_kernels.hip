@@ -19,7 +19,7 @@ constexpr int ROLLOUT_BLOCK = 256;   // default threads per workgroup of the rol
 __global__ __launch_bounds__(256) void pong_reset_kernel(uint32_t* __restrict__ state, int64_t n,
                                                          uint64_t seed, uint64_t host_step,
                                                          const StepCounter* __restrict__ counter,
-                                                         float* __restrict__ obs) {
+                                                         float* __restrict__ obs, bool normalize) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
   const uint64_t step = read_step(counter, host_step);
@@ -27,8 +27,11 @@ __global__ __launch_bounds__(256) void pong_reset_kernel(uint32_t* __restrict__ 
   pong_store(state, n, i, s);
   if (obs) {
     float4* o = reinterpret_cast<float4*>(obs + i * PONG_OBS);
-    o[0] = make_float4(s.bx, s.by, s.vx, s.vy);
-    o[1] = make_float4(s.pa, s.po, 0.0f, 0.0f);
+    float4 lo, hi;
+    if (normalize) pong_observe<true>(s, 0.0f, lo, hi);     // scores are 0 at a reset
+    else pong_observe<false>(s, 0.0f, lo, hi);
+    o[0] = lo;
+    o[1] = hi;
   }
 }
 
@@ -37,7 +40,7 @@ __global__ __launch_bounds__(256) void pong_reset_kernel(uint32_t* __restrict__ 
 // out as one byte per lane: the 64 bytes of a wavefront are contiguous, so the memory pipeline
 // sees a single 64-byte write either way, and packing them by hand (ballot, shift, spread) only
 // added ~25 instructions per step.
-template <bool FULL, bool EXTERNAL_ACTIONS>
+template <bool FULL, bool EXTERNAL_ACTIONS, bool NORMALIZE>
 __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, LaneEpisodes& le,
                                              const int lane, const int64_t wave_base) {
   const int64_t n = a.n;
@@ -69,8 +72,10 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
 
     if (live) {
       float4* o = reinterpret_cast<float4*>(obs_row + lane * PONG_OBS);
-      o[0] = make_float4(s.bx, s.by, s.vx, s.vy);
-      o[1] = make_float4(s.pa, s.po, (float)s.sa, (float)s.so);
+      float4 lo, hi;
+      pong_observe<NORMALIZE>(s, a.inv_score, lo, hi);
+      o[0] = lo;
+      o[1] = hi;
       rew_row[lane] = ev.reward;
       done_row[lane] = done ? 1 : 0;
     }
@@ -103,12 +108,15 @@ __global__ __launch_bounds__(256) void pong_rollout_kernel(PongLaunch a) {
 
   PongLane s = live ? pong_load(a.state, n, i) : pong_idle_lane();
   LaneEpisodes le;
-  if (a.actions) {
-    if (full) rollout_wave<true, true>(a, s, le, lane, wave_base);
-    else rollout_wave<false, true>(a, s, le, lane, wave_base);
+  if (a.normalize) {                    // the optional form takes the general (predicated) loop
+    if (a.actions) rollout_wave<false, true, true>(a, s, le, lane, wave_base);
+    else rollout_wave<false, false, true>(a, s, le, lane, wave_base);
+  } else if (a.actions) {
+    if (full) rollout_wave<true, true, false>(a, s, le, lane, wave_base);
+    else rollout_wave<false, true, false>(a, s, le, lane, wave_base);
   } else {
-    if (full) rollout_wave<true, false>(a, s, le, lane, wave_base);
-    else rollout_wave<false, false>(a, s, le, lane, wave_base);
+    if (full) rollout_wave<true, false, false>(a, s, le, lane, wave_base);
+    else rollout_wave<false, false, false>(a, s, le, lane, wave_base);
   }
   if (live) pong_store(a.state, n, i, s);
   flush_wave_stats<false>(a.stats, le);
@@ -120,10 +128,10 @@ int g_xcd_remap = 1;
 }  // namespace
 
 hipError_t launch_pong_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
-                             const StepCounter* counter, float* obs, hipStream_t stream) {
+                             const StepCounter* counter, float* obs, bool normalize, hipStream_t stream) {
   const unsigned blocks = (unsigned)((n + 255) / 256);
   hipLaunchKernelGGL(pong_reset_kernel, dim3(blocks), dim3(256), 0, stream, state, n, seed, step, counter,
-                     obs);
+                     obs, normalize);
   return hipGetLastError();
 }
 

@@ -285,3 +285,40 @@ def test_config2_largest_sweep_size_sampled():
     assert stats["episodes"] == st["episodes"] and stats["return_sum"] == st["return_sum"]
     # last 4096 environments: final observation equals the oracle's final state
     assert_bit_equal(obs[T - 1, -4096:].cpu().numpy(), p.obs()[-4096:], "C2-262144 final obs tail")
+
+
+@pytest.mark.parametrize("n,external", [(64, False), (1000, True), (4100, False)])
+def test_normalised_observations_match_oracle(n, external):
+    """obs_scaling = ENV_OBS_NORMALIZED: the scaling is done in the step kernel; bit-identical to the
+    oracle's normalised observation, dynamics untouched."""
+    T, seed, ms = 400, 17, 3
+    acts = inputs.pong_actions(T, n, seed=4) if external else None
+    h = b.env_create(b.ENV_PONG, n, seed, {"max_score": ms, "obs_scaling": b.ENV_OBS_NORMALIZED})
+    try:
+        obs0 = torch.empty((n, 8), dtype=torch.float32, device=DEV)
+        b.env_reset(h, obs0)
+        obs, rew, done = bufs(T, n)
+        act = None if acts is None else torch.from_numpy(acts).to(DEV)
+        b.env_rollout(h, T - 1, None if act is None else act[:T - 1], obs[:T - 1], rew[:T - 1], done[:T - 1])
+        b.env_step(h, None if act is None else act[T - 1], obs[T - 1], rew[T - 1], done[T - 1])
+        torch.cuda.synchronize()
+        state = b.env_get_state(h)
+    finally:
+        b.env_destroy(h)
+    p = orc.Pong(n, seed, max_score=ms, normalize=True)
+    o0 = p.reset()
+    oo, orr, od = p.rollout(T, actions=acts, nthreads=4)
+    assert_bit_equal(obs0.cpu().numpy(), o0, "normalised reset obs")
+    assert_bit_equal(obs.cpu().numpy(), oo, "normalised obs")
+    assert_bit_equal(rew.cpu().numpy(), orr, "reward")
+    assert_bit_equal(done.cpu().numpy(), od, "done")
+    _, fields = split_state(state, n, 10)
+    assert_bit_equal(fields, pong_state_fields(p.envs()), "state (raw units)")
+    assert oo[..., 6:8].max() > 0.3                    # some score was shown, scaled
+
+
+def test_normalised_observations_only_for_pong_vectors():
+    for kind in (b.ENV_PONG_PIXELS, b.ENV_BODY, b.ENV_CARTPOLE):
+        with pytest.raises(b.EnvError) as ei:
+            b.env_create(kind, 64, 0, {"obs_scaling": b.ENV_OBS_NORMALIZED})
+        assert ei.value.code == b.ENV_E_UNSUPPORTED

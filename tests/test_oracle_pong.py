@@ -355,3 +355,31 @@ def test_oracle_arithmetic_is_frozen_by_the_committed_digest():
         assert d == want[ms]["sha256"]
         assert st["episodes"] == int(want[ms]["episodes"])
         assert st["return_sum"] == int(want[ms]["return_sum"])
+
+
+def test_normalised_observations_ranges_and_inverse():
+    """Observation scaling at the source (paper App. B.1 item 8): same trajectories, each component
+    mapped into [0,1] or [-1,1] by one float32 multiplication; extremes are reached exactly, and
+    undoing the scaling in float64 returns the raw observation to within the two float32 roundings
+    made (reciprocal, product): relative error <= 2 * 2^-24."""
+    n, T = 256, 3000
+    raw = orc.Pong(n, 31, max_score=3)
+    nor = orc.Pong(n, 31, max_score=3, normalize=True)
+    r0, n0 = raw.reset(), nor.reset()
+    ro, rr, rd = raw.rollout(T, nthreads=4)
+    no, nr, nd = nor.rollout(T, nthreads=4)
+    assert np.array_equal(rr, nr) and np.array_equal(rd, nd)          # dynamics untouched
+    for k in (0, 1, 4, 5, 6, 7):
+        assert no[..., k].min() >= 0.0 and no[..., k].max() <= 1.0, k
+    for k in (2, 3):
+        assert no[..., k].min() >= -1.0 and no[..., k].max() <= 1.0, k
+    assert set(np.unique(no[..., 2])) == {np.float32(-1.0), np.float32(1.0)}
+    top = np.float32(194) * (np.float32(1) / np.float32(194))        # one ulp below 1: a product, not a quotient
+    assert no[..., 4].max() == top and no[..., 4].min() == 0.0        # paddle clamps hit both ends
+    assert no[..., 6].max() < 1.0 and no[..., 6].max() == np.float32(2) * (np.float32(1) / np.float32(3))
+    ranges = np.array([158, 208, 3, 2, 194, 194, 3, 3], np.float64)
+    back = no.astype(np.float64) * ranges
+    assert (np.abs(back - ro) <= 2.0 ** -23 * np.abs(ro.astype(np.float64))).all()
+    assert np.abs(back - ro).max() > 0.0                               # and the bound is not vacuous
+    assert np.array_equal(n0[:, 4], np.full(n, np.float32(97) * (np.float32(1) / np.float32(194))))
+    assert np.array_equal(r0[:, 2] * (np.float32(1) / np.float32(3)), n0[:, 2])
