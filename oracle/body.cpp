@@ -27,6 +27,26 @@
 //   3. joint limits +-1 rad: S = joints sitting at a limit and still moving outwards under v*;
 //      v+ = M-orthogonal projection of v* onto {v_S = 0}: solve M_FF v_F = (M v + h rhs)_F;
 //   4. q+ = q + h v+, joint angles clipped to [-1, 1].
+//
+// Second contact model (solver = 1), after the paper's final solver revision for this case study
+// (App. A.1: "Newton contact solver formulation (acceleration-space QP with Cholesky
+// factorization)"; the paper gives no formulas, so everything below is this repository's reading):
+// the substep's acceleration a minimises the strictly convex, piecewise quadratic
+//     c(a) = 1/2 (a - a0)^T M (a - a0)  +  sum_i  D_i / 2 * min(0, J_i a - aref_i)^2 ,
+// a0 = M^-1 (Q_g + tau - h) being the acceleration without constraints (Gauss' principle with soft
+// one-sided constraints).  Rows i, in this order:
+//   * contact point p = 0..7 below the ground (z_p < 0): two rows, the edges of the friction
+//     pyramid, J = J_z + mu J_x then J_z - mu J_x, row acceleration J a + (dJ/dt qdot), wanted
+//     >= -b (J v) - k z_p, i.e. aref = -b (J v) - k z_p - (dJ/dt qdot);  D = 1 / reg_contact;
+//   * joint j = 3..8 sitting at +1 (row -e_j) or -1 (row +e_j): aref = -b (J v);  D = 1 / reg_limit;
+//   k = 1 / tc^2, b = 2 / tc (critically damped reference, tc = time_const = 0.02 s = 2 h).
+// Solved by Newton's method on the active set (unit steps: the cost is quadratic on each set):
+//   a <- a0;  repeat at most newton_iters times: S = {i : J_i a - aref_i < 0}; stop if S is the set
+//   of the previous pass; a <- (M + sum_S D_i J_i^T J_i)^-1 (M a0 + sum_S D_i aref_i J_i)  (Cholesky).
+// Then v+ = v + h a, q+ = q + h v+, joint angles clipped to [-1, 1] as before.  The constraint
+// forces depend on the acceleration being solved for (implicit), which is what removes the
+// stiffness limit of the explicit penalty spring.
+//
 // Everything is templated on the scalar type.  float64 serves the invariants and is the parity
 // target of the single-step comparison (stepping from a float32 state; `round_state_f32` rounds the
 // state back to the storage format after every step); float32 serves the long-rollout statistics
@@ -72,6 +92,9 @@ struct Params {
   R gravity, contact_k, contact_c, h, gear, z0;
   int substeps, max_episode_steps;
   int round_state_f32;   // round q, v, episode return to float32 after every step (the storage format)
+  int solver;            // 0 penalty spring + limit projection, 1 Newton on the soft-constraint QP
+  int newton_iters;
+  R time_const, reg_contact, reg_limit;
 };
 
 template <class R>
@@ -225,9 +248,116 @@ void clip_actions(const R* a_in, R a[NACT]) {
   }
 }
 
+// ---- Newton contact solver (solver = 1) -----------------------------------------------------------
+const int MAXROW = 2 * NPOINT + NACT;
+
+template <class R>
+struct Rows { int m; R J[MAXROW][NQ]; R aref[MAXROW]; R D[MAXROW]; };
+
+// Constraint rows at (q, v), in the order stated in the header.
+template <class R>
+void constraint_rows(const Params<R>& P, const R* q, const R* v, Rows<R>* rows) {
+  const R k = (R)1 / (P.time_const * P.time_const), b = (R)2 / P.time_const;
+  rows->m = 0;
+  for (int p = 0; p < NPOINT; ++p) {
+    Kin<R> kin;
+    point_kinematics(CONTACT[p], q, v, &kin);
+    if (!(kin.pos[1] < 0)) continue;
+    for (int e = 0; e < 2; ++e) {
+      const R smu = e == 0 ? P.friction_mu : -P.friction_mu;
+      const int i = rows->m++;
+      R jv = 0;
+      for (int j = 0; j < NQ; ++j) {
+        rows->J[i][j] = kin.J[1][j] + smu * kin.J[0][j];
+        jv += rows->J[i][j] * v[j];
+      }
+      rows->aref[i] = -b * jv - k * kin.pos[1] - (kin.jdqd[1] + smu * kin.jdqd[0]);
+      rows->D[i] = (R)1 / P.reg_contact;
+    }
+  }
+  for (int j = 3; j < NQ; ++j) {
+    R sign = 0;
+    if (q[j] >= 1) sign = -1;
+    else if (q[j] <= -1) sign = 1;
+    if (sign == 0) continue;
+    const int i = rows->m++;
+    for (int c = 0; c < NQ; ++c) rows->J[i][c] = 0;
+    rows->J[i][j] = sign;
+    rows->aref[i] = -b * (sign * v[j]);
+    rows->D[i] = (R)1 / P.reg_limit;
+  }
+}
+
+struct NewtonInfo { int rows, passes, converged; uint32_t active; };
+
+// Minimise c(a); f = M a0 (the generalised force without constraints).  Returns false if a
+// factorisation fails.
+template <class R>
+bool newton_solve(const Params<R>& P, const R M[NQ][NQ], const R f[NQ], const Rows<R>& rows, R a[NQ],
+                  NewtonInfo* info) {
+  if (!cholesky_solve(M, f, a)) return false;
+  uint32_t prev = 0;
+  int passes = 0, converged = rows.m == 0;
+  for (int it = 0; it < P.newton_iters && rows.m > 0; ++it) {
+    uint32_t set = 0;
+    for (int i = 0; i < rows.m; ++i) {
+      R r = -rows.aref[i];
+      for (int j = 0; j < NQ; ++j) r += rows.J[i][j] * a[j];
+      if (r < 0) set |= 1u << i;
+    }
+    if (it > 0 && set == prev) { converged = 1; break; }
+    if (it == 0 && set == 0) { converged = 1; prev = 0; break; }
+    R Hm[NQ][NQ], g[NQ];
+    for (int x = 0; x < NQ; ++x) {
+      g[x] = f[x];
+      for (int y = 0; y < NQ; ++y) Hm[x][y] = M[x][y];
+    }
+    for (int i = 0; i < rows.m; ++i) {
+      if (!(set & (1u << i))) continue;
+      for (int x = 0; x < NQ; ++x) {
+        g[x] += rows.D[i] * rows.aref[i] * rows.J[i][x];
+        for (int y = 0; y < NQ; ++y) Hm[x][y] += rows.D[i] * rows.J[i][x] * rows.J[i][y];
+      }
+    }
+    if (!cholesky_solve(Hm, g, a)) return false;
+    prev = set;
+    ++passes;
+  }
+  if (info) { info->rows = rows.m; info->passes = passes; info->converged = converged; info->active = prev; }
+  return true;
+}
+
+template <class R>
+void smooth_force(const Params<R>& P, const R* q, const R* v, const R a[NACT], R M[NQ][NQ], R f[NQ]) {
+  R hb[NQ];
+  mass_matrix(P, q, M);
+  bias_and_gravity(P, q, v, hb, f);                    // f = Q_g
+  for (int j = 0; j < NQ; ++j) f[j] -= hb[j];
+  for (int j = 0; j < NACT; ++j) f[3 + j] += P.gear * a[j] - P.joint_damping * v[3 + j];
+}
+
+template <class R>
+bool substep_newton(const Params<R>& P, R* q, R* v, const R a[NACT], NewtonInfo* info) {
+  R M[NQ][NQ], f[NQ], acc[NQ];
+  smooth_force(P, q, v, a, M, f);
+  Rows<R> rows;
+  constraint_rows(P, q, v, &rows);
+  if (!newton_solve(P, M, f, rows, acc, info)) return false;
+  for (int j = 0; j < NQ; ++j) { v[j] = v[j] + P.h * acc[j]; q[j] = q[j] + P.h * v[j]; }
+  for (int j = 3; j < NQ; ++j) {
+    if (q[j] < -1) q[j] = -1;
+    if (q[j] > 1) q[j] = 1;
+  }
+  return true;
+}
+
 // One substep; a[] already clipped.  limit_mask_out (optional): bit j set if joint j was projected.
 template <class R>
 bool substep(const Params<R>& P, R* q, R* v, const R a[NACT], int* limit_mask_out) {
+  if (P.solver == 1) {
+    if (limit_mask_out) *limit_mask_out = 0;
+    return substep_newton(P, q, v, a, (NewtonInfo*)nullptr);
+  }
   R M[NQ][NQ], hb[NQ], rhs[NQ];
   mass_matrix(P, q, M);
   bias_and_gravity(P, q, v, hb, rhs);                  // rhs = Q_g
@@ -399,6 +529,7 @@ Params<R> default_params() {
   P.armature = (R)0.1; P.joint_damping = (R)3.0; P.friction_mu = (R)0.4;
   P.gravity = (R)9.81; P.contact_k = (R)1e4; P.contact_c = (R)100; P.h = (R)0.01; P.gear = (R)120;
   P.z0 = (R)0.8; P.substeps = 5; P.max_episode_steps = 1000; P.round_state_f32 = 0;
+  P.solver = 0; P.newton_iters = 8; P.time_const = (R)0.02; P.reg_contact = (R)0.02; P.reg_limit = (R)0.5;
   return P;
 }
 
@@ -475,8 +606,10 @@ Batch<R>* create(int64_t n, uint64_t seed, const double* cfg /* armature, dampin
     return create<R>(n, seed, cfg);                                                               \
   }                                                                                               \
   void oracle_body_destroy##SFX(void* h) { delete (Batch<R>*)h; }                                 \
-  void oracle_body_set_params##SFX(void* h, const double* p /* 10: armature damping mu g k c h gear substeps round_state_f32 */) { \
+  void oracle_body_set_params##SFX(void* h, const double* p /* 15: armature damping mu g k c h gear substeps round_state_f32 solver newton_iters time_const reg_contact reg_limit */) { \
     Batch<R>* B = (Batch<R>*)h;                                                                   \
+    B->P.solver = (int)p[10]; B->P.newton_iters = (int)p[11]; B->P.time_const = (R)p[12];         \
+    B->P.reg_contact = (R)p[13]; B->P.reg_limit = (R)p[14];                                       \
     B->P.armature = (R)p[0]; B->P.joint_damping = (R)p[1]; B->P.friction_mu = (R)p[2];            \
     B->P.gravity = (R)p[3]; B->P.contact_k = (R)p[4]; B->P.contact_c = (R)p[5]; B->P.h = (R)p[6]; \
     B->P.gear = (R)p[7]; B->P.substeps = (int)p[8]; B->P.round_state_f32 = (int)p[9];             \
@@ -539,6 +672,21 @@ Batch<R>* create(int64_t n, uint64_t seed, const double* cfg /* armature, dampin
   int32_t oracle_body_substep##SFX(void* h, R* q, R* v, const R* a_in) {                          \
     R a[NACT]; clip_actions(a_in, a); int mask = 0;                                               \
     return substep(((Batch<R>*)h)->P, q, v, a, &mask) ? mask : -1;                                \
+  }                                                                                               \
+  /* Newton contact model, for the pins: rows at (q, v); returns their number */                  \
+  int32_t oracle_body_newton_rows##SFX(void* h, const R* q, const R* v, R* J /* [22][9] */, R* aref, R* D) { \
+    Rows<R> rows; constraint_rows(((Batch<R>*)h)->P, q, v, &rows);                                \
+    std::memcpy(J, rows.J, sizeof rows.J); std::memcpy(aref, rows.aref, sizeof rows.aref);        \
+    std::memcpy(D, rows.D, sizeof rows.D); return rows.m;                                         \
+  }                                                                                               \
+  /* acceleration of one substep at (q, v) under clipped actions; info4 = rows, passes, converged, active set */ \
+  int32_t oracle_body_newton_accel##SFX(void* h, const R* q, const R* v, const R* a_in, R* acc9, R* f9, int32_t* info4) { \
+    const Params<R>& P = ((Batch<R>*)h)->P;                                                       \
+    R a[NACT]; clip_actions(a_in, a); R M[NQ][NQ]; smooth_force(P, q, v, a, M, f9);               \
+    Rows<R> rows; constraint_rows(P, q, v, &rows); NewtonInfo info = {0, 0, 0, 0};                \
+    const bool ok = newton_solve(P, M, f9, rows, acc9, &info);                                    \
+    info4[0] = info.rows; info4[1] = info.passes; info4[2] = info.converged; info4[3] = (int32_t)info.active; \
+    return ok ? 1 : 0;                                                                            \
   }                                                                                               \
   int32_t oracle_body_solve##SFX(const R* A81, const R* b, R* x) {                                \
     R A[NQ][NQ]; std::memcpy(A, A81, sizeof A); return cholesky_solve(A, b, x) ? 1 : 0;           \

@@ -32,6 +32,8 @@ def bind(L):
         g("energy").argtypes = [vp, vp, vp]; g("energy").restype = C.c_double
         g("substep").argtypes = [vp, vp, vp, vp]; g("substep").restype = C.c_int32
         g("solve").argtypes = [vp, vp, vp]; g("solve").restype = C.c_int32
+        g("newton_rows").argtypes = [vp, vp, vp, vp, vp, vp]; g("newton_rows").restype = C.c_int32
+        g("newton_accel").argtypes = [vp, vp, vp, vp, vp, vp, vp]; g("newton_accel").restype = C.c_int32
         g("draw_actions").argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, vp]
     L.oracle_body_link.argtypes = [C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
 
@@ -44,7 +46,8 @@ class Body:
     """Batch of N oracle bodies in float32 (dtype=np.float32) or float64."""
 
     DEFAULTS = dict(armature=0.1, joint_damping=3.0, friction_mu=0.4, gravity=9.81, contact_k=1e4,
-                    contact_c=100.0, h=0.01, gear=120.0, substeps=5, round_state_f32=0)
+                    contact_c=100.0, h=0.01, gear=120.0, substeps=5, round_state_f32=0,
+                    solver=0, newton_iters=8, time_const=0.02, reg_contact=0.02, reg_limit=0.5)
 
     def __init__(self, n, seed, dtype=np.float32, max_episode_steps=1000, **params):
         from oracle import oracle as orc
@@ -66,7 +69,8 @@ class Body:
         p = self.params
         arr = np.array([p["armature"], p["joint_damping"], p["friction_mu"], p["gravity"],
                         p["contact_k"], p["contact_c"], p["h"], p["gear"], p["substeps"],
-                        p["round_state_f32"]], np.float64)
+                        p["round_state_f32"], p["solver"], p["newton_iters"], p["time_const"],
+                        p["reg_contact"], p["reg_limit"]], np.float64)
         self._f("set_params")(self.h, _p(arr))
 
     def set_params(self, **kw):
@@ -149,6 +153,22 @@ class Body:
         q, v = self.arr(q).copy(), self.arr(v).copy()
         mask = self._f("substep")(self.h, _p(q), _p(v), _p(self.arr(a)))
         return q, v, mask
+
+    def newton_rows(self, q, v):
+        """Constraint rows of the Newton contact model at (q, v): J [m,9], aref [m], D [m]."""
+        J, ar, D = np.empty((22, NQ), self.dtype), np.empty(22, self.dtype), np.empty(22, self.dtype)
+        m = self._f("newton_rows")(self.h, _p(self.arr(q)), _p(self.arr(v)), _p(J), _p(ar), _p(D))
+        return J[:m].copy(), ar[:m].copy(), D[:m].copy()
+
+    def newton_accel(self, q, v, a):
+        """Acceleration of one substep, the force without constraints f = M a0, and
+        (rows, passes, converged, active-set bits)."""
+        acc, f = np.empty(NQ, self.dtype), np.empty(NQ, self.dtype)
+        info = np.zeros(4, np.int32)
+        ok = self._f("newton_accel")(self.h, _p(self.arr(q)), _p(self.arr(v)), _p(self.arr(a)), _p(acc), _p(f),
+                                     _p(info))
+        assert ok
+        return acc, f, tuple(int(x) for x in info)
 
     def solve(self, A, b):
         x = np.empty(NQ, self.dtype)
