@@ -66,7 +66,20 @@ typedef struct env_config_t {
   int32_t pixel_layout;       /* pixels: ENV_PIXELS_* below; 0 = default (slot-major)             */
   int32_t step_counter;       /* ENV_STEP_COUNTER_* below; 0 = default (host)                     */
   int32_t obs_scaling;        /* ENV_OBS_* below; 0 = default (raw)                               */
+  int32_t contact_solver;     /* body: ENV_CONTACT_* below; 0 = default (penalty)                 */
 } env_config_t;
+
+/* Ground contact and joint limits of ENV_BODY (other kinds: ENV_E_UNSUPPORTED for NEWTON).
+ *   penalty  explicit spring-damper normal force (k = 1e4, c = 100), friction c*vx clipped to
+ *            +-mu*fn, joint limits by an M-orthogonal velocity projection (the paper's first solver
+ *            revision for this case study, App. A.1);
+ *   newton   the substep's acceleration minimises 1/2 (a-a0)^T M (a-a0) + sum_i D_i/2 min(0, J_i a -
+ *            aref_i)^2 over soft one-sided rows: the two friction-pyramid edges J_z +- mu J_x of
+ *            every contact point below the ground (aref = -b J v - k z - dJ/dt qdot, D = 1/0.02) and
+ *            one row per joint at a limit (aref = -b J v, D = 1/0.5), k = 1/tc^2, b = 2/tc,
+ *            tc = 0.02 s; solved by Newton's method on the active set with Cholesky
+ *            factorisations, at most 8 passes (the paper's final revision: acceleration-space QP). */
+enum { ENV_CONTACT_PENALTY = 1, ENV_CONTACT_NEWTON = 2 };
 
 /* ENV_PONG only (other kinds: ENV_E_UNSUPPORTED).  ENV_OBS_NORMALIZED scales every observation
  * component inside the step kernel (paper App. B.1 item 8) by one float32 multiplication with the

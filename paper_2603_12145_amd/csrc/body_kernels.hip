@@ -19,6 +19,20 @@
 //  * sin / cos of the six joint angles (always in [-1, 1]) come from a polynomial without range
 //    reduction, the link angles from angle addition on top of one sincos of the pitch.
 //
+// Second contact model (solver = Newton; the paper's final solver revision for this case study,
+// App. A.1: an acceleration-space quadratic programme solved by Newton's method with Cholesky
+// factorisations).  The substep's acceleration minimises
+//     1/2 (a - a0)^T M (a - a0) + sum_i D_i / 2 * min(0, J_i a - aref_i)^2,
+// rows i = the two friction-pyramid edges J_z +- mu J_x of every contact point below the ground
+// (aref = -b J v - k z - dJ/dt qdot, k = 1/tc^2, b = 2/tc, tc = 0.02) and one row per joint sitting
+// at a limit (aref = -b J v).  Newton on the active set with unit steps: S = rows with negative
+// residual at the current a; a <- (M + sum_S D J^T J)^-1 (M a0 + sum_S D aref J); stop when S repeats
+// (at most 8 passes).  A contact row of a leg touches only the root and that leg's joints, so
+// M + sum D J^T J keeps the block structure of M and goes through the same block Cholesky; rows are
+// never stored: each pass rebuilds them from the link vectors (8 multiply-adds per leg).  A
+// wavefront leaves the loop when no lane's active set changed; a lane whose set is already stable
+// re-solves the same system and gets the same numbers.
+//
 // Arithmetic is float64 inside a step: the 9x9 system has a condition number of order 10^2, which
 // in float32 leaves a per-step error of about 10^-6..10^-5 of the state, the same size as the
 // agreement asked of this kernel.  MI355X issues float64 FMAs at the rate of unpacked float32, so
@@ -97,11 +111,23 @@ struct Leg {                 // everything one leg contributes, for one substep
   real rhs_x, rhs_z, rhs_th; // ... and this leg's part of the root rows
 };
 
-struct Params { real armature, damping, mu; };
+struct Params {
+  real armature, damping, mu;
+  real d_contact, d_limit, k_ref, b_ref;   // Newton model: 1 / regularisation, reference spring and damper
+};
+
+constexpr real NEWTON_TIME_CONST = 0.02, NEWTON_REG_CONTACT = 0.02, NEWTON_REG_LIMIT = 0.5;
+constexpr int NEWTON_MAX_PASSES = 8;
+
+struct LegRows {             // Newton model: what the contact rows of one leg need besides the link vectors
+  real z[4];                 // height of hip, knee, ankle, toe (rows exist iff < 0)
+  real aref[4][2];           // reference acceleration of the +mu and the -mu edge
+};
 
 // Kinematics, mass-matrix blocks, bias, gravity and contact of one leg.
 // sign = -1 back, +1 front; (st, ct) = sin / cos pitch; jq, jv = the leg's joint angles and rates.
-__device__ __forceinline__ void leg_terms(Leg& g, const real sign, const real st, const real ct,
+template <bool NEWTON>
+__device__ __forceinline__ void leg_terms(Leg& g, LegRows& rows, const real sign, const real st, const real ct,
                                           const real z, const real vx, const real vz, const real vth,
                                           const real* jq, const real* jv, const Params& P) {
   // link angles by angle addition
@@ -152,6 +178,7 @@ __device__ __forceinline__ void leg_terms(Leg& g, const real sign, const real st
   const Vec2 v_hip = Vec2{vx, vz} + vth * g.H;
   const Vec2 v_knee = v_hip + g.w1 * g.E1, v_ank = v_knee + g.w2 * g.E2, v_toe = v_ank + g.w3 * g.E3;
   auto force = [&](real zp, Vec2 vp) -> Vec2 {
+    if (NEWTON) return Vec2{0.0, 0.0};           // contact enters through the constraint rows instead
     real fn = -CONTACT_K * zp - CONTACT_C * vp.z;
     fn = (zp < 0.0 && fn > 0.0) ? fn : 0.0;
     real want = CONTACT_C * vp.x;
@@ -165,6 +192,22 @@ __device__ __forceinline__ void leg_terms(Leg& g, const real sign, const real st
   const Vec2 S1 = S2 + force(z_knee, v_knee);
   const Vec2 S0 = S1 + force(z_hip, v_hip);
   const real c2f = dot(g.E3, S3), c1f = dot(g.E2, S2) + c2f, c0f = dot(g.E1, S1) + c1f;
+  if (NEWTON) {
+    // velocity-product accelerations of the four points: the centre-of-mass ones with whole links
+    const Vec2 a_knee = Hk - D1, a_ank = a_knee - D2, a_toe = a_ank - D3;
+    const real zs[4] = {z_hip, z_knee, z_ank, z_toe};
+    const Vec2 vs[4] = {v_hip, v_knee, v_ank, v_toe};
+    const Vec2 as[4] = {Hk, a_knee, a_ank, a_toe};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      rows.z[k] = zs[k];
+#pragma unroll
+      for (int e = 0; e < 2; ++e) {
+        const real smu = e == 0 ? P.mu : -P.mu;
+        rows.aref[k][e] = -P.b_ref * (vs[k].z + smu * vs[k].x) - P.k_ref * zs[k] - (as[k].z + smu * as[k].x);
+      }
+    }
+  }
 
   // right-hand sides: gravity (-g times the z row of M) - bias + contact; torque and damping are
   // added by the caller
@@ -182,7 +225,8 @@ struct LegFactor {           // Cholesky factor of a leg block and Y = L^-1 C^T
 };
 
 // keep[j] = false removes joint j (row and column of the identity, no coupling to the root).
-__device__ __forceinline__ void factor_leg(LegFactor& f, const Leg& g, const bool keep[3]) {
+template <class Block>   // anything with A[6] and C[3][3]
+__device__ __forceinline__ void factor_leg(LegFactor& f, const Block& g, const bool keep[3]) {
   const real a00 = keep[0] ? g.A[0] : 1.0;
   const real a01 = (keep[0] && keep[1]) ? g.A[1] : 0.0;
   const real a02 = (keep[0] && keep[2]) ? g.A[2] : 0.0;
@@ -221,8 +265,11 @@ __device__ __forceinline__ void backward_leg(const LegFactor& f, const real y[3]
 
 // Solve the 9x9 system with the joints in `keep` (others: v = 0).  R = root block
 // (Mtot, Mtot, m_xth, m_zth, m_thth); b = right-hand side (root 3, back 3, front 3).
-__device__ __forceinline__ void solve_system(const Leg& gb, const Leg& gf, const real mxth, const real mzth,
-                                             const real mthth, const bool keep_b[3], const bool keep_f[3],
+struct RootBlock { real xx, xz, xth, zz, zth, thth; };
+
+template <class Block>
+__device__ __forceinline__ void solve_system(const Block& gb, const Block& gf, const RootBlock& R,
+                                             const bool keep_b[3], const bool keep_f[3],
                                              const real b_root[3], const real b_back[3], const real b_front[3],
                                              real x_root[3], real x_back[3], real x_front[3]) {
   LegFactor fb, ff;
@@ -234,7 +281,7 @@ __device__ __forceinline__ void solve_system(const Leg& gb, const Leg& gf, const
   forward_leg(fb, bb, yb);
   forward_leg(ff, bf, yf);
   // Schur complement of the root block (symmetric 3x3: xx xz xth zz zth thth)
-  real s[3][3] = {{MTOT, 0.0, mxth}, {0.0, MTOT, mzth}, {mxth, mzth, mthth}};
+  real s[3][3] = {{R.xx, R.xz, R.xth}, {R.xz, R.zz, R.zth}, {R.xth, R.zth, R.thth}};
   real br[3];
 #pragma unroll
   for (int r = 0; r < 3; ++r) {
@@ -276,10 +323,12 @@ __device__ __forceinline__ void body_substep(BodyLane& s, const real a[6], const
   real st, ct;
   sincos(s.q[2], &st, &ct);
   Leg gb, gf;
-  leg_terms(gb, -1.0, st, ct, s.q[1], s.v[0], s.v[1], s.v[2], &s.q[3], &s.v[3], P);
-  leg_terms(gf, +1.0, st, ct, s.q[1], s.v[0], s.v[1], s.v[2], &s.q[6], &s.v[6], P);
+  LegRows unused;
+  leg_terms<false>(gb, unused, -1.0, st, ct, s.q[1], s.v[0], s.v[1], s.v[2], &s.q[3], &s.v[3], P);
+  leg_terms<false>(gf, unused, +1.0, st, ct, s.q[1], s.v[0], s.v[1], s.v[2], &s.q[6], &s.v[6], P);
   const real mxth = gb.Pth.x + gf.Pth.x, mzth = gb.Pth.z + gf.Pth.z;
   const real mthth = IT + gb.mthth + gf.mthth;
+  const RootBlock R = {MTOT, 0.0, mxth, MTOT, mzth, mthth};
 
   // b = M v + h * rhs
   real b_root[3], b_back[3], b_front[3];
@@ -312,7 +361,7 @@ __device__ __forceinline__ void body_substep(BodyLane& s, const real a[6], const
   // unconstrained velocity, then the joints to freeze, then the projected velocity
   const bool all[3] = {true, true, true};
   real x_root[3], x_back[3], x_front[3];
-  solve_system(gb, gf, mxth, mzth, mthth, all, all, b_root, b_back, b_front, x_root, x_back, x_front);
+  solve_system(gb, gf, R, all, all, b_root, b_back, b_front, x_root, x_back, x_front);
   bool keep_b[3], keep_f[3];
 #pragma unroll
   for (int m = 0; m < 3; ++m) {
@@ -323,11 +372,151 @@ __device__ __forceinline__ void body_substep(BodyLane& s, const real a[6], const
   // only when no lane needs it
   const bool any_frozen = !(keep_b[0] && keep_b[1] && keep_b[2] && keep_f[0] && keep_f[1] && keep_f[2]);
   if (__ballot(any_frozen) != 0ull)
-    solve_system(gb, gf, mxth, mzth, mthth, keep_b, keep_f, b_root, b_back, b_front, x_root, x_back, x_front);
+    solve_system(gb, gf, R, keep_b, keep_f, b_root, b_back, b_front, x_root, x_back, x_front);
 
 #pragma unroll
   for (int m = 0; m < 3; ++m) {
     s.v[m] = x_root[m]; s.v[3 + m] = x_back[m]; s.v[6 + m] = x_front[m];
+  }
+#pragma unroll
+  for (int j = 0; j < 9; ++j) s.q[j] = s.q[j] + STEP_H * s.v[j];
+#pragma unroll
+  for (int j = 3; j < 9; ++j) s.q[j] = s.q[j] < -1.0 ? -1.0 : (s.q[j] > 1.0 ? 1.0 : s.q[j]);
+}
+
+
+// ---- Newton contact model ---------------------------------------------------------------------------
+
+struct LegBlock { real A[6]; real C[3][3]; };
+
+template <int N> struct Depth { static constexpr int value = N; };
+
+// Calls fn(depth tag, point k, edge e, smu, theta entry, joint entries u[3]) for the eight contact
+// rows of a leg.  Row = (smu, 1, t | u0, u1, u2) over (x, z, theta | the leg's joints): the dot
+// products of the pyramid edge n = (smu, 1) with the Jacobian columns, which are partial sums of
+// the link vectors.
+template <class F>
+__device__ __forceinline__ void for_each_contact_row(const Leg& g, const real mu, F&& fn) {
+#pragma unroll
+  for (int e = 0; e < 2; ++e) {
+    const real smu = e == 0 ? mu : -mu;
+    const real h = g.H.z + smu * g.H.x;
+    const real e1 = g.E1.z + smu * g.E1.x, e2 = g.E2.z + smu * g.E2.x, e3 = g.E3.z + smu * g.E3.x;
+    const real u0[3] = {0.0, 0.0, 0.0};
+    fn(Depth<0>{}, 0, e, smu, h, u0);
+    const real u1[3] = {e1, 0.0, 0.0};
+    fn(Depth<1>{}, 1, e, smu, h + e1, u1);
+    const real u2[3] = {e1 + e2, e2, 0.0};
+    fn(Depth<2>{}, 2, e, smu, h + u2[0], u2);
+    const real u3[3] = {u2[0] + e3, e2 + e3, e3};
+    fn(Depth<3>{}, 3, e, smu, h + u3[0], u3);
+  }
+}
+
+// Bits 0..7 of the result: contact rows of this leg with a negative residual at acceleration
+// (ar = root part, aj = this leg's joints); bits 8..10: its joints' limit rows.
+__device__ __forceinline__ uint32_t leg_active_set(const Leg& g, const LegRows& rows, const real* jq,
+                                                   const real* jv, const real ar[3], const real aj[3],
+                                                   const Params& P) {
+  uint32_t set = 0;
+  for_each_contact_row(g, P.mu, [&](auto depth, int k, int e, real smu, real t, const real* u) {
+    real r = smu * ar[0] + ar[1] + t * ar[2] - rows.aref[k][e];
+#pragma unroll
+    for (int m = 0; m < decltype(depth)::value; ++m) r += u[m] * aj[m];
+    set |= (rows.z[k] < 0.0 && r < 0.0) ? (1u << (2 * k + e)) : 0u;
+  });
+#pragma unroll
+  for (int m = 0; m < 3; ++m) {
+    const real sgn = jq[m] >= 1.0 ? -1.0 : (jq[m] <= -1.0 ? 1.0 : 0.0);
+    const real r = sgn * aj[m] + P.b_ref * sgn * jv[m];          // s a - aref, aref = -b s v
+    set |= (sgn != 0.0 && r < 0.0) ? (1u << (8 + m)) : 0u;
+  }
+  return set;
+}
+
+// Adds D J^T J of the active rows to the leg's blocks and the root block, D aref J to the right-hand
+// sides.
+__device__ __forceinline__ void leg_add_rows(const Leg& g, const LegRows& rows, const real* jq, const real* jv,
+                                             const uint32_t set, const Params& P, LegBlock& B, RootBlock& R,
+                                             real g_root[3], real g_leg[3]) {
+  const int sym[3][3] = {{0, 1, 2}, {1, 3, 4}, {2, 4, 5}};
+  for_each_contact_row(g, P.mu, [&](auto depth, int k, int e, real smu, real t, const real* u) {
+    const real w = (set >> (2 * k + e) & 1u) ? P.d_contact : 0.0;
+    const real aw = w * rows.aref[k][e];
+    const real ws = w * smu, wt = w * t;
+    R.xx += ws * smu; R.xz += ws; R.xth += ws * t; R.zz += w; R.zth += wt; R.thth += wt * t;
+    g_root[0] += aw * smu; g_root[1] += aw; g_root[2] += aw * t;
+#pragma unroll
+    for (int m = 0; m < decltype(depth)::value; ++m) {
+      const real wu = w * u[m];
+      B.C[0][m] += wu * smu; B.C[1][m] += wu; B.C[2][m] += wu * t;
+      g_leg[m] += aw * u[m];
+#pragma unroll
+      for (int c = m; c < decltype(depth)::value; ++c) B.A[sym[m][c]] += wu * u[c];
+    }
+  });
+  const int diag[3] = {0, 3, 5};
+#pragma unroll
+  for (int m = 0; m < 3; ++m) {
+    const real sgn = jq[m] >= 1.0 ? -1.0 : (jq[m] <= -1.0 ? 1.0 : 0.0);
+    const real w = (set >> (8 + m) & 1u) ? P.d_limit : 0.0;
+    B.A[diag[m]] += w;                                            // s^2 = 1
+    g_leg[m] += w * (-P.b_ref * sgn * jv[m]) * sgn;
+  }
+}
+
+// One substep in place, Newton contact model.  a[6]: clipped actions.
+__device__ __forceinline__ void body_substep_newton(BodyLane& s, const real a[6], const Params& P) {
+  real st, ct;
+  sincos(s.q[2], &st, &ct);
+  Leg gb, gf;
+  LegRows rb, rf;
+  leg_terms<true>(gb, rb, -1.0, st, ct, s.q[1], s.v[0], s.v[1], s.v[2], &s.q[3], &s.v[3], P);
+  leg_terms<true>(gf, rf, +1.0, st, ct, s.q[1], s.v[0], s.v[1], s.v[2], &s.q[6], &s.v[6], P);
+  const RootBlock R0 = {MTOT, 0.0, gb.Pth.x + gf.Pth.x, MTOT, gb.Pth.z + gf.Pth.z, IT + gb.mthth + gf.mthth};
+
+  // generalised force without constraints: f = M a0
+  real f_root[3], f_back[3], f_front[3];
+  f_root[0] = gb.rhs_x + gf.rhs_x;
+  f_root[1] = -GRAVITY * MTOT + gb.rhs_z + gf.rhs_z;
+  f_root[2] = gb.rhs_th + gf.rhs_th;
+#pragma unroll
+  for (int m = 0; m < 3; ++m) {
+    f_back[m] = gb.rhs[m] + GEAR * a[m] - P.damping * s.v[3 + m];
+    f_front[m] = gf.rhs[m] + GEAR * a[3 + m] - P.damping * s.v[6 + m];
+  }
+  const bool all[3] = {true, true, true};
+  real x_root[3], x_back[3], x_front[3];
+  solve_system(gb, gf, R0, all, all, f_root, f_back, f_front, x_root, x_back, x_front);
+
+  uint32_t prev = 0;
+  for (int pass = 0; pass < NEWTON_MAX_PASSES; ++pass) {
+    const uint32_t set = leg_active_set(gb, rb, &s.q[3], &s.v[3], x_root, x_back, P) |
+                         (leg_active_set(gf, rf, &s.q[6], &s.v[6], x_root, x_front, P) << 16);
+    // pass 0 compares with the empty set: no row active = the unconstrained acceleration stands
+    if (__ballot(set != prev) == 0ull) break;
+    LegBlock Bb, Bf;
+#pragma unroll
+    for (int k = 0; k < 6; ++k) { Bb.A[k] = gb.A[k]; Bf.A[k] = gf.A[k]; }
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+      for (int c = 0; c < 3; ++c) { Bb.C[r][c] = gb.C[r][c]; Bf.C[r][c] = gf.C[r][c]; }
+    RootBlock R = R0;
+    real g_root[3], g_back[3], g_front[3];
+#pragma unroll
+    for (int m = 0; m < 3; ++m) { g_root[m] = f_root[m]; g_back[m] = f_back[m]; g_front[m] = f_front[m]; }
+    leg_add_rows(gb, rb, &s.q[3], &s.v[3], set & 0xffffu, P, Bb, R, g_root, g_back);
+    leg_add_rows(gf, rf, &s.q[6], &s.v[6], set >> 16, P, Bf, R, g_root, g_front);
+    solve_system(Bb, Bf, R, all, all, g_root, g_back, g_front, x_root, x_back, x_front);
+    prev = set;
+  }
+
+#pragma unroll
+  for (int m = 0; m < 3; ++m) {
+    s.v[m] = s.v[m] + STEP_H * x_root[m];
+    s.v[3 + m] = s.v[3 + m] + STEP_H * x_back[m];
+    s.v[6 + m] = s.v[6 + m] + STEP_H * x_front[m];
   }
 #pragma unroll
   for (int j = 0; j < 9; ++j) s.q[j] = s.q[j] + STEP_H * s.v[j];
@@ -407,13 +596,16 @@ __global__ __launch_bounds__(256) void body_reset_kernel(uint32_t* __restrict__ 
   if (obs) body_observe(obs + i * BODY_OBS, s);
 }
 
+template <bool NEWTON>
 __global__ __launch_bounds__(WAVE) void body_rollout_kernel(BodyLaunch a) {
   a.step0 = launch_first_step(a.counter, a.step0, a.T);
   const int64_t n = a.n;
   const int64_t i = (int64_t)blockIdx.x * WAVE + threadIdx.x;
   const bool live = i < n;
   const int64_t ic = live ? i : n - 1;             // idle lanes shadow the last environment
-  const Params P = {(real)a.armature, (real)a.joint_damping, (real)a.friction_mu};
+  const Params P = {(real)a.armature, (real)a.joint_damping, (real)a.friction_mu,
+                    1.0 / NEWTON_REG_CONTACT, 1.0 / NEWTON_REG_LIMIT,
+                    1.0 / (NEWTON_TIME_CONST * NEWTON_TIME_CONST), 2.0 / NEWTON_TIME_CONST};
   BodyLane s = body_load(a.state, n, ic);
   LaneEpisodes le;
 
@@ -439,7 +631,8 @@ __global__ __launch_bounds__(WAVE) void body_rollout_kernel(BodyLaunch a) {
     }
     real vx_sum = 0.0;
     for (int sub = 0; sub < SUBSTEPS; ++sub) {
-      body_substep(s, act, P);
+      if (NEWTON) body_substep_newton(s, act, P);
+      else body_substep(s, act, P);
       vx_sum += s.v[0];
     }
     float reward = (float)(vx_sum / (real)SUBSTEPS - 0.1 * cost);
@@ -490,7 +683,9 @@ hipError_t launch_body_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t
 }
 
 hipError_t launch_body_rollout(const BodyLaunch& a, hipStream_t stream) {
-  hipLaunchKernelGGL(body_rollout_kernel, dim3((unsigned)((a.n + WAVE - 1) / WAVE)), dim3(WAVE), 0, stream, a);
+  const dim3 grid((unsigned)((a.n + WAVE - 1) / WAVE));
+  if (a.newton) hipLaunchKernelGGL(body_rollout_kernel<true>, grid, dim3(WAVE), 0, stream, a);
+  else hipLaunchKernelGGL(body_rollout_kernel<false>, grid, dim3(WAVE), 0, stream, a);
   return hipGetLastError();
 }
 

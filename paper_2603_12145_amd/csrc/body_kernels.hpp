@@ -24,6 +24,7 @@ struct BodyLaunch {
   int32_t T;
   int32_t max_episode_steps;
   float armature, joint_damping, friction_mu;
+  int32_t newton;        // contact model: 0 penalty spring + limit projection, 1 Newton on the soft-constraint QP
   const float* actions;  // [T,n,6] or nullptr
   float* obs;            // [T,n,17]
   float* reward;         // [T,n]

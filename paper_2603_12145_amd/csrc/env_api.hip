@@ -61,6 +61,7 @@ env_config_t default_config(int kind) {
   c.pixel_layout = ENV_PIXELS_SLOT_MAJOR;
   c.step_counter = ENV_STEP_COUNTER_HOST;
   c.obs_scaling = ENV_OBS_RAW;
+  c.contact_solver = ENV_CONTACT_PENALTY;
   (void)kind;
   return c;
 }
@@ -92,6 +93,11 @@ int merge_config(env_config_t* dst, const env_config_t* src) {
   if (sz >= FIELD_END(env_config_t, obs_scaling) && src->obs_scaling != 0) {
     if (src->obs_scaling != ENV_OBS_RAW && src->obs_scaling != ENV_OBS_NORMALIZED) return ENV_E_ARG;
     dst->obs_scaling = src->obs_scaling;
+  }
+  if (sz >= FIELD_END(env_config_t, contact_solver) && src->contact_solver != 0) {
+    if (src->contact_solver != ENV_CONTACT_PENALTY && src->contact_solver != ENV_CONTACT_NEWTON)
+      return ENV_E_ARG;
+    dst->contact_solver = src->contact_solver;
   }
   if (!std::isfinite(dst->armature) || !std::isfinite(dst->joint_damping) ||
       !std::isfinite(dst->friction_mu))
@@ -182,6 +188,7 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
     b.max_episode_steps = e->cfg.max_episode_steps;
     b.armature = e->cfg.armature; b.joint_damping = e->cfg.joint_damping;
     b.friction_mu = e->cfg.friction_mu;
+    b.newton = e->cfg.contact_solver == ENV_CONTACT_NEWTON;
     b.actions = static_cast<const float*>(actions);
     b.obs = static_cast<float*>(obs); b.reward = reward; b.done = done; b.stats = e->stats;
     err = launch_body_rollout(b, e->stream);
@@ -232,6 +239,7 @@ int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_c
   if (merge_config(&c, cfg) != ENV_OK) return ENV_E_ARG;
   if (c.step_counter == ENV_STEP_COUNTER_DEVICE && kind == ENV_PONG_PIXELS) return ENV_E_UNSUPPORTED;
   if (c.obs_scaling == ENV_OBS_NORMALIZED && kind != ENV_PONG) return ENV_E_UNSUPPORTED;
+  if (c.contact_solver == ENV_CONTACT_NEWTON && kind != ENV_BODY) return ENV_E_UNSUPPORTED;
 
   env_t* e = new (std::nothrow) env_t();
   if (!e) return ENV_E_ALLOC;

@@ -1,0 +1,173 @@
+"""GPU parity: articulated body with the Newton contact model (contact_solver = ENV_CONTACT_NEWTON),
+HIP path vs the float64 CPU oracle, through the C-ABI.  Same bar as the penalty model: a single
+step from an oracle-supplied float32 state within 1e-5 * max(|oracle|, 1) per component (a state
+that sits within rounding of a switching surface may flip a decision: at most 0.1 % of the
+environments), return statistics of 1000-step rollouts within 1 %."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+from oracle.body_binding import Body                   # noqa: E402
+from paper_2603_12145_amd import binding as b         # noqa: E402
+from paper_2603_12145_amd import inputs               # noqa: E402
+from gpu_helpers import assert_bit_equal              # noqa: E402
+from test_gpu_body import bufs, blob_from_oracle_state, state_from_blob, rel_err, TOL   # noqa: E402
+
+DEV = "cuda:0"
+NEWTON = {"contact_solver": b.ENV_CONTACT_NEWTON}
+
+
+def newton_states(n, seed, warm):
+    o = Body(n, seed, np.float64, solver=1)
+    o.reset()
+    if warm:
+        o.rollout(warm, nthreads=8, want_obs=False)
+    return o.get_state().astype(np.float32).astype(np.float64)
+
+
+@pytest.mark.parametrize("warm", [0, 3, 60, 400])
+def test_single_step_from_oracle_states(warm):
+    n, seed = 4096, 4
+    s = newton_states(n, seed, warm)
+    o = Body(n, seed, np.float64, solver=1); o.set_state(s); o.step_count = warm
+    oobs, orew, odone = o.rollout(1, nthreads=8)
+    ostate = o.get_state()
+    h = b.env_create(b.ENV_BODY, n, seed, NEWTON)
+    try:
+        b.env_set_state(h, blob_from_oracle_state(warm, s))
+        obs, rew, done = bufs(1, n)
+        b.env_step(h, None, obs[0], rew[0], done[0])
+        torch.cuda.synchronize()
+        step, gstate = state_from_blob(b.env_get_state(h), n)
+    finally:
+        b.env_destroy(h)
+    assert step == warm + 1
+    e_obs = rel_err(obs[0].cpu().numpy(), oobs[0]).max(axis=1)
+    e_state = rel_err(gstate[:, :18], ostate[:, :18]).max(axis=1)
+    e_rew = rel_err(rew[0].cpu().numpy(), orew[0])
+    worst = np.maximum(np.maximum(e_obs, e_state), e_rew)
+    flips = int((worst > TOL).sum())
+    print("newton warm=%d: median err %.2e, 99.9%% %.2e, max %.2e, beyond 1e-5: %d of %d"
+          % (warm, np.median(worst), np.quantile(worst, 0.999), worst.max(), flips, n))
+    assert flips <= n // 1000
+    assert np.median(worst) < 5e-7
+    assert np.array_equal(done[0].cpu().numpy(), odone[0])
+
+
+def test_single_step_with_external_actions():
+    n, seed, warm = 2048, 15, 25
+    s = newton_states(n, seed, warm)
+    acts = inputs.body_actions(1, n, seed=3, scale=1.5)
+    o = Body(n, seed, np.float64, solver=1); o.set_state(s); o.step_count = warm
+    oobs, orew, _ = o.rollout(1, actions=acts.astype(np.float64), nthreads=8)
+    h = b.env_create(b.ENV_BODY, n, seed, NEWTON)
+    try:
+        b.env_set_state(h, blob_from_oracle_state(warm, s))
+        obs, rew, done = bufs(1, n)
+        b.env_step(h, torch.from_numpy(acts[0]).to(DEV), obs[0], rew[0], done[0])
+        torch.cuda.synchronize()
+    finally:
+        b.env_destroy(h)
+    worst = np.maximum(rel_err(obs[0].cpu().numpy(), oobs[0]).max(axis=1), rel_err(rew[0].cpu().numpy(), orew[0]))
+    assert (worst > TOL).sum() <= n // 1000 and np.median(worst) < 5e-7
+
+
+def test_the_two_contact_models_differ_and_share_the_free_flight():
+    """Airborne bodies inside the joint range step identically under both models (to rounding);
+    bodies on the ground do not."""
+    n, seed = 512, 6
+    air = np.zeros((n, 20))
+    rng = np.random.default_rng(1)
+    air[:, :9] = rng.uniform(-0.8, 0.8, (n, 9)); air[:, 1] = rng.uniform(2.0, 3.0, n)
+    air[:, 9:18] = rng.normal(0, 1.0, (n, 9))
+    air = air.astype(np.float32).astype(np.float64)
+    ground = newton_states(n, seed, 40)
+    res = {}
+    zero = torch.zeros((n, 6), dtype=torch.float32, device=DEV)
+    for name, s in (("air", air), ("ground", ground)):
+        for solver in (b.ENV_CONTACT_PENALTY, b.ENV_CONTACT_NEWTON):
+            h = b.env_create(b.ENV_BODY, n, seed, {"contact_solver": solver})
+            try:
+                b.env_set_state(h, blob_from_oracle_state(0, s))
+                obs, rew, done = bufs(1, n)
+                b.env_step(h, zero, obs[0], rew[0], done[0])     # no torque: no joint reaches a limit
+                torch.cuda.synchronize()
+                res[name, solver] = obs[0].cpu().numpy()
+            finally:
+                b.env_destroy(h)
+    d_air = np.abs(res["air", 1] - res["air", 2]).max()
+    d_ground = np.abs(res["ground", 1] - res["ground", 2]).max(axis=1)
+    assert d_air < 2e-5
+    assert np.median(d_ground) > 1e-3
+
+
+@pytest.mark.parametrize("n", [1, 63, 65, 200])
+def test_rollout_equals_steps_bit_for_bit_and_ragged_batches(n):
+    seed, T = 8, 30
+    outs = []
+    for fused in (True, False):
+        h = b.env_create(b.ENV_BODY, n, seed, dict(NEWTON, max_episode_steps=12))
+        try:
+            b.env_reset(h, None)
+            obs, rew, done = bufs(T, n)
+            if fused:
+                b.env_rollout(h, T, None, obs, rew, done)
+            else:
+                for t in range(T):
+                    b.env_step(h, None, obs[t], rew[t], done[t])
+            torch.cuda.synchronize()
+            outs.append((obs.cpu().numpy(), rew.cpu().numpy(), done.cpu().numpy(), b.env_get_state(h),
+                         b.env_stats(h)))
+        finally:
+            b.env_destroy(h)
+    for k in range(3):
+        assert_bit_equal(outs[0][k], outs[1][k], "fused vs per-step output %d" % k)
+    assert np.array_equal(outs[0][3], outs[1][3])
+    assert outs[0][4]["episodes"] == outs[1][4]["episodes"] == 2 * n and outs[0][4]["nonfinite"] == 0
+
+
+def test_env_i_independent_of_batch_size():
+    seed, T = 21, 40
+    res = []
+    for n in (100, 1000):
+        h = b.env_create(b.ENV_BODY, n, seed, NEWTON)
+        try:
+            b.env_reset(h, None)
+            obs, rew, done = bufs(T, n)
+            b.env_rollout(h, T, None, obs, rew, done)
+            torch.cuda.synchronize()
+            res.append(obs[:, :100].cpu().numpy())
+        finally:
+            b.env_destroy(h)
+    assert_bit_equal(res[0], res[1], "first 100 environments")
+
+
+def test_n8192_t1000_return_statistics():
+    n, seed, T = 8192, 4, 1000
+    h = b.env_create(b.ENV_BODY, n, seed, NEWTON)
+    try:
+        b.env_reset(h, None)
+        obs, rew, done = bufs(T, n)
+        b.env_rollout(h, T, None, obs, rew, done)
+        torch.cuda.synchronize()
+        st = b.env_stats(h)
+        g_ret = rew.sum(dim=0, dtype=torch.float64).cpu().numpy()
+        finite = bool(torch.isfinite(obs).all().item())
+        del obs, rew, done
+    finally:
+        b.env_destroy(h)
+    o = Body(n, seed, np.float64, solver=1, round_state_f32=1)
+    o.reset()
+    _, orew, _ = o.rollout(T, nthreads=16, want_obs=False)
+    o_ret = orew.sum(axis=0)
+    ost = o.stats()
+    assert finite and st["nonfinite"] == 0 == ost["nonfinite"] and st["episodes"] == n == ost["episodes"]
+    gm, om = g_ret.mean(), o_ret.mean()
+    se = np.sqrt((g_ret.var() + o_ret.var()) / n)
+    print("newton returns: GPU mean %.3f sd %.2f | oracle mean %.3f sd %.2f | diff %.3f (%.2f %%), s.e. %.3f"
+          % (gm, g_ret.std(), om, o_ret.std(), gm - om, 100 * abs(gm - om) / abs(om), se))
+    assert abs(gm - om) <= 0.01 * abs(om)
+    assert abs(g_ret.std() - o_ret.std()) <= 0.05 * o_ret.std()
+    assert abs(st["return_sum"] / n - gm) < 1e-2
