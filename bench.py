@@ -29,6 +29,7 @@ PONG_BYTES_PER_ENV_STEP = 37   # 32 obs + 4 reward + 1 done
 CARTPOLE_BYTES_PER_ENV_STEP = 21   # 16 obs + 4 reward + 1 done
 FRAME_BYTES = 84 * 84          # one new frame per env-step
 FP64_PEAK_TFLOPS = 78.6        # MI355X vector float64 (256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz)
+BODY_NEWTON_FLOP_PER_ENV_STEP = 13540   # 5 substeps x (1526 outside the Newton loop + 1.05 solves per environment x 1126), counted in the kernel ISA; a wavefront executes max-over-lanes solves (3.0 on average), which is not counted as useful work
 BODY_FLOP_PER_ENV_STEP = 9400   # 5 substeps x 1876 float64 flops (FMA = 2), counted in the substep loop of the kernel ISA
 
 
@@ -218,9 +219,9 @@ def bench_copy(b, torch, nbytes, launches=20):
                 gbs_each_way=nbytes / (mean_ms * 1e-3) / 1e9)
 
 
-def bench_body(b, torch, n, T, seed, steps):
+def bench_body(b, torch, n, T, seed, steps, newton=False):
     dev = "cuda:0"
-    h = b.env_create(b.ENV_BODY, n, seed, None)
+    h = b.env_create(b.ENV_BODY, n, seed, {"contact_solver": b.ENV_CONTACT_NEWTON} if newton else None)
     obs = torch.empty((T, n, 17), dtype=torch.float32, device=dev)
     rew = torch.empty((T, n), dtype=torch.float32, device=dev)
     done = torch.empty((T, n), dtype=torch.uint8, device=dev)
@@ -229,6 +230,14 @@ def bench_body(b, torch, n, T, seed, steps):
     st = b.env_stats(h)
     b.env_destroy(h)
     mean_ms, std_ms = _mean_std(ms)
+    if newton:
+        flops = BODY_NEWTON_FLOP_PER_ENV_STEP * n * T / (mean_ms * 1e-3) / 1e12
+        return dict(workload="articulated body, Newton contact model, N=%d x T=%d fused rollout" % (n, T),
+                    dtype="f64 in-step arithmetic, f32 state and I/O",
+                    env_steps_per_s=n * T * steps / wall, ms_per_launch=mean_ms,
+                    nonfinite=st["nonfinite"], episodes=st["episodes"],
+                    roofline=dict(bound="alu", achieved=flops, peak=FP64_PEAK_TFLOPS, unit="TFLOP/s",
+                                  frac=flops / FP64_PEAK_TFLOPS, traffic=None))
     flops = BODY_FLOP_PER_ENV_STEP * n * T / (mean_ms * 1e-3) / 1e12
     return dict(workload="articulated body N=%d x T=%d fused rollout" % (n, T), dtype="f64 in-step arithmetic, f32 state and I/O",
                 env_steps_per_s=n * T * steps / wall, ms_per_launch=mean_ms,
@@ -383,6 +392,8 @@ def main():
         fn = {"pixels": lambda: bench_pixels(b, torch, 16384, 3, args.steps),
               "per_step": lambda: bench_pong_per_step(b, torch, 4096, 1, args.steps),
               "body": lambda: bench_body(b, torch, 8192, 1000, 4, args.steps),
+              "body_newton": lambda: [bench_body(b, torch, 8192, 1000, 4, args.steps, newton=True),
+                                      bench_body(b, torch, 262144, 100, 4, args.steps, newton=True)],
               "policy": lambda: [bench_policy_loop(b, torch, 4096, "mlp", 2000, 50),
                                  bench_policy_loop(b, torch, 65536, "mlp", 2000, 50),
                                  bench_policy_loop(b, torch, 4096, "gru", 1000, 50)],
@@ -431,6 +442,7 @@ def main():
                                              frac=gbs / HBM_PEAK_GBS)
         extra["config4_body"] = bench_body(b, torch, 8192, 1000, 4, 2)
         extra["config4_body_n262144_t100"] = bench_body(b, torch, 262144, 100, 4, 2)
+        extra["body_newton_n8192_t1000"] = bench_body(b, torch, 8192, 1000, 4, 2, newton=True)
         extra["cartpole_n65536_t1000"] = bench_cartpole(b, torch, 65536, 1000, 2, 5)
         extra["policy_in_loop_mlp_n4096"] = bench_policy_loop(b, torch, 4096, "mlp", 2000, 50)
         extra["policy_in_loop_gru2m_n4096"] = bench_policy_loop(b, torch, 4096, "gru", 1000, 50)
