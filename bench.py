@@ -366,8 +366,8 @@ def cpu_baseline(n, T, seed):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--n", type=int, default=65536, help="environments (headline: 65536)")
     ap.add_argument("--T", type=int, default=1000)
     ap.add_argument("--skip-extra", action="store_true")

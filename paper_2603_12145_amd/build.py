@@ -2,7 +2,11 @@
 
 Flags: -ffp-contract=off so that no multiply-add is fused behind the source's back (the Pong path is
 compared bit for bit with a scalar CPU implementation; where the body wants an FMA it asks for one
-explicitly), and packed-FP32 instruction selection is disabled.
+explicitly), and packed-FP32 instruction selection is disabled.  The instruction scheduler is told to
+maximise instruction-level parallelism rather than occupancy: the rollout kernels run one wavefront
+per SIMD at the headline size, so only independent instructions of the same wavefront can hide the
+latency of a dependent chain (Pong N = 65536 x T = 1000: 0.47 ms instead of 0.53 ms per launch; the
+other kernels are unaffected).
 """
 import glob
 import os
@@ -16,6 +20,7 @@ LIB = os.path.join(HERE, "libmi355env.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-ffp-contract=off",
          "-fno-fast-math", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-mllvm", "-amdgpu-sched-strategy=max-ilp",
          "-Wall", "-Wno-unused-command-line-argument"]
 
 

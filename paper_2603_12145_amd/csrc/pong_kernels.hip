@@ -40,40 +40,62 @@ __global__ __launch_bounds__(256) void pong_reset_kernel(uint32_t* __restrict__ 
 // out as one byte per lane: the 64 bytes of a wavefront are contiguous, so the memory pipeline
 // sees a single 64-byte write either way, and packing them by hand (ballot, shift, spread) only
 // added ~25 instructions per step.
-template <bool FULL, bool EXTERNAL_ACTIONS, bool NORMALIZE>
+//
+// The Philox blocks are drawn CHUNK steps at a time, one chunk ahead: the draws do not depend on
+// the state, so the 2 * CHUNK multiply chains of a chunk are independent of each other and of the
+// compare/select chains of the transitions they are scheduled between.  With one wavefront per
+// SIMD (N = 65536) nothing else hides the latency of a dependent chain.
+//
+// PAGED (needs a full 256-thread workgroup, see the kernel): the 32-byte observation of a lane is
+// handed through LDS so that each of the two store instructions of a step covers 1 KiB of
+// contiguous memory per wavefront and the four wavefronts of a workgroup write one 4 KiB page after
+// the other, instead of two half-dense instructions per wavefront over its own 2 KiB.
+constexpr int CHUNK = 4;
+
+template <bool FULL, bool EXTERNAL_ACTIONS, bool NORMALIZE, bool PAGED>
 __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, LaneEpisodes& le,
-                                             const int lane, const int64_t wave_base) {
+                                             const int lane, const int64_t wave_base,
+                                             float4* __restrict__ stage, const int64_t block_base) {
   const int64_t n = a.n;
   const uint32_t env = (uint32_t)(wave_base + lane);
   const bool live = FULL || (wave_base + lane < n);
-  float* obs_row = a.obs + wave_base * PONG_OBS;
+  float* obs_row = a.obs + (PAGED ? block_base : wave_base) * PONG_OBS;
   float* rew_row = a.reward + wave_base;
   uint8_t* done_row = a.done + wave_base;
   const uint8_t* act_row = EXTERNAL_ACTIONS ? a.actions + wave_base : nullptr;
+  int parity = 0;
 
-  Draw4 d = philox_draw(a.seed, env, a.step0, 0u);
-  for (int32_t t = 0; t < a.T; ++t) {
-    // draw of the next step first: it does not depend on the state, so its multiply chain
-    // overlaps the compare/select chain of this step's transition
-    const Draw4 d_next = philox_draw(a.seed, env, a.step0 + (uint64_t)t + 1u, 0u);
+  auto one_step = [&](const Draw4& d) {
     int action;
     if (EXTERNAL_ACTIONS) action = live ? (int)act_row[lane] : 0;
     else action = pong_action_from_word(d.w0);
-
     const PongEvent ev = pong_transition(s, action, d.w1, d.w2, a.max_score);
     const bool done = live && ev.done;
-    // selects, not a branch: the loop body stays one basic block, which lets the scheduler
-    // interleave the next step's Philox rounds with this step's transition
+    // selects, not a branch: the loop body stays one basic block
     le.count += done ? 1 : 0;
     le.length_sum += done ? ev.fin_len : 0;
     le.ret_sum_i += done ? ev.fin_ret : 0;
     le.min_key = done ? min(le.min_key, ev.fin_ret) : le.min_key;
     le.max_key = done ? max(le.max_key, ev.fin_ret) : le.max_key;
-
-    if (live) {
+    float4 lo, hi;
+    pong_observe<NORMALIZE>(s, a.inv_score, lo, hi);
+    if (PAGED) {
+      // two buffers, one barrier per step: a thread reaches the barrier of step t+1 only after
+      // its reads of step t have landed (the global stores below need them), so the buffer of
+      // step t is free again when step t+2 writes it
+      float4* st = stage + parity * 512;
+      st[2 * threadIdx.x] = lo;
+      st[2 * threadIdx.x + 1] = hi;
+      __syncthreads();
+      const float4 p0 = st[threadIdx.x], p1 = st[256 + threadIdx.x];
+      float4* o = reinterpret_cast<float4*>(obs_row);
+      o[threadIdx.x] = p0;
+      o[256 + threadIdx.x] = p1;
+      parity ^= 1;
+      rew_row[lane] = ev.reward;
+      done_row[lane] = done ? 1 : 0;
+    } else if (live) {
       float4* o = reinterpret_cast<float4*>(obs_row + lane * PONG_OBS);
-      float4 lo, hi;
-      pong_observe<NORMALIZE>(s, a.inv_score, lo, hi);
       o[0] = lo;
       o[1] = hi;
       rew_row[lane] = ev.reward;
@@ -83,8 +105,25 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
     rew_row += n;
     done_row += n;
     if (EXTERNAL_ACTIONS) act_row += n;
-    d = d_next;
+  };
+
+  int32_t t = 0;
+  if (a.T >= CHUNK) {
+    Draw4 cur[CHUNK];
+#pragma unroll
+    for (int c = 0; c < CHUNK; ++c) cur[c] = philox_draw(a.seed, env, a.step0 + (uint64_t)c, 0u);
+    for (; t + CHUNK <= a.T; t += CHUNK) {
+      Draw4 nxt[CHUNK];
+#pragma unroll
+      for (int c = 0; c < CHUNK; ++c)
+        nxt[c] = philox_draw(a.seed, env, a.step0 + (uint64_t)(t + CHUNK + c), 0u);
+#pragma unroll
+      for (int c = 0; c < CHUNK; ++c) one_step(cur[c]);
+#pragma unroll
+      for (int c = 0; c < CHUNK; ++c) cur[c] = nxt[c];
+    }
   }
+  for (; t < a.T; ++t) one_step(philox_draw(a.seed, env, a.step0 + (uint64_t)t, 0u));
 }
 
 template <bool XCD_REMAP>
@@ -108,21 +147,27 @@ __global__ __launch_bounds__(256) void pong_rollout_kernel(PongLaunch a) {
 
   PongLane s = live ? pong_load(a.state, n, i) : pong_idle_lane();
   LaneEpisodes le;
+  // paged stores need every thread of a 256-thread workgroup at the barrier of every step
+  __shared__ float4 stage[2 * 512];
+  const int64_t block_base = (int64_t)logical_block * blockDim.x;
+  const bool paged = a.paged && blockDim.x == 256 && block_base + 256 <= n;      // workgroup-uniform
   if (a.normalize) {                    // the optional form takes the general (predicated) loop
-    if (a.actions) rollout_wave<false, true, true>(a, s, le, lane, wave_base);
-    else rollout_wave<false, false, true>(a, s, le, lane, wave_base);
+    if (a.actions) rollout_wave<false, true, true, false>(a, s, le, lane, wave_base, stage, block_base);
+    else rollout_wave<false, false, true, false>(a, s, le, lane, wave_base, stage, block_base);
   } else if (a.actions) {
-    if (full) rollout_wave<true, true, false>(a, s, le, lane, wave_base);
-    else rollout_wave<false, true, false>(a, s, le, lane, wave_base);
+    if (full) rollout_wave<true, true, false, false>(a, s, le, lane, wave_base, stage, block_base);
+    else rollout_wave<false, true, false, false>(a, s, le, lane, wave_base, stage, block_base);
   } else {
-    if (full) rollout_wave<true, false, false>(a, s, le, lane, wave_base);
-    else rollout_wave<false, false, false>(a, s, le, lane, wave_base);
+    if (paged) rollout_wave<true, false, false, true>(a, s, le, lane, wave_base, stage, block_base);
+    else if (full) rollout_wave<true, false, false, false>(a, s, le, lane, wave_base, stage, block_base);
+    else rollout_wave<false, false, false, false>(a, s, le, lane, wave_base, stage, block_base);
   }
   if (live) pong_store(a.state, n, i, s);
   flush_wave_stats<false>(a.stats, le);
 }
 
 int g_rollout_block = 0;   // 0 = choose from N
+int g_paged_mode = 2;      // 0 never, 1 whenever possible, 2 = choose from N
 int g_xcd_remap = 1;
 
 }  // namespace
@@ -136,6 +181,12 @@ hipError_t launch_pong_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t
 }
 
 // Measurement knob: threads per workgroup of the rollout kernel (64, 128, 256; 0 = automatic).
+bool set_paged_stores(int mode) {
+  if (mode < 0 || mode > 2) return false;
+  g_paged_mode = mode;
+  return true;
+}
+
 bool set_rollout_block(int threads, int xcd_remap) {
   if (threads != 0 && threads != 64 && threads != 128 && threads != 256) return false;
   g_rollout_block = threads;
@@ -148,8 +199,14 @@ hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream) {
   unsigned blocks = (unsigned)((a.n + block - 1) / block);
   blocks = (blocks + 7u) & ~7u;   // multiple of the XCD count; surplus workgroups exit at once
   const dim3 g(blocks), b(block);
-  if (g_xcd_remap) hipLaunchKernelGGL(pong_rollout_kernel<true>, g, b, 0, stream, a);
-  else hipLaunchKernelGGL(pong_rollout_kernel<false>, g, b, 0, stream, a);
+  // Paged observation stores pay a barrier and an LDS round trip per step.  With one wavefront per
+  // SIMD (N <= 65536) that latency is exposed and the direct stores are faster (0.47 vs 0.58 ms at
+  // N = 65536 x T = 1000); from two wavefronts per SIMD on, the launch is bound by the write
+  // stream and the denser pattern wins (1.86 vs 2.13 ms at N = 262144).
+  PongLaunch a2 = a;
+  a2.paged = g_paged_mode == 2 ? (a.n >= 131072) : g_paged_mode;
+  if (g_xcd_remap) hipLaunchKernelGGL(pong_rollout_kernel<true>, g, b, 0, stream, a2);
+  else hipLaunchKernelGGL(pong_rollout_kernel<false>, g, b, 0, stream, a2);
   return hipGetLastError();
 }
 

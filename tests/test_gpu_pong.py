@@ -322,3 +322,18 @@ def test_normalised_observations_only_for_pong_vectors():
         with pytest.raises(b.EnvError) as ei:
             b.env_create(kind, 64, 0, {"obs_scaling": b.ENV_OBS_NORMALIZED})
         assert ei.value.code == b.ENV_E_UNSUPPORTED
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("n,T", [(868, 7), (868, 250), (256, 4), (2048, 33)])
+def test_both_store_paths_and_every_chunk_remainder(mode, n, T):
+    """The rollout draws its Philox blocks four steps at a time and has two ways of storing
+    observations (direct; through LDS, one 4 KiB page per store instruction, for full 256-thread
+    workgroups).  Both paths, forced on at sizes that mix full and ragged workgroups and at step
+    counts with every remainder modulo 4, must reproduce the oracle bit for bit."""
+    assert b.lib().mi355env_tune_paged_stores(mode) == 0
+    try:
+        g = gpu_rollout(n, 23, T, max_score=2)
+    finally:
+        assert b.lib().mi355env_tune_paged_stores(2) == 0
+    compare(g, oracle_rollout(n, 23, T, max_score=2), n, "stores mode %d n=%d T=%d" % (mode, n, T))
