@@ -1,0 +1,46 @@
+/* mi355env — measurement knobs and yardstick kernels of libmi355env.so.
+ *
+ * Not part of the environment boundary (include/mi355env.h): these exist so that the benchmark and
+ * the tests can time a launch shape against another, force a code path that the library would
+ * otherwise choose from N, and measure what the device does for a plain fill, copy or empty
+ * launch.  All settings are process-wide, take effect at the next launch and are not thread-safe.
+ * Return ENV_OK (0) or ENV_E_ARG (-1) unless stated.
+ */
+#ifndef MI355ENV_TUNING_H
+#define MI355ENV_TUNING_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Pong / cart-pole rollout: threads per workgroup (64, 128, 256; 0 = default 256) and whether
+ * workgroups are remapped so that each XCD owns a contiguous eighth of the environments (default 1). */
+int mi355env_tune_rollout(int threads_per_block, int xcd_remap);
+
+/* Pong rollout observation stores: 0 = direct (two 16-byte stores per lane), 1 = through LDS, one
+ * 4 KiB page per store instruction, wherever a 256-thread workgroup is full, 2 = chosen from N
+ * (default: paged for N >= 131072). */
+int mi355env_tune_paged_stores(int mode);
+
+/* Wave-tile pixel renderer (env-major ring, env_rollout frames): environments per wavefront
+ * (4, 8, 16, 32 or 64) and streaming (non-temporal) stores (0 / 1). */
+int mi355env_tune_pixels(int envs_per_wave, int streaming);
+
+/* Slot-major pixel env_step: 0 = wave-tile renderer, 1 = page renderer as separate launches,
+ * 2 = page renderer fused with the next step's dynamics in one launch (default). */
+int mi355env_tune_plane_path(int mode);
+
+/* Yardsticks, launched on hip_stream: dst[i] = value; dst = src; a kernel that does nothing.
+ * Pointers are device memory, 16-byte aligned, bytes a multiple of 16 (else -1); -3 if the launch
+ * fails. */
+int mi355env_bench_fill(void *dst_dev, size_t bytes, uint32_t value, void *hip_stream);
+int mi355env_bench_copy(void *dst_dev, const void *src_dev, size_t bytes, void *hip_stream);
+int mi355env_bench_empty(void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MI355ENV_TUNING_H */
