@@ -200,3 +200,37 @@ def test_graph_replay_body_policy_in_the_loop():
     acts = np.stack([r[0] for r in rec])
     assert np.isfinite(obs).all() and np.abs(acts).max() > 0.05
     assert np.abs(obs[-1] - obs[0]).max() > 1e-3
+
+
+def test_graph_replay_of_a_fused_rollout_launch():
+    """A captured env_rollout (T = 8, in-kernel actions) replayed five times continues the step
+    sequence exactly as 40 direct steps do: trajectory buffers of every replay match the oracle."""
+    n, T, K = 700, 8, 5
+    s = torch.cuda.Stream()
+    h = b.env_create(b.ENV_PONG, n, 31, dict(DEVICE_COUNTER, max_score=1), stream=s)
+    try:
+        with torch.cuda.stream(s):
+            obs, rew, done = _bufs(b.ENV_PONG, n, T)
+            b.env_reset(h, None)
+            b.env_rollout(h, T, None, obs, rew, done)            # direct call: validates the buffers
+            s.synchronize()
+            got = [(obs.cpu().numpy().copy(), rew.cpu().numpy().copy(), done.cpu().numpy().copy())]
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=s):
+                b.env_rollout(h, T, None, obs, rew, done)
+            for _ in range(K):
+                g.replay()
+                s.synchronize()
+                got.append((obs.cpu().numpy().copy(), rew.cpu().numpy().copy(), done.cpu().numpy().copy()))
+            assert b.env_step_count(h) == T * (K + 1)
+            st = b.env_stats(h)
+    finally:
+        b.env_destroy(h)
+    p = orc.Pong(n, 31, max_score=1)
+    p.reset()
+    for k in range(K + 1):
+        oo, orr, od = p.rollout(T)
+        assert_bit_equal(got[k][0], oo, "launch %d obs" % k)
+        assert_bit_equal(got[k][1], orr, "launch %d reward" % k)
+        assert_bit_equal(got[k][2], od, "launch %d done" % k)
+    assert st["episodes"] == p.stats()["episodes"] > 0
