@@ -1,6 +1,7 @@
 // Planar articulated body ("HalfCheetah-like", paper App. A.1: forward kinematics, mass matrix,
 // bias forces, contact Jacobians, Cholesky; first solver revision = penalty spring): reset and the
-// fused T-step rollout (T = 1 is env_step).  One lane per environment, everything in registers.
+// fused T-step rollout (T = 1 is env_step).  Two lanes per environment (one per leg), everything in
+// registers.
 //
 // Model: q = (x, z, theta, b1, b2, b3, f1, f2, f3); torso of length 1 with the hips at its ends;
 // each leg a chain thigh / shin / foot of uniform rods hanging along d(phi) = (sin phi, -cos phi),
@@ -16,6 +17,10 @@
 //  * the two legs couple only through the root, so with the ordering (back joints, front joints,
 //    root) the Cholesky factor has no fill between the legs: two 3x3 factorisations, two 3x3
 //    triangular solves with three right-hand sides, one 3x3 Schur complement;
+//  * that structure is also the work split: lane 2i carries the root and the back leg of
+//    environment i, lane 2i+1 the root and the front leg; each builds and factors its own leg block,
+//    the root's mass, right-hand side and Schur complement are sums of the two lanes' parts (one
+//    DPP quad permutation per 32-bit half), and both lanes solve the same 3x3 root system;
 //  * sin / cos of the six joint angles (always in [-1, 1]) come from a polynomial without range
 //    reduction, the link angles from angle addition on top of one sincos of the pitch.
 //
@@ -263,126 +268,13 @@ __device__ __forceinline__ void backward_leg(const LegFactor& f, const real y[3]
   x[0] = (t[0] - f.l10 * x[1] - f.l20 * x[2]) * f.i00;
 }
 
-// Solve the 9x9 system with the joints in `keep` (others: v = 0).  R = root block
-// (Mtot, Mtot, m_xth, m_zth, m_thth); b = right-hand side (root 3, back 3, front 3).
-struct RootBlock { real xx, xz, xth, zz, zth, thth; };
-
-template <class Block>
-__device__ __forceinline__ void solve_system(const Block& gb, const Block& gf, const RootBlock& R,
-                                             const bool keep_b[3], const bool keep_f[3],
-                                             const real b_root[3], const real b_back[3], const real b_front[3],
-                                             real x_root[3], real x_back[3], real x_front[3]) {
-  LegFactor fb, ff;
-  factor_leg(fb, gb, keep_b);
-  factor_leg(ff, gf, keep_f);
-  real bb[3], bf[3], yb[3], yf[3];
-#pragma unroll
-  for (int k = 0; k < 3; ++k) { bb[k] = keep_b[k] ? b_back[k] : 0.0; bf[k] = keep_f[k] ? b_front[k] : 0.0; }
-  forward_leg(fb, bb, yb);
-  forward_leg(ff, bf, yf);
-  // Schur complement of the root block (symmetric 3x3: xx xz xth zz zth thth)
-  real s[3][3] = {{R.xx, R.xz, R.xth}, {R.xz, R.zz, R.zth}, {R.xth, R.zth, R.thth}};
-  real br[3];
-#pragma unroll
-  for (int r = 0; r < 3; ++r) {
-#pragma unroll
-    for (int c = 0; c <= r; ++c) {
-      real acc = 0.0;
-#pragma unroll
-      for (int k = 0; k < 3; ++k) acc += fb.Y[k][r] * fb.Y[k][c] + ff.Y[k][r] * ff.Y[k][c];
-      s[r][c] -= acc;
-    }
-    real acc = 0.0;
-#pragma unroll
-    for (int k = 0; k < 3; ++k) acc += fb.Y[k][r] * yb[k] + ff.Y[k][r] * yf[k];
-    br[r] = b_root[r] - acc;
-  }
-  const real i00 = inv_sqrt(s[0][0]);
-  const real l10 = s[1][0] * i00, l20 = s[2][0] * i00;
-  const real i11 = inv_sqrt(s[1][1] - l10 * l10);
-  const real l21 = (s[2][1] - l20 * l10) * i11;
-  const real i22 = inv_sqrt(s[2][2] - l20 * l20 - l21 * l21);
-  const real y0 = br[0] * i00;
-  const real y1 = (br[1] - l10 * y0) * i11;
-  const real y2 = (br[2] - l20 * y0 - l21 * y1) * i22;
-  x_root[2] = y2 * i22;
-  x_root[1] = (y1 - l21 * x_root[2]) * i11;
-  x_root[0] = (y0 - l10 * x_root[1] - l20 * x_root[2]) * i00;
-  backward_leg(fb, yb, x_root, x_back);
-  backward_leg(ff, yf, x_root, x_front);
-}
+struct RootBlock { real xx, xz, xth, zz, zth, thth; };   // symmetric 3x3 over (x, z, pitch)
 
 struct BodyLane {
   real q[9], v[9];
   float ep_ret;
   int ep_len;
 };
-
-// One substep in place.  a[6]: clipped actions.
-__device__ __forceinline__ void body_substep(BodyLane& s, const real a[6], const Params& P) {
-  real st, ct;
-  sincos(s.q[2], &st, &ct);
-  Leg gb, gf;
-  LegRows unused;
-  leg_terms<false>(gb, unused, -1.0, st, ct, s.q[1], s.v[0], s.v[1], s.v[2], &s.q[3], &s.v[3], P);
-  leg_terms<false>(gf, unused, +1.0, st, ct, s.q[1], s.v[0], s.v[1], s.v[2], &s.q[6], &s.v[6], P);
-  const real mxth = gb.Pth.x + gf.Pth.x, mzth = gb.Pth.z + gf.Pth.z;
-  const real mthth = IT + gb.mthth + gf.mthth;
-  const RootBlock R = {MTOT, 0.0, mxth, MTOT, mzth, mthth};
-
-  // b = M v + h * rhs
-  real b_root[3], b_back[3], b_front[3];
-  const real vx = s.v[0], vz = s.v[1], vth = s.v[2];
-  real mv_x = MTOT * vx + mxth * vth, mv_z = MTOT * vz + mzth * vth;
-  real mv_th = mxth * vx + mzth * vz + mthth * vth;
-#pragma unroll
-  for (int m = 0; m < 3; ++m) {
-    mv_x += gb.C[0][m] * s.v[3 + m] + gf.C[0][m] * s.v[6 + m];
-    mv_z += gb.C[1][m] * s.v[3 + m] + gf.C[1][m] * s.v[6 + m];
-    mv_th += gb.C[2][m] * s.v[3 + m] + gf.C[2][m] * s.v[6 + m];
-  }
-  b_root[0] = mv_x + STEP_H * (gb.rhs_x + gf.rhs_x);
-  b_root[1] = mv_z + STEP_H * (-GRAVITY * MTOT + gb.rhs_z + gf.rhs_z);
-  b_root[2] = mv_th + STEP_H * (gb.rhs_th + gf.rhs_th);
-  const int sym[3][3] = {{0, 1, 2}, {1, 3, 4}, {2, 4, 5}};
-#pragma unroll
-  for (int m = 0; m < 3; ++m) {
-    real mb = gb.C[0][m] * vx + gb.C[1][m] * vz + gb.C[2][m] * vth;
-    real mf = gf.C[0][m] * vx + gf.C[1][m] * vz + gf.C[2][m] * vth;
-#pragma unroll
-    for (int k = 0; k < 3; ++k) {
-      mb += gb.A[sym[m][k]] * s.v[3 + k];
-      mf += gf.A[sym[m][k]] * s.v[6 + k];
-    }
-    b_back[m] = mb + STEP_H * (gb.rhs[m] + GEAR * a[m] - P.damping * s.v[3 + m]);
-    b_front[m] = mf + STEP_H * (gf.rhs[m] + GEAR * a[3 + m] - P.damping * s.v[6 + m]);
-  }
-
-  // unconstrained velocity, then the joints to freeze, then the projected velocity
-  const bool all[3] = {true, true, true};
-  real x_root[3], x_back[3], x_front[3];
-  solve_system(gb, gf, R, all, all, b_root, b_back, b_front, x_root, x_back, x_front);
-  bool keep_b[3], keep_f[3];
-#pragma unroll
-  for (int m = 0; m < 3; ++m) {
-    keep_b[m] = !((s.q[3 + m] >= 1.0 && x_back[m] > 0.0) || (s.q[3 + m] <= -1.0 && x_back[m] < 0.0));
-    keep_f[m] = !((s.q[6 + m] >= 1.0 && x_front[m] > 0.0) || (s.q[6 + m] <= -1.0 && x_front[m] < 0.0));
-  }
-  // lanes with nothing to freeze get the same numbers again; the wavefront skips the second solve
-  // only when no lane needs it
-  const bool any_frozen = !(keep_b[0] && keep_b[1] && keep_b[2] && keep_f[0] && keep_f[1] && keep_f[2]);
-  if (__ballot(any_frozen) != 0ull)
-    solve_system(gb, gf, R, keep_b, keep_f, b_root, b_back, b_front, x_root, x_back, x_front);
-
-#pragma unroll
-  for (int m = 0; m < 3; ++m) {
-    s.v[m] = x_root[m]; s.v[3 + m] = x_back[m]; s.v[6 + m] = x_front[m];
-  }
-#pragma unroll
-  for (int j = 0; j < 9; ++j) s.q[j] = s.q[j] + STEP_H * s.v[j];
-#pragma unroll
-  for (int j = 3; j < 9; ++j) s.q[j] = s.q[j] < -1.0 ? -1.0 : (s.q[j] > 1.0 ? 1.0 : s.q[j]);
-}
 
 
 // ---- Newton contact model ---------------------------------------------------------------------------
@@ -465,64 +357,6 @@ __device__ __forceinline__ void leg_add_rows(const Leg& g, const LegRows& rows, 
   }
 }
 
-// One substep in place, Newton contact model.  a[6]: clipped actions.
-__device__ __forceinline__ void body_substep_newton(BodyLane& s, const real a[6], const Params& P) {
-  real st, ct;
-  sincos(s.q[2], &st, &ct);
-  Leg gb, gf;
-  LegRows rb, rf;
-  leg_terms<true>(gb, rb, -1.0, st, ct, s.q[1], s.v[0], s.v[1], s.v[2], &s.q[3], &s.v[3], P);
-  leg_terms<true>(gf, rf, +1.0, st, ct, s.q[1], s.v[0], s.v[1], s.v[2], &s.q[6], &s.v[6], P);
-  const RootBlock R0 = {MTOT, 0.0, gb.Pth.x + gf.Pth.x, MTOT, gb.Pth.z + gf.Pth.z, IT + gb.mthth + gf.mthth};
-
-  // generalised force without constraints: f = M a0
-  real f_root[3], f_back[3], f_front[3];
-  f_root[0] = gb.rhs_x + gf.rhs_x;
-  f_root[1] = -GRAVITY * MTOT + gb.rhs_z + gf.rhs_z;
-  f_root[2] = gb.rhs_th + gf.rhs_th;
-#pragma unroll
-  for (int m = 0; m < 3; ++m) {
-    f_back[m] = gb.rhs[m] + GEAR * a[m] - P.damping * s.v[3 + m];
-    f_front[m] = gf.rhs[m] + GEAR * a[3 + m] - P.damping * s.v[6 + m];
-  }
-  const bool all[3] = {true, true, true};
-  real x_root[3], x_back[3], x_front[3];
-  solve_system(gb, gf, R0, all, all, f_root, f_back, f_front, x_root, x_back, x_front);
-
-  uint32_t prev = 0;
-  for (int pass = 0; pass < NEWTON_MAX_PASSES; ++pass) {
-    const uint32_t set = leg_active_set(gb, rb, &s.q[3], &s.v[3], x_root, x_back, P) |
-                         (leg_active_set(gf, rf, &s.q[6], &s.v[6], x_root, x_front, P) << 16);
-    // pass 0 compares with the empty set: no row active = the unconstrained acceleration stands
-    if (__ballot(set != prev) == 0ull) break;
-    LegBlock Bb, Bf;
-#pragma unroll
-    for (int k = 0; k < 6; ++k) { Bb.A[k] = gb.A[k]; Bf.A[k] = gf.A[k]; }
-#pragma unroll
-    for (int r = 0; r < 3; ++r)
-#pragma unroll
-      for (int c = 0; c < 3; ++c) { Bb.C[r][c] = gb.C[r][c]; Bf.C[r][c] = gf.C[r][c]; }
-    RootBlock R = R0;
-    real g_root[3], g_back[3], g_front[3];
-#pragma unroll
-    for (int m = 0; m < 3; ++m) { g_root[m] = f_root[m]; g_back[m] = f_back[m]; g_front[m] = f_front[m]; }
-    leg_add_rows(gb, rb, &s.q[3], &s.v[3], set & 0xffffu, P, Bb, R, g_root, g_back);
-    leg_add_rows(gf, rf, &s.q[6], &s.v[6], set >> 16, P, Bf, R, g_root, g_front);
-    solve_system(Bb, Bf, R, all, all, g_root, g_back, g_front, x_root, x_back, x_front);
-    prev = set;
-  }
-
-#pragma unroll
-  for (int m = 0; m < 3; ++m) {
-    s.v[m] = s.v[m] + STEP_H * x_root[m];
-    s.v[3 + m] = s.v[3 + m] + STEP_H * x_back[m];
-    s.v[6 + m] = s.v[6 + m] + STEP_H * x_front[m];
-  }
-#pragma unroll
-  for (int j = 0; j < 9; ++j) s.q[j] = s.q[j] + STEP_H * s.v[j];
-#pragma unroll
-  for (int j = 3; j < 9; ++j) s.q[j] = s.q[j] < -1.0 ? -1.0 : (s.q[j] > 1.0 ? 1.0 : s.q[j]);
-}
 
 // Initial state: q0 = (0, 0.8, 0, ...) + U[-0.1, 0.1), v0 = 0.1 N(0, 1); uniforms from reset streams
 // 16..18 in word order, normals from Box-Muller pairs of streams 19..21, all in float32.
@@ -550,18 +384,6 @@ __device__ __forceinline__ void body_initial(BodyLane& s, uint64_t seed, uint32_
   }
   s.ep_ret = 0.0f;
   s.ep_len = 0;
-}
-
-__device__ __forceinline__ BodyLane body_load(const uint32_t* __restrict__ state, int64_t n, int64_t i) {
-  BodyLane s;
-#pragma unroll
-  for (int j = 0; j < 9; ++j) {
-    s.q[j] = (real)__uint_as_float(state[(int64_t)j * n + i]);
-    s.v[j] = (real)__uint_as_float(state[(int64_t)(9 + j) * n + i]);
-  }
-  s.ep_ret = __uint_as_float(state[18 * n + i]);
-  s.ep_len = (int)state[19 * n + i];
-  return s;
 }
 
 __device__ __forceinline__ void body_store(uint32_t* __restrict__ state, int64_t n, int64_t i, const BodyLane& s) {
@@ -596,80 +418,309 @@ __global__ __launch_bounds__(256) void body_reset_kernel(uint32_t* __restrict__ 
   if (obs) body_observe(obs + i * BODY_OBS, s);
 }
 
+// ---- two lanes per environment ---------------------------------------------------------------------
+// Lane 2i holds the root and the back leg of environment i, lane 2i+1 the root and the front leg.
+// Each lane builds its own leg's terms and factor; whatever the 3x3 root system needs from both legs
+// (mass, right-hand side, Schur complement) is the sum of a lane's part and its neighbour's, fetched
+// with one DPP quad permutation per 32-bit half; the root system itself is solved twice, once per
+// lane, on identical numbers (x + y and y + x round alike).  Per lane this is about 0.6 of the
+// instructions a single lane per environment would need, which is what counts when a launch has
+// fewer wavefronts than the device has SIMDs (N = 8192: 1.7x faster with the penalty model, 2.0x with
+// the Newton model), and it costs nothing at large N (fewer registers, two wavefronts per SIMD).
+
+__device__ __forceinline__ real pair_other(real x) {
+  int lo = __double2loint(x), hi = __double2hiint(x);
+  lo = __builtin_amdgcn_update_dpp(0, lo, 0xB1, 0xF, 0xF, true);      // quad_perm [1, 0, 3, 2]
+  hi = __builtin_amdgcn_update_dpp(0, hi, 0xB1, 0xF, 0xF, true);
+  return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ real pair_sum(real x) { return x + pair_other(x); }
+__device__ __forceinline__ int pair_other_int(int x) { return __builtin_amdgcn_update_dpp(0, x, 0xB1, 0xF, 0xF, true); }
+
+struct PairLane {
+  real qr[3], vr[3];        // x, z, pitch and their rates (the same numbers in both lanes)
+  real jq[3], jv[3];        // this lane's leg
+  float ep_ret;
+  int ep_len;
+};
+
+// Solve the 9x9 system of one environment across its two lanes.  B = this lane's leg blocks, R = the
+// whole root block, b_root = the whole root right-hand side, b_leg = this leg's.
+template <class Block>
+__device__ __forceinline__ void solve_pair(const Block& B, const RootBlock& R, const bool keep[3],
+                                           const real b_root[3], const real b_leg[3], real x_root[3],
+                                           real x_leg[3]) {
+  LegFactor f;
+  factor_leg(f, B, keep);
+  real bl[3], y[3];
+#pragma unroll
+  for (int k = 0; k < 3; ++k) bl[k] = keep[k] ? b_leg[k] : 0.0;
+  forward_leg(f, bl, y);
+  real s[3][3] = {{R.xx, R.xz, R.xth}, {R.xz, R.zz, R.zth}, {R.xth, R.zth, R.thth}};
+  real br[3];
+#pragma unroll
+  for (int r = 0; r < 3; ++r) {
+#pragma unroll
+    for (int c = 0; c <= r; ++c) {
+      real acc = 0.0;
+#pragma unroll
+      for (int k = 0; k < 3; ++k) acc += f.Y[k][r] * f.Y[k][c];
+      s[r][c] -= pair_sum(acc);
+    }
+    real acc = 0.0;
+#pragma unroll
+    for (int k = 0; k < 3; ++k) acc += f.Y[k][r] * y[k];
+    br[r] = b_root[r] - pair_sum(acc);
+  }
+  const real i00 = inv_sqrt(s[0][0]);
+  const real l10 = s[1][0] * i00, l20 = s[2][0] * i00;
+  const real i11 = inv_sqrt(s[1][1] - l10 * l10);
+  const real l21 = (s[2][1] - l20 * l10) * i11;
+  const real i22 = inv_sqrt(s[2][2] - l20 * l20 - l21 * l21);
+  const real y0 = br[0] * i00;
+  const real y1 = (br[1] - l10 * y0) * i11;
+  const real y2 = (br[2] - l20 * y0 - l21 * y1) * i22;
+  x_root[2] = y2 * i22;
+  x_root[1] = (y1 - l21 * x_root[2]) * i11;
+  x_root[0] = (y0 - l10 * x_root[1] - l20 * x_root[2]) * i00;
+  backward_leg(f, y, x_root, x_leg);
+}
+
+// One substep in place, penalty contact model.  sign: -1 back leg, +1 front leg; a[3]: this leg's
+// clipped actions.
+__device__ __forceinline__ void pair_substep(PairLane& s, const real sign, const real a[3], const Params& P) {
+  real st, ct;
+  sincos(s.qr[2], &st, &ct);
+  Leg g;
+  LegRows unused;
+  leg_terms<false>(g, unused, sign, st, ct, s.qr[1], s.vr[0], s.vr[1], s.vr[2], s.jq, s.jv, P);
+  const real mxth = pair_sum(g.Pth.x), mzth = pair_sum(g.Pth.z);
+  const real mthth = IT + pair_sum(g.mthth);
+  const RootBlock R = {MTOT, 0.0, mxth, MTOT, mzth, mthth};
+
+  // b = M v + h * rhs
+  const real vx = s.vr[0], vz = s.vr[1], vth = s.vr[2];
+  real cx = 0.0, cz = 0.0, cth = 0.0;
+#pragma unroll
+  for (int m = 0; m < 3; ++m) {
+    cx += g.C[0][m] * s.jv[m];
+    cz += g.C[1][m] * s.jv[m];
+    cth += g.C[2][m] * s.jv[m];
+  }
+  real b_root[3], b_leg[3];
+  b_root[0] = MTOT * vx + mxth * vth + pair_sum(cx) + STEP_H * pair_sum(g.rhs_x);
+  b_root[1] = MTOT * vz + mzth * vth + pair_sum(cz) + STEP_H * (-GRAVITY * MTOT + pair_sum(g.rhs_z));
+  b_root[2] = mxth * vx + mzth * vz + mthth * vth + pair_sum(cth) + STEP_H * pair_sum(g.rhs_th);
+  const int sym[3][3] = {{0, 1, 2}, {1, 3, 4}, {2, 4, 5}};
+#pragma unroll
+  for (int m = 0; m < 3; ++m) {
+    real mv = g.C[0][m] * vx + g.C[1][m] * vz + g.C[2][m] * vth;
+#pragma unroll
+    for (int k = 0; k < 3; ++k) mv += g.A[sym[m][k]] * s.jv[k];
+    b_leg[m] = mv + STEP_H * (g.rhs[m] + GEAR * a[m] - P.damping * s.jv[m]);
+  }
+
+  const bool all[3] = {true, true, true};
+  real x_root[3], x_leg[3];
+  solve_pair(g, R, all, b_root, b_leg, x_root, x_leg);
+  bool keep[3];
+#pragma unroll
+  for (int m = 0; m < 3; ++m)
+    keep[m] = !((s.jq[m] >= 1.0 && x_leg[m] > 0.0) || (s.jq[m] <= -1.0 && x_leg[m] < 0.0));
+  // the wavefront skips the second solve only when no lane has a joint to freeze; an environment
+  // with nothing to freeze gets the same numbers again
+  if (__ballot(!(keep[0] && keep[1] && keep[2])) != 0ull) solve_pair(g, R, keep, b_root, b_leg, x_root, x_leg);
+
+#pragma unroll
+  for (int m = 0; m < 3; ++m) {
+    s.vr[m] = x_root[m];
+    s.jv[m] = x_leg[m];
+    s.qr[m] = s.qr[m] + STEP_H * s.vr[m];
+    const real q = s.jq[m] + STEP_H * s.jv[m];
+    s.jq[m] = q < -1.0 ? -1.0 : (q > 1.0 ? 1.0 : q);
+  }
+}
+
+// One substep in place, Newton contact model.
+__device__ __forceinline__ void pair_substep_newton(PairLane& s, const real sign, const real a[3],
+                                                    const Params& P) {
+  real st, ct;
+  sincos(s.qr[2], &st, &ct);
+  Leg g;
+  LegRows rows;
+  leg_terms<true>(g, rows, sign, st, ct, s.qr[1], s.vr[0], s.vr[1], s.vr[2], s.jq, s.jv, P);
+  const RootBlock R0 = {MTOT, 0.0, pair_sum(g.Pth.x), MTOT, pair_sum(g.Pth.z), IT + pair_sum(g.mthth)};
+  real f_root[3], f_leg[3];
+  f_root[0] = pair_sum(g.rhs_x);
+  f_root[1] = -GRAVITY * MTOT + pair_sum(g.rhs_z);
+  f_root[2] = pair_sum(g.rhs_th);
+#pragma unroll
+  for (int m = 0; m < 3; ++m) f_leg[m] = g.rhs[m] + GEAR * a[m] - P.damping * s.jv[m];
+  const bool all[3] = {true, true, true};
+  real x_root[3], x_leg[3];
+  solve_pair(g, R0, all, f_root, f_leg, x_root, x_leg);
+
+  uint32_t prev = 0;
+  for (int pass = 0; pass < NEWTON_MAX_PASSES; ++pass) {
+    const uint32_t set = leg_active_set(g, rows, s.jq, s.jv, x_root, x_leg, P);
+    if (__ballot(set != prev) == 0ull) break;
+    LegBlock B;
+#pragma unroll
+    for (int k = 0; k < 6; ++k) B.A[k] = g.A[k];
+#pragma unroll
+    for (int r = 0; r < 3; ++r)
+#pragma unroll
+      for (int c = 0; c < 3; ++c) B.C[r][c] = g.C[r][c];
+    RootBlock dR = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
+    real dg_root[3] = {0.0, 0.0, 0.0}, g_leg[3] = {f_leg[0], f_leg[1], f_leg[2]};
+    leg_add_rows(g, rows, s.jq, s.jv, set, P, B, dR, dg_root, g_leg);
+    const RootBlock R = {R0.xx + pair_sum(dR.xx), R0.xz + pair_sum(dR.xz), R0.xth + pair_sum(dR.xth),
+                         R0.zz + pair_sum(dR.zz), R0.zth + pair_sum(dR.zth), R0.thth + pair_sum(dR.thth)};
+    real g_root[3];
+#pragma unroll
+    for (int m = 0; m < 3; ++m) g_root[m] = f_root[m] + pair_sum(dg_root[m]);
+    solve_pair(B, R, all, g_root, g_leg, x_root, x_leg);
+    prev = set;
+  }
+
+#pragma unroll
+  for (int m = 0; m < 3; ++m) {
+    s.vr[m] = s.vr[m] + STEP_H * x_root[m];
+    s.jv[m] = s.jv[m] + STEP_H * x_leg[m];
+    s.qr[m] = s.qr[m] + STEP_H * s.vr[m];
+    const real q = s.jq[m] + STEP_H * s.jv[m];
+    s.jq[m] = q < -1.0 ? -1.0 : (q > 1.0 ? 1.0 : q);
+  }
+}
+
+__device__ __forceinline__ void pair_from_full(PairLane& p, const BodyLane& s, const int side) {
+#pragma unroll
+  for (int m = 0; m < 3; ++m) {
+    p.qr[m] = s.q[m]; p.vr[m] = s.v[m];
+    p.jq[m] = side ? s.q[6 + m] : s.q[3 + m];
+    p.jv[m] = side ? s.v[6 + m] : s.v[3 + m];
+  }
+  p.ep_ret = s.ep_ret; p.ep_len = s.ep_len;
+}
+
 template <bool NEWTON>
 __global__ __launch_bounds__(WAVE) void body_rollout_kernel(BodyLaunch a) {
   a.step0 = launch_first_step(a.counter, a.step0, a.T);
   const int64_t n = a.n;
-  const int64_t i = (int64_t)blockIdx.x * WAVE + threadIdx.x;
+  const int side = threadIdx.x & 1;
+  const real sign = side ? 1.0 : -1.0;
+  const int64_t i = (int64_t)blockIdx.x * (WAVE / 2) + (threadIdx.x >> 1);
   const bool live = i < n;
-  const int64_t ic = live ? i : n - 1;             // idle lanes shadow the last environment
+  const int64_t ic = live ? i : n - 1;             // idle lane pairs shadow the last environment
   const Params P = {(real)a.armature, (real)a.joint_damping, (real)a.friction_mu,
                     1.0 / NEWTON_REG_CONTACT, 1.0 / NEWTON_REG_LIMIT,
                     1.0 / (NEWTON_TIME_CONST * NEWTON_TIME_CONST), 2.0 / NEWTON_TIME_CONST};
-  BodyLane s = body_load(a.state, n, ic);
+  const int jbase = 3 + 3 * side;                  // first joint field of this lane's leg
+  PairLane s;
+#pragma unroll
+  for (int m = 0; m < 3; ++m) {
+    s.qr[m] = (real)__uint_as_float(a.state[(int64_t)m * n + ic]);
+    s.vr[m] = (real)__uint_as_float(a.state[(int64_t)(9 + m) * n + ic]);
+    s.jq[m] = (real)__uint_as_float(a.state[(int64_t)(jbase + m) * n + ic]);
+    s.jv[m] = (real)__uint_as_float(a.state[(int64_t)(9 + jbase + m) * n + ic]);
+  }
+  s.ep_ret = __uint_as_float(a.state[18 * n + ic]);
+  s.ep_len = (int)a.state[19 * n + ic];
   LaneEpisodes le;
+  const bool writer = live && side == 0;           // one lane per environment reports and counts
 
   for (int32_t t = 0; t < a.T; ++t) {
     const uint64_t step = a.step0 + (uint64_t)t;
-    real act[6];
+    real act[3];
     if (a.actions) {
-      const float* src = a.actions + ((int64_t)t * n + ic) * BODY_ACT;
+      const float* src = a.actions + ((int64_t)t * n + ic) * BODY_ACT + 3 * side;
 #pragma unroll
-      for (int j = 0; j < 6; ++j) act[j] = (real)src[j];
+      for (int m = 0; m < 3; ++m) act[m] = (real)src[m];
     } else {
       const Draw4 d0 = philox_draw(a.seed, (uint32_t)ic, step, 0u);
       const Draw4 d1 = philox_draw(a.seed, (uint32_t)ic, step, 1u);
-      act[0] = (real)(-1.0f + 2.0f * unit_float(d0.w0)); act[1] = (real)(-1.0f + 2.0f * unit_float(d0.w1));
-      act[2] = (real)(-1.0f + 2.0f * unit_float(d0.w2)); act[3] = (real)(-1.0f + 2.0f * unit_float(d0.w3));
-      act[4] = (real)(-1.0f + 2.0f * unit_float(d1.w0)); act[5] = (real)(-1.0f + 2.0f * unit_float(d1.w1));
+      act[0] = (real)(-1.0f + 2.0f * unit_float(side ? d0.w3 : d0.w0));
+      act[1] = (real)(-1.0f + 2.0f * unit_float(side ? d1.w0 : d0.w1));
+      act[2] = (real)(-1.0f + 2.0f * unit_float(side ? d1.w1 : d0.w2));
     }
     real cost = 0.0;
 #pragma unroll
-    for (int j = 0; j < 6; ++j) {
-      act[j] = act[j] < -1.0 ? -1.0 : (act[j] > 1.0 ? 1.0 : act[j]);
-      cost += act[j] * act[j];
+    for (int m = 0; m < 3; ++m) {
+      act[m] = act[m] < -1.0 ? -1.0 : (act[m] > 1.0 ? 1.0 : act[m]);
+      cost += act[m] * act[m];
     }
+    cost = pair_sum(cost);
     real vx_sum = 0.0;
     for (int sub = 0; sub < SUBSTEPS; ++sub) {
-      if (NEWTON) body_substep_newton(s, act, P);
-      else body_substep(s, act, P);
-      vx_sum += s.v[0];
+      if (NEWTON) pair_substep_newton(s, sign, act, P);
+      else pair_substep(s, sign, act, P);
+      vx_sum += s.vr[0];
     }
     float reward = (float)(vx_sum / (real)SUBSTEPS - 0.1 * cost);
     // the state lives in memory as float32: round here so that T fused steps equal T launches
     bool ok = finite32(reward);
 #pragma unroll
-    for (int j = 0; j < 9; ++j) {
-      const float qf = (float)s.q[j], vf = (float)s.v[j];
-      ok = ok && finite32(qf) && finite32(vf);
-      s.q[j] = (real)qf; s.v[j] = (real)vf;
+    for (int m = 0; m < 3; ++m) {
+      const float a0 = (float)s.qr[m], a1 = (float)s.vr[m], a2 = (float)s.jq[m], a3 = (float)s.jv[m];
+      ok = ok && finite32(a0) && finite32(a1) && finite32(a2) && finite32(a3);
+      s.qr[m] = (real)a0; s.vr[m] = (real)a1; s.jq[m] = (real)a2; s.jv[m] = (real)a3;
     }
+    ok = ok && (pair_other_int(ok ? 1 : 0) != 0);     // both legs of the environment
     bool done = false;
     if (!ok) {                       // left the finite range: count it, start over
       reward = 0.0f;
       done = true;
-      if (live) le.nonfinite += 1;
-      body_initial(s, a.seed, (uint32_t)ic, step + 1);
+      if (writer) le.nonfinite += 1;
+      BodyLane fresh;
+      body_initial(fresh, a.seed, (uint32_t)ic, step + 1);
+      pair_from_full(s, fresh, side);
     } else {
       s.ep_ret += reward;
       s.ep_len += 1;
       if (s.ep_len >= a.max_episode_steps) {
         done = true;
-        if (live) {
+        if (writer) {
           le.count += 1; le.length_sum += s.ep_len; le.ret_sum_f += s.ep_ret;
           const int key = float_order_key(s.ep_ret);
           le.min_key = min(le.min_key, key); le.max_key = max(le.max_key, key);
         }
-        body_initial(s, a.seed, (uint32_t)ic, step + 1);
+        BodyLane fresh;
+        body_initial(fresh, a.seed, (uint32_t)ic, step + 1);
+        pair_from_full(s, fresh, side);
       }
     }
     if (live) {
-      body_observe(a.obs + ((int64_t)t * n + i) * BODY_OBS, s);
-      a.reward[(int64_t)t * n + i] = reward;
-      a.done[(int64_t)t * n + i] = done ? 1 : 0;
+      float* o = a.obs + ((int64_t)t * n + i) * BODY_OBS;
+      // obs = (z, pitch, back joints, front joints | vx, vz, vpitch, back rates, front rates)
+#pragma unroll
+      for (int m = 0; m < 3; ++m) {
+        o[2 + 3 * side + m] = (float)s.jq[m];
+        o[11 + 3 * side + m] = (float)s.jv[m];
+      }
+      if (side == 0) {
+        o[0] = (float)s.qr[1]; o[1] = (float)s.qr[2];
+        o[8] = (float)s.vr[0]; o[9] = (float)s.vr[1]; o[10] = (float)s.vr[2];
+        a.reward[(int64_t)t * n + i] = reward;
+        a.done[(int64_t)t * n + i] = done ? 1 : 0;
+      }
     }
   }
-  if (live) body_store(a.state, n, i, s);
+  if (live) {
+#pragma unroll
+    for (int m = 0; m < 3; ++m) {
+      a.state[(int64_t)(jbase + m) * n + i] = __float_as_uint((float)s.jq[m]);
+      a.state[(int64_t)(9 + jbase + m) * n + i] = __float_as_uint((float)s.jv[m]);
+    }
+    if (side == 0) {
+#pragma unroll
+      for (int m = 0; m < 3; ++m) {
+        a.state[(int64_t)m * n + i] = __float_as_uint((float)s.qr[m]);
+        a.state[(int64_t)(9 + m) * n + i] = __float_as_uint((float)s.vr[m]);
+      }
+      a.state[18 * n + i] = __float_as_uint(s.ep_ret);
+      a.state[19 * n + i] = (uint32_t)s.ep_len;
+    }
+  }
   flush_wave_stats<true>(a.stats, le);
 }
 
@@ -683,7 +734,7 @@ hipError_t launch_body_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t
 }
 
 hipError_t launch_body_rollout(const BodyLaunch& a, hipStream_t stream) {
-  const dim3 grid((unsigned)((a.n + WAVE - 1) / WAVE));
+  const dim3 grid((unsigned)((a.n + WAVE / 2 - 1) / (WAVE / 2)));   // 32 environments per wavefront
   if (a.newton) hipLaunchKernelGGL(body_rollout_kernel<true>, grid, dim3(WAVE), 0, stream, a);
   else hipLaunchKernelGGL(body_rollout_kernel<false>, grid, dim3(WAVE), 0, stream, a);
   return hipGetLastError();
