@@ -37,6 +37,8 @@ int mi355env_tune_plane_path(int mode);
  * Pointers are device memory, 16-byte aligned, bytes a multiple of 16 (else -1); -3 if the launch
  * fails. */
 int mi355env_bench_fill(void *dst_dev, size_t bytes, uint32_t value, void *hip_stream);
+/* The same fill as one 4 KiB page per 256-thread workgroup, one store per thread, no loop. */
+int mi355env_bench_fill_pages(void *dst_dev, size_t bytes, uint32_t value, void *hip_stream);
 int mi355env_bench_copy(void *dst_dev, const void *src_dev, size_t bytes, void *hip_stream);
 int mi355env_bench_empty(void *hip_stream);
 

@@ -20,6 +20,14 @@ __global__ __launch_bounds__(256) void copy16_kernel(vec16* __restrict__ dst, co
   for (size_t k = (size_t)blockIdx.x * blockDim.x + threadIdx.x; k < chunks; k += stride) dst[k] = src[k];
 }
 
+// One 4 KiB page per 256-thread workgroup, one 16-byte store per thread, workgroups in address
+// order: the launch shape with the highest write rate found on this device.
+__global__ __launch_bounds__(256) void fill_pages_kernel(vec16* __restrict__ dst, size_t chunks, uint32_t value) {
+  const size_t k = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const vec16 v = {value, value, value, value};
+  if (k < chunks) dst[k] = v;
+}
+
 __global__ void empty_kernel() {}
 
 unsigned grid_for(size_t chunks) {
@@ -37,6 +45,16 @@ int mi355env_bench_fill(void* dst_dev, size_t bytes, uint32_t value, void* hip_s
   if (!dst_dev || (bytes & 15) || (reinterpret_cast<uintptr_t>(dst_dev) & 15)) return -1;
   const size_t chunks = bytes / 16;
   hipLaunchKernelGGL(fill16_kernel, dim3(grid_for(chunks)), dim3(256), 0,
+                     static_cast<hipStream_t>(hip_stream), static_cast<vec16*>(dst_dev), chunks, value);
+  return hipGetLastError() == hipSuccess ? 0 : -3;
+}
+
+// Same contract; bytes must also be below 2^32 * 4096.
+int mi355env_bench_fill_pages(void* dst_dev, size_t bytes, uint32_t value, void* hip_stream) {
+  if (!dst_dev || (bytes & 15) || (reinterpret_cast<uintptr_t>(dst_dev) & 15)) return -1;
+  const size_t chunks = bytes / 16, blocks = (chunks + 255) / 256;
+  if (blocks == 0 || blocks > 0x7fffffffull) return -1;
+  hipLaunchKernelGGL(fill_pages_kernel, dim3((unsigned)blocks), dim3(256), 0,
                      static_cast<hipStream_t>(hip_stream), static_cast<vec16*>(dst_dev), chunks, value);
   return hipGetLastError() == hipSuccess ? 0 : -3;
 }
