@@ -98,6 +98,8 @@ enum { ENV_OBS_RAW = 1, ENV_OBS_NORMALIZED = 2 };
  *           the driver the first time they see a buffer; later calls with the same buffers do
  *           not).  Launches of one handle must not overlap.  env_step_count, env_get_state and
  *           env_reset read the device counter; the first two synchronise the stream.
+ *           A handle with the host counter refuses env_step / env_rollout while its stream is
+ *           capturing (ENV_E_STATE): replays would repeat the captured step index.
  *           Not available for ENV_PONG_PIXELS (its step alternates library buffers from the host):
  *           env_create returns ENV_E_UNSUPPORTED. */
 enum { ENV_STEP_COUNTER_HOST = 1, ENV_STEP_COUNTER_DEVICE = 2 };

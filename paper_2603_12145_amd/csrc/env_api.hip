@@ -170,6 +170,13 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
   if (!e) return ENV_E_ARG;
   if (T <= 0) return ENV_E_ARG;
   if (!e->was_reset) return ENV_E_STATE;
+  if (!e->device_counter) {
+    // A launch recorded by stream capture would replay with the step index frozen at capture time
+    // (same random draws every replay): refuse instead of producing silently wrong trajectories.
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(e->stream, &cs) != hipSuccess) (void)hipGetLastError();
+    else if (cs != hipStreamCaptureStatusNone) return ENV_E_STATE;
+  }
   const size_t tn = (size_t)T * (size_t)e->n;
   const size_t obs_bytes = (e->kind == ENV_PONG_PIXELS && ring_mode)
                                ? (size_t)e->n * 4 * FRAME_BYTES
@@ -431,7 +438,9 @@ const char* env_strerror(int code) {
     case ENV_E_ARG: return "bad argument (NULL, size, alignment or not device memory)";
     case ENV_E_ALLOC: return "device allocation failed";
     case ENV_E_HIP: return "HIP runtime call or kernel launch failed";
-    case ENV_E_STATE: return "env_reset (or env_set_state) must be called first";
+    case ENV_E_STATE:
+      return "wrong state for this call (env_reset / env_set_state not called yet, or the stream is "
+             "capturing and the handle keeps its step counter on the host)";
     case ENV_E_UNSUPPORTED: return "not supported for this environment kind";
   }
   return "unknown status";

@@ -234,3 +234,37 @@ def test_graph_replay_of_a_fused_rollout_launch():
         assert_bit_equal(got[k][1], orr, "launch %d reward" % k)
         assert_bit_equal(got[k][2], od, "launch %d done" % k)
     assert st["episodes"] == p.stats()["episodes"] > 0
+
+
+def test_capture_with_the_host_counter_is_refused():
+    """Without the device counter a captured launch would replay the same step index; the call
+    returns ENV_E_STATE during capture and the handle keeps working afterwards."""
+    n = 256
+    s = torch.cuda.Stream()
+    h = b.env_create(b.ENV_PONG, n, 3, None, stream=s)
+    try:
+        with torch.cuda.stream(s):
+            obs, rew, done = _bufs(b.ENV_PONG, n)
+            b.env_reset(h, obs)
+            b.env_step(h, None, obs, rew, done)
+            s.synchronize()
+            g = torch.cuda.CUDAGraph()
+            codes = []
+            with torch.cuda.graph(g, stream=s):
+                obs.add_(0.0)                          # the graph must not be empty
+                try:
+                    b.env_step(h, None, obs, rew, done)
+                except b.EnvError as e:
+                    codes.append(e.code)
+            assert codes == [b.ENV_E_STATE]
+            assert b.env_step_count(h) == 1
+            b.env_step(h, None, obs, rew, done)
+            s.synchronize()
+            assert b.env_step_count(h) == 2
+            got = obs.cpu().numpy()
+    finally:
+        b.env_destroy(h)
+    p = orc.Pong(n, 3)
+    p.reset()
+    oo, _, _ = p.rollout(2)
+    assert_bit_equal(got, oo[1], "obs after the refused capture")
