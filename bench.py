@@ -270,6 +270,19 @@ def bench_cartpole(b, torch, n, T, seed, steps):
                               frac=gbs / HBM_PEAK_GBS, traffic=None))
 
 
+def bench_body_sweep(b, torch, steps=3):
+    """Both body kernels over N (not part of the default run): one table row per size."""
+    rows = []
+    for newton in (False, True):
+        for n, T in ((8192, 400), (16384, 200), (32768, 200), (65536, 100), (131072, 100), (262144, 50),
+                     (524288, 25), (1048576, 12)):
+            r = bench_body(b, torch, n, T, 4, steps, newton=newton)
+            rows.append(dict(model="newton" if newton else "penalty", n=n, T=T, ms_per_launch=r["ms_per_launch"],
+                             env_steps_per_s=r["env_steps_per_s"], tflops=r["roofline"]["achieved"],
+                             frac=r["roofline"]["frac"]))
+    return rows
+
+
 def bench_policy_loop(b, torch, n, policy_kind, steps, steps_per_graph):
     """Policy-in-the-loop rollout: a PyTorch policy reads obs and writes actions, env_step consumes
     them, all on one stream; timed as direct calls and as a replayed HIP graph (device step counter)."""
@@ -404,6 +417,7 @@ def main():
         fn = {"pixels": lambda: bench_pixels(b, torch, 16384, 3, args.steps),
               "per_step": lambda: bench_pong_per_step(b, torch, 4096, 1, args.steps),
               "body": lambda: bench_body(b, torch, 8192, 1000, 4, args.steps),
+              "body_sweep": lambda: bench_body_sweep(b, torch, args.steps),
               "body_newton": lambda: [bench_body(b, torch, 8192, 1000, 4, args.steps, newton=True),
                                       bench_body(b, torch, 262144, 100, 4, args.steps, newton=True)],
               "policy": lambda: [bench_policy_loop(b, torch, 4096, "mlp", 2000, 50),
