@@ -12,15 +12,19 @@ SOURCES = ["philox.cpp", "pong.cpp", "body.cpp", "cartpole.cpp"]
 LIB = os.path.join(HERE, "liboracle.so")
 
 
-def build(force=True):
-    srcs = [os.path.join(HERE, s) for s in SOURCES if os.path.exists(os.path.join(HERE, s))]
-    if not force and os.path.exists(LIB) and all(
-            os.path.getmtime(LIB) >= os.path.getmtime(s) for s in srcs):
-        return LIB
+def build(force=True, src_dir=None, out=None):
+    """src_dir / out: build another copy of the sources into another library (the mutation test
+    compiles deliberately broken copies this way); the defaults are the in-tree ones."""
+    src_dir = src_dir or HERE
+    lib = out or LIB
+    srcs = [os.path.join(src_dir, s) for s in SOURCES if os.path.exists(os.path.join(src_dir, s))]
+    if not force and os.path.exists(lib) and all(
+            os.path.getmtime(lib) >= os.path.getmtime(s) for s in srcs):
+        return lib
     cmd = ["g++", "-std=c++17", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
-           "-pthread", "-Wall", "-Wextra", "-o", LIB] + srcs + ["-lm"]
+           "-pthread", "-Wall", "-Wextra", "-o", lib] + srcs + ["-lm"]
     subprocess.run(cmd, check=True)
-    return LIB
+    return lib
 
 
 if __name__ == "__main__":

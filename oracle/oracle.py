@@ -38,7 +38,8 @@ def lib():
                                                       os.path.join(_HERE, "build_oracle.py"))
         mod = importlib.util.module_from_spec(spec)
         spec.loader.exec_module(mod)
-        path = mod.build(force=False)
+        # MI355ENV_ORACLE_LIB: load another build of the oracle (used by the mutation test only)
+        path = os.environ.get("MI355ENV_ORACLE_LIB") or mod.build(force=False)
         L = C.CDLL(path)
         u32p = C.POINTER(C.c_uint32)
         L.oracle_philox4x32_10.argtypes = [u32p, u32p, u32p]
