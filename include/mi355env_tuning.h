@@ -29,6 +29,11 @@ int mi355env_tune_paged_stores(int mode);
  * (4, 8, 16, 32 or 64) and streaming (non-temporal) stores (0 / 1). */
 int mi355env_tune_pixels(int envs_per_wave, int streaming);
 
+/* Pixel env_rollout (frame trajectory): 0 = one launch whose wavefronts each own a few environments
+ * for all T steps, 1 = a dynamics pass stages a chunk of steps and the page renderer writes the
+ * chunk's frames together, 2 = chosen from N (default: chunked below N = 16384). */
+int mi355env_tune_frame_trajectory(int mode);
+
 /* Slot-major pixel env_step: 0 = wave-tile renderer, 1 = page renderer as separate launches,
  * 2 = page renderer fused with the next step's dynamics in one launch (default). */
 int mi355env_tune_plane_path(int mode);

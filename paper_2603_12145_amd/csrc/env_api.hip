@@ -18,6 +18,7 @@ namespace envk {
 bool set_pixel_tuning(int envs_per_wave, int streaming);
 bool set_rollout_block(int threads, int xcd_remap);
 bool set_paged_stores(int mode);
+bool set_traj_mode(int mode);
 bool set_plane_path(int on);
 }
 
@@ -225,7 +226,7 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
         err = pixel_pipe_step(e->pipe, e->state, x, pixel_plane_mode() == 2, e->stream);
       } else {
         pixel_pipe_invalidate(e->pipe);      // the state moves without the lookahead knowing
-        err = launch_pixel_rollout(x, e->stream);
+        err = launch_pixel_rollout(x, e->pipe, e->stream);
       }
     }
   }
@@ -459,5 +460,8 @@ int mi355env_tune_rollout(int threads_per_block, int xcd_remap) {
 
 // 0 = direct observation stores, 1 = paged through LDS wherever a workgroup is full, 2 = by N.
 int mi355env_tune_paged_stores(int mode) { return set_paged_stores(mode) ? ENV_OK : ENV_E_ARG; }
+
+// Pixel env_rollout: 0 = one launch, 1 = staged and rendered a chunk of steps at a time, 2 = by N.
+int mi355env_tune_frame_trajectory(int mode) { return set_traj_mode(mode) ? ENV_OK : ENV_E_ARG; }
 
 }  // extern "C"

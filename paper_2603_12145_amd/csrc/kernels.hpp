@@ -54,7 +54,10 @@ struct PixelLaunch {
 };
 hipError_t launch_pixel_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
                               uint8_t* ring, bool slot_major, uint32_t* blocks, hipStream_t stream);
-hipError_t launch_pixel_rollout(const PixelLaunch& a, hipStream_t stream);
+struct PixelPipe;
+// pipe: the handle's scratch; its trajectory staging area lets a frame trajectory be rendered
+// a chunk of steps at a time (see launch_pixel_rollout in pixel_kernels.hip).
+hipError_t launch_pixel_rollout(const PixelLaunch& a, PixelPipe& pipe, hipStream_t stream);
 
 // Slot-major pixel step with one-step lookahead.  Every step is the launch F(t) = { hand step t's
 // staged reward / done to the caller and flush its episode statistics; render step t's plane;
@@ -71,6 +74,8 @@ struct PixelPipe {
   int32_t* fin_ret[2] = {nullptr, nullptr};        // [n] return / length of an episode that ended
   int32_t* fin_len[2] = {nullptr, nullptr};
   bool staged = false;                             // staging buffers of parity (step & 1) hold `step`
+  uint32_t* traj_blocks = nullptr;                 // [3][traj_cap] cell blocks of a chunk of a frame trajectory
+  int64_t traj_cap = 0;                            // frames (environment-steps) per chunk
 };
 hipError_t pixel_pipe_create(PixelPipe& p, int64_t n);
 void pixel_pipe_destroy(PixelPipe& p);

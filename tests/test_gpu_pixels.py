@@ -152,18 +152,23 @@ def test_streaming_store_variant_matches():
     b.env_destroy(h)
 
 
-def test_frame_trajectory_rollout_with_external_actions():
+@pytest.mark.parametrize("mode", [0, 1])       # single launch; staged and rendered in chunks
+def test_frame_trajectory_rollout_with_external_actions(mode):
     n, seed, T = 150, 8, 40
     acts = inputs.pong_actions(T, n, seed=2)
+    assert b.lib().mi355env_tune_frame_trajectory(mode) == 0
     h = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"max_score": 1})
-    b.env_reset(h, None)
-    frames = torch.empty((T, n, F, F), dtype=torch.uint8, device=DEV)
-    rew = torch.empty((T, n), dtype=torch.float32, device=DEV)
-    done = torch.empty((T, n), dtype=torch.uint8, device=DEV)
-    b.env_rollout(h, T, torch.from_numpy(acts).to(DEV), frames, rew, done)
-    torch.cuda.synchronize()
-    stats = b.env_stats(h)
-    b.env_destroy(h)
+    try:
+        b.env_reset(h, None)
+        frames = torch.empty((T, n, F, F), dtype=torch.uint8, device=DEV)
+        rew = torch.empty((T, n), dtype=torch.float32, device=DEV)
+        done = torch.empty((T, n), dtype=torch.uint8, device=DEV)
+        b.env_rollout(h, T, torch.from_numpy(acts).to(DEV), frames, rew, done)
+        torch.cuda.synchronize()
+        stats = b.env_stats(h)
+    finally:
+        b.env_destroy(h)
+        assert b.lib().mi355env_tune_frame_trajectory(2) == 0
     p = orc.Pong(n, seed, max_score=1); p.reset()
     stack = np.zeros((n, 4, F, F), np.uint8)
     got = frames.cpu().numpy()
@@ -224,3 +229,45 @@ def test_config3_n16384_t500_final_ring(layout):
     _, fields = split_state(b.env_get_state(h), n, 10)
     assert_bit_equal(fields, pong_state_fields(p.envs()), "C3 state")
     b.env_destroy(h)
+
+
+@pytest.mark.parametrize("n,T", [(70000, 9), (1000, 300)])
+def test_frame_trajectory_rendered_in_chunks(n, T):
+    """env_rollout on the pixel kind stages a chunk of steps (as many as fit 262144 frames, at least
+    one) and renders the chunk's frames together.  Sizes that need several chunks with a ragged
+    last one; rewards and done flags are compared in full, frames at sampled (step, environment)
+    pairs rendered by the oracle from its own state after that step."""
+    seed = 19
+    assert b.lib().mi355env_tune_frame_trajectory(1) == 0        # chunked at any N
+    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"max_score": 1})
+    try:
+        b.env_reset(h, None)
+        frames = torch.empty((T, n, F, F), dtype=torch.uint8, device=DEV)
+        rew = torch.empty((T, n), dtype=torch.float32, device=DEV)
+        done = torch.empty((T, n), dtype=torch.uint8, device=DEV)
+        b.env_rollout(h, T, None, frames, rew, done)
+        torch.cuda.synchronize()
+        stats = b.env_stats(h)
+        state = b.env_get_state(h)
+    finally:
+        b.env_destroy(h)
+        assert b.lib().mi355env_tune_frame_trajectory(2) == 0
+    p = orc.Pong(n, seed, max_score=1)
+    p.reset()
+    oobs, orew, odone = p.rollout(T, nthreads=8)
+    assert_bit_equal(rew.cpu().numpy(), orew, "reward")
+    assert_bit_equal(done.cpu().numpy(), odone, "done")
+    assert stats["episodes"] == p.stats()["episodes"]
+    _, fields = split_state(state, n, 10)
+    assert_bit_equal(fields, pong_state_fields(p.envs()), "final state")
+    rng = np.random.default_rng(3)
+    ts = np.concatenate([rng.integers(0, T, 300), [0, T - 1, T - 1]])
+    es = np.concatenate([rng.integers(0, n, 300), [0, n - 1, 0]])
+    got = frames[torch.from_numpy(ts).to(DEV), torch.from_numpy(es).to(DEV)].cpu().numpy()
+    for k, (t, e) in enumerate(zip(ts, es)):
+        o = oobs[t, e]
+        st = dict(bx=float(o[0]), by=float(o[1]), vx=0.0, vy=0.0, pa=float(o[4]), po=float(o[5]), sa=0, so=0,
+                  ep_ret=0, ep_len=0)
+        assert_bit_equal(got[k], orc.pong_render_one(st), "frame t=%d env=%d" % (t, e))
+    # the frames are not all alike (the ball moves)
+    assert (got[0] != got[1]).any()
