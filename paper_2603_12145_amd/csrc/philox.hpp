@@ -16,8 +16,9 @@ __device__ __forceinline__ void philox_round(uint32_t& c0, uint32_t& c1, uint32_
                                              uint32_t k0, uint32_t k1) {
   const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
   const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
-  const uint32_t t0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-  const uint32_t t2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+  // a ^ b ^ c in one instruction (v_bitop3_b32 with the truth table of a three-way xor)
+  const uint32_t t0 = __builtin_amdgcn_bitop3_b32((uint32_t)(p1 >> 32), c1, k0, 0x96);
+  const uint32_t t2 = __builtin_amdgcn_bitop3_b32((uint32_t)(p0 >> 32), c3, k1, 0x96);
   c1 = (uint32_t)p1;
   c3 = (uint32_t)p0;
   c0 = t0;
