@@ -337,3 +337,38 @@ def test_both_store_paths_and_every_chunk_remainder(mode, n, T):
     finally:
         assert b.lib().mi355env_tune_paged_stores(2) == 0
     compare(g, oracle_rollout(n, 23, T, max_score=2), n, "stores mode %d n=%d T=%d" % (mode, n, T))
+
+
+@pytest.mark.parametrize("device_counter", [False, True])
+def test_step_counter_crosses_2_to_the_32(device_counter):
+    """The step index is 64 bits wide and both halves key Philox: a rollout that starts five steps
+    before 2^32 must keep matching the oracle across the carry (and far beyond it)."""
+    n, T = 300, 12
+    for start in ((1 << 32) - 5, (1 << 40) + 123):
+        p = orc.Pong(n, 41, max_score=2)
+        p.reset()
+        p.rollout(25)                                   # any state will do
+        p.step_count = start
+        fields = pong_state_fields(p.envs().copy())
+        cfg = {"max_score": 2}
+        if device_counter:
+            cfg["step_counter"] = b.ENV_STEP_COUNTER_DEVICE
+        h = b.env_create(b.ENV_PONG, n, 41, cfg)
+        try:
+            b.env_set_state(h, pong_blob(start, fields))
+            assert b.env_step_count(h) == start
+            obs, rew, done = bufs(T, n)
+            b.env_rollout(h, 5, None, obs[:5], rew[:5], done[:5])
+            for t in range(5, T):
+                b.env_step(h, None, obs[t], rew[t], done[t])
+            torch.cuda.synchronize()
+            assert b.env_step_count(h) == start + T
+            blob = b.env_get_state(h)
+        finally:
+            b.env_destroy(h)
+        oo, orr, od = p.rollout(T)
+        assert_bit_equal(obs.cpu().numpy(), oo, "obs from step %d" % start)
+        assert_bit_equal(done.cpu().numpy(), od, "done from step %d" % start)
+        step, got = split_state(blob, n, 10)
+        assert step == start + T
+        assert_bit_equal(got, pong_state_fields(p.envs()), "state")
