@@ -96,6 +96,22 @@ __device__ __forceinline__ void sincos_unit(real x, real& s, real& c) {
   c = 1.0 - x2 * pc;
 }
 
+// sin and cos of the pitch, which is not confined to an interval: reduce by multiples of pi/2 with a
+// two-part constant (exact to ~1e-16 for the |x| < 1e4 a tumbling body can reach), evaluate the
+// unit-interval polynomials on the remainder (|r| <= pi/4) and undo the quadrant.  About half the
+// instructions of the general library routine, which carries a large-argument path.
+__device__ __forceinline__ void sincos_any(real x, real& s, real& c) {
+  const real k = __builtin_rint(x * 0.63661977236758134308);              // x / (pi/2)
+  real r = __builtin_fma(-k, 1.57079632679489655800e+00, x);               // pi/2, leading 53 bits
+  r = __builtin_fma(-k, 6.12323399573676603587e-17, r);                    // ... and the next 53
+  real sr, cr;
+  sincos_unit(r, sr, cr);
+  const int q = (int)k & 3;
+  const real s0 = (q & 1) ? cr : sr, c0 = (q & 1) ? sr : cr;
+  s = (q & 2) ? -s0 : s0;
+  c = ((q + 1) & 2) ? -c0 : c0;
+}
+
 // 1 / sqrt(s) to full precision: hardware estimate plus two Newton steps.
 __device__ __forceinline__ real inv_sqrt(real s) {
   real y = __builtin_amdgcn_rsq(s);
@@ -490,7 +506,7 @@ __device__ __forceinline__ void solve_pair(const Block& B, const RootBlock& R, c
 // clipped actions.
 __device__ __forceinline__ void pair_substep(PairLane& s, const real sign, const real a[3], const Params& P) {
   real st, ct;
-  sincos(s.qr[2], &st, &ct);
+  sincos_any(s.qr[2], st, ct);
   Leg g;
   LegRows unused;
   leg_terms<false>(g, unused, sign, st, ct, s.qr[1], s.vr[0], s.vr[1], s.vr[2], s.jq, s.jv, P);
@@ -545,7 +561,7 @@ __device__ __forceinline__ void pair_substep(PairLane& s, const real sign, const
 __device__ __forceinline__ void pair_substep_newton(PairLane& s, const real sign, const real a[3],
                                                     const Params& P) {
   real st, ct;
-  sincos(s.qr[2], &st, &ct);
+  sincos_any(s.qr[2], st, ct);
   Leg g;
   LegRows rows;
   leg_terms<true>(g, rows, sign, st, ct, s.qr[1], s.vr[0], s.vr[1], s.vr[2], s.jq, s.jv, P);
