@@ -1,0 +1,148 @@
+"""GPU parity on seeded random configurations: sizes around every tile boundary, 62-bit seeds, random
+splits of a rollout into launches, and every option that changes a code path (external actions,
+observation scaling, device step counter, store path, ring layout, renderer) drawn from a fixed
+generator.  Everything is compared bit for bit with the oracle.  Each case is printed before it
+runs."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+from oracle import oracle as orc                      # noqa: E402
+from oracle.cartpole_binding import CartPole          # noqa: E402
+from paper_2603_12145_amd import binding as b         # noqa: E402
+from paper_2603_12145_amd import inputs               # noqa: E402
+from gpu_helpers import assert_bit_equal, split_state, pong_state_fields   # noqa: E402
+
+DEV = "cuda:0"
+
+
+def _trajectory_buffers(T, n, obs_dim):
+    return (torch.empty((T, n, obs_dim), dtype=torch.float32, device=DEV),
+            torch.empty((T, n), dtype=torch.float32, device=DEV),
+            torch.empty((T, n), dtype=torch.uint8, device=DEV))
+
+
+def pong_case(rng, k):
+    n = int(rng.choice([1, 2, 63, 64, 65, 255, 256, 257, 1000, 4097, 20000, 70001]))
+    T = int(rng.integers(1, 400))
+    seed = int(rng.integers(0, 2 ** 62))
+    max_score = int(rng.choice([1, 2, 5, 21]))
+    external, scaled, device_counter = (bool(rng.integers(0, 2)) for _ in range(3))
+    paged = int(rng.integers(0, 3))
+    print("pong case", k, dict(n=n, T=T, seed=seed, max_score=max_score, external=external, scaled=scaled,
+                               device_counter=device_counter, paged=paged), flush=True)
+    acts = inputs.pong_actions(T, n, seed=k) if external else None
+    cfg = {"max_score": max_score}
+    if scaled:
+        cfg["obs_scaling"] = b.ENV_OBS_NORMALIZED
+    if device_counter:
+        cfg["step_counter"] = b.ENV_STEP_COUNTER_DEVICE
+    assert b.lib().mi355env_tune_paged_stores(paged) == 0
+    h = b.env_create(b.ENV_PONG, n, seed, cfg)
+    try:
+        obs0 = torch.empty((n, 8), dtype=torch.float32, device=DEV)
+        b.env_reset(h, obs0)
+        obs, rew, done = _trajectory_buffers(T, n, 8)
+        act = None if acts is None else torch.from_numpy(acts).to(DEV)
+        t = 0
+        while t < T:                                   # the rollout cut into launches at random
+            c = int(min(T - t, rng.integers(1, max(2, T // 2 + 1))))
+            b.env_rollout(h, c, None if act is None else act[t:t + c], obs[t:t + c], rew[t:t + c], done[t:t + c])
+            t += c
+        torch.cuda.synchronize()
+        stats, blob = b.env_stats(h), b.env_get_state(h)
+    finally:
+        b.env_destroy(h)
+    p = orc.Pong(n, seed, max_score=max_score, normalize=scaled)
+    o0 = p.reset()
+    oo, orr, od = p.rollout(T, actions=acts, nthreads=8)
+    assert_bit_equal(obs0.cpu().numpy(), o0, "reset obs")
+    assert_bit_equal(obs.cpu().numpy(), oo, "obs")
+    assert_bit_equal(rew.cpu().numpy(), orr, "reward")
+    assert_bit_equal(done.cpu().numpy(), od, "done")
+    assert stats["episodes"] == p.stats()["episodes"] and stats["return_sum"] == p.stats()["return_sum"]
+    _, fields = split_state(blob, n, 10)
+    assert_bit_equal(fields, pong_state_fields(p.envs()), "state")
+
+
+def cartpole_case(rng, k):
+    n = int(rng.choice([1, 63, 65, 300, 5000, 66000]))
+    T = int(rng.integers(1, 300))
+    seed = int(rng.integers(0, 2 ** 62))
+    max_steps = int(rng.choice([5, 50, 500]))
+    external = bool(rng.integers(0, 2))
+    print("cartpole case", k, dict(n=n, T=T, seed=seed, max_steps=max_steps, external=external), flush=True)
+    acts = inputs.cartpole_actions(T, n, seed=k) if external else None
+    h = b.env_create(b.ENV_CARTPOLE, n, seed, {"max_episode_steps": max_steps})
+    try:
+        b.env_reset(h, None)
+        obs, rew, done = _trajectory_buffers(T, n, 4)
+        b.env_rollout(h, T, None if acts is None else torch.from_numpy(acts).to(DEV), obs, rew, done)
+        torch.cuda.synchronize()
+        stats = b.env_stats(h)
+    finally:
+        b.env_destroy(h)
+    p = CartPole(n, seed, max_steps=max_steps)
+    p.reset()
+    oo, _, od = p.rollout(T, actions=acts, nthreads=8)
+    assert_bit_equal(obs.cpu().numpy(), oo, "obs")
+    assert_bit_equal(done.cpu().numpy(), od, "done")
+    assert stats["episodes"] == p.stats()["episodes"]
+
+
+def pixel_case(rng, k):
+    n = int(rng.choice([1, 17, 100, 257, 3000]))
+    T = int(rng.integers(4, 40))
+    seed = int(rng.integers(0, 2 ** 62))
+    layout = int(rng.choice([b.ENV_PIXELS_SLOT_MAJOR, b.ENV_PIXELS_ENV_MAJOR]))
+    renderer = int(rng.integers(0, 3))
+    print("pixel case", k, dict(n=n, T=T, seed=seed, layout=layout, renderer=renderer), flush=True)
+    assert b.lib().mi355env_tune_plane_path(renderer) == 0
+    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"max_score": 1, "pixel_layout": layout})
+    try:
+        shape = (4, n, 84, 84) if layout == b.ENV_PIXELS_SLOT_MAJOR else (n, 4, 84, 84)
+        ring = torch.zeros(shape, dtype=torch.uint8, device=DEV)
+        b.env_reset(h, ring)
+        rew = torch.empty(n, dtype=torch.float32, device=DEV)
+        done = torch.empty(n, dtype=torch.uint8, device=DEV)
+        p = orc.Pong(n, seed, max_score=1)
+        p.reset()
+        stack = np.zeros((n, 4, 84, 84), np.uint8)
+        for t in range(T):
+            b.env_step(h, None, ring, rew, done)
+            _, orew, odone = p.step(stack=stack)
+            assert_bit_equal(rew.cpu().numpy(), orew, "reward %d" % t)
+            assert_bit_equal(done.cpu().numpy(), odone, "done %d" % t)
+        torch.cuda.synchronize()
+        got = ring.cpu().numpy()
+    finally:
+        b.env_destroy(h)
+    if layout == b.ENV_PIXELS_SLOT_MAJOR:
+        got = np.ascontiguousarray(got.transpose(1, 0, 2, 3))
+    assert_bit_equal(got, stack, "ring after %d steps" % T)      # T >= 4: every slot rewritten
+
+
+def test_random_pong_cases():
+    rng = np.random.default_rng(12345)
+    try:
+        for k in range(12):
+            pong_case(rng, k)
+    finally:
+        assert b.lib().mi355env_tune_paged_stores(2) == 0
+
+
+def test_random_cartpole_cases():
+    rng = np.random.default_rng(23456)
+    for k in range(6):
+        cartpole_case(rng, k)
+
+
+def test_random_pixel_cases():
+    rng = np.random.default_rng(34567)
+    try:
+        for k in range(8):
+            pixel_case(rng, k)
+    finally:
+        assert b.lib().mi355env_tune_plane_path(2) == 0
