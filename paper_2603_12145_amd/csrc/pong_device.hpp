@@ -48,10 +48,19 @@ __device__ __forceinline__ float clampf(float x, float lo, float hi) {
   return __builtin_fminf(__builtin_fmaxf(x, lo), hi);
 }
 
-__device__ __forceinline__ PongEvent pong_transition(PongLane& s, int action, uint32_t w_vx,
-                                                     uint32_t w_vy, int max_score) {
+// The agent's paddle displacement for an action code, and for an action drawn from a Philox word w:
+// floor(3 w / 2^32) is 1 (up) from ceil(2^32 / 3) and 2 (down) from ceil(2^33 / 3), so two
+// comparisons replace the quarter-rate multiply of pong_action_from_word.
+__device__ __forceinline__ float pong_move_of_action(int action) {
+  return (action == 1) ? -4.0f : ((action == 2) ? 4.0f : 0.0f);
+}
+__device__ __forceinline__ float pong_move_of_word(uint32_t w) {
+  return (w >= 0xAAAAAAABu) ? 4.0f : ((w >= 0x55555556u) ? -4.0f : 0.0f);
+}
+
+__device__ __forceinline__ PongEvent pong_transition_move(PongLane& s, const float move, uint32_t w_vx,
+                                                          uint32_t w_vy, int max_score) {
   // agent paddle, then opponent paddle (which looks at the ball before it moves)
-  const float move = (action == 1) ? -4.0f : ((action == 2) ? 4.0f : 0.0f);
   const float pa = clampf(s.pa + move, 0.0f, 194.0f);
   const float chase = clampf((s.by + 1.0f) - (s.po + 8.0f), -3.0f, 3.0f);
   const float po = clampf(s.po + chase, 0.0f, 194.0f);
@@ -109,6 +118,11 @@ __device__ __forceinline__ PongEvent pong_transition(PongLane& s, int action, ui
   s.ep_ret = ev.done ? 0 : ep_ret;
   s.ep_len = ev.done ? 0 : ep_len;
   return ev;
+}
+
+__device__ __forceinline__ PongEvent pong_transition(PongLane& s, int action, uint32_t w_vx,
+                                                     uint32_t w_vy, int max_score) {
+  return pong_transition_move(s, pong_move_of_action(action), w_vx, w_vy, max_score);
 }
 
 // First state of an episode started by env_reset: serve drawn from reset stream 16.

@@ -66,10 +66,10 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
   int parity = 0;
 
   auto one_step = [&](const Draw4& d) {
-    int action;
-    if (EXTERNAL_ACTIONS) action = live ? (int)act_row[lane] : 0;
-    else action = pong_action_from_word(d.w0);
-    const PongEvent ev = pong_transition(s, action, d.w1, d.w2, a.max_score);
+    float move;
+    if (EXTERNAL_ACTIONS) move = pong_move_of_action(live ? (int)act_row[lane] : 0);
+    else move = pong_move_of_word(d.w0);
+    const PongEvent ev = pong_transition_move(s, move, d.w1, d.w2, a.max_score);
     const bool done = live && ev.done;
     // selects, not a branch: the loop body stays one basic block
     le.count += done ? 1 : 0;
