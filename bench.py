@@ -27,6 +27,8 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 PONG_BYTES_PER_ENV_STEP = 37   # 32 obs + 4 reward + 1 done
 CARTPOLE_BYTES_PER_ENV_STEP = 21   # 16 obs + 4 reward + 1 done
+CARTPOLE_VALU_PER_ENV_STEP = 196   # vector instructions in the step loop of the kernel ISA (35 of them quarter-rate integer multiplies)
+VALU_PEAK_TINSTR = 39.3            # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, lane-instructions per second / 1e12
 FRAME_BYTES = 84 * 84          # one new frame per env-step
 FP64_PEAK_TFLOPS = 78.6        # MI355X vector float64 (256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz)
 BODY_NEWTON_FLOP_PER_ENV_STEP = 13540   # 5 substeps x (1526 outside the Newton loop + 1.05 solves per environment x 1126), counted in the kernel ISA; a wavefront executes max-over-lanes solves (3.0 on average), which is not counted as useful work
@@ -264,10 +266,13 @@ def bench_cartpole(b, torch, n, T, seed, steps):
     b.env_destroy(h)
     mean_ms, std_ms = _mean_std(ms)
     gbs = CARTPOLE_BYTES_PER_ENV_STEP * n * T / (mean_ms * 1e-3) / 1e9
+    tinstr = CARTPOLE_VALU_PER_ENV_STEP * n * T / (mean_ms * 1e-3) / 1e12
+    # bound by vector-instruction issue, not by its 21 B per env-step: the roofline is the issue rate
     return dict(workload="cart-pole N=%d x T=%d fused rollout, in-kernel Philox actions" % (n, T), dtype="f32",
                 env_steps_per_s=n * T * steps / wall, ms_per_launch=mean_ms, episodes=st["episodes"],
-                roofline=dict(bound="hbm", achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s",
-                              frac=gbs / HBM_PEAK_GBS, traffic=None))
+                hbm_gbs=gbs, hbm_frac=gbs / HBM_PEAK_GBS,
+                roofline=dict(bound="alu", achieved=tinstr, peak=VALU_PEAK_TINSTR, unit="T lane-instructions/s",
+                              frac=tinstr / VALU_PEAK_TINSTR, traffic=None))
 
 
 def bench_body_sweep(b, torch, steps=3):
