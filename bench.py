@@ -261,7 +261,7 @@ def bench_cartpole(b, torch, n, T, seed, steps):
     rew = torch.empty((T, n), dtype=torch.float32, device=dev)
     done = torch.empty((T, n), dtype=torch.uint8, device=dev)
     b.env_reset(h, None)
-    wall, ms = time_launches(lambda: b.env_rollout(h, T, None, obs, rew, done), steps, 2)
+    wall, ms = time_launches(lambda: b.env_rollout(h, T, None, obs, rew, done), steps, 20)
     st = b.env_stats(h)
     b.env_destroy(h)
     mean_ms, std_ms = _mean_std(ms)
