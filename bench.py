@@ -212,6 +212,25 @@ def bench_fill(b, torch, nbytes, launches=50):
     return out
 
 
+def bench_store_floor(b, torch, n, T, launches=30):
+    """The rollout's trajectory stores with no computation behind them (same buffers, same launch
+    shape): the time the memory system needs for obs[T,N,8] + reward[T,N] + done[T,N]."""
+    import ctypes as C
+    L = b.lib()
+    L.mi355env_bench_trajectory_stores.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]
+    dev = "cuda:0"
+    obs = torch.empty((T, n, 8), dtype=torch.float32, device=dev)
+    rew = torch.empty((T, n), dtype=torch.float32, device=dev)
+    done = torch.empty((T, n), dtype=torch.uint8, device=dev)
+    s = torch.cuda.current_stream().cuda_stream
+    wall, ms = time_launches(lambda: L.mi355env_bench_trajectory_stores(obs.data_ptr(), rew.data_ptr(),
+                                                                        done.data_ptr(), n, T, s), launches, 20)
+    mean_ms, std_ms = _mean_std(ms)
+    gbs = PONG_BYTES_PER_ENV_STEP * n * T / (mean_ms * 1e-3) / 1e9
+    return dict(workload="stores of the Pong rollout only, N=%d x T=%d" % (n, T), ms_per_launch=mean_ms,
+                ms_std=std_ms, gbs=gbs, frac_of_peak=gbs / HBM_PEAK_GBS)
+
+
 def bench_copy(b, torch, nbytes, launches=20):
     """Plain device-to-device copy of known size: calibrates the HBM byte counters."""
     import ctypes as C
@@ -429,6 +448,7 @@ def main():
                                  bench_policy_loop(b, torch, 65536, "mlp", 2000, 50),
                                  bench_policy_loop(b, torch, 4096, "gru", 1000, 50)],
               "cartpole": lambda: bench_cartpole(b, torch, 65536, 1000, 2, args.steps),
+              "store_floor": lambda: bench_store_floor(b, torch, 65536, 1000, args.steps),
               "fill": lambda: bench_fill(b, torch, 1 << 30, args.steps),
               "copy": lambda: bench_copy(b, torch, 1 << 30, args.steps)}[args.only]
         print(json.dumps(fn()))
@@ -462,6 +482,9 @@ def main():
     if not args.skip_extra:
         extra = {}
         extra["fill_yardstick"] = bench_fill(b, torch, 1 << 30)
+        floor = bench_store_floor(b, torch, n, T)
+        floor["rollout_vs_floor"] = floor["ms_per_launch"] / r["mean_ms"]
+        extra["trajectory_store_floor"] = floor
         extra["config1_per_step"] = bench_pong_per_step(b, torch, 4096, 1, 10000)
         extra["config3_pixels"] = bench_pixels(b, torch, 16384, 3, 500)
         extra["config3_pixels_env_major"] = bench_pixels(b, torch, 16384, 3, 500, layout="env_major")

@@ -46,6 +46,11 @@ int mi355env_bench_fill(void *dst_dev, size_t bytes, uint32_t value, void *hip_s
 int mi355env_bench_fill_pages(void *dst_dev, size_t bytes, uint32_t value, void *hip_stream);
 int mi355env_bench_copy(void *dst_dev, const void *src_dev, size_t bytes, void *hip_stream);
 int mi355env_bench_empty(void *hip_stream);
+/* The trajectory stores of the fused Pong rollout without any computation: constant values into
+ * obs_dev float32[T][n][8] (16-byte aligned), reward_dev float32[T][n], done_dev uint8[T][n], in the
+ * rollout's launch shape.  Its duration is the floor the memory system sets for that layout. */
+int mi355env_bench_trajectory_stores(void *obs_dev, void *reward_dev, void *done_dev, int64_t n, int32_t T,
+                                     void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -28,6 +28,27 @@ __global__ __launch_bounds__(256) void fill_pages_kernel(vec16* __restrict__ dst
   if (k < chunks) dst[k] = v;
 }
 
+// The stores of the fused Pong rollout and nothing else: per step every lane writes the 32-byte
+// observation of its environment (two 16-byte stores), a reward dword and a done byte into
+// obs[T][n][8], reward[T][n], done[T][n], with the rollout's workgroup-to-XCD mapping.  What this
+// takes is the floor the memory system sets for that trajectory layout.
+__global__ __launch_bounds__(256) void trajectory_stores_kernel(float* __restrict__ obs, float* __restrict__ reward,
+                                                                uint8_t* __restrict__ done, int64_t n, int T) {
+  const unsigned per_xcd = gridDim.x >> 3;
+  const unsigned logical_block = (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3);
+  const int64_t i = (int64_t)logical_block * 256 + threadIdx.x;
+  if (i >= n) return;
+  const float4 v = make_float4(1.0f, 2.0f, 3.0f, (float)threadIdx.x);
+  for (int t = 0; t < T; ++t) {
+    const int64_t k = (int64_t)t * n + i;
+    float4* o = reinterpret_cast<float4*>(obs + k * 8);
+    o[0] = v;
+    o[1] = v;
+    reward[k] = 1.0f;
+    done[k] = 0;
+  }
+}
+
 __global__ void empty_kernel() {}
 
 unsigned grid_for(size_t chunks) {
@@ -56,6 +77,20 @@ int mi355env_bench_fill_pages(void* dst_dev, size_t bytes, uint32_t value, void*
   if (blocks == 0 || blocks > 0x7fffffffull) return -1;
   hipLaunchKernelGGL(fill_pages_kernel, dim3((unsigned)blocks), dim3(256), 0,
                      static_cast<hipStream_t>(hip_stream), static_cast<vec16*>(dst_dev), chunks, value);
+  return hipGetLastError() == hipSuccess ? 0 : -3;
+}
+
+// obs_dev float32[T][n][8] (16-byte aligned), reward_dev float32[T][n], done_dev uint8[T][n].
+int mi355env_bench_trajectory_stores(void* obs_dev, void* reward_dev, void* done_dev, int64_t n, int32_t T,
+                                     void* hip_stream) {
+  if (!obs_dev || !reward_dev || !done_dev || n <= 0 || T <= 0 || n > (int64_t(1) << 30) ||
+      (reinterpret_cast<uintptr_t>(obs_dev) & 15) || (reinterpret_cast<uintptr_t>(reward_dev) & 3))
+    return -1;
+  unsigned blocks = (unsigned)((n + 255) / 256);
+  blocks = (blocks + 7u) & ~7u;
+  hipLaunchKernelGGL(trajectory_stores_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
+                     static_cast<float*>(obs_dev), static_cast<float*>(reward_dev), static_cast<uint8_t*>(done_dev),
+                     n, T);
   return hipGetLastError() == hipSuccess ? 0 : -3;
 }
 
