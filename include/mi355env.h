@@ -17,7 +17,12 @@
  *    stats / get_state / set_state synchronise that stream.
  *  - All functions return ENV_OK (0) or a negative error code; on error no output buffer is
  *    touched.  No C++ exception crosses this boundary.
- *  - One handle must not be used from two threads at once.
+ *  - One handle must not be used from two threads at once.  A handle belongs to the device that
+ *    was current in env_create; calls made with another device current return ENV_E_STATE.
+ *  - Device pointers are checked for residency and size (the range must lie inside one device
+ *    allocation) before anything is launched.  A handle remembers the last eight (pointer, size)
+ *    pairs that passed and does not ask the driver about them again: a buffer that is freed and
+ *    replaced by a smaller one at the same address is the caller's to keep track of.
  *  - Random draws come from Philox4x32-10 with key = (seed lo, seed hi) and
  *    counter = (env index, step lo, step hi, stream); `step` counts env steps since env_create and
  *    is never rewound, so results do not depend on N nor on how a rollout is cut into calls.
@@ -49,7 +54,8 @@ enum {
   ENV_E_ARG = -1,      /* bad argument: NULL, non-positive size, misaligned or non-device pointer */
   ENV_E_ALLOC = -2,    /* device allocation failed                                                */
   ENV_E_HIP = -3,      /* a HIP runtime call or kernel launch failed                              */
-  ENV_E_STATE = -4,    /* call order: step/rollout before the first env_reset                     */
+  ENV_E_STATE = -4,    /* call order: step/rollout before the first env_reset; capture on a handle
+                          with a host step counter; current device is not the handle's            */
   ENV_E_UNSUPPORTED = -5 /* operation not available for this environment kind                     */
 };
 

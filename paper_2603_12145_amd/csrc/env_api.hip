@@ -143,6 +143,14 @@ bool device_range_ok(env_t* e, const void* p, size_t bytes, size_t align) {
   return true;
 }
 
+// Launches and copies go to the current device: refuse a call made with another device current than
+// the one the handle's memory lives on.
+bool on_own_device(const env_t* e) {
+  int d = -1;
+  if (hipGetDevice(&d) != hipSuccess) { (void)hipGetLastError(); return false; }
+  return d == e->device;
+}
+
 int read_device_step(const env_t* e, uint64_t* out) {
   unsigned long long s = 0;
   if (hipMemcpyAsync(&s, &e->counter->step, sizeof s, hipMemcpyDeviceToHost, e->stream) != hipSuccess ||
@@ -171,6 +179,9 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
   if (!e) return ENV_E_ARG;
   if (T <= 0) return ENV_E_ARG;
   if (!e->was_reset) return ENV_E_STATE;
+  if (!on_own_device(e)) return ENV_E_STATE;
+  // T * n * (bytes per env-step, at most 7056) must fit a size_t with room to spare
+  if ((uint64_t)T > (uint64_t(1) << 48) / (uint64_t)e->n) return ENV_E_ARG;
   if (!e->device_counter) {
     // A launch recorded by stream capture would replay with the step index frozen at capture time
     // (same random draws every replay): refuse instead of producing silently wrong trajectories.
@@ -298,6 +309,7 @@ void env_destroy(env_t* e) {
 
 int env_reset(env_t* e, void* obs_dev) {
   if (!e) return ENV_E_ARG;
+  if (!on_own_device(e)) return ENV_E_STATE;
   hipError_t err;
   const StepCounter* counter = e->device_counter ? e->counter : nullptr;
   if (e->kind == ENV_PONG_PIXELS && obs_dev) {
@@ -338,6 +350,7 @@ int env_rollout(env_t* e, int32_t T, const void* actions_dev, void* obs_dev, flo
 
 int env_stats(env_t* e, env_stats_t* host_out, int reset_counters) {
   if (!e || !host_out) return ENV_E_ARG;
+  if (!on_own_device(e)) return ENV_E_STATE;
   DeviceStats d;
   if (hipMemcpyAsync(&d, e->stats, sizeof d, hipMemcpyDeviceToHost, e->stream) != hipSuccess ||
       hipStreamSynchronize(e->stream) != hipSuccess)
@@ -370,6 +383,7 @@ size_t env_state_bytes(const env_t* e) {
 
 int env_get_state(env_t* e, void* host_buf, size_t bytes) {
   if (!e || !host_buf || bytes != env_state_bytes(e)) return ENV_E_ARG;
+  if (!on_own_device(e)) return ENV_E_STATE;
   std::memcpy(host_buf, &e->step, 8);
   if (e->device_counter) {
     uint64_t s = 0;
@@ -385,6 +399,7 @@ int env_get_state(env_t* e, void* host_buf, size_t bytes) {
 
 int env_set_state(env_t* e, const void* host_buf, size_t bytes) {
   if (!e || !host_buf || bytes != env_state_bytes(e)) return ENV_E_ARG;
+  if (!on_own_device(e)) return ENV_E_STATE;
   if (hipMemcpyAsync(e->state, static_cast<const char*>(host_buf) + 8, bytes - 8,
                      hipMemcpyHostToDevice, e->stream) != hipSuccess ||
       hipStreamSynchronize(e->stream) != hipSuccess)
@@ -440,8 +455,9 @@ const char* env_strerror(int code) {
     case ENV_E_ALLOC: return "device allocation failed";
     case ENV_E_HIP: return "HIP runtime call or kernel launch failed";
     case ENV_E_STATE:
-      return "wrong state for this call (env_reset / env_set_state not called yet, or the stream is "
-             "capturing and the handle keeps its step counter on the host)";
+      return "wrong state for this call (env_reset / env_set_state not called yet, the stream is "
+             "capturing and the handle keeps its step counter on the host, or the current device is "
+             "not the handle's)";
     case ENV_E_UNSUPPORTED: return "not supported for this environment kind";
   }
   return "unknown status";

@@ -210,6 +210,23 @@ def test_error_paths_touch_nothing():
     b.env_destroy(h)
 
 
+def test_sizes_that_would_wrap_are_refused():
+    # T * n * bytes-per-env-step beyond 64 bits must not wrap round into a size that passes the
+    # buffer check: pixel frames (7056 B) at n = 2^20 and T = 2^31 - 1 are 2^63.8 bytes
+    n = 1 << 20
+    h = b.env_create(b.ENV_PONG_PIXELS, n, 1, None)
+    b.env_reset(h, None)
+    L, vp = b.lib(), C.c_void_p
+    frames = torch.empty(1 << 20, dtype=torch.uint8, device=DEV)
+    rew = torch.empty(n, dtype=torch.float32, device=DEV)
+    done = torch.empty(n, dtype=torch.uint8, device=DEV)
+    T = (1 << 31) - 1
+    assert L.env_rollout(h, T, None, vp(frames.data_ptr()), vp(rew.data_ptr()), vp(done.data_ptr())) == b.ENV_E_ARG
+    torch.cuda.synchronize()
+    assert b.env_step_count(h) == 0
+    b.env_destroy(h)
+
+
 def test_non_default_stream():
     n, seed, T = 200, 12, 300
     s = torch.cuda.Stream()
