@@ -153,10 +153,13 @@ def bench_pong_per_step(b, torch, n, seed, launches):
                 hbm_gbs=n * 101 / (wall / launches) / 1e9)
 
 
-def bench_pixels(b, torch, n, seed, launches, warmup=20, layout="slot_major"):
+def bench_pixels(b, torch, n, seed, launches, warmup=20, layout="slot_major", device_counter=False):
     dev = "cuda:0"
     code = b.ENV_PIXELS_SLOT_MAJOR if layout == "slot_major" else b.ENV_PIXELS_ENV_MAJOR
-    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"pixel_layout": code})
+    cfg = {"pixel_layout": code}
+    if device_counter:      # one launch per step that a HIP graph can replay (no staged lookahead)
+        cfg["step_counter"] = b.ENV_STEP_COUNTER_DEVICE
+    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, cfg)
     ring = torch.zeros((4, n, 84, 84) if layout == "slot_major" else (n, 4, 84, 84),
                        dtype=torch.uint8, device=dev)
     rew = torch.empty(n, dtype=torch.float32, device=dev)
@@ -181,16 +184,42 @@ def bench_pixels(b, torch, n, seed, launches, warmup=20, layout="slot_major"):
         done_steps += k
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    graph = {}
+    if device_counter:
+        per_graph = 20
+        st = torch.cuda.Stream()
+        st.wait_stream(torch.cuda.current_stream())
+        b.env_set_stream(h, st)
+        with torch.cuda.stream(st):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=st):
+                for _ in range(per_graph):
+                    b.env_step(h, None, ring, rew, done)
+            for _ in range(3):
+                g.replay()
+            st.synchronize()
+            reps = max(1, launches // per_graph)
+            tg = time.perf_counter()
+            for _ in range(reps):
+                g.replay()
+            st.synchronize()
+            graph_us = 1e6 * (time.perf_counter() - tg) / (reps * per_graph)
+            del g
+        graph = dict(graph_replay_us_per_step=graph_us,
+                     graph_replay_gbs=n * FRAME_BYTES / (graph_us * 1e-6) / 1e9)
     b.env_destroy(h)
     mean_ms = sum(s.elapsed_time(e) for s, e, _ in blocks_ms) / launches
     gbs = n * FRAME_BYTES / (mean_ms * 1e-3) / 1e9
     return dict(workload="pong pixels N=%d, 84x84 u8 frame into a 4-slot ring (%s), one env_step "
-                         "call per step" % (n, "u8[4,N,84,84]" if layout == "slot_major" else "u8[N,4,84,84]"),
+                         "call per step%s" % (n, "u8[4,N,84,84]" if layout == "slot_major" else "u8[N,4,84,84]",
+                                             ", step counter in device memory" if device_counter else ""),
+                **graph,
                 env_steps_per_s=n * launches / wall, us_per_step_events=mean_ms * 1e3,
                 us_per_step_wall=1e6 * wall / launches,
                 roofline=dict(bound="hbm", achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s",
                               frac=gbs / HBM_PEAK_GBS,
-                              traffic=_traffic("pixel_fused_step_n%d" % n) if layout == "slot_major" else None),
+                              traffic=_traffic("pixel_fused_step_n%d" % n)
+                              if layout == "slot_major" and not device_counter else None),
                 launches=launches)
 
 
@@ -439,6 +468,7 @@ def main():
 
     if args.only:
         fn = {"pixels": lambda: bench_pixels(b, torch, 16384, 3, args.steps),
+              "pixels_device_counter": lambda: bench_pixels(b, torch, 16384, 3, args.steps, device_counter=True),
               "per_step": lambda: bench_pong_per_step(b, torch, 4096, 1, args.steps),
               "body": lambda: bench_body(b, torch, 8192, 1000, 4, args.steps),
               "body_sweep": lambda: bench_body_sweep(b, torch, args.steps),
@@ -488,6 +518,7 @@ def main():
         extra["config1_per_step"] = bench_pong_per_step(b, torch, 4096, 1, 10000)
         extra["config3_pixels"] = bench_pixels(b, torch, 16384, 3, 500)
         extra["config3_pixels_env_major"] = bench_pixels(b, torch, 16384, 3, 500, layout="env_major")
+        extra["config3_pixels_device_counter"] = bench_pixels(b, torch, 16384, 3, 500, device_counter=True)
         for nn in (16384, 262144):
             rr = bench_pong_rollout(b, torch, nn, T, seed, max(3, args.steps // 6), 1)
             gbs = PONG_BYTES_PER_ENV_STEP * nn * T / (rr["mean_ms"] * 1e-3) / 1e9

@@ -233,7 +233,13 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
       x.blocks = e->pipe.blocks[0];
       if (ring_mode) x.ring = static_cast<uint8_t*>(obs);
       else x.frames = static_cast<uint8_t*>(obs);
-      if (ring_mode && x.slot_major && T == 1 && pixel_plane_mode() != 0 && e->n < (int64_t)4000000) {
+      const bool plane_step = ring_mode && x.slot_major && T == 1 && pixel_plane_mode() != 0 &&
+                              e->n < (int64_t)4000000;
+      if (plane_step && e->device_counter) {
+        // no lookahead and no buffers alternated from the host: a replayed graph could do neither
+        pixel_pipe_invalidate(e->pipe);
+        err = pixel_counted_step(e->pipe, x, e->stream);
+      } else if (plane_step) {
         err = pixel_pipe_step(e->pipe, e->state, x, pixel_plane_mode() == 2, e->stream);
       } else {
         pixel_pipe_invalidate(e->pipe);      // the state moves without the lookahead knowing
@@ -257,7 +263,6 @@ int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_c
   if (n_envs <= 0 || n_envs > MAX_ENVS) return ENV_E_ARG;
   env_config_t c = default_config(kind);
   if (merge_config(&c, cfg) != ENV_OK) return ENV_E_ARG;
-  if (c.step_counter == ENV_STEP_COUNTER_DEVICE && kind == ENV_PONG_PIXELS) return ENV_E_UNSUPPORTED;
   if (c.obs_scaling == ENV_OBS_NORMALIZED && kind != ENV_PONG) return ENV_E_UNSUPPORTED;
   if (c.contact_solver == ENV_CONTACT_NEWTON && kind != ENV_BODY) return ENV_E_UNSUPPORTED;
 
@@ -314,7 +319,7 @@ int env_reset(env_t* e, void* obs_dev) {
   const StepCounter* counter = e->device_counter ? e->counter : nullptr;
   if (e->kind == ENV_PONG_PIXELS && obs_dev) {
     if (!device_range_ok(e, obs_dev, (size_t)e->n * 4 * FRAME_BYTES, 16)) return ENV_E_ARG;
-    err = launch_pixel_reset(e->state, e->n, e->seed, e->step, static_cast<uint8_t*>(obs_dev),
+    err = launch_pixel_reset(e->state, e->n, e->seed, e->step, counter, static_cast<uint8_t*>(obs_dev),
                              e->cfg.pixel_layout == ENV_PIXELS_SLOT_MAJOR, e->pipe.blocks[0], e->stream);
     pixel_pipe_invalidate(e->pipe);
   } else if (e->kind == ENV_BODY) {

@@ -53,7 +53,8 @@ struct PixelLaunch {
   uint32_t* blocks;       // library scratch [3][n]: packed cell blocks of the newest frame
 };
 hipError_t launch_pixel_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
-                              uint8_t* ring, bool slot_major, uint32_t* blocks, hipStream_t stream);
+                              const StepCounter* counter, uint8_t* ring, bool slot_major, uint32_t* blocks,
+                              hipStream_t stream);
 struct PixelPipe;
 // pipe: the handle's scratch; its trajectory staging area lets a frame trajectory be rendered
 // a chunk of steps at a time (see launch_pixel_rollout in pixel_kernels.hip).
@@ -84,6 +85,9 @@ void pixel_pipe_destroy(PixelPipe& p);
 hipError_t pixel_pipe_step(PixelPipe& p, uint32_t*& state, const PixelLaunch& a, bool lookahead,
                            hipStream_t stream);
 inline void pixel_pipe_invalidate(PixelPipe& p) { p.staged = false; }
+// The same step for a handle whose step counter lives in device memory (a.pong.counter): two
+// launches, dynamics then page renderer, no lookahead, nothing alternated from the host.
+hipError_t pixel_counted_step(const PixelPipe& p, const PixelLaunch& a, hipStream_t stream);
 int pixel_plane_mode();
 
 }  // namespace envk

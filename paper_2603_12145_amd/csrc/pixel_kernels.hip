@@ -86,6 +86,10 @@ __device__ __forceinline__ void store_chunk(chunk_t* dst, const chunk_t v) {
 template <int EPW, int MODE, bool STREAMING>
 __global__ __launch_bounds__(WAVES_PER_BLOCK * WAVE) void pixel_kernel(PixelLaunch a) {
   __shared__ __align__(16) uint8_t tiles[WAVES_PER_BLOCK][FRAME_BYTES];
+  // a handle that keeps its step counter in device memory: read it (and, for a step, advance it)
+  // before any wavefront leaves
+  if (MODE == MODE_RESET) a.pong.step0 = read_step(a.pong.counter, a.pong.step0);
+  else a.pong.step0 = launch_first_step(a.pong.counter, a.pong.step0, a.pong.T);
   const int lane = threadIdx.x & (WAVE - 1);
   const int wave = threadIdx.x >> 6;
   const int64_t n = a.pong.n;
@@ -234,6 +238,7 @@ __global__ __launch_bounds__(256) void pixel_dynamics_kernel(PongLaunch a, const
 // k), reward and done to the caller's [T][n] rows; the state is loaded and stored once.
 __global__ __launch_bounds__(256) void pixel_traj_dynamics_kernel(PongLaunch a, uint32_t* __restrict__ blocks,
                                                                   int64_t frames) {
+  a.step0 = launch_first_step(a.counter, a.step0, a.T);
   const int64_t n = a.n;
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const bool live = i < n;
@@ -311,6 +316,23 @@ __device__ __forceinline__ void render_page(const uint32_t* __restrict__ blocks,
 __global__ __launch_bounds__(256) void plane_render_kernel(const uint32_t* __restrict__ blocks, int64_t n,
                                                            uint8_t* __restrict__ plane) {
   __shared__ __align__(16) uint8_t page[PAGE];
+  render_page(blocks, n, plane, blockIdx.x, page);
+}
+
+// The plane of the step that the previous launch on the stream just took, for a handle whose step
+// counter lives in device memory: that launch advanced the counter to s + 1, the frame after step s
+// goes to ring slot s mod 4.  The grid covers the slot with the most pages (a slot's first and last
+// page depend on its alignment); workgroups beyond this slot's pages leave.
+__global__ __launch_bounds__(256) void plane_render_counted_kernel(const uint32_t* __restrict__ blocks, int64_t n,
+                                                                   uint8_t* __restrict__ ring,
+                                                                   const StepCounter* __restrict__ counter) {
+  __shared__ __align__(16) uint8_t page[PAGE];
+  const uint64_t slot = (counter->step - 1ull) & 3ull;
+  uint8_t* plane = ring + (int64_t)slot * n * FRAME_BYTES;
+  const uintptr_t base = reinterpret_cast<uintptr_t>(plane);
+  const uintptr_t end = base + (uintptr_t)n * FRAME_BYTES;
+  const unsigned pages = (unsigned)(((end + PAGE - 1) >> 12) - (base >> 12));
+  if (blockIdx.x >= pages) return;
   render_page(blocks, n, plane, blockIdx.x, page);
 }
 
@@ -488,9 +510,33 @@ hipError_t pixel_pipe_step(PixelPipe& p, uint32_t*& state, const PixelLaunch& a,
   return hipGetLastError();
 }
 
+// One ring step of a slot-major handle with a device step counter: the lane-per-environment pass
+// (reads and advances the counter, writes reward / done to the caller and the cell blocks to
+// library scratch), then the page renderer, which derives the slot from the advanced counter.
+hipError_t pixel_counted_step(const PixelPipe& p, const PixelLaunch& a, hipStream_t stream) {
+  const int64_t n = a.pong.n;
+  PongLaunch d = a.pong;
+  d.T = 1;
+  hipLaunchKernelGGL(pixel_traj_dynamics_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, d,
+                     p.blocks[0], n);
+  hipError_t err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  unsigned pages = 0;
+  for (int slot = 0; slot < 4; ++slot) {
+    const unsigned here = plane_pages(a.ring + (int64_t)slot * n * FRAME_BYTES, n);
+    pages = here > pages ? here : pages;
+  }
+  hipLaunchKernelGGL(plane_render_counted_kernel, dim3(pages), dim3(256), 0, stream, p.blocks[0], n, a.ring,
+                     a.pong.counter);
+  return hipGetLastError();
+}
+
 hipError_t launch_pixel_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
-                              uint8_t* ring, bool slot_major, uint32_t* blocks, hipStream_t stream) {
-  if (slot_major && g_plane_path != 0 && blocks && n < (int64_t)4000000) {
+                              const StepCounter* counter, uint8_t* ring, bool slot_major, uint32_t* blocks,
+                              hipStream_t stream) {
+  // the page renderer's dynamics pass takes the step from the host; a device counter goes through
+  // the single-launch renderer, which reads it
+  if (!counter && slot_major && g_plane_path != 0 && blocks && n < (int64_t)4000000) {
     PongLaunch p{};
     p.state = state; p.n = n; p.seed = seed; p.step0 = step; p.T = 1;
     const Staged st{blocks, nullptr, nullptr, nullptr, nullptr};
@@ -507,6 +553,7 @@ hipError_t launch_pixel_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_
   PixelLaunch a{};
   a.slot_major = slot_major;
   a.pong.state = state; a.pong.n = n; a.pong.seed = seed; a.pong.step0 = step; a.pong.T = 1;
+  a.pong.counter = const_cast<StepCounter*>(counter);      // only read by the reset kernel
   a.ring = ring;
   return launch_mode<MODE_RESET>(a, stream);
 }
@@ -522,7 +569,8 @@ hipError_t launch_pixel_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_
 hipError_t launch_pixel_rollout(const PixelLaunch& a, PixelPipe& pipe, hipStream_t stream) {
   if (!a.frames) return launch_mode<MODE_RING>(a, stream);
   const int64_t n = a.pong.n;
-  const bool chunked = g_traj_mode == 2 ? n < 16384 : g_traj_mode == 1;
+  // the chunks' step indices are computed on the host: not with a step counter in device memory
+  const bool chunked = !a.pong.counter && (g_traj_mode == 2 ? n < 16384 : g_traj_mode == 1);
   if (!chunked || !pipe.traj_blocks || n > pipe.traj_cap || pipe.traj_cap >= (int64_t)4000000)
     return launch_mode<MODE_FRAMES>(a, stream);
   const int32_t steps_per_chunk = (int32_t)(pipe.traj_cap / n);

@@ -72,7 +72,7 @@ def test_argument_errors_without_gpu(L):
     odd = b.env_config_t(struct_size=C.sizeof(b.env_config_t), step_counter=7)
     assert L.env_create(C.byref(h), 0, 64, 0, C.byref(odd), None) == b.ENV_E_ARG
     dev = b.env_config_t(struct_size=C.sizeof(b.env_config_t), armature=-1, joint_damping=-1,
-                         friction_mu=-1, step_counter=b.ENV_STEP_COUNTER_DEVICE)
+                         friction_mu=-1, obs_scaling=b.ENV_OBS_NORMALIZED)
     assert L.env_create(C.byref(h), b.ENV_PONG_PIXELS, 64, 0, C.byref(dev), None) == b.ENV_E_UNSUPPORTED
     assert L.env_step(None, None, None, None, None) == b.ENV_E_ARG
     assert L.env_rollout(None, 5, None, None, None, None) == b.ENV_E_ARG

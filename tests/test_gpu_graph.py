@@ -236,6 +236,78 @@ def test_graph_replay_of_a_fused_rollout_launch():
     assert st["episodes"] == p.stats()["episodes"] > 0
 
 
+@pytest.mark.parametrize("layout", ["slot", "env"])
+def test_pixel_handle_with_device_counter_matches_the_default_path_and_replays(layout):
+    """Pong pixels: a handle with the step counter in device memory takes one launch per step
+    instead of the staged two-buffer path.  Ring, reward and done must equal the default handle's
+    after every step (which the pixel parity tests tie to the oracle), for direct calls, graph
+    replays and a frame-trajectory rollout, and the episode statistics must agree."""
+    n, seed, K = 600, 21, 70
+    lay = b.ENV_PIXELS_SLOT_MAJOR if layout == "slot" else b.ENV_PIXELS_ENV_MAJOR
+    cfg = {"max_score": 1, "pixel_layout": lay}
+    s = torch.cuda.Stream()
+    FB = 84 * 84
+    out = {}
+    for mode in ("host", "device"):
+        c = dict(cfg)
+        if mode == "device":
+            c.update(DEVICE_COUNTER)
+        h = b.env_create(b.ENV_PONG_PIXELS, n, seed, c, stream=s)
+        try:
+            with torch.cuda.stream(s):
+                ring = torch.zeros(n * 4 * FB, dtype=torch.uint8, device=DEV)
+                rew = torch.empty(n, dtype=torch.float32, device=DEV)
+                done = torch.empty(n, dtype=torch.uint8, device=DEV)
+                rec = []
+
+                def record():
+                    s.synchronize()
+                    rec.append((ring.cpu().numpy().copy(), rew.cpu().numpy().copy(), done.cpu().numpy().copy()))
+
+                b.env_reset(h, ring)
+                s.synchronize()
+                rec.append((ring.cpu().numpy().copy(), None, None))
+                for _ in range(3):
+                    b.env_step(h, None, ring, rew, done); record()
+                if mode == "host":
+                    for _ in range(K):
+                        b.env_step(h, None, ring, rew, done); record()
+                else:
+                    g = torch.cuda.CUDAGraph()
+                    with torch.cuda.graph(g, stream=s):
+                        b.env_step(h, None, ring, rew, done)
+                    assert b.env_step_count(h) == 3
+                    for k in range(K):
+                        g.replay(); record()
+                        if k % 5 == 2:
+                            ring.sum().item()
+                    assert b.env_step_count(h) == 3 + K
+                # a frame trajectory continues from there, then a reset and two more steps
+                T = 6
+                frames = torch.empty(T * n * FB, dtype=torch.uint8, device=DEV)
+                rews = torch.empty((T, n), dtype=torch.float32, device=DEV)
+                dones = torch.empty((T, n), dtype=torch.uint8, device=DEV)
+                b.env_rollout(h, T, None, frames, rews, dones)
+                s.synchronize()
+                rec.append((frames.cpu().numpy().copy(), rews.cpu().numpy().copy(), dones.cpu().numpy().copy()))
+                b.env_reset(h, ring)
+                for _ in range(2):
+                    b.env_step(h, None, ring, rew, done); record()
+                assert b.env_step_count(h) == 3 + K + T + 2
+                out[mode] = (rec, b.env_stats(h), b.env_get_state(h))
+        finally:
+            b.env_destroy(h)
+    hr, dr = out["host"][0], out["device"][0]
+    assert len(hr) == len(dr)
+    for k in range(len(hr)):
+        for name, x, y in zip(("frames", "reward", "done"), hr[k], dr[k]):
+            if x is not None:
+                assert_bit_equal(y, x, "record %d %s (device counter vs default)" % (k, name))
+    assert out["host"][1] == out["device"][1] and out["host"][1]["episodes"] > 0
+    assert_bit_equal(out["device"][2], out["host"][2], "state blob")
+    assert hr[5][0].max() == 255 and (hr[5][0] != hr[4][0]).any()
+
+
 def test_capture_with_the_host_counter_is_refused():
     """Without the device counter a captured launch would replay the same step index; the call
     returns ENV_E_STATE during capture and the handle keeps working afterwards."""
