@@ -205,8 +205,15 @@ def test_truncation_stats_and_nonfinite_guard():
     assert abs(st["return_sum"] - r[:100].sum()) < 1e-3 * max(1.0, abs(r[:100].sum()))
     ep = np.concatenate([r[:50].sum(0), r[50:100].sum(0)])
     assert abs(st["return_min"] - ep.min()) < 1e-3 and abs(st["return_max"] - ep.max()) < 1e-3
-    # poison three environments: they are re-initialised, counted, and report done with reward 0
-    step, s = state_from_blob(b.env_get_state(h), n)
+    # poison three environments of a state taken from the oracle's own 120-step rollout: they are
+    # re-initialised, counted, and report done with reward 0
+    src = Body(n, seed, np.float64, max_episode_steps=50, round_state_f32=1)
+    src.reset()
+    src.rollout(120, nthreads=8, want_obs=False)
+    step = 120
+    s = src.get_state()
+    s[:, :19] = s[:, :19].astype(np.float32).astype(np.float64)
+    assert b.env_step_count(h) == step
     s[5, 3] = np.nan; s[17, 10] = np.inf; s[100, 1] = -np.inf
     b.env_set_state(h, blob_from_oracle_state(step, s))
     b.env_step(h, None, obs[0], rew[0], done[0])
@@ -216,7 +223,7 @@ def test_truncation_stats_and_nonfinite_guard():
     d = done[0].cpu().numpy(); rr = rew[0].cpu().numpy()
     assert set(np.flatnonzero(d)) == {5, 17, 100} and np.all(rr[[5, 17, 100]] == 0)
     assert np.isfinite(obs[0].cpu().numpy()).all()
-    o = Body(n, seed, np.float64)                       # the oracle applies the same guard
+    o = Body(n, seed, np.float64, max_episode_steps=50)   # the oracle applies the same guard
     o.set_state(s); o.step_count = step
     oobs, orew, odone = o.rollout(1)
     assert set(np.flatnonzero(odone[0])) == {5, 17, 100} and o.stats()["nonfinite"] == 3

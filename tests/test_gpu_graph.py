@@ -3,7 +3,8 @@
 A launch recorded in a graph has frozen kernel arguments, so the handle created with
 step_counter = ENV_STEP_COUNTER_DEVICE keeps the step index in device memory.  Checked here:
 direct calls in that mode match the oracle bit for bit; a captured {policy, env_step} graph replayed
-K times matches K direct calls, replay by replay, and (through the recorded actions) the oracle."""
+K times matches K direct calls, replay by replay, and the oracle's own closed loop (the same
+policy rule applied to the oracle's observations): actions, observations, rewards, done flags."""
 import numpy as np
 import pytest
 
@@ -163,18 +164,40 @@ def _run_graph_vs_direct(kind, n, seed, cfg, policy, K, act_shape, act_dtype):
     return g, outs["graph"][1]
 
 
+def _np_pong_policy(obs):
+    """The same rule on the reference side, in float32 like the tensor version."""
+    up = (obs[:, 1] + np.float32(1.0)) < (obs[:, 4] + np.float32(8.0))
+    return np.where(up, 1, 2).astype(np.uint8)
+
+
+def _np_cartpole_policy(obs):
+    return ((obs[:, 2] + np.float32(0.5) * obs[:, 3]) > 0).astype(np.uint8)
+
+
+def _closed_loop_reference(env, policy, T):
+    """The reference's own policy-in-the-loop rollout: its policy sees its observations only."""
+    o = env.reset()
+    acts, obs, rew, done = [], [], [], []
+    for _ in range(T):
+        a = policy(o)
+        oo, rr, dd = env.rollout(1, actions=a[None])
+        o = oo[0]
+        acts.append(a); obs.append(oo[0]); rew.append(rr[0]); done.append(dd[0])
+    return np.stack(acts), np.stack(obs), np.stack(rew), np.stack(done)
+
+
 def test_graph_replay_pong_policy_in_the_loop():
     n, K = 1000, 60
     rec, stats = _run_graph_vs_direct(b.ENV_PONG, n, 12, {"max_score": 1}, _pong_policy, K, (n,), torch.uint8)
     T = len(rec)
-    acts = np.stack([r[0] for r in rec])
     p = orc.Pong(n, 12, max_score=1)
-    p.reset()
-    oo, orr, od = p.rollout(T, actions=acts)
+    acts, oo, orr, od = _closed_loop_reference(p, _np_pong_policy, T)
+    assert_bit_equal(np.stack([r[0] for r in rec]), acts, "actions vs the reference's closed loop")
     assert_bit_equal(np.stack([r[1] for r in rec]), oo, "obs vs oracle")
     assert_bit_equal(np.stack([r[2] for r in rec]), orr, "reward vs oracle")
     assert_bit_equal(np.stack([r[3] for r in rec]), od, "done vs oracle")
     assert stats["episodes"] == p.stats()["episodes"]
+    assert set(np.unique(acts)) == {1, 2}
 
 
 def test_graph_replay_cartpole_policy_in_the_loop():
@@ -182,10 +205,9 @@ def test_graph_replay_cartpole_policy_in_the_loop():
     rec, stats = _run_graph_vs_direct(b.ENV_CARTPOLE, n, 13, {"max_episode_steps": 40}, _cartpole_policy, K,
                                       (n,), torch.uint8)
     T = len(rec)
-    acts = np.stack([r[0] for r in rec])
     p = CartPole(n, 13, max_steps=40)
-    p.reset()
-    oo, _, od = p.rollout(T, actions=acts)
+    acts, oo, _, od = _closed_loop_reference(p, _np_cartpole_policy, T)
+    assert_bit_equal(np.stack([r[0] for r in rec]), acts, "actions vs the reference's closed loop")
     assert_bit_equal(np.stack([r[1] for r in rec]), oo, "obs vs oracle")
     assert_bit_equal(np.stack([r[3] for r in rec]), od, "done vs oracle")
     assert od.sum() >= 2 * n and stats["episodes"] == int(od.sum())
@@ -194,7 +216,7 @@ def test_graph_replay_cartpole_policy_in_the_loop():
 def test_graph_replay_body_policy_in_the_loop():
     n, K = 256, 30
     rec, _ = _run_graph_vs_direct(b.ENV_BODY, n, 14, {}, _body_policy_factory(3), K, (n, 6), torch.float32)
-    # single steps against the float64 oracle from the GPU's own pre-step states are covered by the
+    # single steps against the float64 oracle, from states the oracle supplies, are covered by the
     # body parity tests; here the recorded trajectory must be finite and the policy must have acted
     obs = np.stack([r[1] for r in rec])
     acts = np.stack([r[0] for r in rec])

@@ -75,10 +75,11 @@ def test_l3_cartpole_100_episodes_exact():
 def test_l3_body_100_episodes_epsilon():
     """Body, one full 1000-step episode per index, identical actions.
 
-    (a) Step-level comparison along the performance side's own trajectory (teacher forcing): at
-        every timestep the reference takes the GPU's float32 state and the same action; the two
-        next states must agree within epsilon = 1e-3 — the paper's tolerance — and in fact within
-        1e-5 except where a contact or joint-limit decision sits on its switching surface.
+    (a) Step-level comparison along the reference's trajectory: at every timestep the performance
+        side is handed the reference's state (float32, as the reference keeps it between steps) and
+        takes the same action; the two next states must agree within epsilon = 1e-3 — the paper's
+        tolerance — and in fact within 1e-5 except where a contact or joint-limit decision sits on
+        its switching surface.
     (b) Free-running comparison: both start from the same state and never resynchronise.  The
         penalty contact makes the dynamics sensitive, so trajectories separate after a contact
         decision flips; reported, and the episode returns must agree in distribution."""
@@ -88,39 +89,46 @@ def test_l3_body_100_episodes_epsilon():
     ref.reset()
     s0 = ref.get_state()
 
-    # (b) free-running reference
-    oo, orr, od = ref.rollout(T, actions=acts.astype(np.float64), nthreads=8)
-    assert od[-1].all() and od.sum() == n
-
-    h = b.env_create(b.ENV_BODY, n, seed, None)
-    probe = Body(n, seed, np.float64)
+    h = b.env_create(b.ENV_BODY, n, seed, None)        # stepped from the reference's states
+    free = b.env_create(b.ENV_BODY, n, seed, None)     # (b): set once, then left alone
     try:
-        b.env_set_state(h, blob_from_oracle_state(0, s0))
         act = torch.from_numpy(acts).to(DEV)
+        o1 = torch.empty((n, 17), dtype=torch.float32, device=DEV)
+        r1 = torch.empty(n, dtype=torch.float32, device=DEV)
+        d1 = torch.empty(n, dtype=torch.uint8, device=DEV)
+        worst = np.zeros((T, n))
+        oo = np.empty((T, n, 17)); orr = np.empty((T, n)); od = np.empty((T, n), np.uint8)
+        for t in range(T):
+            prev = ref.get_state()
+            assert np.array_equal(prev[:, :18].astype(np.float32).astype(np.float64), prev[:, :18])
+            oo[t:t + 1], orr[t:t + 1], od[t:t + 1] = ref.rollout(1, actions=acts[t:t + 1].astype(np.float64),
+                                                                 nthreads=4)
+            b.env_set_state(h, blob_from_oracle_state(t, prev))
+            b.env_step(h, act[t], o1, r1, d1)
+            if t == T - 1:                         # the last step resets: compared through obs below
+                break
+            _, cur = state_from_blob(b.env_get_state(h), n)
+            want = ref.get_state()
+            worst[t] = np.maximum(rel_err(cur[:, :18], want[:, :18]).max(axis=1),
+                                  rel_err(r1.cpu().numpy(), orr[t]))
+        torch.cuda.synchronize()
+        assert od[-1].all() and od.sum() == n and d1.cpu().numpy().all()
+        assert rel_err(o1.cpu().numpy(), oo[-1]).max() <= 1e-5      # first observation of the next episode
+
+        b.env_set_state(free, blob_from_oracle_state(0, s0))
         obs = torch.empty((T, n, 17), dtype=torch.float32, device=DEV)
         rew = torch.empty((T, n), dtype=torch.float32, device=DEV)
         done = torch.empty((T, n), dtype=torch.uint8, device=DEV)
-        worst = np.zeros((T, n))
-        prev = s0
-        for t in range(T - 1):                     # the last step resets: compared through obs below
-            b.env_step(h, act[t], obs[t], rew[t], done[t])
-            _, cur = state_from_blob(b.env_get_state(h), n)
-            probe.set_state(prev); probe.step_count = t
-            p_obs, p_rew, _ = probe.rollout(1, actions=acts[t:t + 1].astype(np.float64), nthreads=4)
-            want = probe.get_state()
-            e = np.maximum(rel_err(cur[:, :18], want[:, :18]).max(axis=1),
-                           rel_err(rew[t].cpu().numpy(), p_rew[0]))
-            worst[t] = e
-            prev = cur
-        b.env_step(h, act[T - 1], obs[T - 1], rew[T - 1], done[T - 1])
+        b.env_rollout(free, T, act, obs, rew, done)
         torch.cuda.synchronize()
         gd = done.cpu().numpy()
         go, gr = obs.cpu().numpy(), rew.cpu().numpy()
-        st = b.env_stats(h)
+        st = b.env_stats(free)
     finally:
         b.env_destroy(h)
+        b.env_destroy(free)
     w = worst[:T - 1]
-    print("L3 body, teacher-forced step error over %d env-steps: median %.2e, 99.9%% %.2e, max %.2e; "
+    print("L3 body, step error from the reference's states over %d env-steps: median %.2e, 99.9%% %.2e, max %.2e; "
           "beyond 1e-5: %d, beyond 1e-3: %d" % (w.size, np.median(w), np.quantile(w, 0.999), w.max(),
                                                  int((w > 1e-5).sum()), int((w > 1e-3).sum())))
     assert (w > 1e-3).sum() <= w.size // 10000          # epsilon of the paper's L3 for this workload
