@@ -141,7 +141,7 @@ constexpr real NEWTON_TIME_CONST = 0.02, NEWTON_REG_CONTACT = 0.02, NEWTON_REG_L
 constexpr int NEWTON_MAX_PASSES = 8;
 
 struct LegRows {             // Newton model: what the contact rows of one leg need besides the link vectors
-  real z[4];                 // height of hip, knee, ankle, toe (rows exist iff < 0)
+  uint32_t below;            // bit k: point k (hip, knee, ankle, toe) is under the ground, its rows exist
   real aref[4][2];           // reference acceleration of the +mu and the -mu edge
 };
 
@@ -221,7 +221,7 @@ __device__ __forceinline__ void leg_terms(Leg& g, LegRows& rows, const real sign
     const Vec2 as[4] = {Hk, a_knee, a_ank, a_toe};
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-      rows.z[k] = zs[k];
+      rows.below = (k == 0 ? 0u : rows.below) | (zs[k] < 0.0 ? 1u << k : 0u);
 #pragma unroll
       for (int e = 0; e < 2; ++e) {
         const real smu = e == 0 ? P.mu : -P.mu;
@@ -331,7 +331,7 @@ __device__ __forceinline__ uint32_t leg_active_set(const Leg& g, const LegRows& 
     real r = smu * ar[0] + ar[1] + t * ar[2] - rows.aref[k][e];
 #pragma unroll
     for (int m = 0; m < decltype(depth)::value; ++m) r += u[m] * aj[m];
-    set |= (rows.z[k] < 0.0 && r < 0.0) ? (1u << (2 * k + e)) : 0u;
+    set |= ((rows.below >> k & 1u) && r < 0.0) ? (1u << (2 * k + e)) : 0u;
   });
 #pragma unroll
   for (int m = 0; m < 3; ++m) {
@@ -620,7 +620,7 @@ __device__ __forceinline__ void pair_from_full(PairLane& p, const BodyLane& s, c
 }
 
 template <bool NEWTON>
-__global__ __launch_bounds__(WAVE) void body_rollout_kernel(BodyLaunch a) {
+__global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(2, 2))) void body_rollout_kernel(BodyLaunch a) {
   a.step0 = launch_first_step(a.counter, a.step0, a.T);
   const int64_t n = a.n;
   const int side = threadIdx.x & 1;
