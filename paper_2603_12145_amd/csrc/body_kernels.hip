@@ -344,11 +344,17 @@ __device__ __forceinline__ uint32_t leg_active_set(const Leg& g, const LegRows& 
 
 // Adds D J^T J of the active rows to the leg's blocks and the root block, D aref J to the right-hand
 // sides.
+// SKIP_IDLE_ROWS: leave out a row that is active in no lane of the wavefront (it adds zeros).  The
+// eight wave-uniform branches cost a lone wavefront on its SIMD more than they save (they cut the
+// pass into blocks the scheduler cannot interleave: 21.8 against 21.4 ms at N = 8192) and pay once
+// two wavefronts share a SIMD (14.4 against 15.4 ms at N = 262144), so the launcher picks by N.
+template <bool SKIP_IDLE_ROWS>
 __device__ __forceinline__ void leg_add_rows(const Leg& g, const LegRows& rows, const real* jq, const real* jv,
                                              const uint32_t set, const Params& P, LegBlock& B, RootBlock& R,
                                              real g_root[3], real g_leg[3]) {
   const int sym[3][3] = {{0, 1, 2}, {1, 3, 4}, {2, 4, 5}};
   for_each_contact_row(g, P.mu, [&](auto depth, int k, int e, real smu, real t, const real* u) {
+    if (SKIP_IDLE_ROWS && __ballot(set >> (2 * k + e) & 1u) == 0ull) return;
     const real w = (set >> (2 * k + e) & 1u) ? P.d_contact : 0.0;
     const real aw = w * rows.aref[k][e];
     const real ws = w * smu, wt = w * t;
@@ -558,6 +564,7 @@ __device__ __forceinline__ void pair_substep(PairLane& s, const real sign, const
 }
 
 // One substep in place, Newton contact model.
+template <bool SKIP_IDLE_ROWS>
 __device__ __forceinline__ void pair_substep_newton(PairLane& s, const real sign, const real a[3],
                                                     const Params& P) {
   real st, ct;
@@ -589,7 +596,7 @@ __device__ __forceinline__ void pair_substep_newton(PairLane& s, const real sign
       for (int c = 0; c < 3; ++c) B.C[r][c] = g.C[r][c];
     RootBlock dR = {0.0, 0.0, 0.0, 0.0, 0.0, 0.0};
     real dg_root[3] = {0.0, 0.0, 0.0}, g_leg[3] = {f_leg[0], f_leg[1], f_leg[2]};
-    leg_add_rows(g, rows, s.jq, s.jv, set, P, B, dR, dg_root, g_leg);
+    leg_add_rows<SKIP_IDLE_ROWS>(g, rows, s.jq, s.jv, set, P, B, dR, dg_root, g_leg);
     const RootBlock R = {R0.xx + pair_sum(dR.xx), R0.xz + pair_sum(dR.xz), R0.xth + pair_sum(dR.xth),
                          R0.zz + pair_sum(dR.zz), R0.zth + pair_sum(dR.zth), R0.thth + pair_sum(dR.thth)};
     real g_root[3];
@@ -619,7 +626,7 @@ __device__ __forceinline__ void pair_from_full(PairLane& p, const BodyLane& s, c
   p.ep_ret = s.ep_ret; p.ep_len = s.ep_len;
 }
 
-template <bool NEWTON>
+template <bool NEWTON, bool SKIP_IDLE_ROWS>
 __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(2, 2))) void body_rollout_kernel(BodyLaunch a) {
   a.step0 = launch_first_step(a.counter, a.step0, a.T);
   const int64_t n = a.n;
@@ -668,7 +675,7 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(2, 2))) vo
     cost = pair_sum(cost);
     real vx_sum = 0.0;
     for (int sub = 0; sub < SUBSTEPS; ++sub) {
-      if (NEWTON) pair_substep_newton(s, sign, act, P);
+      if (NEWTON) pair_substep_newton<SKIP_IDLE_ROWS>(s, sign, act, P);
       else pair_substep(s, sign, act, P);
       vx_sum += s.vr[0];
     }
@@ -751,8 +758,9 @@ hipError_t launch_body_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t
 
 hipError_t launch_body_rollout(const BodyLaunch& a, hipStream_t stream) {
   const dim3 grid((unsigned)((a.n + WAVE / 2 - 1) / (WAVE / 2)));   // 32 environments per wavefront
-  if (a.newton) hipLaunchKernelGGL(body_rollout_kernel<true>, grid, dim3(WAVE), 0, stream, a);
-  else hipLaunchKernelGGL(body_rollout_kernel<false>, grid, dim3(WAVE), 0, stream, a);
+  if (a.newton && a.n >= 32768) hipLaunchKernelGGL((body_rollout_kernel<true, true>), grid, dim3(WAVE), 0, stream, a);
+  else if (a.newton) hipLaunchKernelGGL((body_rollout_kernel<true, false>), grid, dim3(WAVE), 0, stream, a);
+  else hipLaunchKernelGGL((body_rollout_kernel<false, false>), grid, dim3(WAVE), 0, stream, a);
   return hipGetLastError();
 }
 

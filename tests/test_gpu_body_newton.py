@@ -27,9 +27,11 @@ def newton_states(n, seed, warm):
     return o.get_state().astype(np.float32).astype(np.float64)
 
 
-@pytest.mark.parametrize("warm", [0, 3, 60, 400])
-def test_single_step_from_oracle_states(warm):
-    n, seed = 4096, 4
+# n = 40000 takes the large-batch instantiation of the kernel (rows idle in a whole wavefront are
+# skipped), the others the small-batch one
+@pytest.mark.parametrize("n,warm", [(4096, 0), (4096, 3), (4096, 60), (4096, 400), (40000, 60)])
+def test_single_step_from_oracle_states(n, warm):
+    seed = 4
     s = newton_states(n, seed, warm)
     o = Body(n, seed, np.float64, solver=1); o.set_state(s); o.step_count = warm
     oobs, orew, odone = o.rollout(1, nthreads=8)
@@ -54,6 +56,26 @@ def test_single_step_from_oracle_states(warm):
     assert flips <= n // 1000
     assert np.median(worst) < 5e-7
     assert np.array_equal(done[0].cpu().numpy(), odone[0])
+
+
+def test_large_and_small_batch_kernels_agree_bit_for_bit():
+    """Environment i does not depend on the batch size, although batches of 32768 and more run a
+    different instantiation of the kernel (idle rows skipped per wavefront)."""
+    seed, T, small, large = 8, 40, 700, 33000
+    outs = []
+    for n in (small, large):
+        h = b.env_create(b.ENV_BODY, n, seed, NEWTON)
+        try:
+            b.env_reset(h, None)
+            obs, rew, done = bufs(T, n)
+            b.env_rollout(h, T, None, obs, rew, done)
+            torch.cuda.synchronize()
+            outs.append((obs[:, :small].cpu().numpy(), rew[:, :small].cpu().numpy()))
+        finally:
+            b.env_destroy(h)
+    assert_bit_equal(outs[1][0], outs[0][0], "obs of the first environments, large vs small batch")
+    assert_bit_equal(outs[1][1], outs[0][1], "reward")
+    assert np.abs(outs[0][0][-1] - outs[0][0][0]).max() > 1e-2
 
 
 def test_single_step_with_external_actions():
