@@ -153,12 +153,15 @@ def bench_pong_per_step(b, torch, n, seed, launches):
                 hbm_gbs=n * 101 / (wall / launches) / 1e9)
 
 
-def bench_pixels(b, torch, n, seed, launches, warmup=20, layout="slot_major", device_counter=False):
+def bench_pixels(b, torch, n, seed, launches, warmup=20, layout="slot_major", device_counter=False,
+                 delta=False):
     dev = "cuda:0"
     code = b.ENV_PIXELS_SLOT_MAJOR if layout == "slot_major" else b.ENV_PIXELS_ENV_MAJOR
     cfg = {"pixel_layout": code}
     if device_counter:      # one launch per step that a HIP graph can replay (no staged lookahead)
         cfg["step_counter"] = b.ENV_STEP_COUNTER_DEVICE
+    if delta:               # opt-in contract: the ring is shared state, a step rewrites only changed pixels
+        cfg["pixel_update"] = b.ENV_PIXELS_DELTA
     h = b.env_create(b.ENV_PONG_PIXELS, n, seed, cfg)
     ring = torch.zeros((4, n, 84, 84) if layout == "slot_major" else (n, 4, 84, 84),
                        dtype=torch.uint8, device=dev)
@@ -210,17 +213,23 @@ def bench_pixels(b, torch, n, seed, launches, warmup=20, layout="slot_major", de
     b.env_destroy(h)
     mean_ms = sum(s.elapsed_time(e) for s, e, _ in blocks_ms) / launches
     gbs = n * FRAME_BYTES / (mean_ms * 1e-3) / 1e9
-    return dict(workload="pong pixels N=%d, 84x84 u8 frame into a 4-slot ring (%s), one env_step "
-                         "call per step%s" % (n, "u8[4,N,84,84]" if layout == "slot_major" else "u8[N,4,84,84]",
-                                             ", step counter in device memory" if device_counter else ""),
-                **graph,
-                env_steps_per_s=n * launches / wall, us_per_step_events=mean_ms * 1e3,
-                us_per_step_wall=1e6 * wall / launches,
-                roofline=dict(bound="hbm", achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s",
-                              frac=gbs / HBM_PEAK_GBS,
-                              traffic=_traffic("pixel_fused_step_n%d" % n)
-                              if layout == "slot_major" and not device_counter else None),
-                launches=launches)
+    out = dict(workload="pong pixels N=%d, 84x84 u8 frame into a 4-slot ring (%s), one env_step "
+                        "call per step%s" % (n, "u8[4,N,84,84]" if layout == "slot_major" else "u8[N,4,84,84]",
+                                            (", step counter in device memory" if device_counter else "")
+                                            + (", delta updates of the slot" if delta else "")),
+               **graph,
+               env_steps_per_s=n * launches / wall, us_per_step_events=mean_ms * 1e3,
+               us_per_step_wall=1e6 * wall / launches, launches=launches)
+    if delta:
+        # only changed pixels are written, so the frame's 7056 bytes are not this path's traffic and
+        # no bandwidth roofline applies: the rate is reported beside the full-write figure instead
+        out["bound"] = "scattered partial-line writes (a few dozen bytes per environment), not a stream"
+        out["whole_frame_equivalent_gbs"] = gbs
+    else:
+        out["roofline"] = dict(bound="hbm", achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s", frac=gbs / HBM_PEAK_GBS,
+                               traffic=_traffic("pixel_fused_step_n%d" % n)
+                               if layout == "slot_major" and not device_counter else None)
+    return out
 
 
 def bench_fill(b, torch, nbytes, launches=50):
@@ -469,6 +478,8 @@ def main():
     if args.only:
         fn = {"pixels": lambda: bench_pixels(b, torch, 16384, 3, args.steps),
               "pixels_device_counter": lambda: bench_pixels(b, torch, 16384, 3, args.steps, device_counter=True),
+              "pixels_delta": lambda: [bench_pixels(b, torch, 16384, 3, args.steps, delta=True),
+                                       bench_pixels(b, torch, 16384, 3, args.steps, delta=True, layout="env_major")],
               "per_step": lambda: bench_pong_per_step(b, torch, 4096, 1, args.steps),
               "body": lambda: bench_body(b, torch, 8192, 1000, 4, args.steps),
               "body_sweep": lambda: bench_body_sweep(b, torch, args.steps),
@@ -519,6 +530,7 @@ def main():
         extra["config3_pixels"] = bench_pixels(b, torch, 16384, 3, 500)
         extra["config3_pixels_env_major"] = bench_pixels(b, torch, 16384, 3, 500, layout="env_major")
         extra["config3_pixels_device_counter"] = bench_pixels(b, torch, 16384, 3, 500, device_counter=True)
+        extra["config3_pixels_delta_updates"] = bench_pixels(b, torch, 16384, 3, 500, delta=True)
         for nn in (16384, 262144):
             rr = bench_pong_rollout(b, torch, nn, T, seed, max(3, args.steps // 6), 1)
             gbs = PONG_BYTES_PER_ENV_STEP * nn * T / (rr["mean_ms"] * 1e-3) / 1e9

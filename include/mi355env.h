@@ -73,6 +73,7 @@ typedef struct env_config_t {
   int32_t step_counter;       /* ENV_STEP_COUNTER_* below; 0 = default (host)                     */
   int32_t obs_scaling;        /* ENV_OBS_* below; 0 = default (raw)                               */
   int32_t contact_solver;     /* body: ENV_CONTACT_* below; 0 = default (penalty)                 */
+  int32_t pixel_update;       /* pixels: ENV_PIXELS_FULL / ENV_PIXELS_DELTA below; 0 = default    */
 } env_config_t;
 
 /* Ground contact and joint limits of ENV_BODY (other kinds: ENV_E_UNSUPPORTED for NEWTON).
@@ -119,6 +120,20 @@ enum { ENV_STEP_COUNTER_HOST = 1, ENV_STEP_COUNTER_DEVICE = 2 };
  *   env-major   uint8[N][4][84][84]  frame at ((i*4 + k) * 7056): each environment's four frames
  *               are adjacent (NCHW order), at the price of a 25 %-dense write stream per step. */
 enum { ENV_PIXELS_SLOT_MAJOR = 1, ENV_PIXELS_ENV_MAJOR = 2 };
+
+/* How env_step brings a ring slot of ENV_PONG_PIXELS up to date (other kinds: ENV_E_UNSUPPORTED for
+ * DELTA).  The ring's contents after a step are the same either way.
+ *   full   every step writes all 7056 bytes of every environment's newest frame (default): the
+ *          slot's previous contents do not matter;
+ *   delta  the slot still holds the frame written four steps earlier, which differs from the new one
+ *          in a few dozen pixels: the step clears the pixels that went dark and sets the ones that
+ *          lit up, and touches nothing else.  This makes the ring shared state: pass the same ring
+ *          to every env_reset / env_step and do not write to it.  The library keeps the rectangles
+ *          of the last five frames (60 B/env) and falls back to a full write of a slot whenever it
+ *          did not itself put the frame of four steps earlier there (first steps after env_create
+ *          or env_set_state, another ring pointer, steps taken through env_rollout in between).
+ *          Needs the host step counter (ENV_E_UNSUPPORTED with ENV_STEP_COUNTER_DEVICE). */
+enum { ENV_PIXELS_FULL = 1, ENV_PIXELS_DELTA = 2 };
 
 /* Statistics of the episodes that ended since the counters were last cleared. */
 typedef struct env_stats_t {

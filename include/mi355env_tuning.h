@@ -38,6 +38,11 @@ int mi355env_tune_frame_trajectory(int mode);
  * 2 = page renderer fused with the next step's dynamics in one launch (default). */
 int mi355env_tune_plane_path(int mode);
 
+/* Inspection, for a handle of ENV_PONG_PIXELS created with pixel_update = ENV_PIXELS_DELTA: how many
+ * env_step calls since env_create rewrote only the changed pixels of their ring slot and how many
+ * fell back to a full write of it.  `e` is the env_t* of include/mi355env.h; host pointers. */
+int mi355env_pixel_update_counts(const void *e, int64_t *delta_steps, int64_t *full_steps);
+
 /* Yardsticks, launched on hip_stream: dst[i] = value; dst = src; a kernel that does nothing.
  * Pointers are device memory, 16-byte aligned, bytes a multiple of 16 (else -1); -3 if the launch
  * fails. */

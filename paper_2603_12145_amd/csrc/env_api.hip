@@ -64,6 +64,7 @@ env_config_t default_config(int kind) {
   c.step_counter = ENV_STEP_COUNTER_HOST;
   c.obs_scaling = ENV_OBS_RAW;
   c.contact_solver = ENV_CONTACT_PENALTY;
+  c.pixel_update = ENV_PIXELS_FULL;
   (void)kind;
   return c;
 }
@@ -100,6 +101,10 @@ int merge_config(env_config_t* dst, const env_config_t* src) {
     if (src->contact_solver != ENV_CONTACT_PENALTY && src->contact_solver != ENV_CONTACT_NEWTON)
       return ENV_E_ARG;
     dst->contact_solver = src->contact_solver;
+  }
+  if (sz >= FIELD_END(env_config_t, pixel_update) && src->pixel_update != 0) {
+    if (src->pixel_update != ENV_PIXELS_FULL && src->pixel_update != ENV_PIXELS_DELTA) return ENV_E_ARG;
+    dst->pixel_update = src->pixel_update;
   }
   if (!std::isfinite(dst->armature) || !std::isfinite(dst->joint_damping) ||
       !std::isfinite(dst->friction_mu))
@@ -235,7 +240,9 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
       else x.frames = static_cast<uint8_t*>(obs);
       const bool plane_step = ring_mode && x.slot_major && T == 1 && pixel_plane_mode() != 0 &&
                               e->n < (int64_t)4000000;
-      if (plane_step && e->device_counter) {
+      if (ring_mode && T == 1 && e->cfg.pixel_update == ENV_PIXELS_DELTA) {
+        err = pixel_delta_step(e->pipe, x, e->stream);
+      } else if (plane_step && e->device_counter) {
         // no lookahead and no buffers alternated from the host: a replayed graph could do neither
         pixel_pipe_invalidate(e->pipe);
         err = pixel_counted_step(e->pipe, x, e->stream);
@@ -265,6 +272,9 @@ int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_c
   if (merge_config(&c, cfg) != ENV_OK) return ENV_E_ARG;
   if (c.obs_scaling == ENV_OBS_NORMALIZED && kind != ENV_PONG) return ENV_E_UNSUPPORTED;
   if (c.contact_solver == ENV_CONTACT_NEWTON && kind != ENV_BODY) return ENV_E_UNSUPPORTED;
+  if (c.pixel_update == ENV_PIXELS_DELTA &&
+      (kind != ENV_PONG_PIXELS || c.step_counter == ENV_STEP_COUNTER_DEVICE))
+    return ENV_E_UNSUPPORTED;
 
   env_t* e = new (std::nothrow) env_t();
   if (!e) return ENV_E_ALLOC;
@@ -285,7 +295,7 @@ int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_c
   if (hipMalloc(reinterpret_cast<void**>(&e->stats), sizeof(DeviceStats) + sizeof(StepCounter)) != hipSuccess) {
     (void)hipGetLastError(); (void)hipFree(e->state); delete e; return ENV_E_ALLOC;
   }
-  if (kind == ENV_PONG_PIXELS && pixel_pipe_create(e->pipe, n_envs) != hipSuccess) {
+  if (kind == ENV_PONG_PIXELS && pixel_pipe_create(e->pipe, n_envs, c.pixel_update == ENV_PIXELS_DELTA) != hipSuccess) {
     (void)hipGetLastError(); (void)hipFree(e->state); (void)hipFree(e->stats); delete e;
     return ENV_E_ALLOC;
   }
@@ -322,6 +332,9 @@ int env_reset(env_t* e, void* obs_dev) {
     err = launch_pixel_reset(e->state, e->n, e->seed, e->step, counter, static_cast<uint8_t*>(obs_dev),
                              e->cfg.pixel_layout == ENV_PIXELS_SLOT_MAJOR, e->pipe.blocks[0], e->stream);
     pixel_pipe_invalidate(e->pipe);
+    if (err == hipSuccess && e->cfg.pixel_update == ENV_PIXELS_DELTA)
+      err = pixel_delta_after_reset(e->pipe, e->state, e->n, e->step, static_cast<const uint8_t*>(obs_dev),
+                                    e->stream);
   } else if (e->kind == ENV_BODY) {
     if (obs_dev && !device_range_ok(e, obs_dev, (size_t)e->n * BODY_OBS * sizeof(float), 4))
       return ENV_E_ARG;
@@ -337,7 +350,10 @@ int env_reset(env_t* e, void* obs_dev) {
     err = launch_pong_reset(e->state, e->n, e->seed, e->step, counter,
                             e->kind == ENV_PONG ? static_cast<float*>(obs_dev) : nullptr,
                             e->cfg.obs_scaling == ENV_OBS_NORMALIZED, e->stream);
-    if (e->kind == ENV_PONG_PIXELS) pixel_pipe_invalidate(e->pipe);
+    if (e->kind == ENV_PONG_PIXELS) {
+      pixel_pipe_invalidate(e->pipe);
+      pixel_delta_forget(e->pipe);          // new episodes, no ring written: its slots are stale
+    }
   }
   if (err != hipSuccess) return ENV_E_HIP;
   e->was_reset = true;
@@ -417,7 +433,10 @@ int env_set_state(env_t* e, const void* host_buf, size_t bytes) {
       return ENV_E_HIP;
   }
   e->was_reset = true;
-  if (e->kind == ENV_PONG_PIXELS) pixel_pipe_invalidate(e->pipe);
+  if (e->kind == ENV_PONG_PIXELS) {
+    pixel_pipe_invalidate(e->pipe);
+    pixel_delta_forget(e->pipe);            // the ring is not part of the state: it no longer matches
+  }
   return ENV_OK;
 }
 
@@ -466,6 +485,16 @@ const char* env_strerror(int code) {
     case ENV_E_UNSUPPORTED: return "not supported for this environment kind";
   }
   return "unknown status";
+}
+
+// How many ring steps of a delta-update handle rewrote only changed pixels, and how many fell back
+// to a full write of the slot.
+int mi355env_pixel_update_counts(const void* handle, int64_t* delta_steps, int64_t* full_steps) {
+  const env_t* e = static_cast<const env_t*>(handle);
+  if (!e || !delta_steps || !full_steps || e->kind != ENV_PONG_PIXELS) return ENV_E_ARG;
+  *delta_steps = e->pipe.delta_steps;
+  *full_steps = e->pipe.full_steps;
+  return ENV_OK;
 }
 
 // Measurement knob, not part of the documented boundary: launch shape of the pixel kernels.

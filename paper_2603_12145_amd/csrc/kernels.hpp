@@ -77,8 +77,14 @@ struct PixelPipe {
   bool staged = false;                             // staging buffers of parity (step & 1) hold `step`
   uint32_t* traj_blocks = nullptr;                 // [3][traj_cap] cell blocks of a chunk of a frame trajectory
   int64_t traj_cap = 0;                            // frames (environment-steps) per chunk
+  // Delta updates of the ring (only allocated for handles created with pixel_update = delta)
+  uint32_t* hist = nullptr;                        // [5][3][n] cell blocks of the last five frames, entry = step mod 5
+  const uint8_t* delta_ring = nullptr;             // the ring the two arrays below speak about
+  int64_t slot_step[4] = {INT64_MIN, INT64_MIN, INT64_MIN, INT64_MIN};   // step whose frame the library put in slot k
+  int64_t hist_step[5] = {INT64_MIN, INT64_MIN, INT64_MIN, INT64_MIN, INT64_MIN};   // step whose blocks entry j holds
+  int64_t delta_steps = 0, full_steps = 0;         // ring steps taken either way since creation
 };
-hipError_t pixel_pipe_create(PixelPipe& p, int64_t n);
+hipError_t pixel_pipe_create(PixelPipe& p, int64_t n, bool delta_updates);
 void pixel_pipe_destroy(PixelPipe& p);
 // One slot-major ring step.  `state` is the handle's committed-state pointer and is swapped with
 // p.state_alt.  a.pong.actions may be null (staged lookahead usable) or external.
@@ -88,6 +94,18 @@ inline void pixel_pipe_invalidate(PixelPipe& p) { p.staged = false; }
 // The same step for a handle whose step counter lives in device memory (a.pong.counter): two
 // launches, dynamics then page renderer, no lookahead, nothing alternated from the host.
 hipError_t pixel_counted_step(const PixelPipe& p, const PixelLaunch& a, hipStream_t stream);
+// Ring step that rewrites only the pixels in which the new frame differs from the one the slot
+// holds (the frame of four steps earlier), or the whole slot when the library cannot vouch for
+// what it holds.  State in place, no lookahead.
+hipError_t pixel_delta_step(PixelPipe& p, const PixelLaunch& a, hipStream_t stream);
+// After env_reset has written the initial frame to all four slots of `ring`: record that, so that
+// the next steps can already be delta updates.  `step` = the handle's step counter.
+hipError_t pixel_delta_after_reset(PixelPipe& p, const uint32_t* state, int64_t n, uint64_t step,
+                                   const uint8_t* ring, hipStream_t stream);
+inline void pixel_delta_forget(PixelPipe& p) {
+  for (auto& s : p.slot_step) s = INT64_MIN;
+  for (auto& s : p.hist_step) s = INT64_MIN;
+}
 int pixel_plane_mode();
 
 }  // namespace envk

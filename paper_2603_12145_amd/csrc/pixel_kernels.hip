@@ -336,6 +336,128 @@ __global__ __launch_bounds__(256) void plane_render_counted_kernel(const uint32_
   render_page(blocks, n, plane, blockIdx.x, page);
 }
 
+// ---- delta updates ----------------------------------------------------------------------------
+// A frame differs from the one four steps earlier in the pixels of three small rectangles.  One
+// launch takes the step and repairs the slot.  A workgroup owns 64 environments: its first
+// wavefront takes their step, one lane per environment (reward / done to the caller, state in
+// place, episode statistics, the new cell blocks to the history) and leaves the slot's old blocks
+// and the new ones in LDS; after the barrier all four wavefronts walk the 192 rectangles, 32 lanes
+// per rectangle.  Lane l stands for pixel (l & 3, l >> 2) of a 4-column x 8-row patch (a paddle
+// covers at most 4 x 8 cells, the ball at most 3 x 2), once anchored at the old block's corner --
+// there it clears its pixel unless one of the new blocks covers it (rectangles may overlap: the
+// ball in front of a paddle) -- and once at the new block's corner, where it sets its pixel unless
+// the old block covered it.  A rectangle that did not move is skipped.  Frame i of the slot starts
+// at base + i * stride.
+template <int ENVS>   // environments per workgroup
+__global__ __launch_bounds__(256) void pixel_delta_step_kernel(PongLaunch a, const uint32_t* __restrict__ old_blocks,
+                                                               uint32_t* __restrict__ new_blocks,
+                                                               uint8_t* __restrict__ base, int64_t stride) {
+  __shared__ uint32_t was[3][ENVS], now[3][ENVS];
+  const int64_t n = a.n;
+  const int64_t env0 = (int64_t)blockIdx.x * ENVS;
+  if (threadIdx.x < WAVE) {
+    const int lane = threadIdx.x;
+    const int64_t i = env0 + lane;
+    const bool live = lane < ENVS && i < n;
+    const int64_t ic = live ? i : n - 1;
+    PongLane s = pong_load(a.state, n, ic);
+    const Draw4 d = philox_draw(a.seed, (uint32_t)ic, a.step0, 0u);
+    const int action = a.actions ? (int)a.actions[ic] : pong_action_from_word(d.w0);
+    const PongEvent ev = pong_transition(s, action, d.w1, d.w2, a.max_score);
+    LaneEpisodes le;
+    if (live && ev.done) {
+      le.count = 1; le.length_sum = ev.fin_len; le.ret_sum_i = ev.fin_ret;
+      le.min_key = ev.fin_ret; le.max_key = ev.fin_ret;
+    }
+    const uint32_t nb[3] = {cell_block(140.0f, s.pa, 4.0f, 16.0f), cell_block(16.0f, s.po, 4.0f, 16.0f),
+                            cell_block(s.bx, s.by, 2.0f, 2.0f)};
+#pragma unroll
+    for (int k = 0; k < 3; ++k) {
+      if (lane < ENVS) {
+        now[k][lane] = nb[k];
+        was[k][lane] = live ? old_blocks[(int64_t)k * n + i] : nb[k];   // an idle lane shows no change
+      }
+      if (live) new_blocks[(int64_t)k * n + i] = nb[k];
+    }
+    if (live) {
+      a.reward[i] = ev.reward;
+      a.done[i] = ev.done ? 1 : 0;
+      pong_store(a.state, n, i, s);
+    }
+    flush_wave_stats<false>(a.stats, le);
+  }
+  __syncthreads();
+  const int dc = threadIdx.x & 3, dr = (threadIdx.x >> 2) & 7;
+  for (int item = threadIdx.x >> 5; item < 3 * ENVS; item += 8) {
+    const int k = item / ENVS, e = item % ENVS;
+    const uint32_t w = was[k][e], v = now[k][e];
+    if (w == v) continue;
+    uint8_t* frame = base + (env0 + e) * stride;
+    const int wc0 = w & 0xff, wc1 = (w >> 8) & 0xff, wr0 = (w >> 16) & 0xff, wr1 = w >> 24;
+    const int nc0 = v & 0xff, nc1 = (v >> 8) & 0xff, nr0 = (v >> 16) & 0xff, nr1 = v >> 24;
+    {
+      const int c = wc0 + dc, r = wr0 + dr;
+      bool lit = false;
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        const uint32_t q = now[j][e];
+        lit = lit || (c >= (int)(q & 0xff) && c < (int)((q >> 8) & 0xff) && r >= (int)((q >> 16) & 0xff) &&
+                      r < (int)(q >> 24));
+      }
+      if (c < wc1 && r < wr1 && !lit) frame[r * FRAME_SIDE + c] = 0;
+    }
+    {
+      const int c = nc0 + dc, r = nr0 + dr;
+      if (c < nc1 && r < nr1 && !(c >= wc0 && c < wc1 && r >= wr0 && r < wr1)) frame[r * FRAME_SIDE + c] = 255;
+    }
+  }
+}
+
+// Whole frames of one slot from their cell blocks, any layout: one wavefront per environment, each
+// lane builds 16-byte chunks by testing its 16 pixels against the three blocks.  Only used for the
+// few steps in which a slot's contents are not known; the page renderer is the fast full write.
+__global__ __launch_bounds__(256) void slot_full_kernel(const uint32_t* __restrict__ blocks, int64_t n,
+                                                        uint8_t* __restrict__ base, int64_t stride) {
+  const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (i >= n) return;
+  const int lane = threadIdx.x & (WAVE - 1);
+  uint32_t b[3];
+#pragma unroll
+  for (int k = 0; k < 3; ++k) b[k] = blocks[(int64_t)k * n + i];
+  chunk_t* frame = reinterpret_cast<chunk_t*>(base + i * stride);
+  for (int chunk = lane; chunk < CHUNKS; chunk += WAVE) {
+    uint32_t words[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int byte = 0; byte < 16; ++byte) {
+      const int p = chunk * 16 + byte, r = p / FRAME_SIDE, c = p - r * FRAME_SIDE;
+      bool lit = false;
+#pragma unroll
+      for (int k = 0; k < 3; ++k)
+        lit = lit || (c >= (int)(b[k] & 0xff) && c < (int)((b[k] >> 8) & 0xff) && r >= (int)((b[k] >> 16) & 0xff) &&
+                      r < (int)(b[k] >> 24));
+      words[byte >> 2] |= lit ? 0xffu << (8 * (byte & 3)) : 0u;
+    }
+    frame[chunk] = chunk_t{words[0], words[1], words[2], words[3]};
+  }
+}
+
+// Cell blocks of the frame that the state as it stands would render, written to `copies` buffers
+// of [3][n] that lie `pitch` words apart.
+__global__ __launch_bounds__(256) void blocks_of_state_kernel(const uint32_t* __restrict__ state, int64_t n,
+                                                              uint32_t* __restrict__ out0, uint32_t* __restrict__ out1,
+                                                              uint32_t* __restrict__ out2, uint32_t* __restrict__ out3) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i >= n) return;
+  const PongLane s = pong_load(state, n, i);
+  const uint32_t b0 = cell_block(140.0f, s.pa, 4.0f, 16.0f), b1 = cell_block(16.0f, s.po, 4.0f, 16.0f);
+  const uint32_t b2 = cell_block(s.bx, s.by, 2.0f, 2.0f);
+  uint32_t* outs[4] = {out0, out1, out2, out3};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    outs[j][0 * n + i] = b0; outs[j][1 * n + i] = b1; outs[j][2 * n + i] = b2;
+  }
+}
+
 // F(t): the first ceil(n / 256) workgroups commit step t (reward / done to the caller, episode
 // statistics) and, if `ahead`, stage step t+1; the remaining workgroups render step t's plane.
 struct FusedStep {
@@ -446,7 +568,7 @@ bool set_plane_path(int mode) {
 }
 int pixel_plane_mode() { return g_plane_path; }
 
-hipError_t pixel_pipe_create(PixelPipe& p, int64_t n) {
+hipError_t pixel_pipe_create(PixelPipe& p, int64_t n, bool delta_updates) {
   auto up = [](size_t b) { return (b + 255) & ~(size_t)255; };
   const size_t state_b = up((size_t)PONG_FIELDS * n * 4), blocks_b = up((size_t)3 * n * 4);
   const size_t word_b = up((size_t)n * 4), done_b = up((size_t)n);
@@ -454,9 +576,12 @@ hipError_t pixel_pipe_create(PixelPipe& p, int64_t n) {
   // thousand frames, so that small batches are rendered many steps at a time
   p.traj_cap = n > TRAJ_MIN_FRAMES ? n : TRAJ_MIN_FRAMES;
   const size_t traj_b = up((size_t)3 * (size_t)p.traj_cap * 4);
-  const hipError_t err = hipMalloc(&p.slab, state_b + 2 * (blocks_b + 3 * word_b + done_b) + traj_b);
+  const size_t hist_b = delta_updates ? up((size_t)5 * 3 * (size_t)n * 4) : 0;
+  const hipError_t err = hipMalloc(&p.slab, state_b + 2 * (blocks_b + 3 * word_b + done_b) + traj_b + hist_b);
   if (err != hipSuccess) return err;
   char* at = static_cast<char*>(p.slab);
+  if (delta_updates) { p.hist = reinterpret_cast<uint32_t*>(at); at += hist_b; }
+  pixel_delta_forget(p);
   p.state_alt = reinterpret_cast<uint32_t*>(at); at += state_b;
   p.traj_blocks = reinterpret_cast<uint32_t*>(at); at += traj_b;
   for (int k = 0; k < 2; ++k) {
@@ -529,6 +654,76 @@ hipError_t pixel_counted_step(const PixelPipe& p, const PixelLaunch& a, hipStrea
   hipLaunchKernelGGL(plane_render_counted_kernel, dim3(pages), dim3(256), 0, stream, p.blocks[0], n, a.ring,
                      a.pong.counter);
   return hipGetLastError();
+}
+
+// 0 <= x mod m < m for negative x too
+static int wrap(int64_t x, int m) { return (int)(((x % m) + m) % m); }
+
+hipError_t pixel_delta_after_reset(PixelPipe& p, const uint32_t* state, int64_t n, uint64_t step,
+                                   const uint8_t* ring, hipStream_t stream) {
+  if (!p.hist) return hipErrorInvalidValue;
+  // All four slots hold the initial frame.  For the bookkeeping that is as if the steps s-4 .. s-1
+  // (s = the next step) had each put that frame into their slot.
+  const int64_t s = (int64_t)step;
+  uint32_t* entry[4];
+  for (int back = 1; back <= 4; ++back) entry[back - 1] = p.hist + (int64_t)wrap(s - back, 5) * 3 * n;
+  hipLaunchKernelGGL(blocks_of_state_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, state, n,
+                     entry[0], entry[1], entry[2], entry[3]);
+  const hipError_t err = hipGetLastError();
+  if (err != hipSuccess) { pixel_delta_forget(p); return err; }
+  pixel_delta_forget(p);
+  p.delta_ring = ring;
+  for (int back = 1; back <= 4; ++back) {
+    p.slot_step[wrap(s - back, 4)] = s - back;
+    p.hist_step[wrap(s - back, 5)] = s - back;
+  }
+  return hipSuccess;
+}
+
+hipError_t pixel_delta_step(PixelPipe& p, const PixelLaunch& a, hipStream_t stream) {
+  if (!p.hist || !a.ring) return hipErrorInvalidValue;
+  const int64_t n = a.pong.n;
+  const int64_t s = (int64_t)a.pong.step0;
+  const int slot = wrap(s, 4), e_new = wrap(s, 5), e_old = wrap(s - 4, 5);
+  if (p.delta_ring != a.ring) { pixel_delta_forget(p); p.delta_ring = a.ring; }
+  uint32_t* new_blocks = p.hist + (int64_t)e_new * 3 * n;
+  const uint32_t* old_blocks = p.hist + (int64_t)e_old * 3 * n;
+  // the slot holds the frame of step s - 4, put there by this library, and its blocks are still kept
+  const bool known = p.slot_step[slot] == s - 4 && p.hist_step[e_old] == s - 4;
+
+  PongLaunch d = a.pong;
+  d.T = 1;
+  p.hist_step[e_new] = INT64_MIN;          // until the launches below are known to be enqueued
+  p.slot_step[slot] = INT64_MIN;
+  uint8_t* base = a.slot_major ? a.ring + (int64_t)slot * n * FRAME_BYTES : a.ring + (int64_t)slot * FRAME_BYTES;
+  const int64_t stride = a.slot_major ? FRAME_BYTES : 4 * (int64_t)FRAME_BYTES;
+  hipError_t err;
+  if (known) {
+    // Few environments per workgroup: the step of a workgroup's environments runs on one wavefront
+    // while the other three wait, so small groups start their pixel work sooner (N = 16384: 15.6 us
+    // per step with 64 environments per workgroup, 10.7 with 32, 9.3 with 16, 8.8 with 8); large
+    // batches have workgroups enough to hide that and prefer fewer of them (N = 131072: 55.7 us
+    // with 16, 61.3 with 8).
+    if (n <= 32768)
+      hipLaunchKernelGGL(pixel_delta_step_kernel<8>, dim3((unsigned)((n + 7) / 8)), dim3(256), 0, stream, d,
+                         old_blocks, new_blocks, base, stride);
+    else
+      hipLaunchKernelGGL(pixel_delta_step_kernel<16>, dim3((unsigned)((n + 15) / 16)), dim3(256), 0, stream, d,
+                         old_blocks, new_blocks, base, stride);
+  } else {
+    hipLaunchKernelGGL(pixel_traj_dynamics_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, d,
+                       new_blocks, n);
+    err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(slot_full_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, stream, new_blocks, n, base,
+                       stride);
+  }
+  err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  p.hist_step[e_new] = s;
+  p.slot_step[slot] = s;
+  (known ? p.delta_steps : p.full_steps) += 1;
+  return hipSuccess;
 }
 
 hipError_t launch_pixel_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,

@@ -37,7 +37,7 @@ def test_every_tuning_symbol_is_exported(L):
     text = open(os.path.join(ROOT, "include", "mi355env_tuning.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = sorted(set(re.findall(r"\b(mi355env_[a-z_]+)\s*\(", text)))
-    assert len(names) == 10, names
+    assert len(names) == 11, names
     for n in names:
         assert hasattr(L, n), n
     assert L.mi355env_tune_paged_stores(9) == -1 and L.mi355env_tune_paged_stores(2) == 0
@@ -85,7 +85,7 @@ def test_argument_errors_without_gpu(L):
 
 def test_binding_struct_layout_matches_header():
     from paper_2603_12145_amd import binding as b
-    assert C.sizeof(b.env_config_t) == 40
+    assert C.sizeof(b.env_config_t) == 44
     assert C.sizeof(b.env_stats_t) == 48
     hdr = open(HEADER).read()
     cfg = re.search(r"typedef struct env_config_t \{(.*?)\} env_config_t;", hdr, re.S).group(1)

@@ -271,3 +271,109 @@ def test_frame_trajectory_rendered_in_chunks(n, T):
         assert_bit_equal(got[k], orc.pong_render_one(st), "frame t=%d env=%d" % (t, e))
     # the frames are not all alike (the ball moves)
     assert (got[0] != got[1]).any()
+
+
+def _update_counts(h):
+    import ctypes as C
+    L = b.lib()
+    L.mi355env_pixel_update_counts.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+    d, f = C.c_int64(-1), C.c_int64(-1)
+    assert L.mi355env_pixel_update_counts(h, C.byref(d), C.byref(f)) == 0
+    return d.value, f.value
+
+
+@pytest.mark.parametrize("layout", ["slot_major", "env_major"])
+@pytest.mark.parametrize("n", [1, 37, 255, 1000])
+def test_delta_updates_leave_the_same_ring_as_the_oracle(n, layout):
+    """pixel_update = delta: a step changes only the pixels in which the new frame differs from the
+    one its slot holds.  The ring must equal the oracle's after every step, through episode ends,
+    external actions, a save / restore, steps taken through env_rollout in between, a change of ring
+    buffer and a second reset -- and most steps must really have been delta updates."""
+    seed, T = 70 + n, 110
+    acts = inputs.pong_actions(T, n, seed=5)
+    dacts = torch.from_numpy(acts).to(DEV)
+    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"max_score": 1, "pixel_layout": LAYOUTS[layout],
+                                                   "pixel_update": b.ENV_PIXELS_DELTA})
+    try:
+        ring = new_ring(n, layout)
+        ring.fill_(77)                                   # env_reset must overwrite all of it
+        rew = torch.empty(n, dtype=torch.float32, device=DEV)
+        done = torch.empty(n, dtype=torch.uint8, device=DEV)
+        b.env_reset(h, ring)
+        p = orc.Pong(n, seed, max_score=1); p.reset()
+        stack = np.zeros((n, 4, F, F), np.uint8); p.fill_stack(stack)
+        torch.cuda.synchronize()
+        assert_bit_equal(ring_as_env_major(ring, layout), stack, "ring after reset")
+        expect_full = 0
+        t = 0
+        while t < T:
+            ext = t % 3 == 1
+            b.env_step(h, dacts[t] if ext else None, ring, rew, done)
+            _, orew, odone = p.step(actions=acts[t] if ext else None, stack=stack)
+            torch.cuda.synchronize()
+            assert_bit_equal(ring_as_env_major(ring, layout), stack, "ring after step %d" % t)
+            assert_bit_equal(rew.cpu().numpy(), orew, "reward step %d" % t)
+            assert_bit_equal(done.cpu().numpy(), odone, "done step %d" % t)
+            t += 1
+            if t == 25:                                  # restore: the library forgets what the slots hold
+                b.env_set_state(h, b.env_get_state(h))
+                expect_full += 4
+            if t == 45:                                  # three steps that write no ring slot, on both sides
+                fr = torch.empty((3, n, F, F), dtype=torch.uint8, device=DEV)
+                r3 = torch.empty((3, n), dtype=torch.float32, device=DEV)
+                d3 = torch.empty((3, n), dtype=torch.uint8, device=DEV)
+                b.env_rollout(h, 3, None, fr, r3, d3)
+                p.rollout(3)
+                t += 3
+                expect_full += 3                         # the slots of the three skipped steps are stale
+            if t == 70:                                  # another buffer with the same contents
+                ring = ring.clone()
+                expect_full += 4
+            if t == 90:                                  # second reset, stale data in the ring first
+                ring.fill_(5)
+                b.env_reset(h, ring)
+                p.reset(); p.fill_stack(stack)
+        delta, full = _update_counts(h)
+        assert full == expect_full and delta == T - 3 - expect_full, (delta, full)
+        assert b.env_stats(h)["episodes"] == p.stats()["episodes"]
+        if n >= 37:
+            assert p.stats()["episodes"] > 0
+    finally:
+        b.env_destroy(h)
+
+
+def test_delta_update_handles_only_for_pixels_with_the_host_counter():
+    for kind in (b.ENV_PONG, b.ENV_BODY, b.ENV_CARTPOLE):
+        with pytest.raises(b.EnvError) as ei:
+            b.env_create(kind, 64, 0, {"pixel_update": b.ENV_PIXELS_DELTA})
+        assert ei.value.code == b.ENV_E_UNSUPPORTED
+    with pytest.raises(b.EnvError) as ei:
+        b.env_create(b.ENV_PONG_PIXELS, 64, 0, {"pixel_update": b.ENV_PIXELS_DELTA,
+                                                "step_counter": b.ENV_STEP_COUNTER_DEVICE})
+    assert ei.value.code == b.ENV_E_UNSUPPORTED
+
+
+@pytest.mark.parametrize("n,T", [(16384, 60), (40000, 40)])
+def test_delta_updates_at_config3_size_match_full_updates(n, T):
+    """N = 16384 (config 3) and a batch beyond 32768, which runs the kernel's other workgroup shape:
+    delta steps leave the ring byte-identical to a handle that rewrites whole frames (which
+    test_config3 ties to the oracle); a ragged last workgroup at N = 40000 + 3."""
+    n, seed = n + (3 if n > 32768 else 0), 3
+    rings = []
+    for upd in (b.ENV_PIXELS_FULL, b.ENV_PIXELS_DELTA):
+        h = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"pixel_update": upd})
+        try:
+            ring = new_ring(n, "slot_major")
+            rew = torch.empty(n, dtype=torch.float32, device=DEV)
+            done = torch.empty(n, dtype=torch.uint8, device=DEV)
+            b.env_reset(h, ring)
+            for _ in range(T):
+                b.env_step(h, None, ring, rew, done)
+            torch.cuda.synchronize()
+            rings.append(ring)
+            if upd == b.ENV_PIXELS_DELTA:
+                assert _update_counts(h) == (T, 0)
+        finally:
+            b.env_destroy(h)
+    assert torch.equal(rings[0], rings[1])
+    assert int(rings[0].max()) == 255
