@@ -156,7 +156,9 @@ def bench_pong_per_step(b, torch, n, seed, launches):
 def bench_pixels(b, torch, n, seed, launches, warmup=20, layout="slot_major", device_counter=False,
                  delta=False):
     dev = "cuda:0"
-    code = b.ENV_PIXELS_SLOT_MAJOR if layout == "slot_major" else b.ENV_PIXELS_ENV_MAJOR
+    code = {"slot_major": b.ENV_PIXELS_SLOT_MAJOR, "env_major": b.ENV_PIXELS_ENV_MAJOR,
+            "ordered": b.ENV_PIXELS_ORDERED}[layout]
+    delta = delta or layout == "ordered"
     cfg = {"pixel_layout": code}
     if device_counter:      # one launch per step that a HIP graph can replay (no staged lookahead)
         cfg["step_counter"] = b.ENV_STEP_COUNTER_DEVICE
@@ -213,8 +215,10 @@ def bench_pixels(b, torch, n, seed, launches, warmup=20, layout="slot_major", de
     b.env_destroy(h)
     mean_ms = sum(s.elapsed_time(e) for s, e, _ in blocks_ms) / launches
     gbs = n * FRAME_BYTES / (mean_ms * 1e-3) / 1e9
-    out = dict(workload="pong pixels N=%d, 84x84 u8 frame into a 4-slot ring (%s), one env_step "
-                        "call per step%s" % (n, "u8[4,N,84,84]" if layout == "slot_major" else "u8[N,4,84,84]",
+    shape = {"slot_major": "a 4-slot ring (u8[4,N,84,84])", "env_major": "a 4-slot ring (u8[N,4,84,84])",
+             "ordered": "an ordered stack (u8[N,4,84,84], newest frame last, all four channels kept current)"}[layout]
+    out = dict(workload="pong pixels N=%d, 84x84 u8 frame into %s, one env_step "
+                        "call per step%s" % (n, shape,
                                             (", step counter in device memory" if device_counter else "")
                                             + (", delta updates of the slot" if delta else "")),
                **graph,
@@ -479,7 +483,8 @@ def main():
         fn = {"pixels": lambda: bench_pixels(b, torch, 16384, 3, args.steps),
               "pixels_device_counter": lambda: bench_pixels(b, torch, 16384, 3, args.steps, device_counter=True),
               "pixels_delta": lambda: [bench_pixels(b, torch, 16384, 3, args.steps, delta=True),
-                                       bench_pixels(b, torch, 16384, 3, args.steps, delta=True, layout="env_major")],
+                                       bench_pixels(b, torch, 16384, 3, args.steps, delta=True, layout="env_major"),
+                                       bench_pixels(b, torch, 16384, 3, args.steps, layout="ordered")],
               "per_step": lambda: bench_pong_per_step(b, torch, 4096, 1, args.steps),
               "body": lambda: bench_body(b, torch, 8192, 1000, 4, args.steps),
               "body_sweep": lambda: bench_body_sweep(b, torch, args.steps),
@@ -531,6 +536,7 @@ def main():
         extra["config3_pixels_env_major"] = bench_pixels(b, torch, 16384, 3, 500, layout="env_major")
         extra["config3_pixels_device_counter"] = bench_pixels(b, torch, 16384, 3, 500, device_counter=True)
         extra["config3_pixels_delta_updates"] = bench_pixels(b, torch, 16384, 3, 500, delta=True)
+        extra["config3_pixels_ordered_stack"] = bench_pixels(b, torch, 16384, 3, 500, layout="ordered")
         for nn in (16384, 262144):
             rr = bench_pong_rollout(b, torch, nn, T, seed, max(3, args.steps // 6), 1)
             gbs = PONG_BYTES_PER_ENV_STEP * nn * T / (rr["mean_ms"] * 1e-3) / 1e9

@@ -114,12 +114,22 @@ enum { ENV_OBS_RAW = 1, ENV_OBS_NORMALIZED = 2 };
  *           longer (25 against 20 us at N = 16384). */
 enum { ENV_STEP_COUNTER_HOST = 1, ENV_STEP_COUNTER_DEVICE = 2 };
 
-/* Layout of the 4-frame ring of ENV_PONG_PIXELS in obs_dev of env_reset / env_step:
+/* Layout of the four frames of ENV_PONG_PIXELS in obs_dev of env_reset / env_step.  The first two
+ * are a ring: the frame after the step with index s goes to slot s mod 4, the other slots keep what
+ * they hold, and the consumer reads the slots in rotated order.
  *   slot-major  uint8[4][N][84][84]  frame of slot k of environment i at ((k*N + i) * 7056);
  *               one step writes one contiguous plane of N frames (the dense stream HBM likes);
  *   env-major   uint8[N][4][84][84]  frame at ((i*4 + k) * 7056): each environment's four frames
- *               are adjacent (NCHW order), at the price of a 25 %-dense write stream per step. */
-enum { ENV_PIXELS_SLOT_MAJOR = 1, ENV_PIXELS_ENV_MAJOR = 2 };
+ *               are adjacent (NCHW order), at the price of a 25 %-dense write stream per step;
+ *   ordered     uint8[N][4][84][84]  a stack, not a ring: channel 3 is the newest frame, channel k
+ *               the one 3-k steps older; every env_step moves the channels down by one and puts
+ *               the new frame on top; env_reset fills all four with the initial frame; env_rollout
+ *               (a frame trajectory) and env_set_state leave it alone.  A consumer can read it as
+ *               it is.  Always maintained by delta updates (see ENV_PIXELS_DELTA below: the same
+ *               rules about the buffer being shared state apply): each channel changes by one
+ *               step's worth of pixels.  When the library cannot vouch for the contents it moves
+ *               the channels physically instead.  Needs the host step counter. */
+enum { ENV_PIXELS_SLOT_MAJOR = 1, ENV_PIXELS_ENV_MAJOR = 2, ENV_PIXELS_ORDERED = 3 };
 
 /* How env_step brings a ring slot of ENV_PONG_PIXELS up to date (other kinds: ENV_E_UNSUPPORTED for
  * DELTA).  The ring's contents after a step are the same either way.

@@ -7,7 +7,7 @@ import ctypes as C
 import os
 
 ENV_PONG, ENV_PONG_PIXELS, ENV_BODY, ENV_CARTPOLE = 0, 1, 2, 3
-ENV_PIXELS_SLOT_MAJOR, ENV_PIXELS_ENV_MAJOR = 1, 2
+ENV_PIXELS_SLOT_MAJOR, ENV_PIXELS_ENV_MAJOR, ENV_PIXELS_ORDERED = 1, 2, 3
 ENV_STEP_COUNTER_HOST, ENV_STEP_COUNTER_DEVICE = 1, 2
 ENV_OBS_RAW, ENV_OBS_NORMALIZED = 1, 2
 ENV_CONTACT_PENALTY, ENV_CONTACT_NEWTON = 1, 2

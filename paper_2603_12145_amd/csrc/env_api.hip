@@ -84,7 +84,8 @@ int merge_config(env_config_t* dst, const env_config_t* src) {
   if (sz >= FIELD_END(env_config_t, friction_mu) && src->friction_mu >= 0.0f)
     dst->friction_mu = src->friction_mu;
   if (sz >= FIELD_END(env_config_t, pixel_layout) && src->pixel_layout != 0) {
-    if (src->pixel_layout != ENV_PIXELS_SLOT_MAJOR && src->pixel_layout != ENV_PIXELS_ENV_MAJOR)
+    if (src->pixel_layout != ENV_PIXELS_SLOT_MAJOR && src->pixel_layout != ENV_PIXELS_ENV_MAJOR &&
+        src->pixel_layout != ENV_PIXELS_ORDERED)
       return ENV_E_ARG;
     dst->pixel_layout = src->pixel_layout;
   }
@@ -240,7 +241,9 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
       else x.frames = static_cast<uint8_t*>(obs);
       const bool plane_step = ring_mode && x.slot_major && T == 1 && pixel_plane_mode() != 0 &&
                               e->n < (int64_t)4000000;
-      if (ring_mode && T == 1 && e->cfg.pixel_update == ENV_PIXELS_DELTA) {
+      if (ring_mode && T == 1 && e->cfg.pixel_layout == ENV_PIXELS_ORDERED) {
+        err = pixel_ordered_step(e->pipe, x, e->stream);
+      } else if (ring_mode && T == 1 && e->cfg.pixel_update == ENV_PIXELS_DELTA) {
         err = pixel_delta_step(e->pipe, x, e->stream);
       } else if (plane_step && e->device_counter) {
         // no lookahead and no buffers alternated from the host: a replayed graph could do neither
@@ -272,6 +275,7 @@ int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_c
   if (merge_config(&c, cfg) != ENV_OK) return ENV_E_ARG;
   if (c.obs_scaling == ENV_OBS_NORMALIZED && kind != ENV_PONG) return ENV_E_UNSUPPORTED;
   if (c.contact_solver == ENV_CONTACT_NEWTON && kind != ENV_BODY) return ENV_E_UNSUPPORTED;
+  if (kind == ENV_PONG_PIXELS && c.pixel_layout == ENV_PIXELS_ORDERED) c.pixel_update = ENV_PIXELS_DELTA;
   if (c.pixel_update == ENV_PIXELS_DELTA &&
       (kind != ENV_PONG_PIXELS || c.step_counter == ENV_STEP_COUNTER_DEVICE))
     return ENV_E_UNSUPPORTED;

@@ -82,6 +82,7 @@ struct PixelPipe {
   const uint8_t* delta_ring = nullptr;             // the ring the two arrays below speak about
   int64_t slot_step[4] = {INT64_MIN, INT64_MIN, INT64_MIN, INT64_MIN};   // step whose frame the library put in slot k
   int64_t hist_step[5] = {INT64_MIN, INT64_MIN, INT64_MIN, INT64_MIN, INT64_MIN};   // step whose blocks entry j holds
+  int64_t stack_step = INT64_MIN;                  // ordered stack: last step whose stack the library produced
   int64_t delta_steps = 0, full_steps = 0;         // ring steps taken either way since creation
 };
 hipError_t pixel_pipe_create(PixelPipe& p, int64_t n, bool delta_updates);
@@ -102,9 +103,14 @@ hipError_t pixel_delta_step(PixelPipe& p, const PixelLaunch& a, hipStream_t stre
 // the next steps can already be delta updates.  `step` = the handle's step counter.
 hipError_t pixel_delta_after_reset(PixelPipe& p, const uint32_t* state, int64_t n, uint64_t step,
                                    const uint8_t* ring, hipStream_t stream);
+// Ordered stack [n][4][84][84] (channel 3 newest): the same step, with all four channels brought
+// up to date by one step's worth of changed pixels each; or, when the library cannot vouch for the
+// channels, by moving them down physically and drawing the new frame on top.
+hipError_t pixel_ordered_step(PixelPipe& p, const PixelLaunch& a, hipStream_t stream);
 inline void pixel_delta_forget(PixelPipe& p) {
   for (auto& s : p.slot_step) s = INT64_MIN;
   for (auto& s : p.hist_step) s = INT64_MIN;
+  p.stack_step = INT64_MIN;
 }
 int pixel_plane_mode();
 

@@ -413,6 +413,111 @@ __global__ __launch_bounds__(256) void pixel_delta_step_kernel(PongLaunch a, con
   }
 }
 
+// The same for the ordered stack: channel k of environment i (frame at ring + (4 i + k) * 7056)
+// showed the frame of step s - 4 + k and must show that of step s - 3 + k, so every channel changes
+// by one step's worth of pixels.  hist_at[f], f = 0..3, are the kept blocks of steps s - 4 + f;
+// the new frame's blocks (f = 4) come from the step itself and go to new_blocks.
+struct FrameHistory { const uint32_t* at[4]; };
+
+template <int ENVS>
+__global__ __launch_bounds__(256) void pixel_ordered_step_kernel(PongLaunch a, FrameHistory hist,
+                                                                 uint32_t* __restrict__ new_blocks,
+                                                                 uint8_t* __restrict__ ring) {
+  __shared__ uint32_t blk[5][3][ENVS];
+  const int64_t n = a.n;
+  const int64_t env0 = (int64_t)blockIdx.x * ENVS;
+  if (threadIdx.x < WAVE) {
+    const int lane = threadIdx.x;
+    const int64_t i = env0 + lane;
+    const bool live = lane < ENVS && i < n;
+    const int64_t ic = live ? i : n - 1;
+    PongLane s = pong_load(a.state, n, ic);
+    const Draw4 d = philox_draw(a.seed, (uint32_t)ic, a.step0, 0u);
+    const int action = a.actions ? (int)a.actions[ic] : pong_action_from_word(d.w0);
+    const PongEvent ev = pong_transition(s, action, d.w1, d.w2, a.max_score);
+    LaneEpisodes le;
+    if (live && ev.done) {
+      le.count = 1; le.length_sum = ev.fin_len; le.ret_sum_i = ev.fin_ret;
+      le.min_key = ev.fin_ret; le.max_key = ev.fin_ret;
+    }
+    const uint32_t nb[3] = {cell_block(140.0f, s.pa, 4.0f, 16.0f), cell_block(16.0f, s.po, 4.0f, 16.0f),
+                            cell_block(s.bx, s.by, 2.0f, 2.0f)};
+    if (lane < ENVS) {
+#pragma unroll
+      for (int k = 0; k < 3; ++k) {
+        blk[4][k][lane] = nb[k];
+#pragma unroll
+        for (int f = 0; f < 4; ++f) blk[f][k][lane] = live ? hist.at[f][(int64_t)k * n + i] : nb[k];
+      }
+    }
+    if (live) {
+#pragma unroll
+      for (int k = 0; k < 3; ++k) new_blocks[(int64_t)k * n + i] = nb[k];
+      a.reward[i] = ev.reward;
+      a.done[i] = ev.done ? 1 : 0;
+      pong_store(a.state, n, i, s);
+    }
+    flush_wave_stats<false>(a.stats, le);
+  }
+  __syncthreads();
+  const int dc = threadIdx.x & 3, dr = (threadIdx.x >> 2) & 7;
+  for (int item = threadIdx.x >> 5; item < 12 * ENVS; item += 8) {
+    const int e = item % ENVS, rect = (item / ENVS) % 3, ch = item / (3 * ENVS);
+    const uint32_t w = blk[ch][rect][e], v = blk[ch + 1][rect][e];
+    if (w == v) continue;
+    uint8_t* frame = ring + ((env0 + e) * 4 + ch) * (int64_t)FRAME_BYTES;
+    const int wc0 = w & 0xff, wc1 = (w >> 8) & 0xff, wr0 = (w >> 16) & 0xff, wr1 = w >> 24;
+    const int nc0 = v & 0xff, nc1 = (v >> 8) & 0xff, nr0 = (v >> 16) & 0xff, nr1 = v >> 24;
+    {
+      const int c = wc0 + dc, r = wr0 + dr;
+      bool lit = false;
+#pragma unroll
+      for (int j = 0; j < 3; ++j) {
+        const uint32_t q = blk[ch + 1][j][e];
+        lit = lit || (c >= (int)(q & 0xff) && c < (int)((q >> 8) & 0xff) && r >= (int)((q >> 16) & 0xff) &&
+                      r < (int)(q >> 24));
+      }
+      if (c < wc1 && r < wr1 && !lit) frame[r * FRAME_SIDE + c] = 0;
+    }
+    {
+      const int c = nc0 + dc, r = nr0 + dr;
+      if (c < nc1 && r < nr1 && !(c >= wc0 && c < wc1 && r >= wr0 && r < wr1)) frame[r * FRAME_SIDE + c] = 255;
+    }
+  }
+}
+
+// Ordered stack, the physical way: channels 1..3 of every environment move down by one, the new
+// frame is built from its cell blocks on top.  One wavefront per environment; a lane reads its
+// chunk of the three channels before it writes any of them.
+__global__ __launch_bounds__(256) void stack_shift_kernel(const uint32_t* __restrict__ blocks, int64_t n,
+                                                          uint8_t* __restrict__ ring) {
+  const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (i >= n) return;
+  const int lane = threadIdx.x & (WAVE - 1);
+  uint32_t b[3];
+#pragma unroll
+  for (int k = 0; k < 3; ++k) b[k] = blocks[(int64_t)k * n + i];
+  chunk_t* stack = reinterpret_cast<chunk_t*>(ring + i * 4 * (int64_t)FRAME_BYTES);
+  for (int chunk = lane; chunk < CHUNKS; chunk += WAVE) {
+    const chunk_t c1 = stack[1 * CHUNKS + chunk], c2 = stack[2 * CHUNKS + chunk], c3 = stack[3 * CHUNKS + chunk];
+    uint32_t words[4] = {0, 0, 0, 0};
+#pragma unroll
+    for (int byte = 0; byte < 16; ++byte) {
+      const int p = chunk * 16 + byte, r = p / FRAME_SIDE, c = p - r * FRAME_SIDE;
+      bool lit = false;
+#pragma unroll
+      for (int k = 0; k < 3; ++k)
+        lit = lit || (c >= (int)(b[k] & 0xff) && c < (int)((b[k] >> 8) & 0xff) && r >= (int)((b[k] >> 16) & 0xff) &&
+                      r < (int)(b[k] >> 24));
+      words[byte >> 2] |= lit ? 0xffu << (8 * (byte & 3)) : 0u;
+    }
+    stack[0 * CHUNKS + chunk] = c1;
+    stack[1 * CHUNKS + chunk] = c2;
+    stack[2 * CHUNKS + chunk] = c3;
+    stack[3 * CHUNKS + chunk] = chunk_t{words[0], words[1], words[2], words[3]};
+  }
+}
+
 // Whole frames of one slot from their cell blocks, any layout: one wavefront per environment, each
 // lane builds 16-byte chunks by testing its 16 pixels against the three blocks.  Only used for the
 // few steps in which a slot's contents are not known; the page renderer is the fast full write.
@@ -677,6 +782,7 @@ hipError_t pixel_delta_after_reset(PixelPipe& p, const uint32_t* state, int64_t 
     p.slot_step[wrap(s - back, 4)] = s - back;
     p.hist_step[wrap(s - back, 5)] = s - back;
   }
+  p.stack_step = s - 1;
   return hipSuccess;
 }
 
@@ -722,6 +828,48 @@ hipError_t pixel_delta_step(PixelPipe& p, const PixelLaunch& a, hipStream_t stre
   if (err != hipSuccess) return err;
   p.hist_step[e_new] = s;
   p.slot_step[slot] = s;
+  (known ? p.delta_steps : p.full_steps) += 1;
+  return hipSuccess;
+}
+
+hipError_t pixel_ordered_step(PixelPipe& p, const PixelLaunch& a, hipStream_t stream) {
+  if (!p.hist || !a.ring) return hipErrorInvalidValue;
+  const int64_t n = a.pong.n;
+  const int64_t s = (int64_t)a.pong.step0;
+  const int e_new = wrap(s, 5);
+  if (p.delta_ring != a.ring) { pixel_delta_forget(p); p.delta_ring = a.ring; }
+  uint32_t* new_blocks = p.hist + (int64_t)e_new * 3 * n;
+  // the channels hold the frames of steps s-4 .. s-1, put there by this library, blocks still kept
+  bool known = p.stack_step == s - 1;
+  FrameHistory hist;
+  for (int f = 0; f < 4; ++f) {
+    const int64_t step = s - 4 + f;
+    known = known && p.hist_step[wrap(step, 5)] == step;
+    hist.at[f] = p.hist + (int64_t)wrap(step, 5) * 3 * n;
+  }
+  PongLaunch d = a.pong;
+  d.T = 1;
+  p.hist_step[e_new] = INT64_MIN;          // until the launches below are known to be enqueued
+  p.stack_step = INT64_MIN;
+  hipError_t err;
+  if (known) {
+    if (n <= 32768)
+      hipLaunchKernelGGL(pixel_ordered_step_kernel<8>, dim3((unsigned)((n + 7) / 8)), dim3(256), 0, stream, d, hist,
+                         new_blocks, a.ring);
+    else
+      hipLaunchKernelGGL(pixel_ordered_step_kernel<16>, dim3((unsigned)((n + 15) / 16)), dim3(256), 0, stream, d,
+                         hist, new_blocks, a.ring);
+  } else {
+    hipLaunchKernelGGL(pixel_traj_dynamics_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, d,
+                       new_blocks, n);
+    err = hipGetLastError();
+    if (err != hipSuccess) return err;
+    hipLaunchKernelGGL(stack_shift_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, stream, new_blocks, n, a.ring);
+  }
+  err = hipGetLastError();
+  if (err != hipSuccess) return err;
+  p.hist_step[e_new] = s;
+  p.stack_step = s;
   (known ? p.delta_steps : p.full_steps) += 1;
   return hipSuccess;
 }

@@ -377,3 +377,90 @@ def test_delta_updates_at_config3_size_match_full_updates(n, T):
             b.env_destroy(h)
     assert torch.equal(rings[0], rings[1])
     assert int(rings[0].max()) == 255
+
+
+@pytest.mark.parametrize("n", [1, 37, 255, 1000])
+def test_ordered_stack_matches_the_oracle(n):
+    """pixel_layout = ordered: uint8[N][4][84][84] with channel 3 the newest frame; every env_step
+    moves the channels down by one and puts the new frame on top.  The reference stack is built
+    from the oracle's frames by exactly that rule.  Checked after every step, through episode
+    ends, external actions, a save / restore, steps taken through env_rollout in between, a change
+    of buffer and a second reset; most steps must have been delta updates, the rest physical
+    moves."""
+    seed, T = 170 + n, 100
+    acts = inputs.pong_actions(T, n, seed=6)
+    dacts = torch.from_numpy(acts).to(DEV)
+    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"max_score": 1, "pixel_layout": b.ENV_PIXELS_ORDERED})
+    try:
+        stack = torch.full((n, 4, F, F), 77, dtype=torch.uint8, device=DEV)
+        rew = torch.empty(n, dtype=torch.float32, device=DEV)
+        done = torch.empty(n, dtype=torch.uint8, device=DEV)
+        b.env_reset(h, stack)
+        p = orc.Pong(n, seed, max_score=1); p.reset()
+        ring = np.zeros((n, 4, F, F), np.uint8); p.fill_stack(ring)     # the oracle's own 4-slot ring
+        want = ring.copy()                                               # after a reset: four times the initial frame
+        torch.cuda.synchronize()
+        assert_bit_equal(stack.cpu().numpy(), want, "stack after reset")
+        expect_moves = 0
+        t = 0
+        while t < T:
+            ext = t % 3 == 2
+            s = p.step_count
+            b.env_step(h, dacts[t] if ext else None, stack, rew, done)
+            _, orew, odone = p.step(actions=acts[t] if ext else None, stack=ring)
+            want[:, :3] = want[:, 1:].copy()
+            want[:, 3] = ring[:, s & 3]                                  # the frame the oracle drew for step s
+            torch.cuda.synchronize()
+            assert_bit_equal(stack.cpu().numpy(), want, "stack after step %d" % t)
+            assert_bit_equal(rew.cpu().numpy(), orew, "reward step %d" % t)
+            assert_bit_equal(done.cpu().numpy(), odone, "done step %d" % t)
+            t += 1
+            if t == 22:
+                b.env_set_state(h, b.env_get_state(h))
+                expect_moves += 4
+            if t == 45:
+                fr = torch.empty((2, n, F, F), dtype=torch.uint8, device=DEV)
+                r2 = torch.empty((2, n), dtype=torch.float32, device=DEV)
+                d2 = torch.empty((2, n), dtype=torch.uint8, device=DEV)
+                b.env_rollout(h, 2, None, fr, r2, d2)
+                p.rollout(2)
+                t += 2
+                expect_moves += 4                    # the kept blocks no longer describe the channels
+            if t == 70:
+                stack = stack.clone()
+                expect_moves += 4
+            if t == 85:
+                stack.fill_(5)
+                b.env_reset(h, stack)
+                p.reset(); p.fill_stack(ring)
+                want = ring.copy()
+        delta, moves = _update_counts(h)
+        assert moves == expect_moves and delta == T - 2 - expect_moves, (delta, moves)
+        assert b.env_stats(h)["episodes"] == p.stats()["episodes"]
+    finally:
+        b.env_destroy(h)
+
+
+def test_ordered_stack_at_config3_size_and_beyond():
+    """N = 16384 and N = 40003 (the kernel's other workgroup shape, ragged last workgroup): channel
+    3 - k of the ordered stack equals the slot of step s - k of a slot-major ring driven by the same
+    seed, after 30 steps."""
+    for n in (16384, 40003):
+        seed, T = 3, 30
+        hr = b.env_create(b.ENV_PONG_PIXELS, n, seed, None)
+        ho = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"pixel_layout": b.ENV_PIXELS_ORDERED})
+        try:
+            ring = new_ring(n, "slot_major")
+            stack = torch.zeros((n, 4, F, F), dtype=torch.uint8, device=DEV)
+            rew = torch.empty(n, dtype=torch.float32, device=DEV)
+            done = torch.empty(n, dtype=torch.uint8, device=DEV)
+            b.env_reset(hr, ring); b.env_reset(ho, stack)
+            for _ in range(T):
+                b.env_step(hr, None, ring, rew, done)
+                b.env_step(ho, None, stack, rew, done)
+            torch.cuda.synchronize()
+            assert _update_counts(ho) == (T, 0)
+            for k in range(4):
+                assert torch.equal(stack[:, 3 - k], ring[(T - 1 - k) & 3]), (n, k)
+        finally:
+            b.env_destroy(hr); b.env_destroy(ho)
