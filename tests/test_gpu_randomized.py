@@ -146,3 +146,95 @@ def test_random_pixel_cases():
             pixel_case(rng, k)
     finally:
         assert b.lib().mi355env_tune_plane_path(2) == 0
+
+
+PIXEL_MODES = {
+    "ring slot-major": dict(pixel_layout=b.ENV_PIXELS_SLOT_MAJOR),
+    "ring env-major": dict(pixel_layout=b.ENV_PIXELS_ENV_MAJOR),
+    "ring slot-major, device counter": dict(pixel_layout=b.ENV_PIXELS_SLOT_MAJOR,
+                                            step_counter=b.ENV_STEP_COUNTER_DEVICE),
+    "ring env-major, device counter": dict(pixel_layout=b.ENV_PIXELS_ENV_MAJOR,
+                                           step_counter=b.ENV_STEP_COUNTER_DEVICE),
+    "ring slot-major, delta": dict(pixel_layout=b.ENV_PIXELS_SLOT_MAJOR, pixel_update=b.ENV_PIXELS_DELTA),
+    "ring env-major, delta": dict(pixel_layout=b.ENV_PIXELS_ENV_MAJOR, pixel_update=b.ENV_PIXELS_DELTA),
+    "ordered stack": dict(pixel_layout=b.ENV_PIXELS_ORDERED),
+}
+
+
+def pixel_call_sequence(rng, k, mode):
+    """A random sequence of calls on one pixel handle -- steps with in-kernel or external actions,
+    frame-trajectory rollouts, save / restore, resets, a change of observation buffer -- with the
+    observation buffer, rewards, done flags and frames compared with the oracle after every call.
+    The reference keeps the oracle's own ring (slot = step mod 4) and, for the ordered stack, moves
+    its channels down on every step, as the boundary defines it."""
+    n = int(rng.choice([1, 9, 64, 130, 300]))
+    seed = int(rng.integers(0, 2 ** 62))
+    calls = int(rng.integers(30, 70))
+    cfg = dict(PIXEL_MODES[mode], max_score=1)
+    ordered = cfg["pixel_layout"] == b.ENV_PIXELS_ORDERED
+    slot_major = cfg["pixel_layout"] == b.ENV_PIXELS_SLOT_MAJOR
+    print("pixel sequence", k, mode, dict(n=n, seed=seed, calls=calls), flush=True)
+
+    def as_env_major(buf):
+        a = buf.cpu().numpy()
+        return np.ascontiguousarray(a.transpose(1, 0, 2, 3)) if slot_major else a
+
+    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, cfg)
+    try:
+        buf = torch.full((4, n, 84, 84) if slot_major else (n, 4, 84, 84), 33, dtype=torch.uint8, device=DEV)
+        rew = torch.empty(n, dtype=torch.float32, device=DEV)
+        done = torch.empty(n, dtype=torch.uint8, device=DEV)
+        p = orc.Pong(n, seed, max_score=1)
+        ring = np.zeros((n, 4, 84, 84), np.uint8)          # the oracle's ring
+        b.env_reset(h, buf)
+        p.reset(); p.fill_stack(ring)
+        want = ring.copy()                                  # what buf must hold (env-major view)
+        assert_bit_equal(as_env_major(buf), want, "after the first reset")
+        for c in range(calls):
+            op = rng.choice(["step", "step", "step", "step", "step_ext", "step_ext", "rollout", "restore",
+                             "reset", "new_buffer"], p=[.2, .2, .15, .15, .08, .07, .05, .04, .03, .03])
+            s = p.step_count
+            if op in ("step", "step_ext"):
+                a = inputs.pong_actions(1, n, seed=1000 * k + c) if op == "step_ext" else None
+                b.env_step(h, None if a is None else torch.from_numpy(a[0]).to(DEV), buf, rew, done)
+                _, orew, odone = p.step(actions=None if a is None else a[0], stack=ring)
+                if ordered:
+                    want[:, :3] = want[:, 1:].copy()
+                    want[:, 3] = ring[:, s & 3]
+                else:
+                    want[:, s & 3] = ring[:, s & 3]
+                assert_bit_equal(rew.cpu().numpy(), orew, "call %d reward" % c)
+                assert_bit_equal(done.cpu().numpy(), odone, "call %d done" % c)
+            elif op == "rollout":
+                T = int(rng.integers(1, 6))
+                fr = torch.empty((T, n, 84, 84), dtype=torch.uint8, device=DEV)
+                rT = torch.empty((T, n), dtype=torch.float32, device=DEV)
+                dT = torch.empty((T, n), dtype=torch.uint8, device=DEV)
+                b.env_rollout(h, T, None, fr, rT, dT)
+                scratch = np.zeros((n, 4, 84, 84), np.uint8)
+                for t in range(T):                          # frames of the oracle, one step at a time
+                    _, orew, odone = p.step(stack=scratch)
+                    assert_bit_equal(fr[t].cpu().numpy(), scratch[:, (s + t) & 3], "call %d frame %d" % (c, t))
+                    assert_bit_equal(rT[t].cpu().numpy(), orew, "call %d reward %d" % (c, t))
+                    assert_bit_equal(dT[t].cpu().numpy(), odone, "call %d done %d" % (c, t))
+            elif op == "restore":
+                b.env_set_state(h, b.env_get_state(h))
+            elif op == "reset":
+                buf.fill_(int(rng.integers(0, 256)))
+                b.env_reset(h, buf)
+                p.reset(); p.fill_stack(ring)
+                want = ring.copy()
+            elif op == "new_buffer":
+                buf = buf.clone()
+            assert_bit_equal(as_env_major(buf), want, "call %d (%s): observation buffer" % (c, op))
+        assert b.env_step_count(h) == p.step_count
+        assert b.env_stats(h)["episodes"] == p.stats()["episodes"]
+    finally:
+        b.env_destroy(h)
+
+
+@pytest.mark.parametrize("mode", sorted(PIXEL_MODES))
+def test_random_pixel_call_sequences(mode):
+    rng = np.random.default_rng(45678 + sorted(PIXEL_MODES).index(mode))
+    for k in range(3):
+        pixel_call_sequence(rng, k, mode)
