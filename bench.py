@@ -484,7 +484,10 @@ def main():
               "pixels_device_counter": lambda: bench_pixels(b, torch, 16384, 3, args.steps, device_counter=True),
               "pixels_delta": lambda: [bench_pixels(b, torch, 16384, 3, args.steps, delta=True),
                                        bench_pixels(b, torch, 16384, 3, args.steps, delta=True, layout="env_major"),
-                                       bench_pixels(b, torch, 16384, 3, args.steps, layout="ordered")],
+                                       bench_pixels(b, torch, 16384, 3, args.steps, layout="ordered"),
+                                       bench_pixels(b, torch, 16384, 3, args.steps, delta=True, device_counter=True),
+                                       bench_pixels(b, torch, 16384, 3, args.steps, layout="ordered",
+                                                    device_counter=True)],
               "per_step": lambda: bench_pong_per_step(b, torch, 4096, 1, args.steps),
               "body": lambda: bench_body(b, torch, 8192, 1000, 4, args.steps),
               "body_sweep": lambda: bench_body_sweep(b, torch, args.steps),

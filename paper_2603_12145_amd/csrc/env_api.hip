@@ -241,10 +241,8 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
       else x.frames = static_cast<uint8_t*>(obs);
       const bool plane_step = ring_mode && x.slot_major && T == 1 && pixel_plane_mode() != 0 &&
                               e->n < (int64_t)4000000;
-      if (ring_mode && T == 1 && e->cfg.pixel_layout == ENV_PIXELS_ORDERED) {
-        err = pixel_ordered_step(e->pipe, x, e->stream);
-      } else if (ring_mode && T == 1 && e->cfg.pixel_update == ENV_PIXELS_DELTA) {
-        err = pixel_delta_step(e->pipe, x, e->stream);
+      if (ring_mode && T == 1 && e->cfg.pixel_update == ENV_PIXELS_DELTA) {
+        err = pixel_update_step(e->pipe, x, e->cfg.pixel_layout == ENV_PIXELS_ORDERED, e->stream);
       } else if (plane_step && e->device_counter) {
         // no lookahead and no buffers alternated from the host: a replayed graph could do neither
         pixel_pipe_invalidate(e->pipe);
@@ -254,6 +252,8 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
       } else {
         pixel_pipe_invalidate(e->pipe);      // the state moves without the lookahead knowing
         err = launch_pixel_rollout(x, e->pipe, e->stream);
+        // ... and steps pass without their frames reaching a delta-updated observation buffer
+        if (err == hipSuccess && e->cfg.pixel_update == ENV_PIXELS_DELTA) err = pixel_update_forget(e->pipe, e->stream);
       }
     }
   }
@@ -276,9 +276,7 @@ int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_c
   if (c.obs_scaling == ENV_OBS_NORMALIZED && kind != ENV_PONG) return ENV_E_UNSUPPORTED;
   if (c.contact_solver == ENV_CONTACT_NEWTON && kind != ENV_BODY) return ENV_E_UNSUPPORTED;
   if (kind == ENV_PONG_PIXELS && c.pixel_layout == ENV_PIXELS_ORDERED) c.pixel_update = ENV_PIXELS_DELTA;
-  if (c.pixel_update == ENV_PIXELS_DELTA &&
-      (kind != ENV_PONG_PIXELS || c.step_counter == ENV_STEP_COUNTER_DEVICE))
-    return ENV_E_UNSUPPORTED;
+  if (c.pixel_update == ENV_PIXELS_DELTA && kind != ENV_PONG_PIXELS) return ENV_E_UNSUPPORTED;
 
   env_t* e = new (std::nothrow) env_t();
   if (!e) return ENV_E_ALLOC;
@@ -337,8 +335,8 @@ int env_reset(env_t* e, void* obs_dev) {
                              e->cfg.pixel_layout == ENV_PIXELS_SLOT_MAJOR, e->pipe.blocks[0], e->stream);
     pixel_pipe_invalidate(e->pipe);
     if (err == hipSuccess && e->cfg.pixel_update == ENV_PIXELS_DELTA)
-      err = pixel_delta_after_reset(e->pipe, e->state, e->n, e->step, static_cast<const uint8_t*>(obs_dev),
-                                    e->stream);
+      err = pixel_update_after_reset(e->pipe, e->state, e->n, e->step, counter,
+                                     static_cast<const uint8_t*>(obs_dev), e->stream);
   } else if (e->kind == ENV_BODY) {
     if (obs_dev && !device_range_ok(e, obs_dev, (size_t)e->n * BODY_OBS * sizeof(float), 4))
       return ENV_E_ARG;
@@ -356,7 +354,8 @@ int env_reset(env_t* e, void* obs_dev) {
                             e->cfg.obs_scaling == ENV_OBS_NORMALIZED, e->stream);
     if (e->kind == ENV_PONG_PIXELS) {
       pixel_pipe_invalidate(e->pipe);
-      pixel_delta_forget(e->pipe);          // new episodes, no ring written: its slots are stale
+      // new episodes, no observation buffer written: what it holds is stale
+      if (err == hipSuccess) err = pixel_update_forget(e->pipe, e->stream);
     }
   }
   if (err != hipSuccess) return ENV_E_HIP;
@@ -439,7 +438,8 @@ int env_set_state(env_t* e, const void* host_buf, size_t bytes) {
   e->was_reset = true;
   if (e->kind == ENV_PONG_PIXELS) {
     pixel_pipe_invalidate(e->pipe);
-    pixel_delta_forget(e->pipe);            // the ring is not part of the state: it no longer matches
+    // the observation buffer is not part of the state: it no longer matches
+    if (pixel_update_forget(e->pipe, e->stream) != hipSuccess) return ENV_E_HIP;
   }
   return ENV_OK;
 }
@@ -496,9 +496,10 @@ const char* env_strerror(int code) {
 int mi355env_pixel_update_counts(const void* handle, int64_t* delta_steps, int64_t* full_steps) {
   const env_t* e = static_cast<const env_t*>(handle);
   if (!e || !delta_steps || !full_steps || e->kind != ENV_PONG_PIXELS) return ENV_E_ARG;
-  *delta_steps = e->pipe.delta_steps;
-  *full_steps = e->pipe.full_steps;
-  return ENV_OK;
+  return pixel_update_counts(const_cast<env_t*>(e)->pipe, e->device_counter, delta_steps, full_steps, e->stream) ==
+                 hipSuccess
+             ? ENV_OK
+             : ENV_E_HIP;
 }
 
 // Measurement knob, not part of the documented boundary: launch shape of the pixel kernels.

@@ -77,13 +77,11 @@ struct PixelPipe {
   bool staged = false;                             // staging buffers of parity (step & 1) hold `step`
   uint32_t* traj_blocks = nullptr;                 // [3][traj_cap] cell blocks of a chunk of a frame trajectory
   int64_t traj_cap = 0;                            // frames (environment-steps) per chunk
-  // Delta updates of the ring (only allocated for handles created with pixel_update = delta)
+  // Delta updates of the observation buffer (only for handles created with pixel_update = delta or
+  // the ordered layout)
   uint32_t* hist = nullptr;                        // [5][3][n] cell blocks of the last five frames, entry = step mod 5
-  const uint8_t* delta_ring = nullptr;             // the ring the two arrays below speak about
-  int64_t slot_step[4] = {INT64_MIN, INT64_MIN, INT64_MIN, INT64_MIN};   // step whose frame the library put in slot k
-  int64_t hist_step[5] = {INT64_MIN, INT64_MIN, INT64_MIN, INT64_MIN, INT64_MIN};   // step whose blocks entry j holds
-  int64_t stack_step = INT64_MIN;                  // ordered stack: last step whose stack the library produced
-  int64_t delta_steps = 0, full_steps = 0;         // ring steps taken either way since creation
+  void* book = nullptr;                            // record of what the observation buffer holds, in device memory
+  unsigned long long host_book[4] = {~0ull, 0, 0, 0};   // ... and the host's copy (handles with the host step counter)
 };
 hipError_t pixel_pipe_create(PixelPipe& p, int64_t n, bool delta_updates);
 void pixel_pipe_destroy(PixelPipe& p);
@@ -95,23 +93,19 @@ inline void pixel_pipe_invalidate(PixelPipe& p) { p.staged = false; }
 // The same step for a handle whose step counter lives in device memory (a.pong.counter): two
 // launches, dynamics then page renderer, no lookahead, nothing alternated from the host.
 hipError_t pixel_counted_step(const PixelPipe& p, const PixelLaunch& a, hipStream_t stream);
-// Ring step that rewrites only the pixels in which the new frame differs from the one the slot
-// holds (the frame of four steps earlier), or the whole slot when the library cannot vouch for
-// what it holds.  State in place, no lookahead.
-hipError_t pixel_delta_step(PixelPipe& p, const PixelLaunch& a, hipStream_t stream);
-// After env_reset has written the initial frame to all four slots of `ring`: record that, so that
-// the next steps can already be delta updates.  `step` = the handle's step counter.
-hipError_t pixel_delta_after_reset(PixelPipe& p, const uint32_t* state, int64_t n, uint64_t step,
-                                   const uint8_t* ring, hipStream_t stream);
-// Ordered stack [n][4][84][84] (channel 3 newest): the same step, with all four channels brought
-// up to date by one step's worth of changed pixels each; or, when the library cannot vouch for the
-// channels, by moving them down physically and drawing the new frame on top.
-hipError_t pixel_ordered_step(PixelPipe& p, const PixelLaunch& a, hipStream_t stream);
-inline void pixel_delta_forget(PixelPipe& p) {
-  for (auto& s : p.slot_step) s = INT64_MIN;
-  for (auto& s : p.hist_step) s = INT64_MIN;
-  p.stack_step = INT64_MIN;
-}
+// One step of a handle that keeps its observation buffer current by delta updates: a ring slot
+// (ordered = false; a.slot_major says which ring) or all four channels of the ordered stack.  One
+// launch; it decides by itself, from a record in device memory, whether the buffer can be repaired
+// or has to be written whole, so it may be recorded in a HIP graph (a.pong.counter set) as well.
+hipError_t pixel_update_step(PixelPipe& p, const PixelLaunch& a, bool ordered, hipStream_t stream);
+// After env_reset has written the initial frame to all four slots / channels of `ring`.
+hipError_t pixel_update_after_reset(PixelPipe& p, const uint32_t* state, int64_t n, uint64_t step,
+                                    const StepCounter* counter, const uint8_t* ring, hipStream_t stream);
+// The buffer no longer matches what the library keeps: the next four steps write whole frames.
+hipError_t pixel_update_forget(PixelPipe& p, hipStream_t stream);
+// Steps that repaired / wrote whole frames since creation (synchronises the stream).
+hipError_t pixel_update_counts(PixelPipe& p, bool device_counter, int64_t* delta_steps, int64_t* full_steps,
+                               hipStream_t stream);
 int pixel_plane_mode();
 
 }  // namespace envk

@@ -337,104 +337,167 @@ __global__ __launch_bounds__(256) void plane_render_counted_kernel(const uint32_
 }
 
 // ---- delta updates ----------------------------------------------------------------------------
-// A frame differs from the one four steps earlier in the pixels of three small rectangles.  One
-// launch takes the step and repairs the slot.  A workgroup owns 64 environments: its first
-// wavefront takes their step, one lane per environment (reward / done to the caller, state in
-// place, episode statistics, the new cell blocks to the history) and leaves the slot's old blocks
-// and the new ones in LDS; after the barrier all four wavefronts walk the 192 rectangles, 32 lanes
-// per rectangle.  Lane l stands for pixel (l & 3, l >> 2) of a 4-column x 8-row patch (a paddle
-// covers at most 4 x 8 cells, the ball at most 3 x 2), once anchored at the old block's corner --
-// there it clears its pixel unless one of the new blocks covers it (rectangles may overlap: the
-// ball in front of a paddle) -- and once at the new block's corner, where it sets its pixel unless
-// the old block covered it.  A rectangle that did not move is skipped.  Frame i of the slot starts
-// at base + i * stride.
-template <int ENVS>   // environments per workgroup
-__global__ __launch_bounds__(256) void pixel_delta_step_kernel(PongLaunch a, const uint32_t* __restrict__ old_blocks,
-                                                               uint32_t* __restrict__ new_blocks,
-                                                               uint8_t* __restrict__ base, int64_t stride) {
-  __shared__ uint32_t was[3][ENVS], now[3][ENVS];
-  const int64_t n = a.n;
-  const int64_t env0 = (int64_t)blockIdx.x * ENVS;
-  if (threadIdx.x < WAVE) {
-    const int lane = threadIdx.x;
-    const int64_t i = env0 + lane;
-    const bool live = lane < ENVS && i < n;
-    const int64_t ic = live ? i : n - 1;
-    PongLane s = pong_load(a.state, n, ic);
-    const Draw4 d = philox_draw(a.seed, (uint32_t)ic, a.step0, 0u);
-    const int action = a.actions ? (int)a.actions[ic] : pong_action_from_word(d.w0);
-    const PongEvent ev = pong_transition(s, action, d.w1, d.w2, a.max_score);
-    LaneEpisodes le;
-    if (live && ev.done) {
-      le.count = 1; le.length_sum = ev.fin_len; le.ret_sum_i = ev.fin_ret;
-      le.min_key = ev.fin_ret; le.max_key = ev.fin_ret;
-    }
-    const uint32_t nb[3] = {cell_block(140.0f, s.pa, 4.0f, 16.0f), cell_block(16.0f, s.po, 4.0f, 16.0f),
-                            cell_block(s.bx, s.by, 2.0f, 2.0f)};
-#pragma unroll
-    for (int k = 0; k < 3; ++k) {
-      if (lane < ENVS) {
-        now[k][lane] = nb[k];
-        was[k][lane] = live ? old_blocks[(int64_t)k * n + i] : nb[k];   // an idle lane shows no change
-      }
-      if (live) new_blocks[(int64_t)k * n + i] = nb[k];
-    }
-    if (live) {
-      a.reward[i] = ev.reward;
-      a.done[i] = ev.done ? 1 : 0;
-      pong_store(a.state, n, i, s);
-    }
-    flush_wave_stats<false>(a.stats, le);
+// A frame differs from the one four steps earlier in the pixels of three small rectangles, so a ring
+// slot can be brought up to date by clearing the pixels that went dark and setting those that lit
+// up; the four channels of an ordered stack (channel k: the frame 3 - k steps back) each change by
+// one step's worth of pixels.  The library keeps the cell blocks of the last five frames (entry =
+// step mod 5) and one launch takes the step and repairs the observation buffer.
+//
+// Whether the buffer holds what the kept blocks say is recorded in device memory, so that the
+// decision is taken inside the launch and a launch recorded in a HIP graph decides anew at every
+// replay: the buffer the record is about, and the first step from which it is good.  A step with
+// another buffer, or before that step, writes whole frames instead (ring: the slot from the new
+// blocks; stack: the channels moved down physically, the new frame on top) and four such steps in
+// a row make the record good again.
+struct PixelBook {
+  unsigned long long valid_from;       // delta updates are right from this step on; NOT_KNOWN until a step sets it
+  unsigned long long ring;             // address of the observation buffer that is about
+  unsigned long long delta_steps, full_steps;
+};
+constexpr unsigned long long NOT_KNOWN = ~0ull;
+
+// The rule, for the host's copy of the record and the device's alike.
+__host__ __device__ inline bool record_says_known(const PixelBook* book, unsigned long long step, const uint8_t* ring) {
+  return book->valid_from != NOT_KNOWN && step >= book->valid_from &&
+         book->ring == (unsigned long long)reinterpret_cast<uintptr_t>(ring);
+}
+// ... and what a step does to the record: a step that could not repair starts (or continues) a run
+// of four whole-frame steps.
+__host__ __device__ inline void record_after_step(PixelBook* book, unsigned long long step, const uint8_t* ring) {
+  const unsigned long long r = (unsigned long long)reinterpret_cast<uintptr_t>(ring);
+  const bool known = record_says_known(book, step, ring);
+  if (book->valid_from == NOT_KNOWN || book->ring != r) {
+    book->ring = r;
+    book->valid_from = step + 4ull;
   }
-  __syncthreads();
-  const int dc = threadIdx.x & 3, dr = (threadIdx.x >> 2) & 7;
-  for (int item = threadIdx.x >> 5; item < 3 * ENVS; item += 8) {
-    const int k = item / ENVS, e = item % ENVS;
-    const uint32_t w = was[k][e], v = now[k][e];
-    if (w == v) continue;
-    uint8_t* frame = base + (env0 + e) * stride;
-    const int wc0 = w & 0xff, wc1 = (w >> 8) & 0xff, wr0 = (w >> 16) & 0xff, wr1 = w >> 24;
-    const int nc0 = v & 0xff, nc1 = (v >> 8) & 0xff, nr0 = (v >> 16) & 0xff, nr1 = v >> 24;
-    {
-      const int c = wc0 + dc, r = wr0 + dr;
-      bool lit = false;
+  (known ? book->delta_steps : book->full_steps) += 1ull;
+}
+
+struct UpdateStep {
+  PongLaunch pong;      // T = 1; pong.counter may be null (then pong.step0 is the step)
+  int known_by_host;    // host step counter: the host's copy of the record says the buffer can be repaired
+                        // (picks the kernel's instantiation; the launch itself does not read it)
+  PixelBook* book;      // device step counter: the record, read by the launch
+  uint32_t* hist;       // [5][3][n]
+  uint8_t* ring;
+  int64_t stride;       // bytes from an environment's frame (stack) to the next environment's
+  int64_t slot_pitch;   // ring: bytes from a slot to the next
+  // host step counter only (the launch works these out itself otherwise):
+  uint32_t* entry[5];   // history entries of the steps s - 4 .. s
+  uint8_t* base;        // frame 0 of the slot this step writes; the stack's start
+};
+
+// 16 bytes of a frame (chunk c = pixels 16 c .. 16 c + 15) from its three cell blocks.
+__device__ __forceinline__ chunk_t chunk_of_blocks(const uint32_t b0, const uint32_t b1, const uint32_t b2, int chunk) {
+  const uint32_t b[3] = {b0, b1, b2};
+  uint32_t words[4] = {0, 0, 0, 0};
 #pragma unroll
-      for (int j = 0; j < 3; ++j) {
-        const uint32_t q = now[j][e];
-        lit = lit || (c >= (int)(q & 0xff) && c < (int)((q >> 8) & 0xff) && r >= (int)((q >> 16) & 0xff) &&
-                      r < (int)(q >> 24));
-      }
-      if (c < wc1 && r < wr1 && !lit) frame[r * FRAME_SIDE + c] = 0;
-    }
-    {
-      const int c = nc0 + dc, r = nr0 + dr;
-      if (c < nc1 && r < nr1 && !(c >= wc0 && c < wc1 && r >= wr0 && r < wr1)) frame[r * FRAME_SIDE + c] = 255;
-    }
+  for (int byte = 0; byte < 16; ++byte) {
+    const int p = chunk * 16 + byte, r = p / FRAME_SIDE, c = p - r * FRAME_SIDE;
+    bool lit = false;
+#pragma unroll
+    for (int k = 0; k < 3; ++k)
+      lit = lit || (c >= (int)(b[k] & 0xff) && c < (int)((b[k] >> 8) & 0xff) && r >= (int)((b[k] >> 16) & 0xff) &&
+                    r < (int)(b[k] >> 24));
+    words[byte >> 2] |= lit ? 0xffu << (8 * (byte & 3)) : 0u;
+  }
+  return chunk_t{words[0], words[1], words[2], words[3]};
+}
+
+// 32 lanes, one rectangle: lane l stands for pixel (l & 3, l >> 2) of a 4-column x 8-row patch (a
+// paddle covers at most 4 x 8 cells, the ball at most 3 x 2), once anchored at the old block's corner
+// -- there it clears its pixel unless one of the new frame's blocks covers it (rectangles may
+// overlap: the ball in front of a paddle) -- and once at the new block's corner, where it sets its
+// pixel unless the old block covered it.
+__device__ __forceinline__ void repair_rectangle(uint8_t* __restrict__ frame, const uint32_t was, const uint32_t now,
+                                                 const uint32_t n0, const uint32_t n1, const uint32_t n2) {
+  const int dc = threadIdx.x & 3, dr = (threadIdx.x >> 2) & 7;
+  const int wc0 = was & 0xff, wc1 = (was >> 8) & 0xff, wr0 = (was >> 16) & 0xff, wr1 = was >> 24;
+  const int nc0 = now & 0xff, nc1 = (now >> 8) & 0xff, nr0 = (now >> 16) & 0xff, nr1 = now >> 24;
+  {
+    const int c = wc0 + dc, r = wr0 + dr;
+    const uint32_t q[3] = {n0, n1, n2};
+    bool lit = false;
+#pragma unroll
+    for (int j = 0; j < 3; ++j)
+      lit = lit || (c >= (int)(q[j] & 0xff) && c < (int)((q[j] >> 8) & 0xff) && r >= (int)((q[j] >> 16) & 0xff) &&
+                    r < (int)(q[j] >> 24));
+    if (c < wc1 && r < wr1 && !lit) frame[r * FRAME_SIDE + c] = 0;
+  }
+  {
+    const int c = nc0 + dc, r = nr0 + dr;
+    if (c < nc1 && r < nr1 && !(c >= wc0 && c < wc1 && r >= wr0 && r < wr1)) frame[r * FRAME_SIDE + c] = 255;
   }
 }
 
-// The same for the ordered stack: channel k of environment i (frame at ring + (4 i + k) * 7056)
-// showed the frame of step s - 4 + k and must show that of step s - 3 + k, so every channel changes
-// by one step's worth of pixels.  hist_at[f], f = 0..3, are the kept blocks of steps s - 4 + f;
-// the new frame's blocks (f = 4) come from the step itself and go to new_blocks.
-struct FrameHistory { const uint32_t* at[4]; };
+// A workgroup owns ENVS environments.  Thread 0 finds out the step and whether the buffer can be
+// repaired.  Then the first wavefront takes the environments' step, one lane each (reward / done to the caller, state in
+// place, episode statistics, the new cell blocks to the history) and leaves old and new blocks in
+// LDS; after the barrier all four wavefronts repair the frames, 32 lanes per rectangle, or write
+// them whole.
+// MODE: the host knows the step and has decided (repair / whole frames), or the launch finds out.
+enum UpdateMode { HOST_REPAIR = 0, HOST_WHOLE = 1, DEVICE_DECIDES = 2 };
 
-template <int ENVS>
-__global__ __launch_bounds__(256) void pixel_ordered_step_kernel(PongLaunch a, FrameHistory hist,
-                                                                 uint32_t* __restrict__ new_blocks,
-                                                                 uint8_t* __restrict__ ring) {
-  __shared__ uint32_t blk[5][3][ENVS];
-  const int64_t n = a.n;
+template <int ENVS, bool ORDERED, int MODE>
+__global__ __launch_bounds__(256) void pixel_update_step_kernel(UpdateStep a) {
+  constexpr int FRAMES = ORDERED ? 5 : 2;                // frames whose blocks are staged; the last is the new one
+  __shared__ uint32_t blk[FRAMES][3][ENVS];
+  __shared__ unsigned long long shared_step;
+  __shared__ int shared_known;
+  // With the step counter on the host, the host also keeps the record and passes the answer.  With
+  // the counter in device memory thread 0 reads counter and record (plain loads: both are written
+  // only by the one-thread launch that follows this one on the stream).  A ticket scheme like the
+  // other kernels' would have thousands of workgroups queue for one atomic here, which costs ten
+  // times the step.
+  uint64_t step = a.pong.step0;
+  bool known = MODE == HOST_REPAIR;
+  if (MODE == DEVICE_DECIDES) {
+    if (threadIdx.x == 0) {
+      const unsigned long long s = __hip_atomic_load(&a.pong.counter->step, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      shared_step = s;
+      shared_known = record_says_known(a.book, s, a.ring) ? 1 : 0;
+    }
+    __syncthreads();
+    step = shared_step;
+    known = shared_known != 0;
+  }
+  const int64_t n = a.pong.n;
   const int64_t env0 = (int64_t)blockIdx.x * ENVS;
+  // History entries of the steps s - 4 + f, f = 0..4 (the last one receives the new frame's blocks),
+  // and where frame 0 of the slot (or stack) starts: from the host when it knows the step, else
+  // worked out here (step s - 4 lives in entry (s + 1) mod 5).
+  uint32_t* entry[5];
+  uint8_t* base = a.base;
+#pragma unroll
+  for (int f = 0; f < 5; ++f) entry[f] = a.entry[f];
+  if (MODE == DEVICE_DECIDES) {
+    // (s + 1) mod 5 in 32-bit arithmetic (2^32 = 1 mod 5): a 64-bit remainder is a long routine here
+    const unsigned first = ((unsigned)step % 5u + (unsigned)(step >> 32) % 5u + 1u) % 5u;
+#pragma unroll
+    for (int f = 0; f < 5; ++f) {
+      const unsigned e = first + (unsigned)f;
+      entry[f] = a.hist + (int64_t)(e >= 5u ? e - 5u : e) * 3 * n;
+    }
+    base = a.ring + (ORDERED ? 0 : (int64_t)(step & 3) * a.slot_pitch);
+  }
+  uint32_t* new_blocks = entry[4];
   if (threadIdx.x < WAVE) {
     const int lane = threadIdx.x;
     const int64_t i = env0 + lane;
     const bool live = lane < ENVS && i < n;
     const int64_t ic = live ? i : n - 1;
-    PongLane s = pong_load(a.state, n, ic);
-    const Draw4 d = philox_draw(a.seed, (uint32_t)ic, a.step0, 0u);
-    const int action = a.actions ? (int)a.actions[ic] : pong_action_from_word(d.w0);
-    const PongEvent ev = pong_transition(s, action, d.w1, d.w2, a.max_score);
+    PongLane s = pong_load(a.pong.state, n, ic);
+    // The kept blocks (ring: of the frame in the slot, f = 0; stack: of the four channels' frames)
+    // do not depend on the step: all loads go out together with the state's, ahead of the
+    // dependent chain of the transition.  Idle lanes read environment n - 1's, a valid address.
+    uint32_t kept[FRAMES - 1][3];
+#pragma unroll
+    for (int f = 0; f < FRAMES - 1; ++f)
+#pragma unroll
+      for (int k = 0; k < 3; ++k) kept[f][k] = known ? entry[f][(int64_t)k * n + ic] : 0u;
+    const Draw4 d = philox_draw(a.pong.seed, (uint32_t)ic, step, 0u);
+    const int action = a.pong.actions ? (int)a.pong.actions[ic] : pong_action_from_word(d.w0);
+    const PongEvent ev = pong_transition(s, action, d.w1, d.w2, a.pong.max_score);
     LaneEpisodes le;
     if (live && ev.done) {
       le.count = 1; le.length_sum = ev.fin_len; le.ret_sum_i = ev.fin_ret;
@@ -445,123 +508,97 @@ __global__ __launch_bounds__(256) void pixel_ordered_step_kernel(PongLaunch a, F
     if (lane < ENVS) {
 #pragma unroll
       for (int k = 0; k < 3; ++k) {
-        blk[4][k][lane] = nb[k];
+        blk[FRAMES - 1][k][lane] = nb[k];
 #pragma unroll
-        for (int f = 0; f < 4; ++f) blk[f][k][lane] = live ? hist.at[f][(int64_t)k * n + i] : nb[k];
+        for (int f = 0; f < FRAMES - 1; ++f) {
+          // ring: the slot's frame, step s - 4; stack: steps s - 4 .. s - 1.  An idle lane shows no change.
+          blk[f][k][lane] = (live && known) ? kept[f][k] : nb[k];      // an idle lane shows no change
+        }
       }
     }
     if (live) {
 #pragma unroll
       for (int k = 0; k < 3; ++k) new_blocks[(int64_t)k * n + i] = nb[k];
-      a.reward[i] = ev.reward;
-      a.done[i] = ev.done ? 1 : 0;
-      pong_store(a.state, n, i, s);
+      a.pong.reward[i] = ev.reward;
+      a.pong.done[i] = ev.done ? 1 : 0;
+      pong_store(a.pong.state, n, i, s);
     }
-    flush_wave_stats<false>(a.stats, le);
+    flush_wave_stats<false>(a.pong.stats, le);
   }
   __syncthreads();
-  const int dc = threadIdx.x & 3, dr = (threadIdx.x >> 2) & 7;
-  for (int item = threadIdx.x >> 5; item < 12 * ENVS; item += 8) {
-    const int e = item % ENVS, rect = (item / ENVS) % 3, ch = item / (3 * ENVS);
-    const uint32_t w = blk[ch][rect][e], v = blk[ch + 1][rect][e];
-    if (w == v) continue;
-    uint8_t* frame = ring + ((env0 + e) * 4 + ch) * (int64_t)FRAME_BYTES;
-    const int wc0 = w & 0xff, wc1 = (w >> 8) & 0xff, wr0 = (w >> 16) & 0xff, wr1 = w >> 24;
-    const int nc0 = v & 0xff, nc1 = (v >> 8) & 0xff, nr0 = (v >> 16) & 0xff, nr1 = v >> 24;
-    {
-      const int c = wc0 + dc, r = wr0 + dr;
-      bool lit = false;
-#pragma unroll
-      for (int j = 0; j < 3; ++j) {
-        const uint32_t q = blk[ch + 1][j][e];
-        lit = lit || (c >= (int)(q & 0xff) && c < (int)((q >> 8) & 0xff) && r >= (int)((q >> 16) & 0xff) &&
-                      r < (int)(q >> 24));
+
+  auto frame_of = [&](int e, int channel) -> uint8_t* {     // channel: of the stack; the ring has its slot in `base`
+    if (ORDERED) return base + ((env0 + e) * 4 + channel) * (int64_t)FRAME_BYTES;
+    return base + (env0 + e) * a.stride;
+  };
+  if (known) {
+    constexpr int ITEMS = (ORDERED ? 12 : 3) * ENVS;
+    for (int item = threadIdx.x >> 5; item < ITEMS; item += 8) {
+      const int e = item % ENVS, rect = (item / ENVS) % 3, ch = item / (3 * ENVS);
+      const uint32_t was = blk[ch][rect][e], now = blk[ch + 1][rect][e];
+      if (was == now) continue;
+      repair_rectangle(frame_of(e, ch), was, now, blk[ch + 1][0][e], blk[ch + 1][1][e],
+                       blk[ch + 1][2][e]);
+    }
+  } else {
+    for (int e = 0; e < ENVS; ++e) {
+      if (env0 + e >= n) break;
+      const uint32_t b0 = blk[FRAMES - 1][0][e], b1 = blk[FRAMES - 1][1][e], b2 = blk[FRAMES - 1][2][e];
+      if (ORDERED) {
+        // channels 1..3 move down by one, the new frame goes on top; a thread reads its chunk of the
+        // three channels before it writes any of them
+        chunk_t* stack = reinterpret_cast<chunk_t*>(frame_of(e, 0));
+        for (int chunk = threadIdx.x; chunk < CHUNKS; chunk += 256) {
+          const chunk_t c1 = stack[1 * CHUNKS + chunk], c2 = stack[2 * CHUNKS + chunk], c3 = stack[3 * CHUNKS + chunk];
+          stack[0 * CHUNKS + chunk] = c1;
+          stack[1 * CHUNKS + chunk] = c2;
+          stack[2 * CHUNKS + chunk] = c3;
+          stack[3 * CHUNKS + chunk] = chunk_of_blocks(b0, b1, b2, chunk);
+        }
+      } else {
+        chunk_t* frame = reinterpret_cast<chunk_t*>(frame_of(e, 0));
+        for (int chunk = threadIdx.x; chunk < CHUNKS; chunk += 256) frame[chunk] = chunk_of_blocks(b0, b1, b2, chunk);
       }
-      if (c < wc1 && r < wr1 && !lit) frame[r * FRAME_SIDE + c] = 0;
-    }
-    {
-      const int c = nc0 + dc, r = nr0 + dr;
-      if (c < nc1 && r < nr1 && !(c >= wc0 && c < wc1 && r >= wr0 && r < wr1)) frame[r * FRAME_SIDE + c] = 255;
     }
   }
 }
 
-// Ordered stack, the physical way: channels 1..3 of every environment move down by one, the new
-// frame is built from its cell blocks on top.  One wavefront per environment; a lane reads its
-// chunk of the three channels before it writes any of them.
-__global__ __launch_bounds__(256) void stack_shift_kernel(const uint32_t* __restrict__ blocks, int64_t n,
-                                                          uint8_t* __restrict__ ring) {
-  const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (i >= n) return;
-  const int lane = threadIdx.x & (WAVE - 1);
-  uint32_t b[3];
-#pragma unroll
-  for (int k = 0; k < 3; ++k) b[k] = blocks[(int64_t)k * n + i];
-  chunk_t* stack = reinterpret_cast<chunk_t*>(ring + i * 4 * (int64_t)FRAME_BYTES);
-  for (int chunk = lane; chunk < CHUNKS; chunk += WAVE) {
-    const chunk_t c1 = stack[1 * CHUNKS + chunk], c2 = stack[2 * CHUNKS + chunk], c3 = stack[3 * CHUNKS + chunk];
-    uint32_t words[4] = {0, 0, 0, 0};
-#pragma unroll
-    for (int byte = 0; byte < 16; ++byte) {
-      const int p = chunk * 16 + byte, r = p / FRAME_SIDE, c = p - r * FRAME_SIDE;
-      bool lit = false;
-#pragma unroll
-      for (int k = 0; k < 3; ++k)
-        lit = lit || (c >= (int)(b[k] & 0xff) && c < (int)((b[k] >> 8) & 0xff) && r >= (int)((b[k] >> 16) & 0xff) &&
-                      r < (int)(b[k] >> 24));
-      words[byte >> 2] |= lit ? 0xffu << (8 * (byte & 3)) : 0u;
-    }
-    stack[0 * CHUNKS + chunk] = c1;
-    stack[1 * CHUNKS + chunk] = c2;
-    stack[2 * CHUNKS + chunk] = c3;
-    stack[3 * CHUNKS + chunk] = chunk_t{words[0], words[1], words[2], words[3]};
-  }
-}
-
-// Whole frames of one slot from their cell blocks, any layout: one wavefront per environment, each
-// lane builds 16-byte chunks by testing its 16 pixels against the three blocks.  Only used for the
-// few steps in which a slot's contents are not known; the page renderer is the fast full write.
-__global__ __launch_bounds__(256) void slot_full_kernel(const uint32_t* __restrict__ blocks, int64_t n,
-                                                        uint8_t* __restrict__ base, int64_t stride) {
-  const int64_t i = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (i >= n) return;
-  const int lane = threadIdx.x & (WAVE - 1);
-  uint32_t b[3];
-#pragma unroll
-  for (int k = 0; k < 3; ++k) b[k] = blocks[(int64_t)k * n + i];
-  chunk_t* frame = reinterpret_cast<chunk_t*>(base + i * stride);
-  for (int chunk = lane; chunk < CHUNKS; chunk += WAVE) {
-    uint32_t words[4] = {0, 0, 0, 0};
-#pragma unroll
-    for (int byte = 0; byte < 16; ++byte) {
-      const int p = chunk * 16 + byte, r = p / FRAME_SIDE, c = p - r * FRAME_SIDE;
-      bool lit = false;
-#pragma unroll
-      for (int k = 0; k < 3; ++k)
-        lit = lit || (c >= (int)(b[k] & 0xff) && c < (int)((b[k] >> 8) & 0xff) && r >= (int)((b[k] >> 16) & 0xff) &&
-                      r < (int)(b[k] >> 24));
-      words[byte >> 2] |= lit ? 0xffu << (8 * (byte & 3)) : 0u;
-    }
-    frame[chunk] = chunk_t{words[0], words[1], words[2], words[3]};
-  }
-}
-
-// Cell blocks of the frame that the state as it stands would render, written to `copies` buffers
-// of [3][n] that lie `pitch` words apart.
-__global__ __launch_bounds__(256) void blocks_of_state_kernel(const uint32_t* __restrict__ state, int64_t n,
-                                                              uint32_t* __restrict__ out0, uint32_t* __restrict__ out1,
-                                                              uint32_t* __restrict__ out2, uint32_t* __restrict__ out3) {
+// After env_reset has written the initial frame to all four slots (channels) of `ring`: that is as
+// if the steps s - 4 .. s - 1 (s = the next step) had each put that frame there, so their history
+// entries get the blocks of the state as it stands and the record is good from step s on.
+__global__ __launch_bounds__(256) void pixel_book_reset_kernel(const uint32_t* __restrict__ state, int64_t n,
+                                                               uint64_t host_step,
+                                                               const StepCounter* __restrict__ counter,
+                                                               PixelBook* __restrict__ book, uint32_t* __restrict__ hist,
+                                                               const uint8_t* ring) {
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const uint64_t step = read_step(counter, host_step);
+  if (i == 0) {
+    book->valid_from = step;
+    book->ring = (unsigned long long)reinterpret_cast<uintptr_t>(ring);
+  }
   if (i >= n) return;
   const PongLane s = pong_load(state, n, i);
   const uint32_t b0 = cell_block(140.0f, s.pa, 4.0f, 16.0f), b1 = cell_block(16.0f, s.po, 4.0f, 16.0f);
   const uint32_t b2 = cell_block(s.bx, s.by, 2.0f, 2.0f);
-  uint32_t* outs[4] = {out0, out1, out2, out3};
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
-    outs[j][0 * n + i] = b0; outs[j][1 * n + i] = b1; outs[j][2 * n + i] = b2;
+  for (int f = 0; f < 4; ++f) {
+    uint32_t* entry = hist + (int64_t)((step + 1 + f) % 5) * 3 * n;
+    entry[0 * n + i] = b0; entry[1 * n + i] = b1; entry[2 * n + i] = b2;
   }
 }
+
+// Behind a step of a handle whose step counter lives in device memory: the step's launch only read
+// counter and record; this one thread brings both up to date.
+__global__ void pixel_book_commit_kernel(StepCounter* counter, PixelBook* book, const uint8_t* ring) {
+  const unsigned long long s = counter->step;
+  record_after_step(book, s, ring);
+  counter->step = s + 1ull;
+}
+
+// The observation buffer no longer matches the kept blocks (state restored, steps taken that did
+// not write it): the next four steps write whole frames.
+__global__ void pixel_book_forget_kernel(PixelBook* book) { book->valid_from = NOT_KNOWN; }
 
 // F(t): the first ceil(n / 256) workgroups commit step t (reward / done to the caller, episode
 // statistics) and, if `ahead`, stage step t+1; the remaining workgroups render step t's plane.
@@ -682,11 +719,18 @@ hipError_t pixel_pipe_create(PixelPipe& p, int64_t n, bool delta_updates) {
   p.traj_cap = n > TRAJ_MIN_FRAMES ? n : TRAJ_MIN_FRAMES;
   const size_t traj_b = up((size_t)3 * (size_t)p.traj_cap * 4);
   const size_t hist_b = delta_updates ? up((size_t)5 * 3 * (size_t)n * 4) : 0;
-  const hipError_t err = hipMalloc(&p.slab, state_b + 2 * (blocks_b + 3 * word_b + done_b) + traj_b + hist_b);
+  const size_t book_b = delta_updates ? up(sizeof(PixelBook)) : 0;
+  hipError_t err = hipMalloc(&p.slab, state_b + 2 * (blocks_b + 3 * word_b + done_b) + traj_b + hist_b + book_b);
   if (err != hipSuccess) return err;
   char* at = static_cast<char*>(p.slab);
-  if (delta_updates) { p.hist = reinterpret_cast<uint32_t*>(at); at += hist_b; }
-  pixel_delta_forget(p);
+  if (delta_updates) {
+    p.hist = reinterpret_cast<uint32_t*>(at); at += hist_b;
+    p.book = at; at += book_b;
+    const PixelBook fresh = {NOT_KNOWN, 0ull, 0ull, 0ull};
+    *reinterpret_cast<PixelBook*>(p.host_book) = fresh;
+    err = hipMemcpy(p.book, &fresh, sizeof fresh, hipMemcpyHostToDevice);
+    if (err != hipSuccess) { (void)hipFree(p.slab); p.slab = nullptr; return err; }
+  }
   p.state_alt = reinterpret_cast<uint32_t*>(at); at += state_b;
   p.traj_blocks = reinterpret_cast<uint32_t*>(at); at += traj_b;
   for (int k = 0; k < 2; ++k) {
@@ -761,117 +805,94 @@ hipError_t pixel_counted_step(const PixelPipe& p, const PixelLaunch& a, hipStrea
   return hipGetLastError();
 }
 
-// 0 <= x mod m < m for negative x too
-static int wrap(int64_t x, int m) { return (int)(((x % m) + m) % m); }
+// The host's copy of the record lives in PixelPipe::host_book (same layout).
+static PixelBook* host_record(PixelPipe& p) { return reinterpret_cast<PixelBook*>(p.host_book); }
+static_assert(sizeof(PixelBook) <= sizeof(PixelPipe::host_book), "PixelPipe::host_book is too small for the record");
 
-hipError_t pixel_delta_after_reset(PixelPipe& p, const uint32_t* state, int64_t n, uint64_t step,
-                                   const uint8_t* ring, hipStream_t stream) {
-  if (!p.hist) return hipErrorInvalidValue;
-  // All four slots hold the initial frame.  For the bookkeeping that is as if the steps s-4 .. s-1
-  // (s = the next step) had each put that frame into their slot.
-  const int64_t s = (int64_t)step;
-  uint32_t* entry[4];
-  for (int back = 1; back <= 4; ++back) entry[back - 1] = p.hist + (int64_t)wrap(s - back, 5) * 3 * n;
-  hipLaunchKernelGGL(blocks_of_state_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, state, n,
-                     entry[0], entry[1], entry[2], entry[3]);
+hipError_t pixel_update_after_reset(PixelPipe& p, const uint32_t* state, int64_t n, uint64_t step,
+                                    const StepCounter* counter, const uint8_t* ring, hipStream_t stream) {
+  if (!p.hist || !p.book) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(pixel_book_reset_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, state, n,
+                     step, counter, static_cast<PixelBook*>(p.book), p.hist, ring);
   const hipError_t err = hipGetLastError();
-  if (err != hipSuccess) { pixel_delta_forget(p); return err; }
-  pixel_delta_forget(p);
-  p.delta_ring = ring;
-  for (int back = 1; back <= 4; ++back) {
-    p.slot_step[wrap(s - back, 4)] = s - back;
-    p.hist_step[wrap(s - back, 5)] = s - back;
+  if (err == hipSuccess && !counter) {
+    host_record(p)->valid_from = step;
+    host_record(p)->ring = (unsigned long long)reinterpret_cast<uintptr_t>(ring);
   }
-  p.stack_step = s - 1;
+  return err;
+}
+
+hipError_t pixel_update_forget(PixelPipe& p, hipStream_t stream) {
+  if (!p.book) return hipSuccess;
+  host_record(p)->valid_from = NOT_KNOWN;
+  hipLaunchKernelGGL(pixel_book_forget_kernel, dim3(1), dim3(1), 0, stream, static_cast<PixelBook*>(p.book));
+  return hipGetLastError();
+}
+
+hipError_t pixel_update_counts(PixelPipe& p, bool device_counter, int64_t* delta_steps, int64_t* full_steps,
+                               hipStream_t stream) {
+  *delta_steps = 0; *full_steps = 0;
+  if (!p.book) return hipSuccess;
+  PixelBook host = *host_record(p);
+  if (device_counter) {
+    hipError_t err = hipMemcpyAsync(&host, p.book, sizeof host, hipMemcpyDeviceToHost, stream);
+    if (err == hipSuccess) err = hipStreamSynchronize(stream);
+    if (err != hipSuccess) return err;
+  }
+  *delta_steps = (int64_t)host.delta_steps;
+  *full_steps = (int64_t)host.full_steps;
   return hipSuccess;
 }
 
-hipError_t pixel_delta_step(PixelPipe& p, const PixelLaunch& a, hipStream_t stream) {
-  if (!p.hist || !a.ring) return hipErrorInvalidValue;
+hipError_t pixel_update_step(PixelPipe& p, const PixelLaunch& a, bool ordered, hipStream_t stream) {
+  if (!p.hist || !p.book || !a.ring) return hipErrorInvalidValue;
   const int64_t n = a.pong.n;
-  const int64_t s = (int64_t)a.pong.step0;
-  const int slot = wrap(s, 4), e_new = wrap(s, 5), e_old = wrap(s - 4, 5);
-  if (p.delta_ring != a.ring) { pixel_delta_forget(p); p.delta_ring = a.ring; }
-  uint32_t* new_blocks = p.hist + (int64_t)e_new * 3 * n;
-  const uint32_t* old_blocks = p.hist + (int64_t)e_old * 3 * n;
-  // the slot holds the frame of step s - 4, put there by this library, and its blocks are still kept
-  const bool known = p.slot_step[slot] == s - 4 && p.hist_step[e_old] == s - 4;
-
-  PongLaunch d = a.pong;
-  d.T = 1;
-  p.hist_step[e_new] = INT64_MIN;          // until the launches below are known to be enqueued
-  p.slot_step[slot] = INT64_MIN;
-  uint8_t* base = a.slot_major ? a.ring + (int64_t)slot * n * FRAME_BYTES : a.ring + (int64_t)slot * FRAME_BYTES;
-  const int64_t stride = a.slot_major ? FRAME_BYTES : 4 * (int64_t)FRAME_BYTES;
-  hipError_t err;
-  if (known) {
-    // Few environments per workgroup: the step of a workgroup's environments runs on one wavefront
-    // while the other three wait, so small groups start their pixel work sooner (N = 16384: 15.6 us
-    // per step with 64 environments per workgroup, 10.7 with 32, 9.3 with 16, 8.8 with 8); large
-    // batches have workgroups enough to hide that and prefer fewer of them (N = 131072: 55.7 us
-    // with 16, 61.3 with 8).
-    if (n <= 32768)
-      hipLaunchKernelGGL(pixel_delta_step_kernel<8>, dim3((unsigned)((n + 7) / 8)), dim3(256), 0, stream, d,
-                         old_blocks, new_blocks, base, stride);
-    else
-      hipLaunchKernelGGL(pixel_delta_step_kernel<16>, dim3((unsigned)((n + 15) / 16)), dim3(256), 0, stream, d,
-                         old_blocks, new_blocks, base, stride);
-  } else {
-    hipLaunchKernelGGL(pixel_traj_dynamics_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, d,
-                       new_blocks, n);
-    err = hipGetLastError();
-    if (err != hipSuccess) return err;
-    hipLaunchKernelGGL(slot_full_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, stream, new_blocks, n, base,
-                       stride);
+  UpdateStep u{};
+  u.pong = a.pong;
+  u.pong.T = 1;
+  u.known_by_host = (!a.pong.counter && record_says_known(host_record(p), a.pong.step0, a.ring)) ? 1 : 0;
+  u.book = static_cast<PixelBook*>(p.book);
+  u.hist = p.hist;
+  u.ring = a.ring;
+  // frame of slot k of environment i: slot-major (k n + i) frames into the ring, else (4 i + k)
+  const bool planes = !ordered && a.slot_major;
+  u.stride = planes ? FRAME_BYTES : 4 * (int64_t)FRAME_BYTES;
+  u.slot_pitch = planes ? n * (int64_t)FRAME_BYTES : FRAME_BYTES;
+  if (!a.pong.counter) {
+    const uint64_t s = a.pong.step0;
+    for (int f = 0; f < 5; ++f) u.entry[f] = p.hist + (int64_t)((s + 1 + f) % 5) * 3 * n;
+    u.base = a.ring + (ordered ? 0 : (int64_t)(s & 3) * u.slot_pitch);
   }
-  err = hipGetLastError();
+  // Few environments per workgroup: their step runs on one wavefront while the other three wait,
+  // so small groups start their pixel work sooner (ring, N = 16384: 15.6 us per step with 64
+  // environments per workgroup, 10.7 with 32, 9.3 with 16, 8.8 with 8; stack: 22.1 with 16, 19.0
+  // with 8, 22.1 with 4); large batches have workgroups enough to hide that and prefer fewer of
+  // them (ring, N = 131072: 55.7 us with 16, 61.3 with 8).
+  const bool small = n <= 32768;
+  const dim3 grid((unsigned)(small ? (n + 7) / 8 : (n + 15) / 16)), block(256);
+  const int mode = u.pong.counter ? DEVICE_DECIDES : (u.known_by_host ? HOST_REPAIR : HOST_WHOLE);
+#define MI355ENV_UPDATE_CASE(ORD, MODE)                                                                    \
+  if (ordered == ORD && mode == MODE) {                                                                   \
+    if (small) hipLaunchKernelGGL((pixel_update_step_kernel<8, ORD, MODE>), grid, block, 0, stream, u);   \
+    else hipLaunchKernelGGL((pixel_update_step_kernel<16, ORD, MODE>), grid, block, 0, stream, u);        \
+  }
+  MI355ENV_UPDATE_CASE(false, HOST_REPAIR)
+  MI355ENV_UPDATE_CASE(false, HOST_WHOLE)
+  MI355ENV_UPDATE_CASE(false, DEVICE_DECIDES)
+  MI355ENV_UPDATE_CASE(true, HOST_REPAIR)
+  MI355ENV_UPDATE_CASE(true, HOST_WHOLE)
+  MI355ENV_UPDATE_CASE(true, DEVICE_DECIDES)
+#undef MI355ENV_UPDATE_CASE
+  hipError_t err = hipGetLastError();
   if (err != hipSuccess) return err;
-  p.hist_step[e_new] = s;
-  p.slot_step[slot] = s;
-  (known ? p.delta_steps : p.full_steps) += 1;
-  return hipSuccess;
-}
-
-hipError_t pixel_ordered_step(PixelPipe& p, const PixelLaunch& a, hipStream_t stream) {
-  if (!p.hist || !a.ring) return hipErrorInvalidValue;
-  const int64_t n = a.pong.n;
-  const int64_t s = (int64_t)a.pong.step0;
-  const int e_new = wrap(s, 5);
-  if (p.delta_ring != a.ring) { pixel_delta_forget(p); p.delta_ring = a.ring; }
-  uint32_t* new_blocks = p.hist + (int64_t)e_new * 3 * n;
-  // the channels hold the frames of steps s-4 .. s-1, put there by this library, blocks still kept
-  bool known = p.stack_step == s - 1;
-  FrameHistory hist;
-  for (int f = 0; f < 4; ++f) {
-    const int64_t step = s - 4 + f;
-    known = known && p.hist_step[wrap(step, 5)] == step;
-    hist.at[f] = p.hist + (int64_t)wrap(step, 5) * 3 * n;
-  }
-  PongLaunch d = a.pong;
-  d.T = 1;
-  p.hist_step[e_new] = INT64_MIN;          // until the launches below are known to be enqueued
-  p.stack_step = INT64_MIN;
-  hipError_t err;
-  if (known) {
-    if (n <= 32768)
-      hipLaunchKernelGGL(pixel_ordered_step_kernel<8>, dim3((unsigned)((n + 7) / 8)), dim3(256), 0, stream, d, hist,
-                         new_blocks, a.ring);
-    else
-      hipLaunchKernelGGL(pixel_ordered_step_kernel<16>, dim3((unsigned)((n + 15) / 16)), dim3(256), 0, stream, d,
-                         hist, new_blocks, a.ring);
-  } else {
-    hipLaunchKernelGGL(pixel_traj_dynamics_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, d,
-                       new_blocks, n);
+  if (u.pong.counter) {
+    hipLaunchKernelGGL(pixel_book_commit_kernel, dim3(1), dim3(1), 0, stream, u.pong.counter, u.book,
+                       static_cast<const uint8_t*>(a.ring));
     err = hipGetLastError();
-    if (err != hipSuccess) return err;
-    hipLaunchKernelGGL(stack_shift_kernel, dim3((unsigned)((n + 3) / 4)), dim3(256), 0, stream, new_blocks, n, a.ring);
+  } else {
+    record_after_step(host_record(p), a.pong.step0, a.ring);
   }
-  err = hipGetLastError();
-  if (err != hipSuccess) return err;
-  p.hist_step[e_new] = s;
-  p.stack_step = s;
-  (known ? p.delta_steps : p.full_steps) += 1;
-  return hipSuccess;
+  return err;
 }
 
 hipError_t launch_pixel_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,

@@ -258,15 +258,23 @@ def test_graph_replay_of_a_fused_rollout_launch():
     assert st["episodes"] == p.stats()["episodes"] > 0
 
 
-@pytest.mark.parametrize("layout", ["slot", "env"])
+PIXEL_VARIANTS = {
+    "slot": {"pixel_layout": b.ENV_PIXELS_SLOT_MAJOR},
+    "env": {"pixel_layout": b.ENV_PIXELS_ENV_MAJOR},
+    "slot-delta": {"pixel_layout": b.ENV_PIXELS_SLOT_MAJOR, "pixel_update": b.ENV_PIXELS_DELTA},
+    "env-delta": {"pixel_layout": b.ENV_PIXELS_ENV_MAJOR, "pixel_update": b.ENV_PIXELS_DELTA},
+    "ordered": {"pixel_layout": b.ENV_PIXELS_ORDERED},
+}
+
+
+@pytest.mark.parametrize("layout", sorted(PIXEL_VARIANTS))
 def test_pixel_handle_with_device_counter_matches_the_default_path_and_replays(layout):
     """Pong pixels: a handle with the step counter in device memory takes one launch per step
     instead of the staged two-buffer path.  Ring, reward and done must equal the default handle's
     after every step (which the pixel parity tests tie to the oracle), for direct calls, graph
     replays and a frame-trajectory rollout, and the episode statistics must agree."""
     n, seed, K = 600, 21, 70
-    lay = b.ENV_PIXELS_SLOT_MAJOR if layout == "slot" else b.ENV_PIXELS_ENV_MAJOR
-    cfg = {"max_score": 1, "pixel_layout": lay}
+    cfg = dict(PIXEL_VARIANTS[layout], max_score=1)
     s = torch.cuda.Stream()
     FB = 84 * 84
     out = {}

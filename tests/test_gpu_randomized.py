@@ -158,6 +158,11 @@ PIXEL_MODES = {
     "ring slot-major, delta": dict(pixel_layout=b.ENV_PIXELS_SLOT_MAJOR, pixel_update=b.ENV_PIXELS_DELTA),
     "ring env-major, delta": dict(pixel_layout=b.ENV_PIXELS_ENV_MAJOR, pixel_update=b.ENV_PIXELS_DELTA),
     "ordered stack": dict(pixel_layout=b.ENV_PIXELS_ORDERED),
+    "ring slot-major, delta, device counter": dict(pixel_layout=b.ENV_PIXELS_SLOT_MAJOR,
+                                                   pixel_update=b.ENV_PIXELS_DELTA,
+                                                   step_counter=b.ENV_STEP_COUNTER_DEVICE),
+    "ordered stack, device counter": dict(pixel_layout=b.ENV_PIXELS_ORDERED,
+                                          step_counter=b.ENV_STEP_COUNTER_DEVICE),
 }
 
 
