@@ -128,7 +128,7 @@ enum { ENV_STEP_COUNTER_HOST = 1, ENV_STEP_COUNTER_DEVICE = 2 };
  *               it is.  Always maintained by delta updates (see ENV_PIXELS_DELTA below: the same
  *               rules about the buffer being shared state apply): each channel changes by one
  *               step's worth of pixels.  When the library cannot vouch for the contents it moves
- *               the channels physically instead.  Needs the host step counter. */
+ *               the channels physically instead (four steps, as above). */
 enum { ENV_PIXELS_SLOT_MAJOR = 1, ENV_PIXELS_ENV_MAJOR = 2, ENV_PIXELS_ORDERED = 3 };
 
 /* How env_step brings a ring slot of ENV_PONG_PIXELS up to date (other kinds: ENV_E_UNSUPPORTED for
@@ -139,10 +139,12 @@ enum { ENV_PIXELS_SLOT_MAJOR = 1, ENV_PIXELS_ENV_MAJOR = 2, ENV_PIXELS_ORDERED =
  *          in a few dozen pixels: the step clears the pixels that went dark and sets the ones that
  *          lit up, and touches nothing else.  This makes the ring shared state: pass the same ring
  *          to every env_reset / env_step and do not write to it.  The library keeps the rectangles
- *          of the last five frames (60 B/env) and falls back to a full write of a slot whenever it
- *          did not itself put the frame of four steps earlier there (first steps after env_create
- *          or env_set_state, another ring pointer, steps taken through env_rollout in between).
- *          Needs the host step counter (ENV_E_UNSUPPORTED with ENV_STEP_COUNTER_DEVICE). */
+ *          of the last five frames (60 B/env) and a record of which buffer they describe and from
+ *          which step on; whenever it cannot vouch for the buffer (no env_reset with it yet,
+ *          env_set_state, another buffer, steps taken through env_rollout in between) the next four
+ *          steps write whole frames, after which delta updates resume.  Works with either step
+ *          counter: with ENV_STEP_COUNTER_DEVICE the record lives in device memory and every
+ *          launch, also a replayed one, decides for itself. */
 enum { ENV_PIXELS_FULL = 1, ENV_PIXELS_DELTA = 2 };
 
 /* Statistics of the episodes that ended since the counters were last cleared. */
