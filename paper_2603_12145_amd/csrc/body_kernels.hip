@@ -628,7 +628,7 @@ __device__ __forceinline__ void pair_from_full(PairLane& p, const BodyLane& s, c
 
 template <bool NEWTON, bool SKIP_IDLE_ROWS>
 __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(2, 2))) void body_rollout_kernel(BodyLaunch a) {
-  a.step0 = launch_first_step(a.counter, a.step0, a.T);
+  a.step0 = launch_first_step(a.counter, a.step0, a.T, a.ticket != 0);
   const int64_t n = a.n;
   const int side = threadIdx.x & 1;
   const real sign = side ? 1.0 : -1.0;
@@ -758,10 +758,13 @@ hipError_t launch_body_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t
 
 hipError_t launch_body_rollout(const BodyLaunch& a, hipStream_t stream) {
   const dim3 grid((unsigned)((a.n + WAVE / 2 - 1) / (WAVE / 2)));   // 32 environments per wavefront
-  if (a.newton && a.n >= 32768) hipLaunchKernelGGL((body_rollout_kernel<true, true>), grid, dim3(WAVE), 0, stream, a);
-  else if (a.newton) hipLaunchKernelGGL((body_rollout_kernel<true, false>), grid, dim3(WAVE), 0, stream, a);
-  else hipLaunchKernelGGL((body_rollout_kernel<false, false>), grid, dim3(WAVE), 0, stream, a);
-  return hipGetLastError();
+  BodyLaunch a2 = a;
+  a2.ticket = grid.x <= TICKET_MAX_BLOCKS;
+  if (a.newton && a.n >= 32768) hipLaunchKernelGGL((body_rollout_kernel<true, true>), grid, dim3(WAVE), 0, stream, a2);
+  else if (a.newton) hipLaunchKernelGGL((body_rollout_kernel<true, false>), grid, dim3(WAVE), 0, stream, a2);
+  else hipLaunchKernelGGL((body_rollout_kernel<false, false>), grid, dim3(WAVE), 0, stream, a2);
+  const hipError_t err = hipGetLastError();
+  return err != hipSuccess ? err : advance_step_counter_behind(a.counter, a.T, grid.x, stream);
 }
 
 }  // namespace envk

@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) void cartpole_reset_kernel(uint32_t* __restric
 }
 
 __global__ __launch_bounds__(256) void cartpole_rollout_kernel(PongLaunch a) {
-  a.step0 = launch_first_step(a.counter, a.step0, a.T);
+  a.step0 = launch_first_step(a.counter, a.step0, a.T, a.ticket != 0);
   const int lane = threadIdx.x & (WAVE - 1);
   const int wave_in_block = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   // XCD-aware mapping as in the Pong rollout: each XCD owns a contiguous eighth of the batch
@@ -159,8 +159,11 @@ hipError_t launch_cartpole_reset(uint32_t* state, int64_t n, uint64_t seed, uint
 hipError_t launch_cartpole_rollout(const PongLaunch& a, hipStream_t stream) {
   unsigned blocks = (unsigned)((a.n + 255) / 256);
   blocks = (blocks + 7u) & ~7u;
-  hipLaunchKernelGGL(cartpole_rollout_kernel, dim3(blocks), dim3(256), 0, stream, a);
-  return hipGetLastError();
+  PongLaunch a2 = a;
+  a2.ticket = blocks <= TICKET_MAX_BLOCKS;
+  hipLaunchKernelGGL(cartpole_rollout_kernel, dim3(blocks), dim3(256), 0, stream, a2);
+  const hipError_t err = hipGetLastError();
+  return err != hipSuccess ? err : advance_step_counter_behind(a.counter, a.T, blocks, stream);
 }
 
 }  // namespace envk

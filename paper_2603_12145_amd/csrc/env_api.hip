@@ -33,7 +33,7 @@ struct mi355env {
   uint32_t* state;        // device SoA [fields][n], every field 4 bytes (pixels: may point into pipe)
   uint32_t* state_alloc;  // the allocation made for it by env_create
   int fields;
-  DeviceStats* stats;     // device
+  DeviceStats* stats;     // device, STATS_STRIPES copies
   StepCounter* counter;   // device, behind stats in the same allocation
   bool device_counter;    // launches read and advance `counter` instead of taking `step` as an argument
   PixelPipe pipe;         // pixels only: second state buffer and the staging buffers of the lookahead
@@ -120,6 +120,12 @@ DeviceStats empty_stats() {
   s.return_max_key = std::numeric_limits<int>::min();
   return s;
 }
+
+// All copies of the statistics block, empty (host side; 32 KiB).
+struct EmptyStats {
+  DeviceStats stripes[STATS_STRIPES];
+  EmptyStats() { for (auto& s : stripes) s = empty_stats(); }
+};
 
 float key_to_float(int key) {
   const int b = key ^ ((key >> 31) & 0x7fffffff);
@@ -293,19 +299,20 @@ int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_c
     (void)hipGetLastError(); delete e; return ENV_E_ALLOC;
   }
   e->state_alloc = e->state;
-  static_assert(sizeof(DeviceStats) % 8 == 0, "the step counter behind the statistics must be 8-byte aligned");
-  if (hipMalloc(reinterpret_cast<void**>(&e->stats), sizeof(DeviceStats) + sizeof(StepCounter)) != hipSuccess) {
+  static_assert(sizeof(DeviceStats) == 128, "one cache line per copy of the statistics");
+  if (hipMalloc(reinterpret_cast<void**>(&e->stats), STATS_STRIPES * sizeof(DeviceStats) + sizeof(StepCounter)) !=
+      hipSuccess) {
     (void)hipGetLastError(); (void)hipFree(e->state); delete e; return ENV_E_ALLOC;
   }
   if (kind == ENV_PONG_PIXELS && pixel_pipe_create(e->pipe, n_envs, c.pixel_update == ENV_PIXELS_DELTA) != hipSuccess) {
     (void)hipGetLastError(); (void)hipFree(e->state); (void)hipFree(e->stats); delete e;
     return ENV_E_ALLOC;
   }
-  e->counter = reinterpret_cast<StepCounter*>(e->stats + 1);
-  const DeviceStats z = empty_stats();
+  e->counter = reinterpret_cast<StepCounter*>(e->stats + STATS_STRIPES);
+  const EmptyStats z;
   if (hipMemsetAsync(e->state, 0, state_bytes, e->stream) != hipSuccess ||
       hipMemsetAsync(e->counter, 0, sizeof(StepCounter), e->stream) != hipSuccess ||
-      hipMemcpyAsync(e->stats, &z, sizeof z, hipMemcpyHostToDevice, e->stream) != hipSuccess ||
+      hipMemcpyAsync(e->stats, z.stripes, sizeof z.stripes, hipMemcpyHostToDevice, e->stream) != hipSuccess ||
       hipStreamSynchronize(e->stream) != hipSuccess) {
     (void)hipGetLastError(); (void)hipFree(e->state); (void)hipFree(e->stats);
     pixel_pipe_destroy(e->pipe); delete e;
@@ -375,10 +382,21 @@ int env_rollout(env_t* e, int32_t T, const void* actions_dev, void* obs_dev, flo
 int env_stats(env_t* e, env_stats_t* host_out, int reset_counters) {
   if (!e || !host_out) return ENV_E_ARG;
   if (!on_own_device(e)) return ENV_E_STATE;
-  DeviceStats d;
-  if (hipMemcpyAsync(&d, e->stats, sizeof d, hipMemcpyDeviceToHost, e->stream) != hipSuccess ||
+  static_assert(STATS_STRIPES * sizeof(DeviceStats) <= 64 * 1024, "the copies are read into a stack buffer");
+  DeviceStats stripes[STATS_STRIPES];
+  if (hipMemcpyAsync(stripes, e->stats, sizeof stripes, hipMemcpyDeviceToHost, e->stream) != hipSuccess ||
       hipStreamSynchronize(e->stream) != hipSuccess)
     return ENV_E_HIP;
+  DeviceStats d = empty_stats();
+  for (const DeviceStats& s : stripes) {
+    d.episodes += s.episodes;
+    d.length_sum += s.length_sum;
+    d.return_sum_i += s.return_sum_i;
+    d.return_sum_f += s.return_sum_f;
+    d.nonfinite += s.nonfinite;
+    d.return_min_key = s.return_min_key < d.return_min_key ? s.return_min_key : d.return_min_key;
+    d.return_max_key = s.return_max_key > d.return_max_key ? s.return_max_key : d.return_max_key;
+  }
   host_out->episodes = (int64_t)d.episodes;
   host_out->length_sum = (int64_t)d.length_sum;
   host_out->nonfinite = (int64_t)d.nonfinite;
@@ -393,8 +411,8 @@ int env_stats(env_t* e, env_stats_t* host_out, int reset_counters) {
     host_out->return_max = any ? (double)d.return_max_key : -INFINITY;
   }
   if (reset_counters) {
-    const DeviceStats z = empty_stats();
-    if (hipMemcpyAsync(e->stats, &z, sizeof z, hipMemcpyHostToDevice, e->stream) != hipSuccess ||
+    const EmptyStats z;
+    if (hipMemcpyAsync(e->stats, z.stripes, sizeof z.stripes, hipMemcpyHostToDevice, e->stream) != hipSuccess ||
         hipStreamSynchronize(e->stream) != hipSuccess)
       return ENV_E_HIP;
   }

@@ -18,6 +18,7 @@ struct PongLaunch {
   uint64_t seed;
   uint64_t step0;         // index of the first step of this launch (used when counter == nullptr)
   StepCounter* counter;   // device-resident step counter, or nullptr
+  int32_t ticket;         // set by the launcher: the launch advances `counter` itself (small grids)
   int32_t T;
   int32_t max_score;
   const uint8_t* actions; // [T,n] or nullptr

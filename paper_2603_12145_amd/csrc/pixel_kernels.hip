@@ -89,7 +89,7 @@ __global__ __launch_bounds__(WAVES_PER_BLOCK * WAVE) void pixel_kernel(PixelLaun
   // a handle that keeps its step counter in device memory: read it (and, for a step, advance it)
   // before any wavefront leaves
   if (MODE == MODE_RESET) a.pong.step0 = read_step(a.pong.counter, a.pong.step0);
-  else a.pong.step0 = launch_first_step(a.pong.counter, a.pong.step0, a.pong.T);
+  else a.pong.step0 = launch_first_step(a.pong.counter, a.pong.step0, a.pong.T, a.pong.ticket != 0);
   const int lane = threadIdx.x & (WAVE - 1);
   const int wave = threadIdx.x >> 6;
   const int64_t n = a.pong.n;
@@ -238,7 +238,7 @@ __global__ __launch_bounds__(256) void pixel_dynamics_kernel(PongLaunch a, const
 // k), reward and done to the caller's [T][n] rows; the state is loaded and stored once.
 __global__ __launch_bounds__(256) void pixel_traj_dynamics_kernel(PongLaunch a, uint32_t* __restrict__ blocks,
                                                                   int64_t frames) {
-  a.step0 = launch_first_step(a.counter, a.step0, a.T);
+  a.step0 = launch_first_step(a.counter, a.step0, a.T, a.ticket != 0);
   const int64_t n = a.n;
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const bool live = i < n;
@@ -645,11 +645,13 @@ int g_envs_per_wave = 16;
 bool g_streaming = false;
 
 template <int MODE>
-hipError_t launch_mode(const PixelLaunch& a, hipStream_t stream) {
+hipError_t launch_mode(const PixelLaunch& launch, hipStream_t stream) {
   const int epw = g_envs_per_wave;
-  const int64_t waves = (a.pong.n + epw - 1) / epw;
+  const int64_t waves = (launch.pong.n + epw - 1) / epw;
   const unsigned blocks = (unsigned)((waves + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
   const dim3 grid(blocks), block(WAVES_PER_BLOCK * WAVE);
+  PixelLaunch a = launch;
+  a.pong.ticket = blocks <= TICKET_MAX_BLOCKS;
 #define MI355ENV_PIXEL_CASE(E)                                                                \
   case E:                                                                                     \
     if (g_streaming) hipLaunchKernelGGL((pixel_kernel<E, MODE, true>), grid, block, 0, stream, a); \
@@ -664,7 +666,9 @@ hipError_t launch_mode(const PixelLaunch& a, hipStream_t stream) {
     default: return hipErrorInvalidValue;
   }
 #undef MI355ENV_PIXEL_CASE
-  return hipGetLastError();
+  const hipError_t err = hipGetLastError();
+  if (err != hipSuccess || MODE == MODE_RESET) return err;      // a reset only reads the counter
+  return advance_step_counter_behind(a.pong.counter, a.pong.T, blocks, stream);
 }
 
 }  // namespace
@@ -791,9 +795,11 @@ hipError_t pixel_counted_step(const PixelPipe& p, const PixelLaunch& a, hipStrea
   const int64_t n = a.pong.n;
   PongLaunch d = a.pong;
   d.T = 1;
-  hipLaunchKernelGGL(pixel_traj_dynamics_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, d,
-                     p.blocks[0], n);
+  const unsigned blocks = (unsigned)((n + 255) / 256);
+  d.ticket = blocks <= TICKET_MAX_BLOCKS;
+  hipLaunchKernelGGL(pixel_traj_dynamics_kernel, dim3(blocks), dim3(256), 0, stream, d, p.blocks[0], n);
   hipError_t err = hipGetLastError();
+  if (err == hipSuccess) err = advance_step_counter_behind(d.counter, 1, blocks, stream);   // before the renderer reads it
   if (err != hipSuccess) return err;
   unsigned pages = 0;
   for (int slot = 0; slot < 4; ++slot) {

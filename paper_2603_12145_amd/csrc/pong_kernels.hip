@@ -128,7 +128,7 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
 
 template <bool XCD_REMAP>
 __global__ __launch_bounds__(256) void pong_rollout_kernel(PongLaunch a) {
-  a.step0 = launch_first_step(a.counter, a.step0, a.T);
+  a.step0 = launch_first_step(a.counter, a.step0, a.T, a.ticket != 0);
   const int lane = threadIdx.x & (WAVE - 1);
   // wave-uniform by construction; readfirstlane tells the compiler so (scalar address math)
   const int wave_in_block = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -205,9 +205,11 @@ hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream) {
   // stream and the denser pattern wins (1.86 vs 2.13 ms at N = 262144).
   PongLaunch a2 = a;
   a2.paged = g_paged_mode == 2 ? (a.n >= 131072) : g_paged_mode;
+  a2.ticket = blocks <= TICKET_MAX_BLOCKS;
   if (g_xcd_remap) hipLaunchKernelGGL(pong_rollout_kernel<true>, g, b, 0, stream, a2);
   else hipLaunchKernelGGL(pong_rollout_kernel<false>, g, b, 0, stream, a2);
-  return hipGetLastError();
+  const hipError_t err = hipGetLastError();
+  return err != hipSuccess ? err : advance_step_counter_behind(a.counter, a.T, blocks, stream);
 }
 
 }  // namespace envk

@@ -1,14 +1,20 @@
 // Per-batch episode statistics: per-lane accumulators are combined with a wave64 butterfly and one
 // lane per wavefront issues the atomics, so the number of atomics is (waves that saw an episode
 // end), not (episodes).  Integer sums make the Pong statistics independent of the order in which
-// wavefronts retire.
+// wavefronts retire.  The block is kept STATS_STRIPES times, one 128-byte line each, and a
+// wavefront adds to the copy its index picks: atomics on one address go through one after the
+// other (about 45 ns each), which for a per-step launch whose every wavefront sees an episode end
+// (cart-pole with random actions, N = 65536: 1024 wavefronts x 5 atomics) was 55 of the step's
+// 60 us.  Whoever reads the statistics adds the copies up.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 namespace envk {
 
-struct DeviceStats {
+constexpr int STATS_STRIPES = 256;
+
+struct alignas(128) DeviceStats {
   unsigned long long episodes;
   unsigned long long length_sum;
   long long return_sum_i;   // Pong: returns are integers
@@ -53,8 +59,9 @@ struct LaneEpisodes {
 
 // Must be called by all 64 lanes of the wavefront (inactive environments pass empty accumulators).
 template <bool FLOAT_RETURNS>
-__device__ __forceinline__ void flush_wave_stats(DeviceStats* __restrict__ st, const LaneEpisodes& le) {
+__device__ __forceinline__ void flush_wave_stats(DeviceStats* __restrict__ stripes, const LaneEpisodes& le) {
   if (__ballot(le.count > 0 || le.nonfinite > 0) == 0ull) return;   // wave-uniform
+  DeviceStats* st = stripes + ((blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) & (STATS_STRIPES - 1));
   const long long cnt = wave_sum((long long)le.count);
   const long long len = wave_sum((long long)le.length_sum);
   const long long bad = wave_sum((long long)le.nonfinite);

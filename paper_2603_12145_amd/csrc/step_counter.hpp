@@ -2,10 +2,13 @@
 // replayed: a kernel argument is frozen at capture time, so the index of the launch's first step
 // (which keys every Philox draw) is read from memory instead, and the launch advances it itself.
 //
-// Protocol, per launch: thread 0 of every workgroup reads the counter, then takes a ticket; the
-// workgroup that takes the last ticket knows every other workgroup has already read, so it alone
-// writes counter + T and clears the tickets.  The next launch on the stream starts after this one
-// has drained, so it reads the advanced value.  Two launches that use one counter must not overlap.
+// Small grids advance it themselves: thread 0 of every workgroup reads the counter, then takes a
+// ticket; the workgroup that takes the last ticket knows every other workgroup has already read,
+// so it alone writes counter + T and clears the tickets.  The tickets are one atomic on one
+// address, about 45 ns each back to back, so above TICKET_MAX_BLOCKS workgroups (a per-step launch
+// of 262144 Pong environments has 1024: 37 us of tickets around 6 us of work) the launch only reads
+// and a one-thread launch behind it does the adding.  Either way the next launch on the stream
+// starts after the counter has moved.  Two launches that use one counter must not overlap.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -18,11 +21,21 @@ struct StepCounter {
   unsigned int pad;
 };
 
+constexpr unsigned TICKET_MAX_BLOCKS = 64;
+
 // Must be called by every thread of every workgroup of a one-dimensional launch, before any early
 // exit.  counter == nullptr: the host passed the step as a kernel argument; nothing is touched.
+// ticket: this launch advances the counter itself (else advance_step_counter_behind follows it).
 // The result is wave-uniform (kept in scalar registers).
-__device__ __forceinline__ uint64_t launch_first_step(StepCounter* counter, uint64_t host_step0, int32_t T) {
+__device__ __forceinline__ uint64_t launch_first_step(StepCounter* counter, uint64_t host_step0, int32_t T,
+                                                      bool ticket) {
   if (!counter) return host_step0;
+  if (!ticket) {
+    const unsigned long long s = __hip_atomic_load(&counter->step, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)s);
+    const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(s >> 32));
+    return ((uint64_t)hi << 32) | lo;
+  }
   __shared__ unsigned long long shared_step;
   if (threadIdx.x == 0) {
     const unsigned long long s = __hip_atomic_load(&counter->step, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
@@ -44,6 +57,19 @@ __device__ __forceinline__ uint64_t launch_first_step(StepCounter* counter, uint
 // For kernels that only read the counter (reset): no ticket, no write.
 __device__ __forceinline__ uint64_t read_step(const StepCounter* counter, uint64_t host_step) {
   return counter ? __hip_atomic_load(&counter->step, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : host_step;
+}
+
+namespace {
+__global__ void step_counter_advance_kernel(StepCounter* counter, int32_t T) {
+  counter->step = counter->step + (unsigned long long)T;
+}
+}  // namespace
+
+// Host side of the second protocol: right behind a launch of `blocks` workgroups that only read.
+inline hipError_t advance_step_counter_behind(StepCounter* counter, int32_t T, unsigned blocks, hipStream_t stream) {
+  if (!counter || blocks <= TICKET_MAX_BLOCKS) return hipSuccess;
+  hipLaunchKernelGGL(step_counter_advance_kernel, dim3(1), dim3(1), 0, stream, counter, T);
+  return hipGetLastError();
 }
 
 }  // namespace envk
