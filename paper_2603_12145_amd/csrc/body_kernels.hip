@@ -632,9 +632,10 @@ __global__ __launch_bounds__(WAVE) __attribute__((amdgpu_waves_per_eu(2, 2))) vo
   const int64_t n = a.n;
   const int side = threadIdx.x & 1;
   const real sign = side ? 1.0 : -1.0;
-  const int64_t i = (int64_t)blockIdx.x * (WAVE / 2) + (threadIdx.x >> 1);
-  const bool live = i < n;
-  const int64_t ic = live ? i : n - 1;             // idle lane pairs shadow the last environment
+  const int64_t i = (int64_t)blockIdx.x * a.envs_per_wave + (threadIdx.x >> 1);
+  const bool live = (int)(threadIdx.x >> 1) < a.envs_per_wave && i < n;
+  // idle lane pairs shadow the wavefront's first environment: they add nothing to its ballots
+  const int64_t ic = live ? i : (int64_t)blockIdx.x * a.envs_per_wave;
   const Params P = {(real)a.armature, (real)a.joint_damping, (real)a.friction_mu,
                     1.0 / NEWTON_REG_CONTACT, 1.0 / NEWTON_REG_LIMIT,
                     1.0 / (NEWTON_TIME_CONST * NEWTON_TIME_CONST), 2.0 / NEWTON_TIME_CONST};
@@ -757,8 +758,15 @@ hipError_t launch_body_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t
 }
 
 hipError_t launch_body_rollout(const BodyLaunch& a, hipStream_t stream) {
-  const dim3 grid((unsigned)((a.n + WAVE / 2 - 1) / (WAVE / 2)));   // 32 environments per wavefront
   BodyLaunch a2 = a;
+  // A wavefront of the Newton model runs as many passes as its slowest environment needs.  When
+  // the batch leaves SIMDs empty anyway, fewer environments per wavefront (the other lanes idle)
+  // mean a smaller maximum: N = 8192 x T = 400 takes 8.46 ms with 32 environments per wavefront,
+  // 8.00 with 16, 7.53 with 8 (12.1 with 4: too many wavefronts per SIMD by then); N = 16384:
+  // 4.31 / 4.13 / 6.74.  The penalty model gains nothing (its second solve is needed by some
+  // environment of almost any group) and keeps 32.
+  a2.envs_per_wave = !a.newton ? 32 : a.n <= 8192 ? 8 : a.n <= 16384 ? 16 : 32;
+  const dim3 grid((unsigned)((a.n + a2.envs_per_wave - 1) / a2.envs_per_wave));
   a2.ticket = grid.x <= TICKET_MAX_BLOCKS;
   if (a.newton && a.n >= 32768) hipLaunchKernelGGL((body_rollout_kernel<true, true>), grid, dim3(WAVE), 0, stream, a2);
   else if (a.newton) hipLaunchKernelGGL((body_rollout_kernel<true, false>), grid, dim3(WAVE), 0, stream, a2);

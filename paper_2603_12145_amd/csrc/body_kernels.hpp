@@ -22,6 +22,7 @@ struct BodyLaunch {
   uint64_t step0;        // used when counter == nullptr
   StepCounter* counter;  // device-resident step counter, or nullptr
   int32_t ticket;        // set by the launcher: the launch advances `counter` itself (small grids)
+  int32_t envs_per_wave; // set by the launcher: environments (lane pairs) a wavefront takes, at most 32
   int32_t T;
   int32_t max_episode_steps;
   float armature, joint_damping, friction_mu;
