@@ -27,7 +27,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 PONG_BYTES_PER_ENV_STEP = 37   # 32 obs + 4 reward + 1 done
 CARTPOLE_BYTES_PER_ENV_STEP = 21   # 16 obs + 4 reward + 1 done
-CARTPOLE_VALU_PER_ENV_STEP = 196   # vector instructions in the step loop of the kernel ISA (35 of them quarter-rate integer multiplies)
+CARTPOLE_VALU_PER_ENV_STEP = 209   # vector instructions in the step loop of the kernel ISA (35 of them quarter-rate integer multiplies)
 VALU_PEAK_TINSTR = 39.3            # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, lane-instructions per second / 1e12
 FRAME_BYTES = 84 * 84          # one new frame per env-step
 FP64_PEAK_TFLOPS = 78.6        # MI355X vector float64 (256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz)

@@ -65,9 +65,19 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
   const uint8_t* act_row = EXTERNAL_ACTIONS ? a.actions + wave_base : nullptr;
   int parity = 0;
 
-  auto one_step = [&](const Draw4& d) {
+  // External actions are fetched two chunks ahead of their use (as the Philox blocks are drawn one
+  // chunk ahead): a load issued in the step that needs it leaves its whole latency exposed, which
+  // doubled the launch (0.95 against 0.44 ms at N = 65536 x T = 1000).  Every lane loads from a
+  // valid address -- an idle lane its wavefront's first environment, a row past the end the last
+  // row -- so that the loads stay unconditional.
+  const int64_t act_lane = live ? lane : 0;
+  auto fetch_action = [&](int32_t row) -> int {
+    return EXTERNAL_ACTIONS ? (int)act_row[(int64_t)(row < a.T ? row : a.T - 1) * n + act_lane] : 0;
+  };
+
+  auto one_step = [&](const Draw4& d, const int action) {
     float move;
-    if (EXTERNAL_ACTIONS) move = pong_move_of_action(live ? (int)act_row[lane] : 0);
+    if (EXTERNAL_ACTIONS) move = pong_move_of_action(live ? action : 0);
     else move = pong_move_of_word(d.w0);
     const PongEvent ev = pong_transition_move(s, move, d.w1, d.w2, a.max_score);
     const bool done = live && ev.done;
@@ -104,7 +114,6 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
     obs_row += n * PONG_OBS;
     rew_row += n;
     done_row += n;
-    if (EXTERNAL_ACTIONS) act_row += n;
   };
 
   int32_t t = 0;
@@ -112,18 +121,46 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
     Draw4 cur[CHUNK];
 #pragma unroll
     for (int c = 0; c < CHUNK; ++c) cur[c] = philox_draw(a.seed, env, a.step0 + (uint64_t)c, 0u);
-    for (; t + CHUNK <= a.T; t += CHUNK) {
+    // one chunk: draw the next chunk's Philox blocks, take this chunk's steps with the actions in
+    // `use`, and (external actions) start the loads of the chunk after next into `fill`
+    auto chunk = [&](const int (&use)[CHUNK], int (&fill)[CHUNK]) {
       Draw4 nxt[CHUNK];
 #pragma unroll
-      for (int c = 0; c < CHUNK; ++c)
+      for (int c = 0; c < CHUNK; ++c) {
         nxt[c] = philox_draw(a.seed, env, a.step0 + (uint64_t)(t + CHUNK + c), 0u);
+        fill[c] = fetch_action(t + 2 * CHUNK + c);
+      }
 #pragma unroll
-      for (int c = 0; c < CHUNK; ++c) one_step(cur[c]);
+      for (int c = 0; c < CHUNK; ++c) one_step(cur[c], use[c]);
 #pragma unroll
       for (int c = 0; c < CHUNK; ++c) cur[c] = nxt[c];
+      t += CHUNK;
+    };
+    if (EXTERNAL_ACTIONS) {
+      // Three sets of action registers take turns (in use, loaded, being loaded), three chunks per
+      // trip, so that no set is ever copied into another: a copy would make the wavefront wait for
+      // a load it has only just issued, and with it (memory operations complete in order) for
+      // every store before that.
+      int s0[CHUNK], s1[CHUNK], s2[CHUNK];
+#pragma unroll
+      for (int c = 0; c < CHUNK; ++c) {
+        s0[c] = fetch_action(c);
+        s1[c] = fetch_action(CHUNK + c);
+      }
+      while (t + 3 * CHUNK <= a.T) {
+        chunk(s0, s2);
+        chunk(s1, s0);
+        chunk(s2, s1);
+      }
+      // at most two whole chunks are left; s0 and s1 hold their actions
+      if (t + CHUNK <= a.T) chunk(s0, s2);
+      if (t + CHUNK <= a.T) chunk(s1, s0);
+    } else {
+      int none[CHUNK] = {}, sink[CHUNK];
+      while (t + CHUNK <= a.T) chunk(none, sink);
     }
   }
-  for (; t < a.T; ++t) one_step(philox_draw(a.seed, env, a.step0 + (uint64_t)t, 0u));
+  for (; t < a.T; ++t) one_step(philox_draw(a.seed, env, a.step0 + (uint64_t)t, 0u), fetch_action(t));
 }
 
 template <bool XCD_REMAP>
