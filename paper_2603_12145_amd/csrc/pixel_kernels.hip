@@ -245,9 +245,23 @@ __global__ __launch_bounds__(256) void pixel_traj_dynamics_kernel(PongLaunch a, 
   const int64_t ic = live ? i : n - 1;
   PongLane s = pong_load(a.state, n, ic);
   LaneEpisodes le;
-  for (int32_t t = 0; t < a.T; ++t) {
+  // external actions are fetched AHEAD steps before their use (a load issued in the step that
+  // needs it leaves its whole latency exposed in this short loop); rows past the end read the last
+  constexpr int AHEAD = 8;
+  auto fetch_action = [&](int32_t row) -> int {
+    return a.actions ? (int)a.actions[(int64_t)(row < a.T ? row : a.T - 1) * n + ic] : 0;
+  };
+  int pending[AHEAD];
+#pragma unroll
+  for (int k = 0; k < AHEAD; ++k) pending[k] = fetch_action(k);
+  for (int32_t t0 = 0; t0 < a.T; t0 += AHEAD)
+#pragma unroll
+  for (int k = 0; k < AHEAD; ++k) {
+    const int32_t t = t0 + k;
+    if (t >= a.T) break;                                  // uniform
     const Draw4 d = philox_draw(a.seed, (uint32_t)ic, a.step0 + (uint64_t)t, 0u);
-    const int action = a.actions ? (int)a.actions[(int64_t)t * n + ic] : pong_action_from_word(d.w0);
+    const int action = a.actions ? pending[k] : pong_action_from_word(d.w0);
+    pending[k] = fetch_action(t + AHEAD);
     const PongEvent ev = pong_transition(s, action, d.w1, d.w2, a.max_score);
     const bool done = live && ev.done;
     le.count += done ? 1 : 0;
