@@ -56,6 +56,12 @@ int mi355env_bench_empty(void *hip_stream);
  * rollout's launch shape.  Its duration is the floor the memory system sets for that layout. */
 int mi355env_bench_trajectory_stores(void *obs_dev, void *reward_dev, void *done_dev, int64_t n, int32_t T,
                                      void *hip_stream);
+/* The same with every wavefront put to sleep for sleep x 64 cycles after each step (sleep = 0, or
+ * 8..15; else -1).  Unpaced, wavefronts drift apart over the rows of the trajectory and the memory
+ * system does worse than when they all write the same row at the rate it drains at: the best
+ * paced time, not the unpaced one, is what the memory system can do for this layout. */
+int mi355env_bench_trajectory_stores_paced(void *obs_dev, void *reward_dev, void *done_dev, int64_t n, int32_t T,
+                                           int32_t sleep, void *hip_stream);
 
 #ifdef __cplusplus
 }

@@ -30,8 +30,12 @@ __global__ __launch_bounds__(256) void fill_pages_kernel(vec16* __restrict__ dst
 
 // The stores of the fused Pong rollout and nothing else: per step every lane writes the 32-byte
 // observation of its environment (two 16-byte stores), a reward dword and a done byte into
-// obs[T][n][8], reward[T][n], done[T][n], with the rollout's workgroup-to-XCD mapping.  What this
-// takes is the floor the memory system sets for that trajectory layout.
+// obs[T][n][8], reward[T][n], done[T][n], with the rollout's workgroup-to-XCD mapping.  SLEEP > 0
+// puts the wavefront to sleep for SLEEP x 64 cycles after every step: issued as fast as they can be,
+// the stores of different wavefronts drift over many rows of the trajectory and the memory system
+// thrashes (5.6 TB/s at N = 65536); paced to the rate it drains at, all wavefronts stay on the same
+// row and it takes 6.7 TB/s.
+template <int SLEEP>
 __global__ __launch_bounds__(256) void trajectory_stores_kernel(float* __restrict__ obs, float* __restrict__ reward,
                                                                 uint8_t* __restrict__ done, int64_t n, int T) {
   const unsigned per_xcd = gridDim.x >> 3;
@@ -46,6 +50,7 @@ __global__ __launch_bounds__(256) void trajectory_stores_kernel(float* __restric
     o[1] = v;
     reward[k] = 1.0f;
     done[k] = 0;
+    if (SLEEP > 0) __builtin_amdgcn_s_sleep(SLEEP);
   }
 }
 
@@ -80,18 +85,38 @@ int mi355env_bench_fill_pages(void* dst_dev, size_t bytes, uint32_t value, void*
   return hipGetLastError() == hipSuccess ? 0 : -3;
 }
 
-// obs_dev float32[T][n][8] (16-byte aligned), reward_dev float32[T][n], done_dev uint8[T][n].
-int mi355env_bench_trajectory_stores(void* obs_dev, void* reward_dev, void* done_dev, int64_t n, int32_t T,
-                                     void* hip_stream) {
+// obs_dev float32[T][n][8] (16-byte aligned), reward_dev float32[T][n], done_dev uint8[T][n];
+// sleep: 0 (none), or 8..15 units of 64 cycles per step.
+int mi355env_bench_trajectory_stores_paced(void* obs_dev, void* reward_dev, void* done_dev, int64_t n, int32_t T,
+                                           int32_t sleep, void* hip_stream) {
   if (!obs_dev || !reward_dev || !done_dev || n <= 0 || T <= 0 || n > (int64_t(1) << 30) ||
       (reinterpret_cast<uintptr_t>(obs_dev) & 15) || (reinterpret_cast<uintptr_t>(reward_dev) & 3))
     return -1;
   unsigned blocks = (unsigned)((n + 255) / 256);
   blocks = (blocks + 7u) & ~7u;
-  hipLaunchKernelGGL(trajectory_stores_kernel, dim3(blocks), dim3(256), 0, static_cast<hipStream_t>(hip_stream),
-                     static_cast<float*>(obs_dev), static_cast<float*>(reward_dev), static_cast<uint8_t*>(done_dev),
-                     n, T);
+  const dim3 g(blocks), b(256);
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  float* o = static_cast<float*>(obs_dev);
+  float* r = static_cast<float*>(reward_dev);
+  uint8_t* d = static_cast<uint8_t*>(done_dev);
+  switch (sleep) {
+    case 0: hipLaunchKernelGGL(trajectory_stores_kernel<0>, g, b, 0, st, o, r, d, n, T); break;
+    case 8: hipLaunchKernelGGL(trajectory_stores_kernel<8>, g, b, 0, st, o, r, d, n, T); break;
+    case 9: hipLaunchKernelGGL(trajectory_stores_kernel<9>, g, b, 0, st, o, r, d, n, T); break;
+    case 10: hipLaunchKernelGGL(trajectory_stores_kernel<10>, g, b, 0, st, o, r, d, n, T); break;
+    case 11: hipLaunchKernelGGL(trajectory_stores_kernel<11>, g, b, 0, st, o, r, d, n, T); break;
+    case 12: hipLaunchKernelGGL(trajectory_stores_kernel<12>, g, b, 0, st, o, r, d, n, T); break;
+    case 13: hipLaunchKernelGGL(trajectory_stores_kernel<13>, g, b, 0, st, o, r, d, n, T); break;
+    case 14: hipLaunchKernelGGL(trajectory_stores_kernel<14>, g, b, 0, st, o, r, d, n, T); break;
+    case 15: hipLaunchKernelGGL(trajectory_stores_kernel<15>, g, b, 0, st, o, r, d, n, T); break;
+    default: return -1;
+  }
   return hipGetLastError() == hipSuccess ? 0 : -3;
+}
+
+int mi355env_bench_trajectory_stores(void* obs_dev, void* reward_dev, void* done_dev, int64_t n, int32_t T,
+                                     void* hip_stream) {
+  return mi355env_bench_trajectory_stores_paced(obs_dev, reward_dev, done_dev, n, T, 0, hip_stream);
 }
 
 // One workgroup that does nothing: the floor of what a launch costs on this stream.
