@@ -20,9 +20,15 @@ extern "C" {
  * workgroups are remapped so that each XCD owns a contiguous eighth of the environments (default 1). */
 int mi355env_tune_rollout(int threads_per_block, int xcd_remap);
 
+/* Pong rollout: steps per chunk of the main loop (the Philox blocks of a chunk are drawn while the
+ * previous chunk's steps run): 2, 4 or 8; 0 = chosen from N (default: 8 up to N = 49152, 4 below
+ * N = 61440, 2 above).  Only the full-wavefront, in-kernel-action, raw-observation loop with direct
+ * stores has the three variants; every other loop uses 4. */
+int mi355env_tune_rollout_chunk(int steps);
+
 /* Pong rollout observation stores: 0 = direct (two 16-byte stores per lane), 1 = through LDS, one
  * 4 KiB page per store instruction, wherever a 256-thread workgroup is full, 2 = chosen from N
- * (default: paged for N >= 131072). */
+ * (default: paged for N >= 73728). */
 int mi355env_tune_paged_stores(int mode);
 
 /* Wave-tile pixel renderer (env-major ring, env_rollout frames): environments per wavefront

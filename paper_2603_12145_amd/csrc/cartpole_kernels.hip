@@ -102,6 +102,9 @@ __global__ __launch_bounds__(256) void cartpole_reset_kernel(uint32_t* __restric
   if (obs) reinterpret_cast<float4*>(obs)[i] = make_float4(s.x, s.xd, s.th, s.thd);
 }
 
+// EXTERNAL_ACTIONS: one kernel per loop, so that each gets a register allocation and an instruction
+// order of its own.
+template <bool EXTERNAL_ACTIONS>
 __global__ __launch_bounds__(256) void cartpole_rollout_kernel(PongLaunch a) {
   a.step0 = launch_first_step(a.counter, a.step0, a.T, a.ticket != 0);
   const int lane = threadIdx.x & (WAVE - 1);
@@ -120,7 +123,7 @@ __global__ __launch_bounds__(256) void cartpole_rollout_kernel(PongLaunch a) {
   float4* obs_row = reinterpret_cast<float4*>(a.obs) + wave_base;
   float* rew_row = a.reward + wave_base;
   uint8_t* done_row = a.done + wave_base;
-  const uint8_t* act_row = a.actions ? a.actions + wave_base : nullptr;
+  const uint8_t* act_row = EXTERNAL_ACTIONS ? a.actions + wave_base : nullptr;
   auto one_step = [&](const int32_t t, const int action) {
     const uint64_t step = a.step0 + (uint64_t)t;
     int fin_len;
@@ -138,7 +141,7 @@ __global__ __launch_bounds__(256) void cartpole_rollout_kernel(PongLaunch a) {
     }
     obs_row += n; rew_row += n; done_row += n;
   };
-  if (!act_row) {
+  if (!EXTERNAL_ACTIONS) {
     for (int32_t t = 0; t < a.T; ++t)
       one_step(t, (int)(philox_draw(a.seed, (uint32_t)ic, a.step0 + (uint64_t)t, 0u).w0 >> 31));
   } else {
@@ -184,7 +187,8 @@ hipError_t launch_cartpole_rollout(const PongLaunch& a, hipStream_t stream) {
   blocks = (blocks + 7u) & ~7u;
   PongLaunch a2 = a;
   a2.ticket = blocks <= TICKET_MAX_BLOCKS;
-  hipLaunchKernelGGL(cartpole_rollout_kernel, dim3(blocks), dim3(256), 0, stream, a2);
+  if (a.actions) hipLaunchKernelGGL(cartpole_rollout_kernel<true>, dim3(blocks), dim3(256), 0, stream, a2);
+  else hipLaunchKernelGGL(cartpole_rollout_kernel<false>, dim3(blocks), dim3(256), 0, stream, a2);
   const hipError_t err = hipGetLastError();
   return err != hipSuccess ? err : advance_step_counter_behind(a.counter, a.T, blocks, stream);
 }

@@ -17,6 +17,7 @@ using namespace envk;
 namespace envk {
 bool set_pixel_tuning(int envs_per_wave, int streaming);
 bool set_rollout_block(int threads, int xcd_remap);
+bool set_rollout_chunk(int steps);
 bool set_paged_stores(int mode);
 bool set_traj_mode(int mode);
 bool set_plane_path(int on);
@@ -530,6 +531,9 @@ int mi355env_tune_plane_path(int on) { return set_plane_path(on) ? ENV_OK : ENV_
 int mi355env_tune_rollout(int threads_per_block, int xcd_remap) {
   return set_rollout_block(threads_per_block, xcd_remap) ? ENV_OK : ENV_E_ARG;
 }
+
+// Steps per chunk of the Pong rollout's main loop: 2, 4 or 8; 0 = chosen from N.
+int mi355env_tune_rollout_chunk(int steps) { return set_rollout_chunk(steps) ? ENV_OK : ENV_E_ARG; }
 
 // 0 = direct observation stores, 1 = paged through LDS wherever a workgroup is full, 2 = by N.
 int mi355env_tune_paged_stores(int mode) { return set_paged_stores(mode) ? ENV_OK : ENV_E_ARG; }

@@ -50,9 +50,7 @@ __global__ __launch_bounds__(256) void pong_reset_kernel(uint32_t* __restrict__ 
 // handed through LDS so that each of the two store instructions of a step covers 1 KiB of
 // contiguous memory per wavefront and the four wavefronts of a workgroup write one 4 KiB page after
 // the other, instead of two half-dense instructions per wavefront over its own 2 KiB.
-constexpr int CHUNK = 4;
-
-template <bool FULL, bool EXTERNAL_ACTIONS, bool NORMALIZE, bool PAGED>
+template <bool FULL, bool EXTERNAL_ACTIONS, bool NORMALIZE, bool PAGED, int CHUNK = 4>
 __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, LaneEpisodes& le,
                                              const int lane, const int64_t wave_base,
                                              float4* __restrict__ stage, const int64_t block_base) {
@@ -163,7 +161,18 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
   for (; t < a.T; ++t) one_step(philox_draw(a.seed, env, a.step0 + (uint64_t)t, 0u), fetch_action(t));
 }
 
-template <bool XCD_REMAP>
+// Every variant of the main loop is a kernel of its own: inlined into one kernel they share a
+// register allocation and a scheduling budget, and the order the compiler picks for one loop then
+// depends on which other loops exist (the same source ran between 0.40 and 0.44 ms at N = 65536).
+// A kernel holds its loop for full wavefronts and the general loop for a ragged last wavefront.
+enum RolloutVariant {
+  V_RAW_2, V_RAW_4, V_RAW_8,   // in-kernel actions, raw observations, direct stores; steps per chunk
+  V_PAGED,                     // ... with observation stores paged through LDS
+  V_EXTERNAL,                  // external actions, raw observations
+  V_NORMALIZED, V_NORMALIZED_EXTERNAL
+};
+
+template <int VARIANT>
 __global__ __launch_bounds__(256) void pong_rollout_kernel(PongLaunch a) {
   a.step0 = launch_first_step(a.counter, a.step0, a.T, a.ticket != 0);
   const int lane = threadIdx.x & (WAVE - 1);
@@ -174,7 +183,7 @@ __global__ __launch_bounds__(256) void pong_rollout_kernel(PongLaunch a) {
   // done is written as 8 contiguous slices, each through a single L2, instead of being
   // interleaved across all eight at workgroup granularity.
   const unsigned per_xcd = gridDim.x >> 3;
-  const unsigned logical_block = XCD_REMAP ? (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3) : blockIdx.x;
+  const unsigned logical_block = a.xcd_remap ? (blockIdx.x & 7u) * per_xcd + (blockIdx.x >> 3) : blockIdx.x;
   const int64_t wave_base = ((int64_t)logical_block * (blockDim.x >> 6) + wave_in_block) * WAVE;
   const int64_t n = a.n;
   if (wave_base >= n) return;
@@ -185,19 +194,17 @@ __global__ __launch_bounds__(256) void pong_rollout_kernel(PongLaunch a) {
   PongLane s = live ? pong_load(a.state, n, i) : pong_idle_lane();
   LaneEpisodes le;
   // paged stores need every thread of a 256-thread workgroup at the barrier of every step
-  __shared__ float4 stage[2 * 512];
+  __shared__ float4 stage[VARIANT == V_PAGED ? 2 * 512 : 1];
   const int64_t block_base = (int64_t)logical_block * blockDim.x;
-  const bool paged = a.paged && blockDim.x == 256 && block_base + 256 <= n;      // workgroup-uniform
-  if (a.normalize) {                    // the optional form takes the general (predicated) loop
-    if (a.actions) rollout_wave<false, true, true, false>(a, s, le, lane, wave_base, stage, block_base);
-    else rollout_wave<false, false, true, false>(a, s, le, lane, wave_base, stage, block_base);
-  } else if (a.actions) {
-    if (full) rollout_wave<true, true, false, false>(a, s, le, lane, wave_base, stage, block_base);
-    else rollout_wave<false, true, false, false>(a, s, le, lane, wave_base, stage, block_base);
-  } else {
-    if (paged) rollout_wave<true, false, false, true>(a, s, le, lane, wave_base, stage, block_base);
-    else if (full) rollout_wave<true, false, false, false>(a, s, le, lane, wave_base, stage, block_base);
-    else rollout_wave<false, false, false, false>(a, s, le, lane, wave_base, stage, block_base);
+  constexpr bool EXTERNAL = VARIANT == V_EXTERNAL || VARIANT == V_NORMALIZED_EXTERNAL;
+  constexpr bool NORMALIZE = VARIANT == V_NORMALIZED || VARIANT == V_NORMALIZED_EXTERNAL;
+  if (VARIANT == V_PAGED && blockDim.x == 256 && block_base + 256 <= n) {       // workgroup-uniform
+    rollout_wave<true, false, false, true, 4>(a, s, le, lane, wave_base, stage, block_base);
+  } else if (full && !NORMALIZE) {
+    constexpr int CHUNK = VARIANT == V_RAW_2 ? 2 : VARIANT == V_RAW_8 ? 8 : 4;
+    rollout_wave<true, EXTERNAL, false, false, CHUNK>(a, s, le, lane, wave_base, stage, block_base);
+  } else {                              // ragged wavefront; the normalised form always
+    rollout_wave<false, EXTERNAL, NORMALIZE, false, 4>(a, s, le, lane, wave_base, stage, block_base);
   }
   if (live) pong_store(a.state, n, i, s);
   flush_wave_stats<false>(a.stats, le);
@@ -206,6 +213,7 @@ __global__ __launch_bounds__(256) void pong_rollout_kernel(PongLaunch a) {
 int g_rollout_block = 0;   // 0 = choose from N
 int g_paged_mode = 2;      // 0 never, 1 whenever possible, 2 = choose from N
 int g_xcd_remap = 1;
+int g_rollout_chunk = 0;   // 0 = choose from N
 
 }  // namespace
 
@@ -224,6 +232,12 @@ bool set_paged_stores(int mode) {
   return true;
 }
 
+bool set_rollout_chunk(int steps) {
+  if (steps != 0 && steps != 2 && steps != 4 && steps != 8) return false;
+  g_rollout_chunk = steps;
+  return true;
+}
+
 bool set_rollout_block(int threads, int xcd_remap) {
   if (threads != 0 && threads != 64 && threads != 128 && threads != 256) return false;
   g_rollout_block = threads;
@@ -237,14 +251,35 @@ hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream) {
   blocks = (blocks + 7u) & ~7u;   // multiple of the XCD count; surplus workgroups exit at once
   const dim3 g(blocks), b(block);
   // Paged observation stores pay a barrier and an LDS round trip per step.  With one wavefront per
-  // SIMD (N <= 65536) that latency is exposed and the direct stores are faster (0.47 vs 0.58 ms at
-  // N = 65536 x T = 1000); from two wavefronts per SIMD on, the launch is bound by the write
-  // stream and the denser pattern wins (1.86 vs 2.13 ms at N = 262144).
+  // SIMD (N <= 65536) that latency is exposed and the direct stores are faster (0.396 vs 0.487 ms at
+  // N = 65536 x T = 1000); as soon as some SIMDs hold a second wavefront the launch is bound by the
+  // write stream and the denser pattern wins (N = 81920: 0.599 vs 0.707 ms; N = 131072: 0.884 vs
+  // 0.922; N = 262144: 1.565 vs 1.719).
   PongLaunch a2 = a;
-  a2.paged = g_paged_mode == 2 ? (a.n >= 131072) : g_paged_mode;
+  a2.paged = g_paged_mode == 2 ? (a.n >= 73728) : g_paged_mode;
   a2.ticket = blocks <= TICKET_MAX_BLOCKS;
-  if (g_xcd_remap) hipLaunchKernelGGL(pong_rollout_kernel<true>, g, b, 0, stream, a2);
-  else hipLaunchKernelGGL(pong_rollout_kernel<false>, g, b, 0, stream, a2);
+  // Steps per chunk of the main loop (Philox blocks are drawn one chunk ahead).  Measured at
+  // T = 1000 with chunks of 2 / 4 / 8 steps: N = 16384: 0.324 / 0.325 / 0.302 ms; N = 49152:
+  // 0.324 / 0.327 / 0.307; N = 57344: 0.342 / 0.332 / 0.369; N = 65536: 0.383 / 0.397 / 0.417;
+  // N = 98304: 0.687 / 0.695 / 0.705.  With fewer wavefronts than SIMDs long chunks give the
+  // scheduler more independent work to cover latency with; with one wavefront per SIMD the launch
+  // runs against the write stream and short chunks spread the stores more evenly.
+  const int chunk = g_rollout_chunk ? g_rollout_chunk : (a.n <= 49152 ? 8 : a.n < 61440 ? 4 : 2);
+  a2.xcd_remap = g_xcd_remap;
+  int variant;
+  if (a.normalize) variant = a.actions ? V_NORMALIZED_EXTERNAL : V_NORMALIZED;
+  else if (a.actions) variant = V_EXTERNAL;
+  else if (a2.paged && block == 256) variant = V_PAGED;
+  else variant = chunk == 2 ? V_RAW_2 : chunk == 8 ? V_RAW_8 : V_RAW_4;
+  switch (variant) {
+    case V_RAW_2: hipLaunchKernelGGL(pong_rollout_kernel<V_RAW_2>, g, b, 0, stream, a2); break;
+    case V_RAW_4: hipLaunchKernelGGL(pong_rollout_kernel<V_RAW_4>, g, b, 0, stream, a2); break;
+    case V_RAW_8: hipLaunchKernelGGL(pong_rollout_kernel<V_RAW_8>, g, b, 0, stream, a2); break;
+    case V_PAGED: hipLaunchKernelGGL(pong_rollout_kernel<V_PAGED>, g, b, 0, stream, a2); break;
+    case V_EXTERNAL: hipLaunchKernelGGL(pong_rollout_kernel<V_EXTERNAL>, g, b, 0, stream, a2); break;
+    case V_NORMALIZED: hipLaunchKernelGGL(pong_rollout_kernel<V_NORMALIZED>, g, b, 0, stream, a2); break;
+    default: hipLaunchKernelGGL(pong_rollout_kernel<V_NORMALIZED_EXTERNAL>, g, b, 0, stream, a2); break;
+  }
   const hipError_t err = hipGetLastError();
   return err != hipSuccess ? err : advance_step_counter_behind(a.counter, a.T, blocks, stream);
 }
