@@ -28,6 +28,7 @@ struct PongLaunch {
   DeviceStats* stats;
   int32_t paged;          // set by the launcher: observation stores go through LDS, one 4 KiB page at a time
   int32_t xcd_remap;      // set by the launcher (Pong rollout): each XCD owns a contiguous eighth of the batch
+  int32_t pace;           // set by the launcher (paced loop): least time between two chunks, in 1/256 of 10 ns
   int32_t normalize;      // Pong vector obs only: 1 = scale every component at the source
   float inv_score;        // 1 / max_score in float32 (used when normalize)
 };

@@ -58,8 +58,15 @@ __device__ __forceinline__ float pong_move_of_word(uint32_t w) {
   return (w >= 0xAAAAAAABu) ? 4.0f : ((w >= 0x55555556u) ? -4.0f : 0.0f);
 }
 
-__device__ __forceinline__ PongEvent pong_transition_move(PongLane& s, const float move, uint32_t w_vx,
-                                                          uint32_t w_vy, int max_score) {
+// What one step does to paddles and ball, before any bookkeeping: s.bx, s.by, s.vx, s.vy are
+// updated (a point re-serves the ball), the moved paddles and the point flags are returned.
+struct PongFlight {
+  float pa, po;           // paddles after their move (an episode end puts them back to 97)
+  bool point_a, point_o;  // the agent / the opponent scored in this step
+  float reward;
+};
+
+__device__ __forceinline__ PongFlight pong_flight(PongLane& s, const float move, uint32_t w_vx, uint32_t w_vy) {
   // agent paddle, then opponent paddle (which looks at the ball before it moves)
   const float pa = clampf(s.pa + move, 0.0f, 194.0f);
   const float chase = clampf((s.by + 1.0f) - (s.po + 8.0f), -3.0f, 3.0f);
@@ -92,32 +99,110 @@ __device__ __forceinline__ PongEvent pong_transition_move(PongLane& s, const flo
   bx = hit_o ? 20.0f : bx;
 
   // points and re-serve (paddles stay put)
-  const bool point_a = bx < 0.0f;
-  const bool point_o = (!point_a) & (bx + 2.0f > 160.0f);
-  const bool point = point_a | point_o;
-  PongEvent ev;
-  ev.reward = point_a ? 1.0f : (point_o ? -1.0f : 0.0f);
-  const int sa = s.sa + (point_a ? 1 : 0);
-  const int so = s.so + (point_o ? 1 : 0);
-  bx = point ? 79.0f : bx;
-  by = point ? 104.0f : by;
-  vx = point ? pong_serve_vx(w_vx) : vx;
-  vy = point ? pong_serve_vy(w_vy) : vy;
+  PongFlight f;
+  f.pa = pa; f.po = po;
+  f.point_a = bx < 0.0f;
+  f.point_o = (!f.point_a) & (bx + 2.0f > 160.0f);
+  const bool point = f.point_a | f.point_o;
+  f.reward = f.point_a ? 1.0f : (f.point_o ? -1.0f : 0.0f);
+  // both operands of every select are computed first: a call inside the conditional operator is
+  // a branch to the compiler, which it may or may not turn back into a select
+  const float serve_vx = pong_serve_vx(w_vx), serve_vy = pong_serve_vy(w_vy);
+  s.bx = point ? 79.0f : bx;
+  s.by = point ? 104.0f : by;
+  s.vx = point ? serve_vx : vx;
+  s.vy = point ? serve_vy : vy;
+  return f;
+}
 
+__device__ __forceinline__ PongEvent pong_transition_move(PongLane& s, const float move, uint32_t w_vx,
+                                                          uint32_t w_vy, int max_score) {
+  const PongFlight f = pong_flight(s, move, w_vx, w_vy);
+  PongEvent ev;
+  ev.reward = f.reward;
+  const int sa = s.sa + (f.point_a ? 1 : 0);
+  const int so = s.so + (f.point_o ? 1 : 0);
   // episode bookkeeping and auto-reset
-  const int ep_ret = s.ep_ret + (point_a ? 1 : 0) - (point_o ? 1 : 0);
+  const int ep_ret = s.ep_ret + (f.point_a ? 1 : 0) - (f.point_o ? 1 : 0);
   const int ep_len = s.ep_len + 1;
   ev.done = (sa == max_score) | (so == max_score);
   ev.fin_ret = ep_ret;
   ev.fin_len = ep_len;
-  s.bx = bx; s.by = by; s.vx = vx; s.vy = vy;
-  s.pa = ev.done ? 97.0f : pa;
-  s.po = ev.done ? 97.0f : po;
+  s.pa = ev.done ? 97.0f : f.pa;
+  s.po = ev.done ? 97.0f : f.po;
   s.sa = ev.done ? 0 : sa;
   s.so = ev.done ? 0 : so;
   s.ep_ret = ev.done ? 0 : ep_ret;
   s.ep_len = ev.done ? 0 : ep_len;
   return ev;
+}
+
+// Episode bookkeeping of one lane for the length of a launch, kept in a form that costs three
+// vector instructions per step instead of fourteen (return so far, length so far, and the five
+// accumulators of the episode statistics).  R counts points (agent minus opponent) and is never
+// put back to zero; R0 is its value when the lane's last episode ended, so the return so far is
+// R - R0; the length so far after the launch's k-th step is k + len0.  What an episode's end adds to
+// the statistics is taken from these later, at a flush (see pong_books_flush): its return is
+// R0 - R0_seen, and the lengths of all episodes a lane finished in a launch add up to
+// (length at the start) + (steps of the launch) - (length at the end), which needs no per-step work.
+// A flush can tell episode ends apart only if at most one happened in the lane since the last
+// flush.  An episode ends on a point, every point re-serves the ball from the centre at |vx| = 3,
+// and from there it needs 27 steps to reach either edge: whatever state a lane was given, two
+// episode ends are at least 27 steps apart, so a flush every 8 steps or fewer misses none.
+// Unsigned arithmetic: differences are exact modulo 2^32.
+struct PongBooks {
+  uint32_t R, R0, R0_seen, len0;
+  unsigned long long ended;   // wave-uniform: the lanes in which an episode ended since the last flush
+};
+
+__device__ __forceinline__ PongBooks pong_books_open(const PongLane& s) {
+  return PongBooks{(uint32_t)s.ep_ret, 0u, 0u, (uint32_t)s.ep_len, 0ull};
+}
+
+// Step number `steps_taken` (1-based) of the launch.  s.ep_ret and s.ep_len are not maintained;
+// pong_books_close puts them back.  Returns the step's reward and done flag.
+__device__ __forceinline__ PongFlight pong_transition_booked(PongLane& s, PongBooks& b, const float move,
+                                                             uint32_t w_vx, uint32_t w_vy, int max_score,
+                                                             uint32_t steps_taken, bool& done) {
+  const PongFlight f = pong_flight(s, move, w_vx, w_vy);
+  const int sa = s.sa + (f.point_a ? 1 : 0);
+  const int so = s.so + (f.point_o ? 1 : 0);
+  b.R += f.point_a ? 1u : 0u;
+  b.R -= f.point_o ? 1u : 0u;
+  done = (sa == max_score) | (so == max_score);
+  b.R0 = done ? b.R : b.R0;
+  b.len0 = done ? 0u - steps_taken : b.len0;
+  b.ended |= __ballot(done);
+  s.pa = done ? 97.0f : f.pa;
+  s.po = done ? 97.0f : f.po;
+  s.sa = done ? 0 : sa;
+  s.so = done ? 0 : so;
+  return f;
+}
+
+// Wave-uniform branch; all lanes of the wavefront call it.  `counts` = the lane owns an environment.
+template <class Episodes>
+__device__ __forceinline__ void pong_books_flush(PongBooks& b, Episodes& le, bool counts) {
+  if (b.ended == 0ull) return;
+  if (__builtin_amdgcn_inverse_ballot_w64(b.ended) && counts) {   // the mask itself becomes the lanes' predicate
+    const int fin_ret = (int)(b.R0 - b.R0_seen);
+    le.count += 1;
+    le.ret_sum_i += fin_ret;
+    le.min_key = min(le.min_key, fin_ret);
+    le.max_key = max(le.max_key, fin_ret);
+    b.R0_seen = b.R0;
+  }
+  b.ended = 0ull;
+}
+
+// After `steps` steps: restores s.ep_ret / s.ep_len and adds the finished episodes' lengths.
+template <class Episodes>
+__device__ __forceinline__ void pong_books_close(PongLane& s, const PongBooks& b, Episodes& le, uint32_t steps,
+                                                 bool counts) {
+  const uint32_t len_end = steps + b.len0;
+  le.length_sum += counts ? (int)((uint32_t)s.ep_len + steps - len_end) : 0;
+  s.ep_ret = (int)(b.R - b.R0);
+  s.ep_len = (int)len_end;
 }
 
 __device__ __forceinline__ PongEvent pong_transition(PongLane& s, int action, uint32_t w_vx,

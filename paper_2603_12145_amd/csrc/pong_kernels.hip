@@ -50,7 +50,7 @@ __global__ __launch_bounds__(256) void pong_reset_kernel(uint32_t* __restrict__ 
 // handed through LDS so that each of the two store instructions of a step covers 1 KiB of
 // contiguous memory per wavefront and the four wavefronts of a workgroup write one 4 KiB page after
 // the other, instead of two half-dense instructions per wavefront over its own 2 KiB.
-template <bool FULL, bool EXTERNAL_ACTIONS, bool NORMALIZE, bool PAGED, int CHUNK = 4>
+template <bool FULL, bool EXTERNAL_ACTIONS, bool NORMALIZE, bool PAGED, int CHUNK = 4, bool LEAN = false, bool PACED = false>
 __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, LaneEpisodes& le,
                                              const int lane, const int64_t wave_base,
                                              float4* __restrict__ stage, const int64_t block_base) {
@@ -62,6 +62,7 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
   uint8_t* done_row = a.done + wave_base;
   const uint8_t* act_row = EXTERNAL_ACTIONS ? a.actions + wave_base : nullptr;
   int parity = 0;
+  const uint32_t obs_off = (uint32_t)lane * (PONG_OBS * 4u), rew_off = (uint32_t)lane * 4u, done_off = (uint32_t)lane;
 
   // External actions are fetched two chunks ahead of their use (as the Philox blocks are drawn one
   // chunk ahead): a load issued in the step that needs it leaves its whole latency exposed, which
@@ -73,18 +74,32 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
     return EXTERNAL_ACTIONS ? (int)act_row[(int64_t)(row < a.T ? row : a.T - 1) * n + act_lane] : 0;
   };
 
-  auto one_step = [&](const Draw4& d, const int action) {
+  // Episode bookkeeping.  Plain: every step adds to the lane's statistics with selects (no branch:
+  // the steps of a chunk stay one basic block).  LEAN: an episode's end only leaves a mark in a
+  // step and is added to the statistics at the next flush, once per chunk; eight vector
+  // instructions fewer per step, which pays where the launch is bound by instruction issue.
+  PongBooks books = pong_books_open(s);
+
+  auto one_step = [&](const Draw4& d, const int action, const uint32_t steps_taken) {
     float move;
     if (EXTERNAL_ACTIONS) move = pong_move_of_action(live ? action : 0);
     else move = pong_move_of_word(d.w0);
-    const PongEvent ev = pong_transition_move(s, move, d.w1, d.w2, a.max_score);
-    const bool done = live && ev.done;
-    // selects, not a branch: the loop body stays one basic block
-    le.count += done ? 1 : 0;
-    le.length_sum += done ? ev.fin_len : 0;
-    le.ret_sum_i += done ? ev.fin_ret : 0;
-    le.min_key = done ? min(le.min_key, ev.fin_ret) : le.min_key;
-    le.max_key = done ? max(le.max_key, ev.fin_ret) : le.max_key;
+    float reward;
+    bool done;
+    if constexpr (LEAN) {
+      bool ended;
+      reward = pong_transition_booked(s, books, move, d.w1, d.w2, a.max_score, steps_taken, ended).reward;
+      done = live && ended;
+    } else {
+      const PongEvent ev = pong_transition_move(s, move, d.w1, d.w2, a.max_score);
+      reward = ev.reward;
+      done = live && ev.done;
+      le.count += done ? 1 : 0;
+      le.length_sum += done ? ev.fin_len : 0;
+      le.ret_sum_i += done ? ev.fin_ret : 0;
+      le.min_key = done ? min(le.min_key, ev.fin_ret) : le.min_key;
+      le.max_key = done ? max(le.max_key, ev.fin_ret) : le.max_key;
+    }
     float4 lo, hi;
     pong_observe<NORMALIZE>(s, a.inv_score, lo, hi);
     if (PAGED) {
@@ -100,21 +115,26 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
       o[threadIdx.x] = p0;
       o[256 + threadIdx.x] = p1;
       parity ^= 1;
-      rew_row[lane] = ev.reward;
+      rew_row[lane] = reward;
       done_row[lane] = done ? 1 : 0;
     } else if (live) {
-      float4* o = reinterpret_cast<float4*>(obs_row + lane * PONG_OBS);
+      float4* o = reinterpret_cast<float4*>(reinterpret_cast<char*>(obs_row) + obs_off);
       o[0] = lo;
       o[1] = hi;
-      rew_row[lane] = ev.reward;
-      done_row[lane] = done ? 1 : 0;
+      *reinterpret_cast<float*>(reinterpret_cast<char*>(rew_row) + rew_off) = reward;
+      done_row[done_off] = done ? 1 : 0;
     }
     obs_row += n * PONG_OBS;
     rew_row += n;
     done_row += n;
   };
 
+  // PACED: the chunks of a wavefront start no closer together than a.pace (in 1/256 of a tick of
+  // the 100 MHz constant clock)
+  const uint32_t period = PACED ? (uint32_t)a.pace : 0u;
+  uint32_t slot = PACED ? ((uint32_t)__builtin_amdgcn_s_memrealtime() << 8) : 0u;
   int32_t t = 0;
+  static_assert(CHUNK <= 8, "a lane may end at most one episode between two flushes");
   if (a.T >= CHUNK) {
     Draw4 cur[CHUNK];
 #pragma unroll
@@ -122,6 +142,20 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
     // one chunk: draw the next chunk's Philox blocks, take this chunk's steps with the actions in
     // `use`, and (external actions) start the loads of the chunk after next into `fill`
     auto chunk = [&](const int (&use)[CHUNK], int (&fill)[CHUNK]) {
+      // the previous chunk's episode ends, here rather than behind its steps: the branch then sits
+      // where the loop's own branch already ends the basic block, and draws and steps stay together
+      if constexpr (LEAN) pong_books_flush(books, le, live);
+      if constexpr (PACED) {
+        // wave-uniform and scalar throughout (32-bit clock arithmetic: the differences are small,
+        // so wrap-around is harmless); ends: the clock advances, and the looks at it are capped
+        uint32_t now = (uint32_t)__builtin_amdgcn_s_memrealtime() << 8;
+        for (int look = 0; look < 64 && (int32_t)(now - slot) < 0; ++look) {
+          __builtin_amdgcn_s_sleep(1);
+          now = (uint32_t)__builtin_amdgcn_s_memrealtime() << 8;
+        }
+        // a late wavefront does not catch up in a burst
+        slot = ((int32_t)(now - slot) > (int32_t)period ? now : slot) + period;
+      }
       Draw4 nxt[CHUNK];
 #pragma unroll
       for (int c = 0; c < CHUNK; ++c) {
@@ -129,7 +163,7 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
         fill[c] = fetch_action(t + 2 * CHUNK + c);
       }
 #pragma unroll
-      for (int c = 0; c < CHUNK; ++c) one_step(cur[c], use[c]);
+      for (int c = 0; c < CHUNK; ++c) one_step(cur[c], use[c], (uint32_t)(t + c + 1));
 #pragma unroll
       for (int c = 0; c < CHUNK; ++c) cur[c] = nxt[c];
       t += CHUNK;
@@ -158,7 +192,12 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
       while (t + CHUNK <= a.T) chunk(none, sink);
     }
   }
-  for (; t < a.T; ++t) one_step(philox_draw(a.seed, env, a.step0 + (uint64_t)t, 0u), fetch_action(t));
+  if constexpr (LEAN) pong_books_flush(books, le, live);
+  for (; t < a.T; ++t) {
+    one_step(philox_draw(a.seed, env, a.step0 + (uint64_t)t, 0u), fetch_action(t), (uint32_t)(t + 1));
+    if constexpr (LEAN) pong_books_flush(books, le, live);
+  }
+  if constexpr (LEAN) pong_books_close(s, books, le, (uint32_t)a.T, live);
 }
 
 // Every variant of the main loop is a kernel of its own: inlined into one kernel they share a
@@ -167,6 +206,7 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
 // A kernel holds its loop for full wavefronts and the general loop for a ragged last wavefront.
 enum RolloutVariant {
   V_RAW_2, V_RAW_4, V_RAW_8,   // in-kernel actions, raw observations, direct stores; steps per chunk
+  V_PACED,                     // ... two steps per chunk, lean bookkeeping, chunks keep to a clock
   V_PAGED,                     // ... with observation stores paged through LDS
   V_EXTERNAL,                  // external actions, raw observations
   V_NORMALIZED, V_NORMALIZED_EXTERNAL
@@ -201,8 +241,9 @@ __global__ __launch_bounds__(256) void pong_rollout_kernel(PongLaunch a) {
   if (VARIANT == V_PAGED && blockDim.x == 256 && block_base + 256 <= n) {       // workgroup-uniform
     rollout_wave<true, false, false, true, 4>(a, s, le, lane, wave_base, stage, block_base);
   } else if (full && !NORMALIZE) {
-    constexpr int CHUNK = VARIANT == V_RAW_2 ? 2 : VARIANT == V_RAW_8 ? 8 : 4;
-    rollout_wave<true, EXTERNAL, false, false, CHUNK>(a, s, le, lane, wave_base, stage, block_base);
+    constexpr int CHUNK = (VARIANT == V_RAW_2 || VARIANT == V_PACED) ? 2 : VARIANT == V_RAW_8 ? 8 : 4;
+    constexpr bool PACED = VARIANT == V_PACED;
+    rollout_wave<true, EXTERNAL, false, false, CHUNK, PACED, PACED>(a, s, le, lane, wave_base, stage, block_base);
   } else {                              // ragged wavefront; the normalised form always
     rollout_wave<false, EXTERNAL, NORMALIZE, false, 4>(a, s, le, lane, wave_base, stage, block_base);
   }
@@ -214,6 +255,7 @@ int g_rollout_block = 0;   // 0 = choose from N
 int g_paged_mode = 2;      // 0 never, 1 whenever possible, 2 = choose from N
 int g_xcd_remap = 1;
 int g_rollout_chunk = 0;   // 0 = choose from N
+int g_rollout_pace = 0;    // GB/s the paced variant keeps the write stream to; 0 = choose from N, -1 = never paced
 
 }  // namespace
 
@@ -238,6 +280,12 @@ bool set_rollout_chunk(int steps) {
   return true;
 }
 
+bool set_rollout_pace(int gb_per_s) {
+  if (gb_per_s < -1 || gb_per_s > 8000) return false;
+  g_rollout_pace = gb_per_s;
+  return true;
+}
+
 bool set_rollout_block(int threads, int xcd_remap) {
   if (threads != 0 && threads != 64 && threads != 128 && threads != 256) return false;
   g_rollout_block = threads;
@@ -250,31 +298,48 @@ hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream) {
   unsigned blocks = (unsigned)((a.n + block - 1) / block);
   blocks = (blocks + 7u) & ~7u;   // multiple of the XCD count; surplus workgroups exit at once
   const dim3 g(blocks), b(block);
-  // Paged observation stores pay a barrier and an LDS round trip per step.  With one wavefront per
-  // SIMD (N <= 65536) that latency is exposed and the direct stores are faster (0.396 vs 0.487 ms at
-  // N = 65536 x T = 1000); as soon as some SIMDs hold a second wavefront the launch is bound by the
-  // write stream and the denser pattern wins (N = 81920: 0.599 vs 0.707 ms; N = 131072: 0.884 vs
-  // 0.922; N = 262144: 1.565 vs 1.719).
   PongLaunch a2 = a;
-  a2.paged = g_paged_mode == 2 ? (a.n >= 73728) : g_paged_mode;
   a2.ticket = blocks <= TICKET_MAX_BLOCKS;
-  // Steps per chunk of the main loop (Philox blocks are drawn one chunk ahead).  Measured at
-  // T = 1000 with chunks of 2 / 4 / 8 steps: N = 16384: 0.324 / 0.325 / 0.302 ms; N = 49152:
-  // 0.324 / 0.327 / 0.307; N = 57344: 0.342 / 0.332 / 0.369; N = 65536: 0.383 / 0.397 / 0.417;
-  // N = 98304: 0.687 / 0.695 / 0.705.  With fewer wavefronts than SIMDs long chunks give the
-  // scheduler more independent work to cover latency with; with one wavefront per SIMD the launch
-  // runs against the write stream and short chunks spread the stores more evenly.
-  const int chunk = g_rollout_chunk ? g_rollout_chunk : (a.n <= 49152 ? 8 : a.n < 61440 ? 4 : 2);
   a2.xcd_remap = g_xcd_remap;
+  // Which loop runs the in-kernel-action, raw-observation rollout (ms per launch at T = 1000, one
+  // box, same process):
+  //  * N <= 53248 (fewer wavefronts than SIMDs, latency bound): 8 steps per chunk -- long chunks
+  //    give the scheduler more independent work to cover latency with (N = 16384: 0.337 / 0.323 /
+  //    0.309 with 2 / 4 / 8 steps).
+  //  * up to N = 61440: 2 steps per chunk (N = 57344: 0.337 / 0.410 / 0.419).  A wavefront takes a
+  //    step every 337 ns here, and the memory system still keeps up with N x 37 B per 337 ns.
+  //  * N = 61440 ... 262144: above that it does not keep up, stores queue, the wavefronts drift
+  //    over many rows of the trajectory arrays and the write stream drops from 6.4 to 5.4 TB/s
+  //    (N = 65536: 0.432 ms).  The paced loop holds every wavefront to one chunk per
+  //    (rows x N x 37 B / rate) of the constant 100 MHz clock, a rate just under what the memory
+  //    system drains: N = 65536: 0.386 ms at 6.6 TB/s; N = 81920: 0.519 (unpaced 0.730, paged
+  //    0.605); N = 131072: 0.824 (1.009, 0.958); N = 262144: 1.648 (2.090, 1.858) at 6.0 TB/s.
+  //    Asking for more than the memory system drains drops the launch back to the unpaced time
+  //    (N = 131072: 1.07 at 6.4 TB/s), hence the margin.
+  //  * above N = 262144 the wavefronts are not all resident at once and a clock cannot align them:
+  //    observation stores paged through LDS (N = 2^20: 7.4 ms per 1000 steps against 8.6 direct).
+  //    Paged stores pay a barrier and an LDS round trip per step, which is exposed latency with
+  //    one wavefront per SIMD (N = 65536: 0.484 ms).
+  int rate = g_rollout_pace;
+  if (rate == 0) rate = a.n < 61440 || a.n > 262144 ? -1 : a.n <= 65536 ? 6600 : 6000;
+  a2.paged = g_paged_mode == 2 ? (a.n >= 73728 && rate <= 0) : g_paged_mode;
+  const int chunk = g_rollout_chunk ? g_rollout_chunk : (a.n <= 53248 ? 8 : 2);
   int variant;
   if (a.normalize) variant = a.actions ? V_NORMALIZED_EXTERNAL : V_NORMALIZED;
   else if (a.actions) variant = V_EXTERNAL;
   else if (a2.paged && block == 256) variant = V_PAGED;
+  else if (rate > 0) variant = V_PACED;
   else variant = chunk == 2 ? V_RAW_2 : chunk == 8 ? V_RAW_8 : V_RAW_4;
+  // time per chunk of two rows, in 1/256 of a 10 ns tick
+  if (variant == V_PACED) {
+    const double q = 2.0 * (double)a.n * 37.0 / ((double)rate * 1e9) * 1e8 * 256.0;
+    a2.pace = q < 1073741824.0 ? (int32_t)q : 1073741824;    // 32-bit clock arithmetic in the kernel
+  }
   switch (variant) {
     case V_RAW_2: hipLaunchKernelGGL(pong_rollout_kernel<V_RAW_2>, g, b, 0, stream, a2); break;
     case V_RAW_4: hipLaunchKernelGGL(pong_rollout_kernel<V_RAW_4>, g, b, 0, stream, a2); break;
     case V_RAW_8: hipLaunchKernelGGL(pong_rollout_kernel<V_RAW_8>, g, b, 0, stream, a2); break;
+    case V_PACED: hipLaunchKernelGGL(pong_rollout_kernel<V_PACED>, g, b, 0, stream, a2); break;
     case V_PAGED: hipLaunchKernelGGL(pong_rollout_kernel<V_PAGED>, g, b, 0, stream, a2); break;
     case V_EXTERNAL: hipLaunchKernelGGL(pong_rollout_kernel<V_EXTERNAL>, g, b, 0, stream, a2); break;
     case V_NORMALIZED: hipLaunchKernelGGL(pong_rollout_kernel<V_NORMALIZED>, g, b, 0, stream, a2); break;

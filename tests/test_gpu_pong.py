@@ -141,6 +141,52 @@ def test_set_state_from_oracle_state_then_step():
     assert_bit_equal(done.cpu().numpy(), od, "done after set_state")
 
 
+@pytest.mark.parametrize("pace", [-1, 6600])
+@pytest.mark.parametrize("T,external", [(1, False), (5, False), (64, False), (203, False), (203, True)])
+def test_states_outside_the_games_own_reach(T, external, pace):
+    # States a game never produces, planted in the oracle's records and handed to the GPU: a ball
+    # far faster than a serve, outside the field, scores one short of the end, and a return / length
+    # so far that do not match the scores.  The episode bookkeeping (return and length of every
+    # finished episode, statistics, the state blob) must still agree with the oracle exactly.
+    n, seed, max_score = 200, 31, 2
+    p = orc.Pong(n, seed, max_score=max_score); p.reset(); p.rollout(17)
+    e = p.envs()
+    rng = np.random.default_rng(5)
+    e["vx"][:] = rng.choice(np.array([-90.0, -60.0, -3.0, 3.0, 7.5, 60.0, 200.0], np.float32), n)
+    e["bx"][::7] = -40.0
+    e["bx"][3::7] = 400.0
+    e["sa"][:] = rng.integers(0, max_score, n)
+    e["so"][:] = rng.integers(0, max_score, n)
+    e["ep_ret"][:] = rng.integers(-1000, 1000, n)
+    e["ep_len"][:] = rng.integers(0, 1 << 20, n)
+    blob = pong_blob(p.step_count, pong_state_fields(e))
+    actions = inputs.pong_actions(T, n, 8) if external else None
+    h = b.env_create(b.ENV_PONG, n, seed, {"max_score": max_score})
+    b.env_set_state(h, blob)
+    obs, rew, done = bufs(T, n)
+    assert b.lib().mi355env_tune_rollout_pace(pace) == 0
+    try:
+        b.env_rollout(h, T, None if actions is None else torch.from_numpy(actions).to(DEV), obs, rew, done)
+        torch.cuda.synchronize()
+    finally:
+        assert b.lib().mi355env_tune_rollout_pace(0) == 0
+    stats, state = b.env_stats(h), b.env_get_state(h)
+    b.env_destroy(h)
+    oo, orr, od = p.rollout(T, actions=actions)
+    assert_bit_equal(obs.cpu().numpy(), oo, "obs")
+    assert_bit_equal(rew.cpu().numpy(), orr, "reward")
+    assert_bit_equal(done.cpu().numpy(), od, "done")
+    assert od.sum() > 0 or T < 5
+    want = p.stats()
+    for k in ("episodes", "length_sum", "return_sum"):
+        assert stats[k] == want[k], (k, stats[k], want[k])
+    if want["episodes"]:
+        assert stats["return_min"] == want["return_min"] and stats["return_max"] == want["return_max"]
+    step, fields = split_state(state, n, 10)
+    assert step == p.step_count
+    assert_bit_equal(fields, pong_state_fields(p.envs()), "state blob")
+
+
 def test_stats_reset_counters():
     h = b.env_create(b.ENV_PONG, 256, 3, {"max_score": 1})
     b.env_reset(h, None)
@@ -354,6 +400,26 @@ def test_both_store_paths_and_every_chunk_remainder(mode, n, T):
     finally:
         assert b.lib().mi355env_tune_paged_stores(2) == 0
     compare(g, oracle_rollout(n, 23, T, max_score=2), n, "stores mode %d n=%d T=%d" % (mode, n, T))
+
+
+@pytest.mark.parametrize("loop", ["chunk2", "chunk4", "chunk8", "paced", "paced_slow"])
+@pytest.mark.parametrize("T,max_score", [(1, 1), (19, 1), (250, 1), (1000, 2)])
+def test_every_variant_of_the_main_loop(loop, T, max_score):
+    """The full-wavefront loop exists with 2, 4 and 8 steps per chunk, and in a paced form whose
+    chunks keep to a clock and whose episode statistics are marked in the step and brought up to
+    date once per chunk; the launcher picks by N.  Each one, forced on, must give the oracle's
+    trajectories, statistics and final state; max_score = 1 ends an episode at every point.
+    "paced_slow" asks for a rate so low that every chunk really waits for its slot."""
+    n, seed = 64 * 9 + 40, 41
+    L = b.lib()
+    chunk, pace = {"chunk2": (2, -1), "chunk4": (4, -1), "chunk8": (8, -1), "paced": (0, 6600),
+                   "paced_slow": (0, 1)}[loop]
+    assert L.mi355env_tune_rollout_chunk(chunk) == 0 and L.mi355env_tune_rollout_pace(pace) == 0
+    try:
+        g = gpu_rollout(n, seed, T, max_score=max_score)
+    finally:
+        assert L.mi355env_tune_rollout_chunk(0) == 0 and L.mi355env_tune_rollout_pace(0) == 0
+    compare(g, oracle_rollout(n, seed, T, max_score=max_score), n, "%s T=%d" % (loop, T))
 
 
 @pytest.mark.parametrize("device_counter", [False, True])
