@@ -85,8 +85,8 @@ def bench_pong_rollout(b, torch, n, T, seed, steps, warmup):
     b.env_destroy(h)
     del obs, rew, done
     mean_ms, std_ms = _mean_std(ms)
-    return dict(wall=wall, mean_ms=mean_ms, std_ms=std_ms, env_steps=n * T * steps,
-                episodes=stats["episodes"])
+    return dict(wall=wall, mean_ms=mean_ms, std_ms=std_ms, min_ms=min(ms), max_ms=max(ms),
+                env_steps=n * T * steps, episodes=stats["episodes"])
 
 
 def bench_pong_per_step(b, torch, n, seed, launches):
@@ -469,7 +469,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=60)
     ap.add_argument("--n", type=int, default=65536, help="environments (headline: 65536)")
     ap.add_argument("--T", type=int, default=1000)
     ap.add_argument("--skip-extra", action="store_true")
@@ -553,11 +553,11 @@ def main():
         extra["config3_pixels_delta_updates"] = bench_pixels(b, torch, 16384, 3, 500, delta=True)
         extra["config3_pixels_ordered_stack"] = bench_pixels(b, torch, 16384, 3, 500, layout="ordered")
         for nn in (16384, 262144):
-            rr = bench_pong_rollout(b, torch, nn, T, seed, max(3, args.steps // 6), 1)
+            rr = bench_pong_rollout(b, torch, nn, T, seed, max(3, args.steps // 6), 3)
             gbs = PONG_BYTES_PER_ENV_STEP * nn * T / (rr["mean_ms"] * 1e-3) / 1e9
             extra["config2_n%d" % nn] = dict(env_steps_per_s=rr["env_steps"] / rr["wall"],
-                                             ms_per_launch=rr["mean_ms"], hbm_gbs=gbs,
-                                             frac=gbs / HBM_PEAK_GBS)
+                                             ms_per_launch=rr["mean_ms"], ms_min=rr["min_ms"],
+                                             ms_max=rr["max_ms"], hbm_gbs=gbs, frac=gbs / HBM_PEAK_GBS)
         extra["config4_body"] = bench_body(b, torch, 8192, 1000, 4, 2)
         extra["config4_body_n262144_t100"] = bench_body(b, torch, 262144, 100, 4, 2)
         extra["body_newton_n8192_t1000"] = bench_body(b, torch, 8192, 1000, 4, 2, newton=True)

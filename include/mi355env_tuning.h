@@ -30,7 +30,7 @@ int mi355env_tune_rollout_chunk(int steps);
  * chunk, episode statistics brought up to date once per chunk instead of in every step) and starts
  * a chunk no sooner than 2 * N * 37 B / gb_per_s after the previous one, by the constant 100 MHz
  * clock, whatever N; 0 = chosen from N (default: paced at 6600 GB/s for N = 61440 ... 65536, at
- * 6000 GB/s up to N = 262144, not paced elsewhere); -1 = never paced.  Results are identical. */
+ * 5800 GB/s up to N = 131072, at 5600 GB/s up to N = 262144, not paced elsewhere); -1 = never paced.  Results are identical. */
 int mi355env_tune_rollout_pace(int gb_per_s);
 
 /* Pong rollout observation stores: 0 = direct (two 16-byte stores per lane), 1 = through LDS, one

@@ -312,16 +312,20 @@ hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream) {
   //    over many rows of the trajectory arrays and the write stream drops from 6.4 to 5.4 TB/s
   //    (N = 65536: 0.432 ms).  The paced loop holds every wavefront to one chunk per
   //    (rows x N x 37 B / rate) of the constant 100 MHz clock, a rate just under what the memory
-  //    system drains: N = 65536: 0.386 ms at 6.6 TB/s; N = 81920: 0.519 (unpaced 0.730, paged
-  //    0.605); N = 131072: 0.824 (1.009, 0.958); N = 262144: 1.648 (2.090, 1.858) at 6.0 TB/s.
-  //    Asking for more than the memory system drains drops the launch back to the unpaced time
-  //    (N = 131072: 1.07 at 6.4 TB/s), hence the margin.
+  //    system drains: N = 65536: 0.380 ms at 6.6 TB/s; N = 81920: 0.536 (unpaced 0.730, paged
+  //    0.609) and N = 131072: 0.847 (1.009, 0.957) at 5.8 TB/s; N = 262144: 1.742 (2.090, 1.840)
+  //    at 5.6 TB/s.  Asking for more than the memory system drains is worse than not pacing at
+  //    all, and a launch that has fallen behind does not recover (N = 131072: 0.778 ms at
+  //    6.4 TB/s, 1.31 at 6.6; N = 262144: 1.634 at 6.0, 2.73 at 6.2; stretching the period when
+  //    chunks run late did not bring a launch back), and where the edge lies moves with the box
+  //    and with what the device did just before, hence rates 8-10 % under the edges seen.  At
+  //    N <= 65536 there is no edge: the loop's own pace (0.372 ms per 1000 steps) is the limit.
   //  * above N = 262144 the wavefronts are not all resident at once and a clock cannot align them:
   //    observation stores paged through LDS (N = 2^20: 7.4 ms per 1000 steps against 8.6 direct).
   //    Paged stores pay a barrier and an LDS round trip per step, which is exposed latency with
   //    one wavefront per SIMD (N = 65536: 0.484 ms).
   int rate = g_rollout_pace;
-  if (rate == 0) rate = a.n < 61440 || a.n > 262144 ? -1 : a.n <= 65536 ? 6600 : 6000;
+  if (rate == 0) rate = a.n < 61440 || a.n > 262144 ? -1 : a.n <= 65536 ? 6600 : a.n <= 131072 ? 5800 : 5600;
   a2.paged = g_paged_mode == 2 ? (a.n >= 73728 && rate <= 0) : g_paged_mode;
   const int chunk = g_rollout_chunk ? g_rollout_chunk : (a.n <= 53248 ? 8 : 2);
   int variant;
