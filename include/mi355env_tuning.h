@@ -23,14 +23,16 @@ int mi355env_tune_rollout(int threads_per_block, int xcd_remap);
 /* Pong rollout: steps per chunk of the main loop (the Philox blocks of a chunk are drawn while the
  * previous chunk's steps run): 2, 4 or 8; 0 = chosen from N (default: 8 up to N = 53248, 2 above).
  * Only the full-wavefront, in-kernel-action, raw-observation loop with direct stores that is not
- * paced (below) has the three variants; the paced loop uses 2, every other loop 4. */
+ * paced (below) has the three variants; the paced loop uses 2, the loops with external actions 8, every other loop 4. */
 int mi355env_tune_rollout_chunk(int steps);
 
 /* Pacing of the same loop.  gb_per_s > 0: every full wavefront runs the paced loop (two steps per
  * chunk, episode statistics brought up to date once per chunk instead of in every step) and starts
  * a chunk no sooner than 2 * N * 37 B / gb_per_s after the previous one, by the constant 100 MHz
  * clock, whatever N; 0 = chosen from N (default: paced at 6600 GB/s for N = 61440 ... 65536, at
- * 5800 GB/s up to N = 131072, at 5600 GB/s up to N = 262144, not paced elsewhere); -1 = never paced.  Results are identical. */
+ * 5800 GB/s up to N = 131072, at 5600 GB/s up to N = 262144, not paced elsewhere; with
+ * external actions paced for N = 98305 ... 262144 only, eight steps per chunk); -1 = never paced.
+ * Results are identical. */
 int mi355env_tune_rollout_pace(int gb_per_s);
 
 /* Pong rollout observation stores: 0 = direct (two 16-byte stores per lane), 1 = through LDS, one

@@ -157,16 +157,26 @@ __global__ __launch_bounds__(256) void cartpole_rollout_kernel(PongLaunch a) {
     int pending[AHEAD];
 #pragma unroll
     for (int k = 0; k < AHEAD; ++k) pending[k] = fetch_action(k);
-    for (int32_t t = 0; t < a.T; t += AHEAD) {
+    // These first loads are waited for here, once.  Otherwise the compiler's wait-count
+    // bookkeeping carries "just issued, nothing behind them" into the loop header, where it is
+    // merged with the loop's own state, and every trip then waits for everything in flight,
+    // stores included.  For the same reason the main loop has no branch inside a trip.
+#pragma unroll
+    for (int k = 0; k < AHEAD; ++k) asm volatile("" : : "v"(pending[k]));
+    asm volatile("" : : "v"(s.x), "v"(s.xd), "v"(s.th), "v"(s.thd), "v"(s.ep_len));   // the state's loads too
+    int32_t t = 0;
+    for (; t + AHEAD <= a.T; t += AHEAD) {
 #pragma unroll
       for (int k = 0; k < AHEAD; ++k) {
-        if (t + k < a.T) {                       // wave-uniform
-          const int action = live ? pending[k] : 0;
-          pending[k] = fetch_action(t + k + AHEAD);
-          one_step(t + k, action);
-        }
+        const int action = live ? pending[k] : 0;
+        pending[k] = fetch_action(t + k + AHEAD);
+        one_step(t + k, action);
       }
     }
+    // fewer than AHEAD steps are left and their actions have been fetched
+#pragma unroll
+    for (int k = 0; k < AHEAD; ++k)
+      if (t + k < a.T) one_step(t + k, live ? pending[k] : 0);     // wave-uniform
   }
   if (live) cart_store(a.state, n, i, s);
   flush_wave_stats<false>(a.stats, le);

@@ -66,7 +66,7 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
 
   // External actions are fetched two chunks ahead of their use (as the Philox blocks are drawn one
   // chunk ahead): a load issued in the step that needs it leaves its whole latency exposed, which
-  // doubled the launch (0.95 against 0.44 ms at N = 65536 x T = 1000).  Every lane loads from a
+  // doubled the launch (0.95 against 0.44 ms at N = 65536 x T = 1000; fetched ahead: 0.46).  Every lane loads from a
   // valid address -- an idle lane its wavefront's first environment, a row past the end the last
   // row -- so that the loads stay unconditional.
   const int64_t act_lane = live ? lane : 0;
@@ -134,7 +134,7 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
   const uint32_t period = PACED ? (uint32_t)a.pace : 0u;
   uint32_t slot = PACED ? ((uint32_t)__builtin_amdgcn_s_memrealtime() << 8) : 0u;
   int32_t t = 0;
-  static_assert(CHUNK <= 8, "a lane may end at most one episode between two flushes");
+  static_assert(!LEAN || CHUNK <= 8, "a lane may end at most one episode between two flushes");
   if (a.T >= CHUNK) {
     Draw4 cur[CHUNK];
 #pragma unroll
@@ -179,6 +179,12 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
         s0[c] = fetch_action(c);
         s1[c] = fetch_action(CHUNK + c);
       }
+      // These first loads are waited for here, once, before the loop.  Otherwise the compiler's
+      // wait-count bookkeeping carries "just issued, nothing behind them" into the loop header,
+      // where it is merged with the loop's own state, and every trip then begins by waiting for
+      // everything in flight, stores included (0.63 ms at N = 65536 x T = 1000).
+#pragma unroll
+      for (int c = 0; c < CHUNK; ++c) asm volatile("" : : "v"(s0[c]), "v"(s1[c]));
       while (t + 3 * CHUNK <= a.T) {
         chunk(s0, s2);
         chunk(s1, s0);
@@ -209,6 +215,7 @@ enum RolloutVariant {
   V_PACED,                     // ... two steps per chunk, lean bookkeeping, chunks keep to a clock
   V_PAGED,                     // ... with observation stores paged through LDS
   V_EXTERNAL,                  // external actions, raw observations
+  V_EXTERNAL_PACED,            // ... lean bookkeeping, chunks keep to a clock
   V_NORMALIZED, V_NORMALIZED_EXTERNAL
 };
 
@@ -236,13 +243,15 @@ __global__ __launch_bounds__(256) void pong_rollout_kernel(PongLaunch a) {
   // paged stores need every thread of a 256-thread workgroup at the barrier of every step
   __shared__ float4 stage[VARIANT == V_PAGED ? 2 * 512 : 1];
   const int64_t block_base = (int64_t)logical_block * blockDim.x;
-  constexpr bool EXTERNAL = VARIANT == V_EXTERNAL || VARIANT == V_NORMALIZED_EXTERNAL;
+  constexpr bool EXTERNAL = VARIANT == V_EXTERNAL || VARIANT == V_EXTERNAL_PACED || VARIANT == V_NORMALIZED_EXTERNAL;
   constexpr bool NORMALIZE = VARIANT == V_NORMALIZED || VARIANT == V_NORMALIZED_EXTERNAL;
   if (VARIANT == V_PAGED && blockDim.x == 256 && block_base + 256 <= n) {       // workgroup-uniform
     rollout_wave<true, false, false, true, 4>(a, s, le, lane, wave_base, stage, block_base);
   } else if (full && !NORMALIZE) {
-    constexpr int CHUNK = (VARIANT == V_RAW_2 || VARIANT == V_PACED) ? 2 : VARIANT == V_RAW_8 ? 8 : 4;
-    constexpr bool PACED = VARIANT == V_PACED;
+    // external actions: 8, so that the loads run 8 to 16 steps ahead of their use (4: 0.69 ms at
+    // N = 65536 x T = 1000, 8: 0.46 ms) -- a load queues behind the wavefront's own stores
+    constexpr int CHUNK = (VARIANT == V_RAW_2 || VARIANT == V_PACED) ? 2 : (VARIANT == V_RAW_8 || EXTERNAL) ? 8 : 4;
+    constexpr bool PACED = VARIANT == V_PACED || VARIANT == V_EXTERNAL_PACED;
     rollout_wave<true, EXTERNAL, false, false, CHUNK, PACED, PACED>(a, s, le, lane, wave_base, stage, block_base);
   } else {                              // ragged wavefront; the normalised form always
     rollout_wave<false, EXTERNAL, NORMALIZE, false, 4>(a, s, le, lane, wave_base, stage, block_base);
@@ -330,13 +339,16 @@ hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream) {
   const int chunk = g_rollout_chunk ? g_rollout_chunk : (a.n <= 53248 ? 8 : 2);
   int variant;
   if (a.normalize) variant = a.actions ? V_NORMALIZED_EXTERNAL : V_NORMALIZED;
-  else if (a.actions) variant = V_EXTERNAL;
+  // external actions: pacing pays only from two wavefronts per SIMD on (N = 131072: 1.24 against
+  // 1.37 ms, N = 262144: 2.54 against 2.80; N = 65536: 0.56 against 0.46)
+  else if (a.actions) variant = rate > 0 && (g_rollout_pace > 0 || a.n > 98304) ? V_EXTERNAL_PACED : V_EXTERNAL;
   else if (a2.paged && block == 256) variant = V_PAGED;
   else if (rate > 0) variant = V_PACED;
   else variant = chunk == 2 ? V_RAW_2 : chunk == 8 ? V_RAW_8 : V_RAW_4;
-  // time per chunk of two rows, in 1/256 of a 10 ns tick
-  if (variant == V_PACED) {
-    const double q = 2.0 * (double)a.n * 37.0 / ((double)rate * 1e9) * 1e8 * 256.0;
+  // time per chunk, in 1/256 of a 10 ns tick
+  if (variant == V_PACED || variant == V_EXTERNAL_PACED) {
+    const double rows = variant == V_PACED ? 2.0 : 8.0;
+    const double q = rows * (double)a.n * 37.0 / ((double)rate * 1e9) * 1e8 * 256.0;
     a2.pace = q < 1073741824.0 ? (int32_t)q : 1073741824;    // 32-bit clock arithmetic in the kernel
   }
   switch (variant) {
@@ -345,6 +357,7 @@ hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream) {
     case V_RAW_8: hipLaunchKernelGGL(pong_rollout_kernel<V_RAW_8>, g, b, 0, stream, a2); break;
     case V_PACED: hipLaunchKernelGGL(pong_rollout_kernel<V_PACED>, g, b, 0, stream, a2); break;
     case V_PAGED: hipLaunchKernelGGL(pong_rollout_kernel<V_PAGED>, g, b, 0, stream, a2); break;
+    case V_EXTERNAL_PACED: hipLaunchKernelGGL(pong_rollout_kernel<V_EXTERNAL_PACED>, g, b, 0, stream, a2); break;
     case V_EXTERNAL: hipLaunchKernelGGL(pong_rollout_kernel<V_EXTERNAL>, g, b, 0, stream, a2); break;
     case V_NORMALIZED: hipLaunchKernelGGL(pong_rollout_kernel<V_NORMALIZED>, g, b, 0, stream, a2); break;
     default: hipLaunchKernelGGL(pong_rollout_kernel<V_NORMALIZED_EXTERNAL>, g, b, 0, stream, a2); break;
