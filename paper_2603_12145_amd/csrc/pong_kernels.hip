@@ -50,6 +50,12 @@ __global__ __launch_bounds__(256) void pong_reset_kernel(uint32_t* __restrict__ 
 // handed through LDS so that each of the two store instructions of a step covers 1 KiB of
 // contiguous memory per wavefront and the four wavefronts of a workgroup write one 4 KiB page after
 // the other, instead of two half-dense instructions per wavefront over its own 2 KiB.
+//
+// PACED: a chunk starts no sooner than a.pace after the previous one, by the constant 100 MHz
+// clock.  Left alone, the wavefronts of a launch of 61440 environments or more issue their stores
+// faster than the memory system drains them; the stores queue, the wavefronts drift apart over
+// many rows of the trajectory arrays, and the write stream settles at 5.4 TB/s instead of 6.4.
+// LEAN: see PongBooks.
 template <bool FULL, bool EXTERNAL_ACTIONS, bool NORMALIZE, bool PAGED, int CHUNK = 4, bool LEAN = false, bool PACED = false>
 __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, LaneEpisodes& le,
                                              const int lane, const int64_t wave_base,
@@ -66,9 +72,9 @@ __device__ __forceinline__ void rollout_wave(const PongLaunch& a, PongLane& s, L
 
   // External actions are fetched two chunks ahead of their use (as the Philox blocks are drawn one
   // chunk ahead): a load issued in the step that needs it leaves its whole latency exposed, which
-  // doubled the launch (0.95 against 0.44 ms at N = 65536 x T = 1000; fetched ahead: 0.46).  Every lane loads from a
-  // valid address -- an idle lane its wavefront's first environment, a row past the end the last
-  // row -- so that the loads stay unconditional.
+  // doubled the launch (0.95 against 0.44 ms at N = 65536 x T = 1000; fetched ahead: 0.46).
+  // Every lane loads from a valid address -- an idle lane its wavefront's first environment, a row
+  // past the end the last row -- so that the loads stay unconditional.
   const int64_t act_lane = live ? lane : 0;
   auto fetch_action = [&](int32_t row) -> int {
     return EXTERNAL_ACTIONS ? (int)act_row[(int64_t)(row < a.T ? row : a.T - 1) * n + act_lane] : 0;
