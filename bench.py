@@ -347,6 +347,29 @@ def bench_cartpole(b, torch, n, T, seed, steps):
                               frac=tinstr / VALU_PEAK_TINSTR, traffic=None))
 
 
+def bench_external_actions(b, torch, n, T, steps):
+    """Fused rollouts that read their actions from a caller's buffer [T, N] (uint8) instead of
+    drawing them in the kernel: Pong and cart-pole, same shapes as the in-kernel-action lines."""
+    from paper_2603_12145_amd import inputs
+    dev = "cuda:0"
+    out = {}
+    for name, kind, dim, acts in (("pong", b.ENV_PONG, 8, inputs.pong_actions(T, n, 11)),
+                                  ("cartpole", b.ENV_CARTPOLE, 4, inputs.cartpole_actions(T, n, 12))):
+        h = b.env_create(kind, n, 2, None)
+        obs = torch.empty((T, n, dim), dtype=torch.float32, device=dev)
+        rew = torch.empty((T, n), dtype=torch.float32, device=dev)
+        done = torch.empty((T, n), dtype=torch.uint8, device=dev)
+        act = torch.from_numpy(acts).to(dev)
+        b.env_reset(h, None)
+        wall, ms = time_launches(lambda: b.env_rollout(h, T, act, obs, rew, done), steps, 20)
+        b.env_destroy(h)
+        mean_ms, _ = _mean_std(ms)
+        out[name] = dict(ms_per_launch=mean_ms, env_steps_per_s=n * T * steps / wall)
+        del obs, rew, done, act
+    out["workload"] = "env_rollout with external actions, N=%d x T=%d" % (n, T)
+    return out
+
+
 def bench_body_sweep(b, torch, steps=3):
     """Both body kernels over N (not part of the default run): one table row per size."""
     rows = []
@@ -508,6 +531,7 @@ def main():
                                  bench_policy_loop(b, torch, 65536, "mlp", 2000, 50),
                                  bench_policy_loop(b, torch, 4096, "gru", 1000, 50)],
               "cartpole": lambda: bench_cartpole(b, torch, 65536, 1000, 2, args.steps),
+              "external_actions": lambda: bench_external_actions(b, torch, 65536, 1000, args.steps),
               "store_floor": lambda: bench_store_floor(b, torch, 65536, 1000, args.steps),
               "fill": lambda: bench_fill(b, torch, 1 << 30, args.steps),
               "copy": lambda: bench_copy(b, torch, 1 << 30, args.steps)}[args.only]
@@ -562,6 +586,7 @@ def main():
         extra["config4_body_n262144_t100"] = bench_body(b, torch, 262144, 100, 4, 2)
         extra["body_newton_n8192_t1000"] = bench_body(b, torch, 8192, 1000, 4, 2, newton=True)
         extra["cartpole_n65536_t1000"] = bench_cartpole(b, torch, 65536, 1000, 2, 5)
+        extra["external_actions_n65536_t1000"] = bench_external_actions(b, torch, 65536, 1000, 5)
         extra["policy_in_loop_mlp_n4096"] = bench_policy_loop(b, torch, 4096, "mlp", 2000, 50)
         extra["policy_in_loop_gru2m_n4096"] = bench_policy_loop(b, torch, 4096, "gru", 1000, 50)
         line["extra"] = extra
