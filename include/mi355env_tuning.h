@@ -46,7 +46,8 @@ int mi355env_tune_pixels(int envs_per_wave, int streaming);
 
 /* Pixel env_rollout (frame trajectory): 0 = one launch whose wavefronts each own a few environments
  * for all T steps, 1 = a dynamics pass stages a chunk of steps and the page renderer writes the
- * chunk's frames together, 2 = chosen from N (default: chunked below N = 16384). */
+ * chunk's frames together (wherever the staging area allows: N <= 262144 and the step counter on the
+ * host), 2 = chosen from N (default: chunked except for N = 16384 ... 24575). */
 int mi355env_tune_frame_trajectory(int mode);
 
 /* Slot-major pixel env_step: 0 = wave-tile renderer, 1 = page renderer as separate launches,

@@ -284,53 +284,80 @@ __global__ __launch_bounds__(256) void pixel_traj_dynamics_kernel(PongLaunch a, 
 
 constexpr int PAGE = 4096;
 
-// One 4 KiB-aligned page of a plane: zero an LDS page, poke the lit pixels of the (at most two)
-// frames overlapping it -- 192 candidate pixels, one per thread -- store 16 bytes per thread.
-// Offsets are counted in 16-byte chunks (441 per frame, 256 per page) and fit 32 bits: the host
-// only takes this path for n * 441 < 2^31.
-__device__ __forceinline__ void render_page(const uint32_t* __restrict__ blocks, int64_t n,
-                                            uint8_t* __restrict__ plane, unsigned page_index, uint8_t* page) {
+// U consecutive 4 KiB-aligned pages of a plane: zero U LDS pages, poke the lit pixels of the (at
+// most two) frames overlapping each page -- 192 candidate pixels per page, one per thread -- store
+// 16 bytes per thread and page.  Offsets are counted in 16-byte chunks (441 per frame, 256 per
+// page) and fit 32 bits: the host only takes this path for n * 441 < 2^31.  With U > 1 the cell
+// blocks of all U pages are loaded up front and the workgroup passes two barriers for U pages
+// instead of two per page: on planes of hundreds of megabytes a workgroup's life is otherwise
+// mostly the latency of that load (frame trajectories of 262144 frames: 4.9 TB/s with U = 1).
+template <int U>
+__device__ __forceinline__ void render_pages(const uint32_t* __restrict__ blocks, int64_t n,
+                                             uint8_t* __restrict__ plane, unsigned group_index, uint8_t* pages) {
   const int tid = threadIdx.x;
   const int total = (int)n * CHUNKS;                                  // chunks in the plane
   // chunk offsets relative to the start of the plane; the first page may begin before it
   const int lead = (int)((reinterpret_cast<uintptr_t>(plane) & (PAGE - 1)) >> 4);
-  const int page_off = (int)page_index * (PAGE / 16) - lead;
-  const int lo = page_off < 0 ? 0 : page_off;
-  const int hi = page_off + PAGE / 16 < total ? page_off + PAGE / 16 : total;
-  const int f_first = (int)((unsigned)lo / (unsigned)CHUNKS);
-  const int f_last = (int)((unsigned)(hi - 1) / (unsigned)CHUNKS);     // f_first or f_first + 1
-
   // threads 0..191: (frame, rectangle) pair tid / 32, pixel tid % 32 of a 4-column x 8-row patch
-  // (a paddle covers at most 4 x 8 cells, the ball at most 3 x 2).  The cell block is loaded
-  // before the page is zeroed so that its latency overlaps the zeroing and the barrier.
+  // (a paddle covers at most 4 x 8 cells, the ball at most 3 x 2).  The cell blocks are loaded
+  // before the pages are zeroed so that their latency overlaps the zeroing and the barrier.
   const int pair = tid >> 5;
   const bool from_last = pair >= 3;
-  const bool candidate = pair < 6 && !(from_last && f_last == f_first);
-  const int f = from_last ? f_last : f_first;
-  uint32_t blk = 0;
-  if (candidate) blk = blocks[(int64_t)(from_last ? pair - 3 : pair) * n + f];
+  int page_off[U], lo[U], hi[U], f[U];
+  bool candidate[U];
+  uint32_t blk[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    page_off[u] = (int)(group_index * (unsigned)U + (unsigned)u) * (PAGE / 16) - lead;
+    lo[u] = page_off[u] < 0 ? 0 : page_off[u];
+    hi[u] = page_off[u] + PAGE / 16 < total ? page_off[u] + PAGE / 16 : total;
+    const bool any = lo[u] < hi[u];                                    // a page past the end of the plane: nothing to do
+    const int f_first = (int)((unsigned)lo[u] / (unsigned)CHUNKS);
+    const int f_last = any ? (int)((unsigned)(hi[u] - 1) / (unsigned)CHUNKS) : f_first;   // f_first or f_first + 1
+    candidate[u] = any && pair < 6 && !(from_last && f_last == f_first);
+    f[u] = from_last ? f_last : f_first;
+    blk[u] = 0;
+    if (candidate[u]) blk[u] = blocks[(int64_t)(from_last ? pair - 3 : pair) * n + f[u]];
+  }
 
-  chunk_t* page16 = reinterpret_cast<chunk_t*>(page);
-  page16[tid] = chunk_t{0, 0, 0, 0};
+  chunk_t* pages16 = reinterpret_cast<chunk_t*>(pages);
+#pragma unroll
+  for (int u = 0; u < U; ++u) pages16[u * (PAGE / 16) + tid] = chunk_t{0, 0, 0, 0};
   __syncthreads();
 
-  if (candidate) {
-    const int c_lo = blk & 0xff, c_end = (blk >> 8) & 0xff;
-    const int r_lo = (blk >> 16) & 0xff, r_end = blk >> 24;
-    const int c = c_lo + (tid & 3), r = r_lo + ((tid >> 2) & 7);
-    const int off = (f * CHUNKS - page_off) * 16 + r * FRAME_SIDE + c;   // byte offset inside the page
-    if (c < c_end && r < r_end && off >= 0 && off < PAGE) page[off] = 255;
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    if (candidate[u]) {
+      const int c_lo = blk[u] & 0xff, c_end = (blk[u] >> 8) & 0xff;
+      const int r_lo = (blk[u] >> 16) & 0xff, r_end = blk[u] >> 24;
+      const int c = c_lo + (tid & 3), r = r_lo + ((tid >> 2) & 7);
+      const int off = (f[u] * CHUNKS - page_off[u]) * 16 + r * FRAME_SIDE + c;   // byte offset inside the page
+      if (c < c_end && r < r_end && off >= 0 && off < PAGE) pages[u * PAGE + off] = 255;
+    }
   }
   __syncthreads();
 
-  const int mine = page_off + tid;
-  if (mine >= lo && mine < hi) reinterpret_cast<chunk_t*>(plane)[mine] = page16[tid];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    const int mine = page_off[u] + tid;
+    if (mine >= lo[u] && mine < hi[u]) reinterpret_cast<chunk_t*>(plane)[mine] = pages16[u * (PAGE / 16) + tid];
+  }
 }
 
+__device__ __forceinline__ void render_page(const uint32_t* __restrict__ blocks, int64_t n,
+                                            uint8_t* __restrict__ plane, unsigned page_index, uint8_t* page) {
+  render_pages<1>(blocks, n, plane, page_index, page);
+}
+
+#ifndef RENDER_U
+#define RENDER_U 4
+#endif
+// U = 1: one page per workgroup; U = RENDER_U: that many consecutive pages per workgroup
+template <int U>
 __global__ __launch_bounds__(256) void plane_render_kernel(const uint32_t* __restrict__ blocks, int64_t n,
                                                            uint8_t* __restrict__ plane) {
-  __shared__ __align__(16) uint8_t page[PAGE];
-  render_page(blocks, n, plane, blockIdx.x, page);
+  __shared__ __align__(16) uint8_t pages[U * PAGE];
+  render_pages<U>(blocks, n, plane, blockIdx.x, pages);
 }
 
 // The plane of the step that the previous launch on the stream just took, for a handle whose step
@@ -701,7 +728,7 @@ bool set_pixel_tuning(int envs_per_wave, int streaming) {
 namespace {
 
 int g_plane_path = 2;   // slot-major ring steps: 0 wave renderer, 1 page renderer without lookahead, 2 with
-int g_traj_mode = 2;    // frame trajectories: 0 single launch, 1 chunked, 2 = chosen from N
+int g_traj_mode = 2;    // frame trajectories: 0 single launch, 1 chunked wherever possible, 2 = chosen from N
 
 unsigned plane_pages(const uint8_t* plane, int64_t n) {
   const uintptr_t base = reinterpret_cast<uintptr_t>(plane);
@@ -929,7 +956,7 @@ hipError_t launch_pixel_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_
     hipError_t err = hipGetLastError();
     for (int slot = 0; slot < 4 && err == hipSuccess; ++slot) {
       uint8_t* plane = ring + (int64_t)slot * n * FRAME_BYTES;
-      hipLaunchKernelGGL(plane_render_kernel, dim3(plane_pages(plane, n)), dim3(256), 0, stream, blocks, n, plane);
+      hipLaunchKernelGGL(plane_render_kernel<1>, dim3(plane_pages(plane, n)), dim3(256), 0, stream, blocks, n, plane);
       err = hipGetLastError();
     }
     return err;
@@ -946,15 +973,16 @@ hipError_t launch_pixel_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_
 // sequential, so the launch is cut into chunks of as many steps as the staging area holds: a
 // lane-per-environment pass runs the chunk's steps and leaves 12 bytes per frame (three cell
 // blocks), then the page renderer writes the chunk's frames as one long plane.  Parallelism is then
-// steps x environments, not environments: N = 1024 x T = 256 goes from 0.36 to 3.0 TB/s, N = 4096 x
-// T = 64 from 1.4 to 4.1 TB/s.  From N = 16384 on the single-launch renderer, whose wavefronts each
-// own a few environments for all T steps, has parallelism enough and is faster (5.6 against
-// 4.6 TB/s at N = 16384 x T = 32), so it keeps those sizes.
+// steps x environments, not environments: N = 1024 x T = 256 goes from 0.36 to 3.4 TB/s, N = 4096 x
+// T = 64 from 1.4 to 4.9 TB/s.  The single-launch renderer, whose wavefronts each own a few
+// environments for all T steps, gives 5.6 TB/s at N = 16384 and 5.0-5.1 TB/s from N = 32768 on; the
+// staged path gives 5.5 and 5.6-5.7 TB/s there, so it takes every size but N = 16384 ... 24575
+// (batches beyond the staging area and handles with a device step counter take the single launch).
 hipError_t launch_pixel_rollout(const PixelLaunch& a, PixelPipe& pipe, hipStream_t stream) {
   if (!a.frames) return launch_mode<MODE_RING>(a, stream);
   const int64_t n = a.pong.n;
   // the chunks' step indices are computed on the host: not with a step counter in device memory
-  const bool chunked = !a.pong.counter && (g_traj_mode == 2 ? n < 16384 : g_traj_mode == 1);
+  const bool chunked = !a.pong.counter && (g_traj_mode == 1 || (g_traj_mode == 2 && (n < 16384 || n >= 24576)));
   if (!chunked || !pipe.traj_blocks || n > pipe.traj_cap || pipe.traj_cap >= (int64_t)4000000)
     return launch_mode<MODE_FRAMES>(a, stream);
   const int32_t steps_per_chunk = (int32_t)(pipe.traj_cap / n);
@@ -972,8 +1000,13 @@ hipError_t launch_pixel_rollout(const PixelLaunch& a, PixelPipe& pipe, hipStream
     hipError_t err = hipGetLastError();
     if (err != hipSuccess) return err;
     uint8_t* plane = a.frames + (int64_t)t0 * n * FRAME_BYTES;
-    hipLaunchKernelGGL(plane_render_kernel, dim3(plane_pages(plane, frames)), dim3(256), 0, stream,
-                       pipe.traj_blocks, frames, plane);
+    // long planes: several pages per workgroup (see render_pages)
+    const unsigned pages = plane_pages(plane, frames);
+    if (pages >= 65536u)
+      hipLaunchKernelGGL(plane_render_kernel<RENDER_U>, dim3((pages + RENDER_U - 1) / RENDER_U), dim3(256), 0, stream,
+                         pipe.traj_blocks, frames, plane);
+    else
+      hipLaunchKernelGGL(plane_render_kernel<1>, dim3(pages), dim3(256), 0, stream, pipe.traj_blocks, frames, plane);
     err = hipGetLastError();
     if (err != hipSuccess) return err;
   }

@@ -273,6 +273,44 @@ def test_frame_trajectory_rendered_in_chunks(n, T):
     assert (got[0] != got[1]).any()
 
 
+@pytest.mark.parametrize("offset", [0, 2064])
+def test_long_plane_renderer_every_frame(offset):
+    """A frame trajectory long enough (more than 65536 pages of 4 KiB) for the renderer that gives a
+    workgroup four consecutive pages, with a plane that starts off a page boundary and ends inside
+    a group of four: every frame is compared with the oracle's rendering of its own state, and the
+    bytes in front of and behind the trajectory must stay untouched."""
+    n, T, seed = 613, 67, 29
+    assert b.lib().mi355env_tune_frame_trajectory(1) == 0
+    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"max_score": 1})
+    try:
+        b.env_reset(h, None)
+        nbytes = T * n * F * F
+        raw = torch.full((offset + nbytes + 8192,), 7, dtype=torch.uint8, device=DEV)
+        frames = raw[offset:offset + nbytes].view(T, n, F, F)
+        assert frames.data_ptr() % 16 == 0
+        rew = torch.empty((T, n), dtype=torch.float32, device=DEV)
+        done = torch.empty((T, n), dtype=torch.uint8, device=DEV)
+        b.env_rollout(h, T, None, frames, rew, done)
+        torch.cuda.synchronize()
+    finally:
+        b.env_destroy(h)
+        assert b.lib().mi355env_tune_frame_trajectory(2) == 0
+    assert int(raw[:offset].min().item() if offset else 7) == 7 and int(raw[offset + nbytes:].min().item()) == 7
+    assert int(raw[offset + nbytes:].max().item()) == 7
+    p = orc.Pong(n, seed, max_score=1)
+    p.reset()
+    oobs, orew, odone = p.rollout(T, nthreads=8)
+    assert_bit_equal(rew.cpu().numpy(), orew, "reward")
+    got = frames.cpu().numpy()
+    want = np.empty_like(got)
+    for t in range(T):
+        for e in range(n):
+            o = oobs[t, e]
+            want[t, e] = orc.pong_render_one(dict(bx=float(o[0]), by=float(o[1]), vx=0.0, vy=0.0, pa=float(o[4]),
+                                                  po=float(o[5]), sa=0, so=0, ep_ret=0, ep_len=0))
+    assert_bit_equal(got, want, "frames")
+
+
 def _update_counts(h):
     import ctypes as C
     L = b.lib()
