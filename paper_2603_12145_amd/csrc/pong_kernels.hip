@@ -351,10 +351,17 @@ hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream) {
   else if (a2.paged && block == 256) variant = V_PAGED;
   else if (rate > 0) variant = V_PACED;
   else variant = chunk == 2 ? V_RAW_2 : chunk == 8 ? V_RAW_8 : V_RAW_4;
-  // time per chunk, in 1/256 of a 10 ns tick
+  // time per chunk, in 1/256 of a tick of the constant clock (100 MHz on this device; asked of the
+  // runtime rather than assumed)
   if (variant == V_PACED || variant == V_EXTERNAL_PACED) {
     const double rows = variant == V_PACED ? 2.0 : 8.0;
-    const double q = rows * (double)a.n * 37.0 / ((double)rate * 1e9) * 1e8 * 256.0;
+    int dev = 0, khz = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0) {
+      (void)hipGetLastError();
+      khz = 100000;
+    }
+    const double q = rows * (double)a.n * 37.0 / ((double)rate * 1e9) * ((double)khz * 1e3) * 256.0;
     a2.pace = q < 1073741824.0 ? (int32_t)q : 1073741824;    // 32-bit clock arithmetic in the kernel
   }
   switch (variant) {
