@@ -19,6 +19,7 @@ bool set_pixel_tuning(int envs_per_wave, int streaming);
 bool set_rollout_block(int threads, int xcd_remap);
 bool set_rollout_chunk(int steps);
 bool set_rollout_pace(int gb_per_s);
+bool set_rollout_split(int mode);
 bool set_paged_stores(int mode);
 bool set_traj_mode(int mode);
 bool set_plane_path(int on);
@@ -535,6 +536,10 @@ int mi355env_tune_rollout(int threads_per_block, int xcd_remap) {
 
 // Steps per chunk of the Pong rollout's main loop: 2, 4 or 8; 0 = chosen from N.
 int mi355env_tune_rollout_chunk(int steps) { return set_rollout_chunk(steps) ? ENV_OK : ENV_E_ARG; }
+
+// Pong rollout with a second wavefront per 64 environments drawing the Philox blocks: 0 = chosen
+// from N and T, 1 = never, 2 = whenever the launch has in-kernel actions and raw observations.
+int mi355env_tune_rollout_split(int mode) { return set_rollout_split(mode) ? ENV_OK : ENV_E_ARG; }
 
 // Pong rollout pacing: the write rate (GB/s) the paced loop holds the launch to; forces that loop
 // for any N.  0 = chosen from N, -1 = never paced.

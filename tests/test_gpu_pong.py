@@ -402,23 +402,27 @@ def test_both_store_paths_and_every_chunk_remainder(mode, n, T):
     compare(g, oracle_rollout(n, 23, T, max_score=2), n, "stores mode %d n=%d T=%d" % (mode, n, T))
 
 
-@pytest.mark.parametrize("loop", ["chunk2", "chunk4", "chunk8", "paced", "paced_slow"])
+@pytest.mark.parametrize("loop", ["chunk2", "chunk4", "chunk8", "paced", "paced_slow", "split", "unsplit"])
 @pytest.mark.parametrize("T,max_score", [(1, 1), (19, 1), (250, 1), (1000, 2)])
 def test_every_variant_of_the_main_loop(loop, T, max_score):
     """The full-wavefront loop exists with 2, 4 and 8 steps per chunk, and in a paced form whose
     chunks keep to a clock and whose episode statistics are marked in the step and brought up to
     date once per chunk; the launcher picks by N.  Each one, forced on, must give the oracle's
     trajectories, statistics and final state; max_score = 1 ends an episode at every point.
-    "paced_slow" asks for a rate so low that every chunk really waits for its slot."""
+    "paced_slow" asks for a rate so low that every chunk really waits for its slot.  "split" gives
+    every 64 environments a second wavefront that draws their Philox blocks (the default for
+    small batches and T >= 32; forced here for every T), "unsplit" is the default without it."""
     n, seed = 64 * 9 + 40, 41
     L = b.lib()
-    chunk, pace = {"chunk2": (2, -1), "chunk4": (4, -1), "chunk8": (8, -1), "paced": (0, 6600),
-                   "paced_slow": (0, 1)}[loop]
+    chunk, pace, split = {"chunk2": (2, -1, 0), "chunk4": (4, -1, 0), "chunk8": (8, -1, 0), "paced": (0, 6600, 0),
+                          "paced_slow": (0, 1, 0), "split": (0, 0, 2), "unsplit": (0, 0, 1)}[loop]
     assert L.mi355env_tune_rollout_chunk(chunk) == 0 and L.mi355env_tune_rollout_pace(pace) == 0
+    assert L.mi355env_tune_rollout_split(split) == 0
     try:
         g = gpu_rollout(n, seed, T, max_score=max_score)
     finally:
         assert L.mi355env_tune_rollout_chunk(0) == 0 and L.mi355env_tune_rollout_pace(0) == 0
+        assert L.mi355env_tune_rollout_split(0) == 0
     compare(g, oracle_rollout(n, seed, T, max_score=max_score), n, "%s T=%d" % (loop, T))
 
 
