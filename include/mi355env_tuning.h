@@ -26,7 +26,7 @@ int mi355env_tune_rollout(int threads_per_block, int xcd_remap);
  * paced (below) has the three variants; the paced loop uses 2, the loops with external actions 8, every other loop 4. */
 int mi355env_tune_rollout_chunk(int steps);
 
-/* Pong rollout, small batches: 0 = default (for N <= 32768 and T >= 32, in-kernel actions and raw
+/* Pong rollout, small batches: 0 = default (for N <= 16384 and T >= 32, in-kernel actions and raw
  * observations, every 64 environments get a second wavefront that draws their Philox blocks and
  * hands them over through LDS), 1 = never, 2 = for any N and T.  Results are identical. */
 int mi355env_tune_rollout_split(int mode);

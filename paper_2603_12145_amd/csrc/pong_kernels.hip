@@ -274,9 +274,11 @@ __global__ __launch_bounds__(256) void pong_rollout_kernel(PongLaunch a) {
 // and the stores.  Both wavefronts pass the same number of barriers (1 + ceil(T / SPLIT_STEPS));
 // the buffer the producer fills in a round is the one the consumer finished with before the
 // previous barrier.  N <= 16384 (one workgroup per CU): 0.245 against 0.307 ms per 1000 steps; up
-// to N = 32768: 0.298 against 0.311.  A second producer changes nothing: what is left is the
-// dependent chain of the transition itself (paddles, flight, hits, point, scores, episode end),
-// about 590 cycles per step for 75 instructions.
+// to N = 32768, where CUs hold two workgroups: 0.30-0.31 against 0.311, so the launcher stops at
+// 16384.  A second producer changes nothing: what is left is the dependent chain of the
+// transition itself (paddles, flight, hits, point, scores, episode end), about 590 cycles per
+// step for 75 instructions; and giving the consumer two sets of environments to take side by side
+// only serialises what idle SIMDs would do in parallel (0.44 ms).
 constexpr int SPLIT_STEPS = 8;
 
 template <bool FULL>
@@ -441,10 +443,10 @@ hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream) {
   if (rate == 0) rate = a.n < 61440 || a.n > 262144 ? -1 : a.n <= 65536 ? 6600 : a.n <= 131072 ? 5800 : 5600;
   a2.paged = g_paged_mode == 2 ? (a.n >= 73728 && rate <= 0) : g_paged_mode;
   const int chunk = g_rollout_chunk ? g_rollout_chunk : (a.n <= 53248 ? 8 : 2);
-  // two wavefronts per 64 environments: in-kernel actions, raw observations, a launch that leaves
-  // at least half of the SIMDs empty and is long enough for the hand-over to pay
+  // two wavefronts per 64 environments: in-kernel actions, raw observations, a launch of at most
+  // one workgroup per CU that is long enough for the hand-over to pay
   const bool split = !a.normalize && !a.actions && g_paged_mode != 1 && rate <= 0 && g_rollout_chunk == 0 &&
-                     (g_rollout_split == 2 || (g_rollout_split == 0 && a.n <= 32768 && a.T >= 4 * SPLIT_STEPS));
+                     (g_rollout_split == 2 || (g_rollout_split == 0 && a.n <= 16384 && a.T >= 4 * SPLIT_STEPS));
   if (split) {
     unsigned wgs = (unsigned)((a.n + WAVE - 1) / WAVE);
     wgs = (wgs + 7u) & ~7u;
