@@ -25,7 +25,7 @@ def _trajectory_buffers(T, n, obs_dim):
 
 
 def pong_case(rng, k):
-    n = int(rng.choice([1, 2, 63, 64, 65, 255, 256, 257, 1000, 4097, 20000, 70001]))
+    n = int(rng.choice([1, 2, 63, 64, 65, 255, 256, 257, 1000, 4097, 16384, 20000, 70001, 131100]))
     T = int(rng.integers(1, 400))
     seed = int(rng.integers(0, 2 ** 62))
     max_score = int(rng.choice([1, 2, 5, 21]))
@@ -62,7 +62,9 @@ def pong_case(rng, k):
     assert_bit_equal(obs.cpu().numpy(), oo, "obs")
     assert_bit_equal(rew.cpu().numpy(), orr, "reward")
     assert_bit_equal(done.cpu().numpy(), od, "done")
-    assert stats["episodes"] == p.stats()["episodes"] and stats["return_sum"] == p.stats()["return_sum"]
+    want = p.stats()
+    assert stats["episodes"] == want["episodes"] and stats["return_sum"] == want["return_sum"]
+    assert stats["length_sum"] == want["length_sum"]
     _, fields = split_state(blob, n, 10)
     assert_bit_equal(fields, pong_state_fields(p.envs()), "state")
 
@@ -127,7 +129,7 @@ def pixel_case(rng, k):
 def test_random_pong_cases():
     rng = np.random.default_rng(12345)
     try:
-        for k in range(12):
+        for k in range(18):
             pong_case(rng, k)
     finally:
         assert b.lib().mi355env_tune_paged_stores(2) == 0
