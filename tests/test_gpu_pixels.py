@@ -231,6 +231,31 @@ def test_config3_n16384_t500_final_ring(layout):
     b.env_destroy(h)
 
 
+def test_ring_steps_on_a_long_plane():
+    """From 65536 pages of 4 KiB per plane on (N >= 38044) the step's renderer gives a workgroup
+    four consecutive pages; N = 40003 ends inside such a group and off a page boundary.  Whole ring,
+    rewards, done flags and state against the oracle after 21 steps (slot 0 written six times)."""
+    n, seed, T = 40003, 13, 21
+    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"max_score": 1})
+    ring = new_ring(n, "slot_major")
+    rew = torch.empty((T, n), dtype=torch.float32, device=DEV)
+    done = torch.empty((T, n), dtype=torch.uint8, device=DEV)
+    b.env_reset(h, ring)
+    for t in range(T):
+        b.env_step(h, None, ring, rew[t], done[t])
+    torch.cuda.synchronize()
+    p = orc.Pong(n, seed, max_score=1); p.reset()
+    _, orew, odone = p.rollout(T - 4, nthreads=16, want_obs=False)
+    stack = np.zeros((n, 4, F, F), np.uint8)
+    _, orew2, odone2 = p.rollout(4, stack=stack, nthreads=16, want_obs=False)
+    assert_bit_equal(rew.cpu().numpy(), np.concatenate([orew, orew2]), "reward")
+    assert_bit_equal(done.cpu().numpy(), np.concatenate([odone, odone2]), "done")
+    assert_bit_equal(ring_as_env_major(ring, "slot_major"), stack, "ring")
+    _, fields = split_state(b.env_get_state(h), n, 10)
+    assert_bit_equal(fields, pong_state_fields(p.envs()), "state")
+    b.env_destroy(h)
+
+
 @pytest.mark.parametrize("n,T", [(70000, 9), (1000, 300)])
 def test_frame_trajectory_rendered_in_chunks(n, T):
     """env_rollout on the pixel kind stages a chunk of steps (as many as fit 262144 frames, at least
