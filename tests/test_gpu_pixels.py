@@ -298,13 +298,14 @@ def test_frame_trajectory_rendered_in_chunks(n, T):
     assert (got[0] != got[1]).any()
 
 
+@pytest.mark.parametrize("n,T", [(613, 67), (5003, 11)])
 @pytest.mark.parametrize("offset", [0, 2064])
-def test_long_plane_renderer_every_frame(offset):
-    """A frame trajectory long enough (more than 65536 pages of 4 KiB) for the renderer that gives a
-    workgroup four consecutive pages, with a plane that starts off a page boundary and ends inside
-    a group of four: every frame is compared with the oracle's rendering of its own state, and the
+def test_trajectory_renderers_every_frame(offset, n, T):
+    """Frame trajectories long enough (more than 65536 pages of 4 KiB) for the renderer that gives a
+    workgroup four consecutive pages, with planes that start off a page boundary and end inside a
+    group of four: every frame is compared with the oracle's rendering of its own state, and the
     bytes in front of and behind the trajectory must stay untouched."""
-    n, T, seed = 613, 67, 29
+    seed = 29
     assert b.lib().mi355env_tune_frame_trajectory(1) == 0
     h = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"max_score": 1})
     try:
