@@ -681,7 +681,7 @@ struct FusedStep {
   Staged now, ahead_to;         // staged step t (read), staging buffers for step t + 1 (written)
   uint8_t* plane;
   unsigned commit_blocks;       // ceil(n / 256)
-  int commit_first;             // commit workgroups before (1) or after (0) the render pages
+  unsigned commit_at;           // index of the first commit workgroup: 0 = in front of the render groups
   int ahead;
 };
 
@@ -689,14 +689,13 @@ struct FusedStep {
 template <int U>
 __global__ __launch_bounds__(256) void pixel_fused_step_kernel(FusedStep a) {
   __shared__ __align__(16) uint8_t page[U * PAGE];
-  // The commit / lookahead workgroups sit either before or after the render pages in the grid.
-  // In front their latency hides completely under the render (best for small batches, where it is
-  // a sizeable part of the step); for large batches a few hundred workgroups in front of the page
-  // stream cost more than they hide (measured), so they go last.
+  // The commit / lookahead workgroups sit in front of the render groups, where their latency hides
+  // completely under the render, or, for the batch sizes where a few hundred workgroups in front of
+  // the page stream cost more than they hide (measured, see the launcher), three quarters in.
   const unsigned pages = gridDim.x - a.commit_blocks;
-  const unsigned first_commit = a.commit_first ? 0u : pages;
+  const unsigned first_commit = a.commit_at < pages ? a.commit_at : pages;
   if (blockIdx.x < first_commit || blockIdx.x >= first_commit + a.commit_blocks) {
-    render_pages<U>(a.now.blocks, a.next.n, a.plane, a.commit_first ? blockIdx.x - a.commit_blocks : blockIdx.x, page);
+    render_pages<U>(a.now.blocks, a.next.n, a.plane, blockIdx.x < first_commit ? blockIdx.x : blockIdx.x - a.commit_blocks, page);
     return;
   }
   const int64_t n = a.next.n;
@@ -854,7 +853,11 @@ hipError_t pixel_pipe_step(PixelPipe& p, uint32_t*& state, const PixelLaunch& a,
   f.ahead_to = staged_of(p, k ^ 1);
   f.plane = a.ring + (int64_t)(a.pong.step0 & 3) * n * FRAME_BYTES;
   f.commit_blocks = commit_blocks;
-  f.commit_first = n <= 24576 ? 1 : 0;
+  // Where the commit / lookahead workgroups sit among the render groups (us per step, in front /
+  // three quarters in / behind): N = 32768: 42.0 / 37.0 / 38.0; N = 65536 (four pages per render
+  // workgroup from here on): 75.7 / 85.6 / 85.0; N = 262144: 297.5 / 309.1 / 315.8.
+  const unsigned render_pages_total = plane_pages(f.plane, n);
+  f.commit_at = (n <= 24576 || render_pages_total >= 65536u) ? 0u : render_pages_total / 4u * 3u;
   f.ahead = lookahead ? 1 : 0;
   // long planes: four pages per render workgroup (N = 131072: 187 -> 163 us per step, N = 262144:
   // 393 -> 317 us; see render_pages)
