@@ -572,6 +572,8 @@ def main():
         extra["trajectory_stores_only"] = floor
         extra["config1_per_step"] = bench_pong_per_step(b, torch, 4096, 1, 10000)
         extra["config3_pixels"] = bench_pixels(b, torch, 16384, 3, 500)
+        for nn, st in ((32768, 300), (262144, 60)):      # the same step on larger batches (context, not the target)
+            extra["pixels_n%d" % nn] = bench_pixels(b, torch, nn, 3, st)
         extra["config3_pixels_env_major"] = bench_pixels(b, torch, 16384, 3, 500, layout="env_major")
         extra["config3_pixels_device_counter"] = bench_pixels(b, torch, 16384, 3, 500, device_counter=True)
         extra["config3_pixels_delta_updates"] = bench_pixels(b, torch, 16384, 3, 500, delta=True)
