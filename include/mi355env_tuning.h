@@ -42,11 +42,12 @@ int mi355env_tune_rollout_pace(int gb_per_s);
 
 /* Pong rollout observation stores: 0 = direct (two 16-byte stores per lane), 1 = through LDS, one
  * 4 KiB page per store instruction, wherever a 256-thread workgroup is full, 2 = chosen from N
- * (default: paged for N >= 73728). */
+ * (default: paged above N = 262144, where the loop is not paced). */
 int mi355env_tune_paged_stores(int mode);
 
 /* Wave-tile pixel renderer (env-major ring, env_rollout frames): environments per wavefront
- * (4, 8, 16, 32 or 64) and streaming (non-temporal) stores (0 / 1). */
+ * (4, 8, 16, 32 or 64; 0 = default: 8 up to N = 12288, 16 above) and streaming (non-temporal)
+ * stores (0 / 1). */
 int mi355env_tune_pixels(int envs_per_wave, int streaming);
 
 /* Pixel env_rollout (frame trajectory): 0 = one launch whose wavefronts each own a few environments

@@ -721,12 +721,14 @@ __global__ __launch_bounds__(256) void pixel_fused_step_kernel(FusedStep a) {
   if (a.ahead) stage_step<false>(a.next, a.state_now, a.state_next, a.ahead_to, i);
 }
 
-int g_envs_per_wave = 16;
+int g_envs_per_wave = 0;   // 0 = chosen from N
 bool g_streaming = false;
 
 template <int MODE>
 hipError_t launch_mode(const PixelLaunch& launch, hipStream_t stream) {
-  const int epw = g_envs_per_wave;
+  // environments per wavefront: 16; 8 for small batches, which then spread over twice the SIMDs
+  // (env-major ring step at N = 8192: 16.1 against 25.7 us; N = 16384: 29.8 / 30.2)
+  const int epw = g_envs_per_wave ? g_envs_per_wave : (launch.pong.n <= 12288 ? 8 : 16);
   const int64_t waves = (launch.pong.n + epw - 1) / epw;
   const unsigned blocks = (unsigned)((waves + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK);
   const dim3 grid(blocks), block(WAVES_PER_BLOCK * WAVE);
@@ -756,8 +758,8 @@ hipError_t launch_mode(const PixelLaunch& launch, hipStream_t stream) {
 // Launch-shape knobs for measurement sweeps: environments per wavefront (4..64, power of two) and
 // whether frame stores carry the non-temporal hint.
 bool set_pixel_tuning(int envs_per_wave, int streaming) {
-  if (envs_per_wave != 4 && envs_per_wave != 8 && envs_per_wave != 16 && envs_per_wave != 32 &&
-      envs_per_wave != 64)
+  if (envs_per_wave != 0 && envs_per_wave != 4 && envs_per_wave != 8 && envs_per_wave != 16 &&
+      envs_per_wave != 32 && envs_per_wave != 64)
     return false;
   g_envs_per_wave = envs_per_wave;
   g_streaming = streaming != 0;

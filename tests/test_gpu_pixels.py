@@ -36,7 +36,7 @@ def _tune(epw, streaming=0):
 @pytest.fixture(autouse=True)
 def _default_tuning():
     yield
-    _tune(16, 0)
+    _tune(0, 0)
     assert b.lib().mi355env_tune_plane_path(2) == 0
 
 
