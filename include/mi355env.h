@@ -111,7 +111,7 @@ enum { ENV_OBS_RAW = 1, ENV_OBS_NORMALIZED = 2 };
  *           the ring slot from the counter (the default path computes the next step under the
  *           render of this one and alternates library buffers from the host, which a replayed
  *           graph cannot do); results are the same bit for bit, a step takes about a quarter
- *           longer (25 against 20 us at N = 16384). */
+ *           longer (24 against 19 us at N = 16384). */
 enum { ENV_STEP_COUNTER_HOST = 1, ENV_STEP_COUNTER_DEVICE = 2 };
 
 /* Layout of the four frames of ENV_PONG_PIXELS in obs_dev of env_reset / env_step.  The first two
