@@ -222,7 +222,8 @@ enum RolloutVariant {
   V_PAGED,                     // ... with observation stores paged through LDS
   V_EXTERNAL,                  // external actions, raw observations
   V_EXTERNAL_PACED,            // ... lean bookkeeping, chunks keep to a clock
-  V_NORMALIZED, V_NORMALIZED_EXTERNAL
+  V_NORMALIZED, V_NORMALIZED_EXTERNAL,
+  V_NORMALIZED_PACED           // normalised observations in the paced loop
 };
 
 template <int VARIANT>
@@ -250,9 +251,11 @@ __global__ __launch_bounds__(256) void pong_rollout_kernel(PongLaunch a) {
   __shared__ float4 stage[VARIANT == V_PAGED ? 2 * 512 : 1];
   const int64_t block_base = (int64_t)logical_block * blockDim.x;
   constexpr bool EXTERNAL = VARIANT == V_EXTERNAL || VARIANT == V_EXTERNAL_PACED || VARIANT == V_NORMALIZED_EXTERNAL;
-  constexpr bool NORMALIZE = VARIANT == V_NORMALIZED || VARIANT == V_NORMALIZED_EXTERNAL;
+  constexpr bool NORMALIZE = VARIANT == V_NORMALIZED || VARIANT == V_NORMALIZED_EXTERNAL || VARIANT == V_NORMALIZED_PACED;
   if (VARIANT == V_PAGED && blockDim.x == 256 && block_base + 256 <= n) {       // workgroup-uniform
     rollout_wave<true, false, false, true, 4>(a, s, le, lane, wave_base, stage, block_base);
+  } else if (full && VARIANT == V_NORMALIZED_PACED) {
+    rollout_wave<true, false, true, false, 2, true, true>(a, s, le, lane, wave_base, stage, block_base);
   } else if (full && !NORMALIZE) {
     // external actions: 8, so that the loads run 8 to 16 steps ahead of their use (4: 0.69 ms at
     // N = 65536 x T = 1000, 8: 0.46 ms) -- a load queues behind the wavefront's own stores
@@ -457,7 +460,7 @@ hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream) {
     return e != hipSuccess ? e : advance_step_counter_behind(a.counter, a.T, wgs, stream);
   }
   int variant;
-  if (a.normalize) variant = a.actions ? V_NORMALIZED_EXTERNAL : V_NORMALIZED;
+  if (a.normalize) variant = a.actions ? V_NORMALIZED_EXTERNAL : rate > 0 ? V_NORMALIZED_PACED : V_NORMALIZED;
   // external actions: pacing pays only from two wavefronts per SIMD on (N = 131072: 1.24 against
   // 1.37 ms, N = 262144: 2.54 against 2.80; N = 65536: 0.56 against 0.46)
   else if (a.actions) variant = rate > 0 && (g_rollout_pace > 0 || a.n > 98304) ? V_EXTERNAL_PACED : V_EXTERNAL;
@@ -466,8 +469,8 @@ hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream) {
   else variant = chunk == 2 ? V_RAW_2 : chunk == 8 ? V_RAW_8 : V_RAW_4;
   // time per chunk, in 1/256 of a tick of the constant clock (100 MHz on this device; asked of the
   // runtime rather than assumed)
-  if (variant == V_PACED || variant == V_EXTERNAL_PACED) {
-    const double rows = variant == V_PACED ? 2.0 : 8.0;
+  if (variant == V_PACED || variant == V_EXTERNAL_PACED || variant == V_NORMALIZED_PACED) {
+    const double rows = variant == V_EXTERNAL_PACED ? 8.0 : 2.0;
     int dev = 0, khz = 0;
     if (hipGetDevice(&dev) != hipSuccess ||
         hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0) {
@@ -486,6 +489,7 @@ hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream) {
     case V_EXTERNAL_PACED: hipLaunchKernelGGL(pong_rollout_kernel<V_EXTERNAL_PACED>, g, b, 0, stream, a2); break;
     case V_EXTERNAL: hipLaunchKernelGGL(pong_rollout_kernel<V_EXTERNAL>, g, b, 0, stream, a2); break;
     case V_NORMALIZED: hipLaunchKernelGGL(pong_rollout_kernel<V_NORMALIZED>, g, b, 0, stream, a2); break;
+    case V_NORMALIZED_PACED: hipLaunchKernelGGL(pong_rollout_kernel<V_NORMALIZED_PACED>, g, b, 0, stream, a2); break;
     default: hipLaunchKernelGGL(pong_rollout_kernel<V_NORMALIZED_EXTERNAL>, g, b, 0, stream, a2); break;
   }
   const hipError_t err = hipGetLastError();

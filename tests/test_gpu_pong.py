@@ -350,11 +350,14 @@ def test_config2_largest_sweep_size_sampled():
     assert_bit_equal(obs[T - 1, -4096:].cpu().numpy(), p.obs()[-4096:], "C2-262144 final obs tail")
 
 
-@pytest.mark.parametrize("n,external", [(64, False), (1000, True), (4100, False)])
-def test_normalised_observations_match_oracle(n, external):
+@pytest.mark.parametrize("n,external,pace", [(64, False, 0), (1000, True, 0), (4100, False, 0), (4100, False, 6600),
+                                             (1000, True, 6600)])
+def test_normalised_observations_match_oracle(n, external, pace):
     """obs_scaling = ENV_OBS_NORMALIZED: the scaling is done in the step kernel; bit-identical to the
-    oracle's normalised observation, dynamics untouched."""
+    oracle's normalised observation, dynamics untouched.  pace > 0 forces the paced loop, which
+    large batches take, on these small ones."""
     T, seed, ms = 400, 17, 3
+    assert b.lib().mi355env_tune_rollout_pace(pace) == 0
     acts = inputs.pong_actions(T, n, seed=4) if external else None
     h = b.env_create(b.ENV_PONG, n, seed, {"max_score": ms, "obs_scaling": b.ENV_OBS_NORMALIZED})
     try:
@@ -366,8 +369,10 @@ def test_normalised_observations_match_oracle(n, external):
         b.env_step(h, None if act is None else act[T - 1], obs[T - 1], rew[T - 1], done[T - 1])
         torch.cuda.synchronize()
         state = b.env_get_state(h)
+        stats = b.env_stats(h)
     finally:
         b.env_destroy(h)
+        assert b.lib().mi355env_tune_rollout_pace(0) == 0
     p = orc.Pong(n, seed, max_score=ms, normalize=True)
     o0 = p.reset()
     oo, orr, od = p.rollout(T, actions=acts, nthreads=4)
@@ -378,6 +383,8 @@ def test_normalised_observations_match_oracle(n, external):
     _, fields = split_state(state, n, 10)
     assert_bit_equal(fields, pong_state_fields(p.envs()), "state (raw units)")
     assert oo[..., 6:8].max() > 0.3                    # some score was shown, scaled
+    want = p.stats()
+    assert all(stats[k] == want[k] for k in ("episodes", "length_sum", "return_sum")), (stats, want)
 
 
 def test_normalised_observations_only_for_pong_vectors():
