@@ -471,11 +471,16 @@ hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream) {
   // runtime rather than assumed)
   if (variant == V_PACED || variant == V_EXTERNAL_PACED || variant == V_NORMALIZED_PACED) {
     const double rows = variant == V_EXTERNAL_PACED ? 8.0 : 2.0;
+    static int khz_of_device[64] = {};                       // asked once per device
     int dev = 0, khz = 0;
-    if (hipGetDevice(&dev) != hipSuccess ||
-        hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0) {
-      (void)hipGetLastError();
-      khz = 100000;
+    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); dev = -1; }
+    if (dev >= 0 && dev < 64) khz = khz_of_device[dev];
+    if (khz <= 0) {
+      if (dev < 0 || hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0) {
+        (void)hipGetLastError();
+        khz = 100000;
+      }
+      if (dev >= 0 && dev < 64) khz_of_device[dev] = khz;
     }
     const double q = rows * (double)a.n * 37.0 / ((double)rate * 1e9) * ((double)khz * 1e3) * 256.0;
     a2.pace = q < 1073741824.0 ? (int32_t)q : 1073741824;    // 32-bit clock arithmetic in the kernel

@@ -224,13 +224,13 @@ def test_graph_replay_body_policy_in_the_loop():
     assert np.abs(obs[-1] - obs[0]).max() > 1e-3
 
 
-@pytest.mark.parametrize("n,T", [(700, 8), (40000, 8), (700, 40), (5000, 40)])
+@pytest.mark.parametrize("n,T", [(700, 8), (40000, 8), (700, 40), (5000, 40), (65536, 8)])
 def test_graph_replay_of_a_fused_rollout_launch(n, T):
     """A captured env_rollout (in-kernel actions) replayed five times continues the step sequence
     exactly as the same number of direct steps does: trajectory buffers of every replay match the
     oracle.  The small grid advances the device step counter itself, the large one leaves it to the
     one-thread launch recorded behind it; T = 40 on a small batch takes the kernel with two
-    wavefronts per 64 environments."""
+    wavefronts per 64 environments, N = 65536 the paced loop."""
     K = 5
     s = torch.cuda.Stream()
     h = b.env_create(b.ENV_PONG, n, 31, dict(DEVICE_COUNTER, max_score=1), stream=s)
