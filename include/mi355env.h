@@ -11,8 +11,10 @@
  *  - Every pointer named *_dev is DEVICE memory owned by the caller (e.g. a PyTorch tensor's
  *    data_ptr()), row-major, exactly the documented shape, alive until the stream has run the call.
  *    Every pointer named *_host / host_* is HOST memory owned by the caller.
- *  - The library owns only its SoA state and the episode-statistics block (allocated by
- *    env_create, freed by env_destroy).  step / reset / rollout never allocate.
+ *  - The library owns only its SoA state, the episode-statistics block and, for ENV_PONG_PIXELS,
+ *    its staging buffers (a second state buffer, about 100 B/env of staged step results and cell
+ *    blocks, 3 MB for frame trajectories; with delta updates 60 B/env more), all allocated by
+ *    env_create and freed by env_destroy.  step / reset / rollout never allocate.
  *  - step / reset / rollout enqueue work on the handle's stream and return without waiting;
  *    stats / get_state / set_state synchronise that stream.
  *  - All functions return ENV_OK (0) or a negative error code; on error no output buffer is
