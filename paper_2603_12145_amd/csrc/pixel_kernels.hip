@@ -387,9 +387,7 @@ __device__ __forceinline__ void render_page(const uint32_t* __restrict__ blocks,
   render_pages<1>(blocks, n, plane, page_index, page);
 }
 
-#ifndef RENDER_U
-#define RENDER_U 4
-#endif
+constexpr int RENDER_U = 4;   // pages per render workgroup on long planes (2: 4.9 TB/s, 4: 5.7, 8: 5.5)
 // U = 1: one page per workgroup; U = RENDER_U: that many consecutive pages per workgroup
 template <int U>
 __global__ __launch_bounds__(256) void plane_render_kernel(const uint32_t* __restrict__ blocks, int64_t n,
