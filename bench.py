@@ -523,6 +523,10 @@ def main():
                                        bench_pixels(b, torch, 16384, 3, args.steps, layout="ordered",
                                                     device_counter=True)],
               "per_step": lambda: bench_pong_per_step(b, torch, 4096, 1, args.steps),
+              "sweep": lambda: {"n%d" % nn: bench_pong_rollout(b, torch, nn, 1000, 2, args.steps, 10)
+                                for nn in (16384, 131072, 262144)},
+              "pixels_large": lambda: [bench_pixels(b, torch, 32768, 3, args.steps),
+                                       bench_pixels(b, torch, 262144, 3, max(20, args.steps // 5))],
               "body": lambda: bench_body(b, torch, 8192, 1000, 4, args.steps),
               "body_sweep": lambda: bench_body_sweep(b, torch, args.steps),
               "body_newton": lambda: [bench_body(b, torch, 8192, 1000, 4, args.steps, newton=True),
