@@ -427,3 +427,133 @@ def test_thousand_step_rollouts_are_bounded_and_returns_have_the_expected_scale(
     # action cost alone is -200 in expectation; the forward part is small for random actions
     assert abs(ret.mean() + 200) < 15 and ret.std() < 120
     assert abs(st["return_sum"] / n - ret.mean()) < 1e-2 and se < 6
+
+
+# ------------------------------------------------------------------ reward, action words, guards
+
+def test_reward_is_mean_of_the_five_substep_velocities_minus_action_cost():
+    """Benchmark configuration: reward = forward velocity - 0.1 |a|^2, with frame skip 5.  The forward
+    term is the mean of the five post-update x velocities, which equals (x_after - x_before) / (5 h)
+    because every substep moves x by h times its new velocity; both forms are checked, the first
+    through the single-substep entry point, the second from the states alone."""
+    n = 48
+    b = Body(n, 13, np.float64); b.reset()
+    b.rollout(23, nthreads=4)                                   # legs on the ground, joints at limits
+    s0 = b.get_state()
+    acts = RNG.uniform(-1.6, 1.6, (1, n, 6))                    # some beyond the clip
+    _, rew, done = b.rollout(1, acts)
+    s1 = b.get_state()
+    assert not done.any()
+    clipped = np.clip(acts[0], -1, 1)
+    cost = 0.1 * (clipped ** 2).sum(-1)
+    # (1) from the states: x advanced by h * (sum of the five new velocities)
+    fwd_from_x = (s1[:, 0] - s0[:, 0]) / (5 * 0.01)
+    assert np.abs(rew[0] - (fwd_from_x - cost)).max() < 1e-11
+    # (2) five single substeps, averaging the post-update x velocity of each
+    last_vs_mean = 0.0
+    for e in range(n):
+        q, v = s0[e, :9].copy(), s0[e, 9:18].copy()
+        vx = []
+        for _ in range(5):
+            q, v, mask = b.substep(q, v, acts[0, e])
+            assert mask >= 0
+            vx.append(v[0])
+        want = sum(vx) / 5 - cost[e]
+        assert abs(rew[0, e] - want) <= 4 * np.spacing(abs(want)) + 1e-15
+        assert np.array_equal(q, s1[e, :9]) and np.array_equal(v, s1[e, 9:18])
+        last_vs_mean = max(last_vs_mean, abs(vx[-1] - sum(vx) / 5))
+    # the case can tell the mean from the last substep's velocity
+    assert last_vs_mean > 1e-2
+    # episode return accumulates exactly this reward
+    assert np.allclose(s1[:, 18] - s0[:, 18], rew[0], rtol=0, atol=1e-12)
+    assert np.array_equal(s1[:, 19], s0[:, 19] + 1)
+
+
+def test_action_words_stream_by_stream():
+    """Actions 0..3 are words 0..3 of the per-step block of stream 0, actions 4 and 5 words 0 and 1
+    of stream 1; a = -1 + 2 u with u = (w >> 8) * 2^-24, all in float32."""
+    from oracle import oracle as orc
+    table = [(0, 0), (0, 1), (0, 2), (0, 3), (1, 0), (1, 1)]      # action j <- (stream, word)
+    seed = 0x1234567_89abcdef
+    b = Body(1, seed, np.float32)
+    seen = set()
+    for env, step in [(0, 0), (1, 0), (0, 1), (7, 12345), (4095, 2 ** 32 + 5), (2 ** 31 + 3, 999)]:
+        a = b.draw_actions(env, step)
+        blocks = {s: orc.draw_block(seed, env, step, s) for s in (0, 1)}
+        for j, (stream, word) in enumerate(table):
+            w = blocks[stream][word]
+            u = np.float32(w >> 8) * np.float32(2.0 ** -24)
+            want = np.float32(-1.0) + np.float32(2.0) * u
+            assert a[j] == want and a.dtype == np.float32, (env, step, j)
+            seen.add(w)
+    assert len(seen) == 36                                        # no word serves two actions
+    # the rollout uses exactly these draws: external actions equal to them give the same step
+    n = 5
+    c = Body(n, 77, np.float64); c.reset()
+    d = Body(n, 77, np.float64); d.reset()
+    acts = np.array([[c.draw_actions(e, t) for e in range(n)] for t in range(3)])
+    oc, rc, _ = c.rollout(3)
+    od, rd, _ = d.rollout(3, acts)
+    assert np.array_equal(oc, od) and np.array_equal(rc, rd)
+
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float64])
+def test_a_state_outside_the_finite_range_is_counted_and_reinitialised(dtype):
+    """A state that leaves the finite range ends the step with done = 1 and reward 0, is counted as
+    non-finite (not as an episode) and is re-initialised from the reset streams at step + 1."""
+    n, start = 6, 41
+    b = Body(n, 19, dtype); b.reset()
+    b.rollout(start)
+    s = b.get_state()
+    bad = {1: (4, np.nan), 3: (11, np.inf), 4: (0, -np.inf)}      # env -> (component, value)
+    for e, (j, val) in bad.items():
+        s[e, j] = val
+    b.set_state(s)
+    b.stats(clear=True)
+    obs, rew, done = b.rollout(1)
+    st = b.stats()
+    after = b.get_state()
+    fresh = Body(n, 19, dtype); fresh.step_count = start + 1
+    fresh_obs = fresh.reset()
+    fresh_state = fresh.get_state()
+    for e in range(n):
+        if e in bad:
+            assert done[0, e] == 1 and rew[0, e] == 0
+            assert np.array_equal(after[e], fresh_state[e])       # q, v, return 0, length 0
+            assert np.array_equal(obs[0, e], fresh_obs[e])
+        else:
+            assert done[0, e] == 0 and np.isfinite(rew[0, e]) and rew[0, e] != 0
+            assert after[e, 19] == s[e, 19] + 1
+    assert st["nonfinite"] == 3 and st["episodes"] == 0 and st["length_sum"] == 0
+    assert st["return_sum"] == 0
+    assert np.isfinite(after).all() and np.isfinite(obs).all() and np.isfinite(rew).all()
+    # the other environments are untouched by their neighbours' fate
+    ref = Body(n, 19, dtype); ref.reset(); ref.rollout(start)
+    o2, r2, _ = ref.rollout(1)
+    good = [e for e in range(n) if e not in bad]
+    assert np.array_equal(o2[0, good], obs[0, good]) and np.array_equal(r2[0, good], rew[0, good])
+
+
+def test_rounding_the_state_to_the_storage_format():
+    """round_state_f32: after every step q, v, the episode return and the reward are rounded to
+    float32 (the format the state is kept in); nothing else changes."""
+    n = 40
+    a = Body(n, 23, np.float64); a.reset(); a.rollout(30, nthreads=4)
+    s = a.get_state().astype(np.float32).astype(np.float64)
+    plain = Body(n, 23, np.float64); plain.set_state(s); plain.step_count = 30
+    rounded = Body(n, 23, np.float64, round_state_f32=1); rounded.set_state(s); rounded.step_count = 30
+    o_p, r_p, _ = plain.rollout(1)
+    o_r, r_r, _ = rounded.rollout(1)
+    sp, sr = plain.get_state(), rounded.get_state()
+    f32 = lambda x: x.astype(np.float32).astype(np.float64)
+    assert np.array_equal(sr[:, :18], f32(sp[:, :18]))
+    assert np.array_equal(sr[:, 18], f32(sp[:, 18])) and np.array_equal(sr[:, 19], sp[:, 19])
+    assert np.array_equal(r_r, f32(r_p)) and np.array_equal(o_r, f32(o_p))
+    assert not np.array_equal(sr[:, :18], sp[:, :18])             # the rounding is visible
+    # second step: starts from the rounded state, so it equals a fresh step from that state
+    again = Body(n, 23, np.float64, round_state_f32=1); again.set_state(sr); again.step_count = 31
+    o2, r2, _ = rounded.rollout(1)
+    o3, r3, _ = again.rollout(1)
+    assert np.array_equal(o2, o3) and np.array_equal(r2, r3)
+    # off by default
+    assert Body(1, 1, np.float64).params["round_state_f32"] == 0

@@ -52,6 +52,22 @@ MUTANTS = [
     ("body: friction pushes along the motion", "body.cpp", "ft = -want;", "ft = want;", BODY),
     ("body: limit projection keeps the coupling column", "body.cpp",
      "for (int k = 0; k < NQ; ++k) { M[j][k] = 0; M[k][j] = 0; }", "for (int k = 0; k < NQ; ++k) { M[j][k] = 0; }", BODY),
+    ("body: reward takes the last substep's velocity", "body.cpp",
+     "R reward = vx_sum / (R)P.substeps - (R)0.1 * cost;", "R reward = e->v[0] - (R)0.1 * cost;", BODY),
+    ("body: action cost of the unclipped action", "body.cpp",
+     "cost += a[j] * a[j];", "cost += a_in[j] * a_in[j];", BODY),
+    ("body: fifth action reuses a word of stream 0", "body.cpp",
+     "a[4] = (R)(-1.0f + 2.0f * oracle_u01(w1[0]));", "a[4] = (R)(-1.0f + 2.0f * oracle_u01(w0[0]));", BODY),
+    ("body: non-finite step keeps its reward", "body.cpp",
+     "    info->done = 1;\n    reward = 0;\n", "    info->done = 1;\n", BODY),
+    ("body: non-finite step counted as an episode", "body.cpp",
+     "if (info.nonfinite) st->nonfinite += 1;\n      else if (info.done) {",
+     "if (info.nonfinite) st->nonfinite += 1;\n      if (info.done) {", BODY),
+    ("body: non-finite state re-initialised with this step's draws", "body.cpp",
+     "info->fin_len = e->ep_len + 1;\n    reset_env(P, e, seed, env, step + 1);",
+     "info->fin_len = e->ep_len + 1;\n    reset_env(P, e, seed, env, step);", BODY),
+    ("body: storage rounding skips the velocities", "body.cpp",
+     "e->q[j] = (R)(float)e->q[j]; e->v[j] = (R)(float)e->v[j];", "e->q[j] = (R)(float)e->q[j];", BODY),
     ("newton: velocity-product term dropped from the reference", "body.cpp",
      "rows->aref[i] = -b * jv - k * kin.pos[1] - (kin.jdqd[1] + smu * kin.jdqd[0]);",
      "rows->aref[i] = -b * jv - k * kin.pos[1];", NEWTON),
