@@ -3,7 +3,11 @@
  * Not part of the environment boundary (include/mi355env.h): these exist so that the benchmark and
  * the tests can time a launch shape against another, force a code path that the library would
  * otherwise choose from N, and measure what the device does for a plain fill, copy or empty
- * launch.  All settings are process-wide, take effect at the next launch and are not thread-safe.
+ * launch.  All mi355env_tune_* settings are PROCESS-WIDE: they change which kernel every handle of
+ * the process launches from its next call on, they are plain globals without locks, and they must
+ * not be called while another thread is inside any call on any handle.  They never change a
+ * result, only the launch shape.  A program that is not measuring has no reason to call them; a
+ * test that does restores the defaults when it ends (0 / the documented default of each knob).
  * Return ENV_OK (0) or ENV_E_ARG (-1) unless stated.
  */
 #ifndef MI355ENV_TUNING_H

@@ -187,6 +187,34 @@ def test_states_outside_the_games_own_reach(T, external, pace):
     assert_bit_equal(fields, pong_state_fields(p.envs()), "state blob")
 
 
+def test_negative_zeros_in_a_restored_state_are_stored_as_positive_zeros():
+    # env_set_state stores -0.0 as +0.0 in the float fields (the game never produces a negative
+    # zero, and the step's sign-bit tests stand for comparisons with 0).  The GPU given negative
+    # zeros must therefore behave exactly like the oracle given the same state with positive ones.
+    n, seed, T = 128, 17, 40
+    p = orc.Pong(n, seed); p.reset(); p.rollout(9)
+    e = p.envs()
+    e["by"][::3] = 0.0; e["vy"][::3] = 0.0          # ball resting on the top wall
+    e["by"][1::3] = 0.0                             # ... or leaving it
+    e["pa"][::5] = 0.0; e["po"][::4] = 0.0
+    minus = pong_state_fields(e).copy()
+    zeros = minus[:6] == 0
+    assert zeros.sum() > n // 2
+    minus[:6][zeros] = 0x80000000
+    h = b.env_create(b.ENV_PONG, n, seed, None)
+    b.env_set_state(h, pong_blob(p.step_count, minus))
+    _, stored = split_state(b.env_get_state(h), n, 10)
+    assert_bit_equal(stored, pong_state_fields(e), "stored state")
+    obs, rew, done = bufs(T, n)
+    b.env_rollout(h, T, None, obs, rew, done)
+    torch.cuda.synchronize()
+    b.env_destroy(h)
+    oo, orr, od = p.rollout(T)
+    assert_bit_equal(obs.cpu().numpy(), oo, "obs")
+    assert_bit_equal(rew.cpu().numpy(), orr, "reward")
+    assert_bit_equal(done.cpu().numpy(), od, "done")
+
+
 def test_stats_reset_counters():
     h = b.env_create(b.ENV_PONG, 256, 3, {"max_score": 1})
     b.env_reset(h, None)
