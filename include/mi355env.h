@@ -60,6 +60,9 @@ enum {
                           with a host step counter; current device is not the handle's            */
   ENV_E_UNSUPPORTED = -5 /* operation not available for this environment kind                     */
 };
+/* There is no status code for a state that left the finite range: step / rollout return before the
+ * kernel has run, so a device-side condition cannot be their return value.  Such an environment is
+ * re-initialised inside the kernel (done = 1, reward = 0) and counted in env_stats_t.nonfinite. */
 
 /* Optional configuration (NULL = defaults).  struct_size = sizeof(env_config_t) as compiled by the
  * caller; fields beyond struct_size keep their defaults.  A zero/negative value in a field means
@@ -149,7 +152,8 @@ enum { ENV_PIXELS_SLOT_MAJOR = 1, ENV_PIXELS_ENV_MAJOR = 2, ENV_PIXELS_ORDERED =
  *          launch, also a replayed one, decides for itself. */
 enum { ENV_PIXELS_FULL = 1, ENV_PIXELS_DELTA = 2 };
 
-/* Statistics of the episodes that ended since the counters were last cleared. */
+/* Statistics of the episodes that ended since the counters were last cleared (the per-batch
+ * episode bookkeeping a training loop logs; reduced on the device, one atomic set per wavefront). */
 typedef struct env_stats_t {
   int64_t episodes;
   int64_t length_sum;
@@ -159,22 +163,32 @@ typedef struct env_stats_t {
   int64_t nonfinite; /* body: environments re-initialised because their state left the finite range */
 } env_stats_t;
 
-/* Create N environments of `kind`.  seed keys every random draw.  hip_stream is a hipStream_t
+/* Paper section 3.1 (problem statement): the unit being built is an environment whose step / reset
+ * reproduce a reference's observations, rewards and termination signals for any seed and action
+ * sequence; App. B.1 item 3 and App. B.2 item 8: one object, one call, for the whole batch.
+ * Create N environments of `kind`.  seed keys every random draw.  hip_stream is a hipStream_t
  * (NULL = the null stream) on the current device; the handle keeps using it.  Allocates
  * state (Pong: 40 B/env, body: 80 B/env, cart-pole: 24 B/env) on the current device.  *out is set only on success. */
 int env_create(env_t **out, int kind, int64_t n_envs, uint64_t seed, const env_config_t *cfg,
                void *hip_stream);
 
-/* Free the handle and its device memory (synchronises the stream first).  NULL is ignored. */
+/* Counterpart of env_create (App. B.1 item 7 / App. B.2 item 2: buffers live as long as the
+ * environment, nothing is allocated per step).
+ * Free the handle and its device memory (synchronises the stream first).  NULL is ignored. */
 void env_destroy(env_t *e);
 
-/* Start a new episode in every environment, drawing the initial state from the reset streams at
+/* Paper section 3.1 and App. B.3 (the interface that optimisation must not change: step, reset,
+ * observation / reward shapes); App. B.1 item 4: reset, like step, is one launch for the batch.
+ * Start a new episode in every environment, drawing the initial state from the reset streams at
  * the current step counter.  obs_dev (may be NULL): Pong float32[N,8]; body float32[N,17];
  * pixels: the ring (4*N*7056 bytes, layout per cfg.pixel_layout) — all four slots of every
  * environment receive the initial frame.  16-byte aligned (body: 4-byte). */
 int env_reset(env_t *e, void *obs_dev);
 
-/* Advance every environment by one step (one kernel launch).
+/* Paper section 3.1 (per-step outputs: observation, reward, termination); App. B.1 items 3-4 (a
+ * single-instance step batched over N, one launch per batch step); items 6-7 (uint8 flags and
+ * actions, float32 only where arithmetic needs it, caller-provided output buffers).
+ * Advance every environment by one step (one kernel launch).
  * actions_dev: Pong uint8[N] in {0 stay, 1 up, 2 down} (other values = stay); body float32[N,6],
  * clipped to [-1,1]; cart-pole uint8[N], 1 = push right, anything else = push left;
  * NULL = draw the actions from this step's Philox block inside the kernel.
@@ -184,7 +198,9 @@ int env_reset(env_t *e, void *obs_dev);
  * obs_dev must be 16-byte aligned (body: 4-byte), reward_dev 4-byte aligned.  None may be NULL. */
 int env_step(env_t *e, const void *actions_dev, void *obs_dev, float *reward_dev, uint8_t *done_dev);
 
-/* T steps fused into one kernel launch; state stays in registers between steps.
+/* Paper App. B.1 item 5 (the rollout loop fused into one kernel, no per-step dispatch) and App. A.1
+ * "Puffer Pong" (a whole rollout as a single GPU kernel with no host-device transfer).
+ * T steps fused into one kernel launch; state stays in registers between steps.
  * actions_dev: [T,N] (Pong uint8) / [T,N,6] (body float32) or NULL (in-kernel Philox draws).
  * obs_dev: float32[T,N,obs_dim] (Pong, body); pixels: uint8[T,N,84,84], frame t of the rollout.
  * reward_dev float32[T,N]; done_dev uint8[T,N].  Alignment as for env_step.  Equivalent, bit for
@@ -192,7 +208,10 @@ int env_step(env_t *e, const void *actions_dev, void *obs_dev, float *reward_dev
 int env_rollout(env_t *e, int32_t T, const void *actions_dev, void *obs_dev, float *reward_dev,
                 uint8_t *done_dev);
 
-/* Copy the episode statistics to *host_out; clear the device counters if reset_counters != 0. */
+/* Paper section 3.2, level 3 (episodes compared over matched seeds) needs episode returns and
+ * lengths per batch; this is their device-side reduction read back.
+ * Copy the episode statistics to *host_out; clear the device counters if reset_counters != 0.
+ * Synchronises the stream. */
 int env_stats(env_t *e, env_stats_t *host_out, int reset_counters);
 
 /* Size in bytes of the state blob of get/set_state: 8 + 4 * fields * N, where the blob is
@@ -203,12 +222,17 @@ int env_stats(env_t *e, env_stats_t *host_out, int reset_counters);
  * Cart-pole (6 fields): x, xdot, theta, thetadot, return so far (float32), length so far (int32). */
 size_t env_state_bytes(const env_t *e);
 
-/* Copy the state blob to / from host memory (bytes must equal env_state_bytes).  set_state also
- * marks the handle as reset.  Rendered frames are not part of the state. */
+/* Paper App. C (module translation prompt: all of a simulator's registers in one plain structure,
+ * for saving and loading state) and section 3.2, level 3 (rollouts replayed from matched states).
+ * Copy the state blob to / from host memory (bytes must equal env_state_bytes); both synchronise
+ * the stream.  set_state also marks the handle as reset.  Rendered frames are not part of the
+ * state.  Values are taken as they are, except that a negative zero in a float32 field of Pong is
+ * stored as +0 (the game never produces one; the step's sign tests treat the two alike this way). */
 int env_get_state(env_t *e, void *host_buf, size_t bytes);
 int env_set_state(env_t *e, const void *host_buf, size_t bytes);
 
-/* Floats (or bytes, for pixels: 4*84*84) per environment in obs_dev of env_step; <0 on bad kind. */
+/* Shapes of the interface (App. B.3: fixed observation / reward shapes).
+ * Floats (or bytes, for pixels: 4*84*84) per environment in obs_dev of env_step; <0 on bad kind. */
 int env_obs_dim(int kind);
 /* Elements per environment in actions_dev (Pong 1 x uint8, body 6 x float32). */
 int env_action_dim(int kind);
@@ -217,7 +241,10 @@ int64_t env_num_envs(const env_t *e);
  * (returns UINT64_MAX if that fails). */
 uint64_t env_step_count(const env_t *e);
 
-/* Enqueue all later work of the handle on another stream of the same device (e.g. the stream a
+/* For the policy-in-the-loop rollout (paper section 4.1, throughput table, row "GRU Rollout (2M)":
+ * policy and environment step in one device-side loop): env_step recorded on the stream a graph
+ * capture runs on.
+ * Enqueue all later work of the handle on another stream of the same device (e.g. the stream a
  * graph capture runs on).  The caller orders the two streams; nothing is synchronised here. */
 int env_set_stream(env_t *e, void *hip_stream);
 

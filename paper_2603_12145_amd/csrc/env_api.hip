@@ -6,6 +6,7 @@
 #include <cstring>
 #include <limits>
 #include <new>
+#include <vector>
 
 #include "../../include/mi355env.h"
 #include "kernels.hpp"
@@ -445,8 +446,27 @@ int env_get_state(env_t* e, void* host_buf, size_t bytes) {
 int env_set_state(env_t* e, const void* host_buf, size_t bytes) {
   if (!e || !host_buf || bytes != env_state_bytes(e)) return ENV_E_ARG;
   if (!on_own_device(e)) return ENV_E_STATE;
-  if (hipMemcpyAsync(e->state, static_cast<const char*>(host_buf) + 8, bytes - 8,
-                     hipMemcpyHostToDevice, e->stream) != hipSuccess ||
+  const char* fields = static_cast<const char*>(host_buf) + 8;
+  // Pong: a negative zero in a float field (the game never produces one) is stored as +0, so that
+  // the step's sign-bit tests and the comparisons they stand for agree on every state.
+  std::vector<uint32_t> fixed;
+  if (e->kind == ENV_PONG || e->kind == ENV_PONG_PIXELS) {
+    const size_t words = (size_t)PONG_FLOAT_FIELDS * (size_t)e->n;
+    bool any = false;
+    for (size_t k = 0; k < words && !any; ++k) {
+      uint32_t w;
+      std::memcpy(&w, fields + 4 * k, 4);
+      any = w == 0x80000000u;
+    }
+    if (any) {
+      try { fixed.resize((bytes - 8) / 4); } catch (const std::bad_alloc&) { return ENV_E_ALLOC; }
+      std::memcpy(fixed.data(), fields, bytes - 8);
+      for (size_t k = 0; k < words; ++k)
+        if (fixed[k] == 0x80000000u) fixed[k] = 0u;
+      fields = reinterpret_cast<const char*>(fixed.data());
+    }
+  }
+  if (hipMemcpyAsync(e->state, fields, bytes - 8, hipMemcpyHostToDevice, e->stream) != hipSuccess ||
       hipStreamSynchronize(e->stream) != hipSuccess)
     return ENV_E_HIP;
   std::memcpy(&e->step, host_buf, 8);

@@ -20,6 +20,7 @@ namespace envk {
 
 constexpr int PONG_FIELDS = 10;  // bx by vx vy pa po | sa so ep_ret ep_len
 constexpr int PONG_OBS = 8;
+constexpr int PONG_FLOAT_FIELDS = 6;   // the first six fields are float32, the rest int32
 
 struct PongLane {
   float bx, by, vx, vy, pa, po;
