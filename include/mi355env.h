@@ -58,7 +58,8 @@ enum {
   ENV_E_HIP = -3,      /* a HIP runtime call or kernel launch failed                              */
   ENV_E_STATE = -4,    /* call order: step/rollout before the first env_reset; capture on a handle
                           with a host step counter; current device is not the handle's            */
-  ENV_E_UNSUPPORTED = -5 /* operation not available for this environment kind                     */
+  ENV_E_UNSUPPORTED = -5, /* operation not available for this environment kind                    */
+  ENV_E_TOO_LARGE = -6   /* size beyond the fixed maximum of env_step_pixels_noalloc              */
 };
 /* There is no status code for a state that left the finite range: step / rollout return before the
  * kernel has run, so a device-side condition cannot be their return value.  Such an environment is
@@ -247,6 +248,35 @@ uint64_t env_step_count(const env_t *e);
  * Enqueue all later work of the handle on another stream of the same device (e.g. the stream a
  * graph capture runs on).  The caller orders the two streams; nothing is synchronised here. */
 int env_set_stream(env_t *e, void *hip_stream);
+
+/* For callers that cannot allocate device memory: code running under a HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  One env_step of Pong with pixel observations on
+ * the slot-major ring, as env_step does it for an ENV_PONG_PIXELS handle, but without a handle: the
+ * caller owns the state, and what a handle would have allocated -- the partial episode statistics
+ * and the 12 bytes per environment that the dynamics pass stages for the renderer -- lives in a
+ * fixed array inside the library (800 KiB per device, held until the process ends), which limits
+ * the batch to ENV_NOALLOC_MAX_ENVS environments (more: ENV_E_TOO_LARGE).  The call allocates and
+ * frees nothing, takes no handle and synchronises nothing; it enqueues four small launches on
+ * hip_stream (NULL = the null stream) of the current device.
+ *   state_dev   in/out, uint32[10][n]: the fields of the Pong state blob (env_state_bytes above)
+ *               without the leading step counter, e.g. copied from env_get_state
+ *   step        index of this step = env steps taken before it; keys the random draws (with seed)
+ *               and selects the ring slot, step mod 4
+ *   actions_dev uint8[n] or NULL (in-kernel draws), as for env_step
+ *   ring_dev    uint8[4][n][84][84], 16-byte aligned; only slot step mod 4 is written
+ *   reward_dev  float32[n];  done_dev uint8[n]
+ *   stats_dev   optional (NULL = none), 8-byte aligned DEVICE memory: receives the statistics of the
+ *               episodes that ended in THIS step (nonfinite = 0)
+ * Results are those of env_step on a handle in the same state, bit for bit.  All calls on one
+ * device share the one array: calls that overlap in time on one device (two streams, two threads)
+ * race on it; calls on one stream do not.  Device pointers are checked like env_step's and the
+ * ranges that passed are remembered, so make one direct call with the same buffers before
+ * recording a call in a graph. */
+#define ENV_NOALLOC_MAX_ENVS 65536
+int env_step_pixels_noalloc(int64_t n_envs, uint64_t seed, uint64_t step, int32_t max_score,
+                            void *state_dev, const uint8_t *actions_dev, uint8_t *ring_dev,
+                            float *reward_dev, uint8_t *done_dev, env_stats_t *stats_dev,
+                            void *hip_stream);
 
 /* Static string for a status code. */
 const char *env_strerror(int code);

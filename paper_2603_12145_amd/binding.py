@@ -12,7 +12,8 @@ ENV_STEP_COUNTER_HOST, ENV_STEP_COUNTER_DEVICE = 1, 2
 ENV_OBS_RAW, ENV_OBS_NORMALIZED = 1, 2
 ENV_CONTACT_PENALTY, ENV_CONTACT_NEWTON = 1, 2
 ENV_PIXELS_FULL, ENV_PIXELS_DELTA = 1, 2
-ENV_OK, ENV_E_ARG, ENV_E_ALLOC, ENV_E_HIP, ENV_E_STATE, ENV_E_UNSUPPORTED = 0, -1, -2, -3, -4, -5
+ENV_OK, ENV_E_ARG, ENV_E_ALLOC, ENV_E_HIP, ENV_E_STATE, ENV_E_UNSUPPORTED, ENV_E_TOO_LARGE = 0, -1, -2, -3, -4, -5, -6
+ENV_NOALLOC_MAX_ENVS = 65536
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmi355env.so")
@@ -63,6 +64,9 @@ def lib():
         L.env_step_count.argtypes = [vp]; L.env_step_count.restype = C.c_uint64
         L.env_set_stream.argtypes = [vp, vp]
         L.env_strerror.argtypes = [C.c_int]; L.env_strerror.restype = C.c_char_p
+        L.env_step_pixels_noalloc.argtypes = [C.c_int64, C.c_uint64, C.c_uint64, C.c_int32, vp, vp, vp, vp, vp,
+                                              vp, vp]
+        L.env_step_pixels_noalloc.restype = C.c_int
         for f in (L.env_create, L.env_reset, L.env_step, L.env_rollout, L.env_stats,
                   L.env_get_state, L.env_set_state, L.env_obs_dim, L.env_action_dim,
                   L.env_set_stream):
@@ -174,3 +178,15 @@ def env_set_stream(h, stream):
     """stream: torch.cuda.Stream (or a raw hipStream_t address)."""
     addr = stream if isinstance(stream, int) else stream.cuda_stream
     _check(lib().env_set_stream(h, C.c_void_p(addr)), "env_set_stream")
+
+
+def env_step_pixels_noalloc(n_envs, seed, step, max_score, state, actions, ring, reward, done, stats=None,
+                            stream=None):
+    """state: uint32/int32 device tensor [10, n] (in/out); stats: optional device tensor of 48 bytes
+    (an env_stats_t); stream: torch.cuda.Stream or None (torch's current stream)."""
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    _check(lib().env_step_pixels_noalloc(int(n_envs), int(seed), int(step), int(max_score), _dev_ptr(state),
+                                         _dev_ptr(actions), _dev_ptr(ring), _dev_ptr(reward), _dev_ptr(done),
+                                         _dev_ptr(stats), C.c_void_p(s.cuda_stream)), "env_step_pixels_noalloc")
+

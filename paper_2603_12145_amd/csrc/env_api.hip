@@ -528,6 +528,7 @@ const char* env_strerror(int code) {
              "capturing and the handle keeps its step counter on the host, or the current device is "
              "not the handle's)";
     case ENV_E_UNSUPPORTED: return "not supported for this environment kind";
+    case ENV_E_TOO_LARGE: return "more environments than env_step_pixels_noalloc's fixed scratch array holds";
   }
   return "unknown status";
 }

@@ -1067,3 +1067,148 @@ hipError_t launch_pixel_rollout(const PixelLaunch& a, PixelPipe& pipe, hipStream
 }
 
 }  // namespace envk
+
+// ---- one entry point that allocates nothing ---------------------------------------------------
+// env_step_pixels_noalloc (include/mi355env.h): the slot-major pixel step without a handle, for
+// callers that cannot allocate.  The two kinds of scratch a handle's pixel step keeps in memory from
+// env_create -- the 256 partial copies of the episode statistics and the staged cell blocks that
+// the lane-per-environment pass hands to the page renderer, 12 bytes per environment -- live in
+// one file-scope device array instead, of fixed size.  Every device has its own copy of the array
+// at its own address; the address is asked for once per device and kept.
+#include <mutex>
+
+#include "../../include/mi355env.h"
+
+namespace envk {
+namespace {
+
+struct NoAllocScratch {
+  DeviceStats stripes[STATS_STRIPES];                      // partial episode statistics, 32 KiB
+  uint32_t blocks[3 * ENV_NOALLOC_MAX_ENVS];               // staged cell blocks [3][n], 768 KiB
+};
+
+__global__ __launch_bounds__(STATS_STRIPES) void noalloc_clear_stats_kernel(DeviceStats* __restrict__ stripes) {
+  DeviceStats z;
+  z.episodes = 0; z.length_sum = 0; z.return_sum_i = 0; z.return_sum_f = 0.0;
+  z.return_min_key = INT32_MAX; z.return_max_key = INT32_MIN; z.nonfinite = 0;
+  stripes[threadIdx.x] = z;
+}
+
+// One wavefront adds the copies up and writes the result in the boundary's layout.
+__global__ __launch_bounds__(64) void noalloc_reduce_stats_kernel(const DeviceStats* __restrict__ stripes,
+                                                                  env_stats_t* __restrict__ out) {
+  long long episodes = 0, length = 0, ret = 0;
+  int mn = INT32_MAX, mx = INT32_MIN;
+  for (int k = threadIdx.x; k < STATS_STRIPES; k += 64) {
+    const DeviceStats s = stripes[k];
+    episodes += (long long)s.episodes; length += (long long)s.length_sum; ret += s.return_sum_i;
+    mn = min(mn, s.return_min_key); mx = max(mx, s.return_max_key);
+  }
+  episodes = wave_sum(episodes); length = wave_sum(length); ret = wave_sum(ret);
+  mn = wave_min(mn); mx = wave_max(mx);
+  if (threadIdx.x == 0) {
+    out->episodes = episodes; out->length_sum = length; out->return_sum = (double)ret;
+    out->return_min = episodes > 0 ? (double)mn : (double)INFINITY;
+    out->return_max = episodes > 0 ? (double)mx : -(double)INFINITY;
+    out->nonfinite = 0;
+  }
+}
+
+}  // namespace
+}  // namespace envk
+
+static __device__ __align__(256) unsigned char scratch[sizeof(envk::NoAllocScratch)];
+
+namespace {
+
+constexpr int NOALLOC_MAX_DEVICES = 64;
+std::mutex g_noalloc_mutex;
+void* g_scratch_of_device[NOALLOC_MAX_DEVICES] = {};        // device address of `scratch`, per device
+struct CheckedRange { int device; const void* p; size_t bytes; };
+CheckedRange g_noalloc_seen[16] = {};
+int g_noalloc_seen_next = 0;
+
+// Device address of this device's copy of `scratch` (the array's name is only a host-side handle).
+int noalloc_scratch(int device, envk::NoAllocScratch** out) {
+  std::lock_guard<std::mutex> lock(g_noalloc_mutex);
+  if (!g_scratch_of_device[device]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) { (void)hipGetLastError(); return ENV_E_HIP; }
+    g_scratch_of_device[device] = p;
+  }
+  *out = static_cast<envk::NoAllocScratch*>(g_scratch_of_device[device]);
+  return ENV_OK;
+}
+
+// [p, p + bytes) lies inside one device allocation; ranges that passed are remembered (no driver
+// query for them again, so that a call with known buffers can be recorded by a stream capture).
+bool noalloc_range_ok(int device, const void* p, size_t bytes, size_t align) {
+  if (!p || (reinterpret_cast<uintptr_t>(p) & (align - 1))) return false;
+  std::lock_guard<std::mutex> lock(g_noalloc_mutex);
+  for (const CheckedRange& r : g_noalloc_seen)
+    if (r.p == p && r.device == device && r.bytes >= bytes) return true;
+  hipPointerAttribute_t attr;
+  if (hipPointerGetAttributes(&attr, p) != hipSuccess) { (void)hipGetLastError(); return false; }
+  if (attr.type != hipMemoryTypeDevice && attr.type != hipMemoryTypeManaged) return false;
+  hipDeviceptr_t base = nullptr;
+  size_t size = 0;
+  if (hipMemGetAddressRange(&base, &size, const_cast<void*>(p)) != hipSuccess) { (void)hipGetLastError(); return false; }
+  const uintptr_t lo = reinterpret_cast<uintptr_t>(base), q = reinterpret_cast<uintptr_t>(p);
+  if (q < lo || q + bytes > lo + size) return false;
+  g_noalloc_seen[g_noalloc_seen_next] = {device, p, bytes};
+  g_noalloc_seen_next = (g_noalloc_seen_next + 1) % 16;
+  return true;
+}
+
+}  // namespace
+
+extern "C" int env_step_pixels_noalloc(int64_t n_envs, uint64_t seed, uint64_t step, int32_t max_score,
+                                       void* state_dev, const uint8_t* actions_dev, uint8_t* ring_dev,
+                                       float* reward_dev, uint8_t* done_dev, env_stats_t* stats_dev,
+                                       void* hip_stream) {
+  using namespace envk;
+  if (n_envs <= 0 || max_score <= 0) return ENV_E_ARG;
+  if (n_envs > ENV_NOALLOC_MAX_ENVS) return ENV_E_TOO_LARGE;
+  int device = -1;
+  if (hipGetDevice(&device) != hipSuccess) { (void)hipGetLastError(); return ENV_E_HIP; }
+  if (device < 0 || device >= NOALLOC_MAX_DEVICES) return ENV_E_UNSUPPORTED;
+  const size_t n = (size_t)n_envs;
+  if (!noalloc_range_ok(device, state_dev, n * PONG_FIELDS * 4, 4)) return ENV_E_ARG;
+  if (!noalloc_range_ok(device, ring_dev, n * 4 * FRAME_BYTES, 16)) return ENV_E_ARG;
+  if (!noalloc_range_ok(device, reward_dev, n * sizeof(float), 4)) return ENV_E_ARG;
+  if (!noalloc_range_ok(device, done_dev, n, 1)) return ENV_E_ARG;
+  if (actions_dev && !noalloc_range_ok(device, actions_dev, n, 1)) return ENV_E_ARG;
+  if (stats_dev && !noalloc_range_ok(device, stats_dev, sizeof(env_stats_t), 8)) return ENV_E_ARG;
+  NoAllocScratch* sc = nullptr;
+  const int rc = noalloc_scratch(device, &sc);
+  if (rc != ENV_OK) return rc;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+  // the array keeps the previous call's contents: the statistics must start empty (a fill kernel,
+  // not a memset node, so that the call can be recorded in a graph); the cell blocks of all n
+  // environments are written by the pass below before the renderer reads them
+  hipLaunchKernelGGL(noalloc_clear_stats_kernel, dim3(1), dim3(STATS_STRIPES), 0, stream, sc->stripes);
+  if (hipGetLastError() != hipSuccess) return ENV_E_HIP;
+  PongLaunch d{};
+  d.state = static_cast<uint32_t*>(state_dev); d.n = n_envs; d.seed = seed; d.step0 = step;
+  d.counter = nullptr; d.ticket = 0; d.T = 1; d.max_score = max_score; d.actions = actions_dev;
+  d.obs = nullptr; d.reward = reward_dev; d.done = done_dev; d.stats = sc->stripes;
+  const unsigned groups = (unsigned)((n_envs + 255) / 256);
+  if (actions_dev) hipLaunchKernelGGL(pixel_traj_dynamics_kernel<true>, dim3(groups), dim3(256), 0, stream, d, sc->blocks, n_envs);
+  else hipLaunchKernelGGL(pixel_traj_dynamics_kernel<false>, dim3(groups), dim3(256), 0, stream, d, sc->blocks, n_envs);
+  if (hipGetLastError() != hipSuccess) return ENV_E_HIP;
+  uint8_t* plane = ring_dev + (int64_t)(step & 3ull) * n_envs * FRAME_BYTES;
+  const unsigned pages = plane_pages(plane, n_envs);
+  if (pages >= 65536u)
+    hipLaunchKernelGGL(plane_render_kernel<RENDER_U>, dim3((pages + RENDER_U - 1) / RENDER_U), dim3(256), 0, stream,
+                       sc->blocks, n_envs, plane);
+  else
+    hipLaunchKernelGGL(plane_render_kernel<1>, dim3(pages), dim3(256), 0, stream, sc->blocks, n_envs, plane);
+  if (hipGetLastError() != hipSuccess) return ENV_E_HIP;
+  if (stats_dev) {
+    hipLaunchKernelGGL(noalloc_reduce_stats_kernel, dim3(1), dim3(64), 0, stream, sc->stripes, stats_dev);
+    if (hipGetLastError() != hipSuccess) return ENV_E_HIP;
+  }
+  return ENV_OK;
+}
+

@@ -52,7 +52,7 @@ def test_dims_and_strings(L):
     assert b.env_obs_dim(b.ENV_CARTPOLE) == 4 and b.env_action_dim(b.ENV_CARTPOLE) == 1
     assert b.env_obs_dim(99) == b.ENV_E_ARG
     assert b.env_action_dim(b.ENV_PONG) == 1 and b.env_action_dim(b.ENV_BODY) == 6
-    for code in (0, -1, -2, -3, -4, -5, -99):
+    for code in (0, -1, -2, -3, -4, -5, -6, -99):
         assert isinstance(b.env_strerror(code), str) and b.env_strerror(code)
 
 
