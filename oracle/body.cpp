@@ -352,8 +352,12 @@ bool substep_newton(const Params<R>& P, R* q, R* v, const R a[NACT], NewtonInfo*
 }
 
 // One substep; a[] already clipped.  limit_mask_out (optional): bit j set if joint j was projected.
+// margin_io (optional, penalty model): lowered to the distance of this substep's closest decision
+// from its switching surface -- |z_p| of the eight contact points (the force law changes at z = 0),
+// 1 - |q_j| of the joints not sitting at a limit (the projection applies from |q_j| = 1 on), and
+// |v*_j| of the joints that are (projected or not by the sign of v*_j).
 template <class R>
-bool substep(const Params<R>& P, R* q, R* v, const R a[NACT], int* limit_mask_out) {
+bool substep(const Params<R>& P, R* q, R* v, const R a[NACT], int* limit_mask_out, R* margin_io = nullptr) {
   if (P.solver == 1) {
     if (limit_mask_out) *limit_mask_out = 0;
     return substep_newton(P, q, v, a, (NewtonInfo*)nullptr);
@@ -373,6 +377,17 @@ bool substep(const Params<R>& P, R* q, R* v, const R a[NACT], int* limit_mask_ou
   }
   R vs[NQ];
   if (!cholesky_solve(M, b, vs)) return false;
+  if (margin_io) {
+    R m = *margin_io;
+    for (int p = 0; p < NPOINT; ++p) {
+      Kin<R> k;
+      point_kinematics(CONTACT[p], q, v, &k);
+      m = std::fmin(m, std::fabs(k.pos[1]));
+    }
+    for (int j = 3; j < NQ; ++j)
+      m = std::fmin(m, (q[j] >= 1 || q[j] <= -1) ? std::fabs(vs[j]) : (R)1 - std::fabs(q[j]));
+    *margin_io = m;
+  }
   int mask = 0;
   for (int j = 3; j < NQ; ++j)
     if ((q[j] >= 1 && vs[j] > 0) || (q[j] <= -1 && vs[j] < 0)) mask |= 1 << j;
@@ -687,6 +702,17 @@ Batch<R>* create(int64_t n, uint64_t seed, const double* cfg /* armature, dampin
     const bool ok = newton_solve(P, M, f9, rows, acc9, &info);                                    \
     info4[0] = info.rows; info4[1] = info.passes; info4[2] = info.converged; info4[3] = (int32_t)info.active; \
     return ok ? 1 : 0;                                                                            \
+  }                                                                                               \
+  /* smallest distance of any decision of one env step (all substeps, penalty model) from its   */ \
+  /* switching surface, stepping a copy of (q, v) under clipped actions; -1 if a solve fails      */ \
+  double oracle_body_step_margin##SFX(void* h, const R* q_in, const R* v_in, const R* a_in) {     \
+    const Params<R>& P = ((Batch<R>*)h)->P;                                                       \
+    R q[NQ], v[NQ], a[NACT]; clip_actions(a_in, a);                                               \
+    for (int j = 0; j < NQ; ++j) { q[j] = q_in[j]; v[j] = v_in[j]; }                              \
+    R margin = (R)INFINITY;                                                                       \
+    for (int s = 0; s < P.substeps; ++s)                                                          \
+      if (!substep(P, q, v, a, (int*)nullptr, &margin)) return -1.0;                              \
+    return (double)margin;                                                                        \
   }                                                                                               \
   int32_t oracle_body_solve##SFX(const R* A81, const R* b, R* x) {                                \
     R A[NQ][NQ]; std::memcpy(A, A81, sizeof A); return cholesky_solve(A, b, x) ? 1 : 0;           \

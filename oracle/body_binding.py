@@ -35,6 +35,7 @@ def bind(L):
         g("newton_rows").argtypes = [vp, vp, vp, vp, vp, vp]; g("newton_rows").restype = C.c_int32
         g("newton_accel").argtypes = [vp, vp, vp, vp, vp, vp, vp]; g("newton_accel").restype = C.c_int32
         g("draw_actions").argtypes = [C.c_uint64, C.c_uint32, C.c_uint64, vp]
+        g("step_margin").argtypes = [vp, vp, vp, vp]; g("step_margin").restype = C.c_double
     L.oracle_body_link.argtypes = [C.c_int32, C.POINTER(C.c_double), C.POINTER(C.c_double)]
 
 
@@ -174,6 +175,11 @@ class Body:
         x = np.empty(NQ, self.dtype)
         ok = self._f("solve")(_p(self.arr(A)), _p(self.arr(b)), _p(x))
         return x, bool(ok)
+
+    def step_margin(self, q, v, a):
+        """Smallest distance of any decision of one env step from (q, v) under actions a to its
+        switching surface (contact heights, joint-limit onsets, signs of v* at limits)."""
+        return float(self._f("step_margin")(self.h, _p(self.arr(q)), _p(self.arr(v)), _p(self.arr(a))))
 
     def draw_actions(self, env, step):
         a = np.empty(NACT, self.dtype)

@@ -4,8 +4,10 @@ Bar: a single step from an oracle-supplied float32 state agrees with the float64
 |gpu - oracle| <= 1e-5 * max(|oracle|, 1) per state component; 1000-step return statistics agree
 within 1 %.  The kernel computes a step in float64 from the float32 state, as the float64 oracle
 does, so both take every contact / joint-limit decision in the same precision; the two can still
-disagree on a decision that sits within rounding of its switching surface, which the tests report
-as a flip (allowed for at most 0.1 % of the environments)."""
+disagree on a decision that sits within rounding of its switching surface.  An environment beyond
+the tolerance is accepted only if the oracle reports such a decision for its step (a contact point
+within 1e-9 of the ground, a joint within 1e-9 of its limit, a limit joint whose free velocity is
+below 1e-9); there is no blanket allowance."""
 import math
 
 import numpy as np
@@ -49,6 +51,22 @@ def rel_err(got, want):
     return np.abs(got.astype(np.float64) - want) / np.maximum(np.abs(want), 1.0)
 
 
+MARGIN = 1e-9
+
+
+def unexplained(worst, s, action_of):
+    """Indices of the environments beyond TOL whose step has no decision within MARGIN of its
+    switching surface (s [n,20]: the state the step started from; action_of(e): its six actions)."""
+    o = Body(1, 1, np.float64)
+    bad = []
+    for e in np.flatnonzero(worst > TOL):
+        m = o.step_margin(s[e, :9], s[e, 9:18], np.asarray(action_of(e), np.float64))
+        print("env %d: error %.2e, closest decision %.2e from its switching surface" % (e, worst[e], m))
+        if not 0 <= m < MARGIN:
+            bad.append(int(e))
+    return bad
+
+
 def oracle_states(n, seed, warm_steps):
     """float32-representable states from all phases of motion (float64 oracle rollout)."""
     o = Body(n, seed, np.float64)
@@ -81,7 +99,7 @@ def test_single_step_from_oracle_states(warm):
     flips = int((worst > TOL).sum())
     print("warm=%d: median err %.2e, 99.9%% %.2e, max %.2e, beyond 1e-5: %d of %d"
           % (warm, np.median(worst), np.quantile(worst, 0.999), worst.max(), flips, n))
-    assert flips <= n // 1000
+    assert unexplained(worst, s, lambda e: o.draw_actions(e, warm)) == []
     assert np.median(worst) < 5e-7
     assert np.array_equal(done[0].cpu().numpy(), odone[0])
 
@@ -99,7 +117,7 @@ def test_single_step_with_external_actions_and_clipping():
     torch.cuda.synchronize()
     b.env_destroy(h)
     worst = np.maximum(rel_err(obs[0].cpu().numpy(), oobs[0]).max(axis=1), rel_err(rew[0].cpu().numpy(), orew[0]))
-    assert (worst > TOL).sum() <= n // 1000 and np.median(worst) < 5e-7
+    assert unexplained(worst, s, lambda e: acts[0, e]) == [] and np.median(worst) < 5e-7
     # with zero actions the result differs (the external actions are really used)
     assert np.abs(oobs[0][:, 11:]).max() > 1.0
 
@@ -247,7 +265,7 @@ def test_config_fields_reach_the_kernel():
         torch.cuda.synchronize()
         b.env_destroy(h)
         outs[name] = obs[0].cpu().numpy()
-        assert np.quantile(rel_err(outs[name], oobs[0]).max(axis=1), 0.99) < TOL
+        assert rel_err(outs[name], oobs[0]).max() < TOL
     assert np.abs(outs["default"] - outs["literal"]).max() > 1e-2
 
 
@@ -268,12 +286,28 @@ def test_config4_n8192_t1000_return_statistics():
     _, orew, _ = o.rollout(T, nthreads=16, want_obs=False)
     o_ret = orew.astype(np.float64).sum(0)
     se = math.sqrt(g_ret.var() / n + o_ret.var() / n)
-    print("return mean gpu %.3f oracle %.3f (diff %.3f, s.e. of diff %.3f); std gpu %.2f oracle %.2f"
-          % (g_ret.mean(), o_ret.mean(), g_ret.mean() - o_ret.mean(), se, g_ret.std(), o_ret.std()))
+
+    def se_of_std(x):            # standard error of a sample standard deviation: sqrt((m4 - s^4) / (4 n s^2))
+        d = x - x.mean()
+        return math.sqrt(max((d ** 4).mean() - x.var() ** 2, 0.0) / (4 * len(x) * x.var()))
+    se_std = math.sqrt(se_of_std(g_ret) ** 2 + se_of_std(o_ret) ** 2)
+    print("return mean gpu %.3f oracle %.3f (diff %.3f = %.2f %%, s.e. of diff %.3f); std gpu %.2f oracle %.2f "
+          "(diff %.2f %%, s.e. of diff %.2f %%)"
+          % (g_ret.mean(), o_ret.mean(), g_ret.mean() - o_ret.mean(),
+             100 * abs(g_ret.mean() - o_ret.mean()) / abs(o_ret.mean()), se, g_ret.std(), o_ret.std(),
+             100 * abs(g_ret.std() - o_ret.std()) / o_ret.std(), 100 * se_std / o_ret.std()))
+    # The bar: return statistics within 1 %.  The mean is held to it.  The two sides decorrelate
+    # within some fifty steps (penalty contact amplifies a last-bit difference), so over 1000 steps
+    # they are two independent samples of 8192 returns: the standard deviations of two such samples
+    # differ by 1.1 % at one standard error, which makes "within 1 %" a coin toss for the spread
+    # whatever the kernel does; it is held to three standard errors of the difference instead.
     assert abs(g_ret.mean() - o_ret.mean()) < 0.01 * abs(o_ret.mean())
-    assert abs(g_ret.std() - o_ret.std()) < 0.05 * o_ret.std()
+    assert abs(g_ret.std() - o_ret.std()) < 3.0 * se_std
+    assert se_std < 0.02 * o_ret.std()
     assert abs(st["return_sum"] / n - g_ret.mean()) < 1e-2
     # the first step is identical physics from identical initial states
     o1 = Body(n, seed, np.float64); o1.reset()
+    o1_state0 = o1.get_state()
     oo, _, _ = o1.rollout(1, nthreads=16)
-    assert np.quantile(rel_err(obs[0].cpu().numpy(), oo[0]).max(axis=1), 0.999) < TOL
+    first = rel_err(obs[0].cpu().numpy(), oo[0]).max(axis=1)
+    assert unexplained(first, o1_state0, lambda e: o1.draw_actions(e, 0)) == []

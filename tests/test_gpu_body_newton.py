@@ -1,8 +1,8 @@
 """GPU parity: articulated body with the Newton contact model (contact_solver = ENV_CONTACT_NEWTON),
 HIP path vs the float64 CPU oracle, through the C-ABI.  Same bar as the penalty model: a single
-step from an oracle-supplied float32 state within 1e-5 * max(|oracle|, 1) per component (a state
-that sits within rounding of a switching surface may flip a decision: at most 0.1 % of the
-environments), return statistics of 1000-step rollouts within 1 %."""
+step from an oracle-supplied float32 state within 1e-5 * max(|oracle|, 1) per component (no
+allowance for flipped decisions: this model's cost is C1, so a row on its switching surface
+contributes nothing either way), mean and standard deviation of 1000-step returns within 1 %."""
 import numpy as np
 import pytest
 
@@ -53,7 +53,7 @@ def test_single_step_from_oracle_states(n, warm):
     flips = int((worst > TOL).sum())
     print("newton warm=%d: median err %.2e, 99.9%% %.2e, max %.2e, beyond 1e-5: %d of %d"
           % (warm, np.median(worst), np.quantile(worst, 0.999), worst.max(), flips, n))
-    assert flips <= n // 1000
+    assert flips == 0            # the model's cost is C1: no decision can move a step by more than rounding
     assert np.median(worst) < 5e-7
     assert np.array_equal(done[0].cpu().numpy(), odone[0])
 
@@ -93,7 +93,7 @@ def test_single_step_with_external_actions():
     finally:
         b.env_destroy(h)
     worst = np.maximum(rel_err(obs[0].cpu().numpy(), oobs[0]).max(axis=1), rel_err(rew[0].cpu().numpy(), orew[0]))
-    assert (worst > TOL).sum() <= n // 1000 and np.median(worst) < 5e-7
+    assert (worst > TOL).sum() == 0 and np.median(worst) < 5e-7
 
 
 def test_the_two_contact_models_differ_and_share_the_free_flight():
@@ -191,5 +191,5 @@ def test_n8192_t1000_return_statistics():
     print("newton returns: GPU mean %.3f sd %.2f | oracle mean %.3f sd %.2f | diff %.3f (%.2f %%), s.e. %.3f"
           % (gm, g_ret.std(), om, o_ret.std(), gm - om, 100 * abs(gm - om) / abs(om), se))
     assert abs(gm - om) <= 0.01 * abs(om)
-    assert abs(g_ret.std() - o_ret.std()) <= 0.05 * o_ret.std()
+    assert abs(g_ret.std() - o_ret.std()) <= 0.01 * o_ret.std()
     assert abs(st["return_sum"] / n - gm) < 1e-2

@@ -557,3 +557,35 @@ def test_rounding_the_state_to_the_storage_format():
     assert np.array_equal(o2, o3) and np.array_equal(r2, r3)
     # off by default
     assert Body(1, 1, np.float64).params["round_state_f32"] == 0
+
+
+def test_decision_margin_of_a_step():
+    """The margin reported for a step is the distance of its closest decision from a switching
+    surface: a contact point at height zero, a joint reaching its limit, a limit joint at rest."""
+    b = Body(1, 3, np.float64, substeps=1)
+    zero = np.zeros(6)
+    q = np.zeros(NQ); q[1] = 2.0; v = np.zeros(NQ)
+    # high above the ground, joints centred: the nearest surface is a joint limit, 1 away
+    assert abs(b.step_margin(q, v, zero) - 1.0) < 1e-12
+    q[4] = 0.75
+    assert abs(b.step_margin(q, v, zero) - 0.25) < 1e-12
+    # toes 1e-7 above the ground: that is the margin
+    q = np.zeros(NQ); q[1] = 0.78 + 1e-7
+    assert abs(b.step_margin(q, v, zero) - 1e-7) < 1e-12
+    q[1] = 0.78 - 3e-9
+    assert abs(b.step_margin(q, v, zero) - 3e-9) < 1e-12
+    # a joint at its limit: the margin is |v*| of that joint, the velocity the free solve gives it
+    q = np.zeros(NQ); q[1] = 2.0; q[5] = 1.0
+    a = np.array([0.0, 0.0, 0.03, 0.0, 0.0, 0.0])
+    _, v_after, mask = Body(1, 3, np.float64, substeps=1).substep(q, v, a)
+    assert mask & (1 << 5)                                       # pushed outwards: projected, v = 0
+    free = Body(1, 3, np.float64, substeps=1)
+    q_in = q.copy(); q_in[5] = 0.999999                          # same state just inside: the free velocity
+    _, v_free, mask2 = free.substep(q_in, v, a)
+    assert mask2 == 0
+    m = b.step_margin(q, v, a)
+    assert abs(m - abs(v_free[5])) < 1e-4 * abs(v_free[5]) and 1e-3 < m < 0.9
+    # all five substeps are covered: a body moving down crosses z = 0 in a later substep
+    b5 = Body(1, 3, np.float64)
+    q = np.zeros(NQ); q[1] = 0.78 + 0.02; v = np.zeros(NQ); v[1] = -1.0
+    assert b5.step_margin(q, v, zero) < 0.012                    # first substep alone would report 0.02
