@@ -30,6 +30,7 @@ CARTPOLE_BYTES_PER_ENV_STEP = 21   # 16 obs + 4 reward + 1 done
 CARTPOLE_VALU_PER_ENV_STEP = 209   # vector instructions in the step loop of the kernel ISA (35 of them quarter-rate integer multiplies)
 VALU_PEAK_TINSTR = 39.3            # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, lane-instructions per second / 1e12
 FRAME_BYTES = 84 * 84          # one new frame per env-step
+FP32_PEAK_TFLOPS = 157.3       # MI355X vector float32, packed operations counted
 FP64_PEAK_TFLOPS = 78.6        # MI355X vector float64 (256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz)
 BODY_NEWTON_FLOP_PER_ENV_STEP = 13540   # 5 substeps x (1526 outside the Newton loop + 1.05 solves per environment x 1126), counted in the kernel ISA; a wavefront executes max-over-lanes solves (3.0 on average), which is not counted as useful work
 BODY_FLOP_PER_ENV_STEP = 9400   # 5 substeps x 1876 float64 flops (FMA = 2), counted in the substep loop of the kernel ISA
@@ -347,9 +348,14 @@ def bench_copy(b, torch, nbytes, launches=20):
                 gbs_each_way=nbytes / (mean_ms * 1e-3) / 1e9)
 
 
-def bench_body(b, torch, n, T, seed, steps, newton=False):
+def bench_body(b, torch, n, T, seed, steps, newton=False, f32=False):
     dev = "cuda:0"
-    h = b.env_create(b.ENV_BODY, n, seed, {"contact_solver": b.ENV_CONTACT_NEWTON} if newton else None)
+    cfg = {}
+    if newton:
+        cfg["contact_solver"] = b.ENV_CONTACT_NEWTON
+    if f32:
+        cfg["body_arithmetic"] = b.ENV_BODY_F32
+    h = b.env_create(b.ENV_BODY, n, seed, cfg or None)
     obs = torch.empty((T, n, 17), dtype=torch.float32, device=dev)
     rew = torch.empty((T, n), dtype=torch.float32, device=dev)
     done = torch.empty((T, n), dtype=torch.uint8, device=dev)
@@ -358,6 +364,19 @@ def bench_body(b, torch, n, T, seed, steps, newton=False):
     st = b.env_stats(h)
     b.env_destroy(h)
     mean_ms, std_ms = _mean_std(ms)
+    if f32:
+        # the same flops in float32, against the published float32 vector peak (which assumes packed
+        # operations; they are switched off in this build, so the unpacked issue rate, half of it, is
+        # the ceiling this code can reach)
+        per = BODY_NEWTON_FLOP_PER_ENV_STEP if newton else BODY_FLOP_PER_ENV_STEP
+        flops = per * n * T / (mean_ms * 1e-3) / 1e12
+        return dict(workload="articulated body%s, float32 arithmetic (opt-in), N=%d x T=%d fused rollout"
+                             % (", Newton contact model" if newton else "", n, T),
+                    dtype="f32", env_steps_per_s=n * T * steps / wall, ms_per_launch=mean_ms,
+                    nonfinite=st["nonfinite"], episodes=st["episodes"],
+                    roofline=dict(bound="alu", achieved=flops, peak=FP32_PEAK_TFLOPS, unit="TFLOP/s",
+                                  frac=flops / FP32_PEAK_TFLOPS, frac_of_unpacked_rate=flops / FP64_PEAK_TFLOPS,
+                                  traffic=None))
     if newton:
         flops = BODY_NEWTON_FLOP_PER_ENV_STEP * n * T / (mean_ms * 1e-3) / 1e12
         return dict(workload="articulated body, Newton contact model, N=%d x T=%d fused rollout" % (n, T),
@@ -574,6 +593,8 @@ def main():
               "pixels_large": lambda: [bench_pixels(b, torch, 32768, 3, args.steps),
                                        bench_pixels(b, torch, 262144, 3, max(20, args.steps // 5))],
               "body": lambda: bench_body(b, torch, 8192, 1000, 4, args.steps),
+              "body_f32": lambda: [bench_body(b, torch, 8192, 1000, 4, args.steps, f32=True),
+                                   bench_body(b, torch, 262144, 100, 4, args.steps, f32=True)],
               "body_sweep": lambda: bench_body_sweep(b, torch, args.steps),
               "body_newton": lambda: [bench_body(b, torch, 8192, 1000, 4, args.steps, newton=True),
                                       bench_body(b, torch, 262144, 100, 4, args.steps, newton=True)],
@@ -652,6 +673,8 @@ def main():
         extra["config4_body"] = bench_body(b, torch, 8192, 1000, 4, 2)
         extra["config4_body_n262144_t100"] = bench_body(b, torch, 262144, 100, 4, 2)
         extra["body_newton_n8192_t1000"] = bench_body(b, torch, 8192, 1000, 4, 2, newton=True)
+        extra["config4_body_f32"] = bench_body(b, torch, 8192, 1000, 4, 2, f32=True)
+        extra["config4_body_f32_n262144_t100"] = bench_body(b, torch, 262144, 100, 4, 2, f32=True)
         extra["cartpole_n65536_t1000"] = bench_cartpole(b, torch, 65536, 1000, 2, 5)
         extra["external_actions_n65536_t1000"] = bench_external_actions(b, torch, 65536, 1000, 5)
         extra["policy_in_loop_mlp_n4096"] = bench_policy_loop(b, torch, 4096, "mlp", 2000, 50)

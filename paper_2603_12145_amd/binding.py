@@ -12,6 +12,7 @@ ENV_STEP_COUNTER_HOST, ENV_STEP_COUNTER_DEVICE = 1, 2
 ENV_OBS_RAW, ENV_OBS_NORMALIZED = 1, 2
 ENV_CONTACT_PENALTY, ENV_CONTACT_NEWTON = 1, 2
 ENV_PIXELS_FULL, ENV_PIXELS_DELTA = 1, 2
+ENV_BODY_F64, ENV_BODY_F32 = 1, 2
 ENV_OK, ENV_E_ARG, ENV_E_ALLOC, ENV_E_HIP, ENV_E_STATE, ENV_E_UNSUPPORTED, ENV_E_TOO_LARGE = 0, -1, -2, -3, -4, -5, -6
 ENV_NOALLOC_MAX_ENVS = 65536
 
@@ -26,7 +27,7 @@ class env_config_t(C.Structure):
                 ("joint_damping", C.c_float), ("friction_mu", C.c_float),
                 ("pixel_layout", C.c_int32), ("step_counter", C.c_int32),
                 ("obs_scaling", C.c_int32), ("contact_solver", C.c_int32),
-                ("pixel_update", C.c_int32)]
+                ("pixel_update", C.c_int32), ("body_arithmetic", C.c_int32)]
 
 
 class env_stats_t(C.Structure):
@@ -105,7 +106,7 @@ def env_create(kind, n_envs, seed, cfg=None, stream=None):
     if cfg is not None:
         c = env_config_t(struct_size=C.sizeof(env_config_t), max_score=0, max_episode_steps=0,
                          armature=-1.0, joint_damping=-1.0, friction_mu=-1.0, pixel_layout=0,
-                         step_counter=0, obs_scaling=0, contact_solver=0, pixel_update=0)
+                         step_counter=0, obs_scaling=0, contact_solver=0, pixel_update=0, body_arithmetic=0)
         for k, v in cfg.items():
             setattr(c, k, v)
     s = torch.cuda.current_stream() if stream is None else stream

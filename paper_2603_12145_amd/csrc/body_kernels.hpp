@@ -27,6 +27,7 @@ struct BodyLaunch {
   int32_t max_episode_steps;
   float armature, joint_damping, friction_mu;
   int32_t newton;        // contact model: 0 penalty spring + limit projection, 1 Newton on the soft-constraint QP
+  int32_t f32;           // arithmetic inside a step: 0 float64 (default), 1 float32
   const float* actions;  // [T,n,6] or nullptr
   float* obs;            // [T,n,17]
   float* reward;         // [T,n]

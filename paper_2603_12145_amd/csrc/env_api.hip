@@ -69,6 +69,7 @@ env_config_t default_config(int kind) {
   c.obs_scaling = ENV_OBS_RAW;
   c.contact_solver = ENV_CONTACT_PENALTY;
   c.pixel_update = ENV_PIXELS_FULL;
+  c.body_arithmetic = ENV_BODY_F64;
   (void)kind;
   return c;
 }
@@ -110,6 +111,10 @@ int merge_config(env_config_t* dst, const env_config_t* src) {
   if (sz >= FIELD_END(env_config_t, pixel_update) && src->pixel_update != 0) {
     if (src->pixel_update != ENV_PIXELS_FULL && src->pixel_update != ENV_PIXELS_DELTA) return ENV_E_ARG;
     dst->pixel_update = src->pixel_update;
+  }
+  if (sz >= FIELD_END(env_config_t, body_arithmetic) && src->body_arithmetic != 0) {
+    if (src->body_arithmetic != ENV_BODY_F64 && src->body_arithmetic != ENV_BODY_F32) return ENV_E_ARG;
+    dst->body_arithmetic = src->body_arithmetic;
   }
   if (!std::isfinite(dst->armature) || !std::isfinite(dst->joint_damping) ||
       !std::isfinite(dst->friction_mu))
@@ -225,6 +230,7 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
     b.armature = e->cfg.armature; b.joint_damping = e->cfg.joint_damping;
     b.friction_mu = e->cfg.friction_mu;
     b.newton = e->cfg.contact_solver == ENV_CONTACT_NEWTON;
+    b.f32 = e->cfg.body_arithmetic == ENV_BODY_F32;
     b.actions = static_cast<const float*>(actions);
     b.obs = static_cast<float*>(obs); b.reward = reward; b.done = done; b.stats = e->stats;
     err = launch_body_rollout(b, e->stream);
@@ -285,6 +291,7 @@ int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_c
   if (merge_config(&c, cfg) != ENV_OK) return ENV_E_ARG;
   if (c.obs_scaling == ENV_OBS_NORMALIZED && kind != ENV_PONG) return ENV_E_UNSUPPORTED;
   if (c.contact_solver == ENV_CONTACT_NEWTON && kind != ENV_BODY) return ENV_E_UNSUPPORTED;
+  if (c.body_arithmetic == ENV_BODY_F32 && kind != ENV_BODY) return ENV_E_UNSUPPORTED;
   if (kind == ENV_PONG_PIXELS && c.pixel_layout == ENV_PIXELS_ORDERED) c.pixel_update = ENV_PIXELS_DELTA;
   if (c.pixel_update == ENV_PIXELS_DELTA && kind != ENV_PONG_PIXELS) return ENV_E_UNSUPPORTED;
 

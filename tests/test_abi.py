@@ -85,7 +85,7 @@ def test_argument_errors_without_gpu(L):
 
 def test_binding_struct_layout_matches_header():
     from paper_2603_12145_amd import binding as b
-    assert C.sizeof(b.env_config_t) == 44
+    assert C.sizeof(b.env_config_t) == 48
     assert C.sizeof(b.env_stats_t) == 48
     hdr = open(HEADER).read()
     cfg = re.search(r"typedef struct env_config_t \{(.*?)\} env_config_t;", hdr, re.S).group(1)
