@@ -30,3 +30,24 @@ def _default_tuning(request):
     L.mi355env_tune_pixels(0, 0)
     L.mi355env_tune_frame_trajectory(2)
     L.mi355env_tune_plane_path(2)
+
+
+@pytest.fixture
+def l3_report(request):
+    """Collects one row per workload of the level-3 rollout comparison; the rows are printed as one
+    table at the end of the session (below), whether or not output capture is on."""
+    rows = request.config.__dict__.setdefault("_l3_rows", [])
+    return rows.append
+
+
+def pytest_terminal_summary(terminalreporter, exitstatus, config):
+    rows = getattr(config, "_l3_rows", None)
+    if not rows:
+        return
+    tr = terminalreporter
+    tr.section("level-3 rollout comparison: HIP path vs CPU oracle, matched seeds and actions")
+    head = ("workload", "mode", "episodes", "env-steps", "max error", "result")
+    table = [head] + [tuple(str(r[k]) for k in head) for r in rows]
+    width = [max(len(row[c]) for row in table) for c in range(len(head))]
+    for row in table:
+        tr.write_line("  ".join(cell.ljust(w) for cell, w in zip(row, width)))

@@ -39,7 +39,7 @@ def _gpu(kind, n, seed, T, cfg, actions, obs_dim, act_dtype):
         b.env_destroy(h)
 
 
-def test_l3_pong_100_episodes_exact():
+def test_l3_pong_100_episodes_exact(l3_report):
     n, seed, T = EPISODES, 101, 12000
     acts = inputs.pong_actions(T, n, seed=7)
     p = orc.Pong(n, seed)
@@ -54,9 +54,11 @@ def test_l3_pong_100_episodes_exact():
     ost = p.stats()
     assert st["episodes"] == ost["episodes"] >= EPISODES and st["return_sum"] == ost["return_sum"]
     print("L3 Pong: %d episodes, %d env-steps compared, all outputs identical" % (st["episodes"], n * T))
+    l3_report({"workload": "Pong (vector obs)", "mode": "exact", "episodes": st["episodes"], "env-steps": n * T,
+               "max error": "0 (bit-identical)", "result": "obs, reward, done identical at every timestep"})
 
 
-def test_l3_cartpole_100_episodes_exact():
+def test_l3_cartpole_100_episodes_exact(l3_report):
     n, seed, T = EPISODES, 102, 700
     acts = inputs.cartpole_actions(T, n, seed=8)
     p = CartPole(n, seed)
@@ -70,10 +72,23 @@ def test_l3_cartpole_100_episodes_exact():
     assert_bit_equal(gd, od, "L3 CartPole done")
     assert st["episodes"] == p.stats()["episodes"] >= EPISODES
     print("L3 CartPole: %d episodes, all outputs identical" % st["episodes"])
+    l3_report({"workload": "CartPole", "mode": "exact", "episodes": st["episodes"], "env-steps": n * T,
+               "max error": "0 (bit-identical)", "result": "obs, reward, done identical at every timestep"})
 
 
-def test_l3_body_100_episodes_epsilon():
-    """Body, one full 1000-step episode per index, identical actions.
+# Free-running episodes (never resynchronised): the first step at which an episode leaves the
+# epsilon = 1e-3 band.  Measured: penalty contact, median step 48 (28 ... 87); Newton contact, median
+# step 84 (40 ... 358); no episode of either model stays inside the band for 1000 steps -- a
+# last-bit difference grows by a contact switch (penalty) or along the chaotic motion itself
+# (Newton), in the kernel and between the oracle's own float32 and float64 forms alike.  The
+# assertions hold the measured figures within the ranges below.
+FREE_RUN = {0: dict(name="penalty", median_first=(30, 80), within=(0, 3)),
+            1: dict(name="newton", median_first=(50, 140), within=(0, 3))}
+
+
+@pytest.mark.parametrize("solver", [0, 1], ids=["penalty", "newton"])
+def test_l3_body_100_episodes_epsilon(solver, l3_report):
+    """Body, one full 1000-step episode per index, identical actions, both contact models.
 
     (a) Step-level comparison along the reference's trajectory: at every timestep the performance
         side is handed the reference's state (float32, as the reference keeps it between steps) and
@@ -85,12 +100,13 @@ def test_l3_body_100_episodes_epsilon():
         decision flips; reported, and the episode returns must agree in distribution."""
     n, seed, T = EPISODES, 103, 1000
     acts = inputs.body_actions(T, n, seed=9, scale=1.0)
-    ref = Body(n, seed, np.float64, round_state_f32=1)
+    ref = Body(n, seed, np.float64, round_state_f32=1, solver=solver)
     ref.reset()
     s0 = ref.get_state()
+    cfg = {"contact_solver": b.ENV_CONTACT_NEWTON} if solver else None
 
-    h = b.env_create(b.ENV_BODY, n, seed, None)        # stepped from the reference's states
-    free = b.env_create(b.ENV_BODY, n, seed, None)     # (b): set once, then left alone
+    h = b.env_create(b.ENV_BODY, n, seed, cfg)         # stepped from the reference's states
+    free = b.env_create(b.ENV_BODY, n, seed, cfg)      # (b): set once, then left alone
     try:
         act = torch.from_numpy(acts).to(DEV)
         o1 = torch.empty((n, 17), dtype=torch.float32, device=DEV)
@@ -131,8 +147,11 @@ def test_l3_body_100_episodes_epsilon():
     print("L3 body, step error from the reference's states over %d env-steps: median %.2e, 99.9%% %.2e, max %.2e; "
           "beyond 1e-5: %d, beyond 1e-3: %d" % (w.size, np.median(w), np.quantile(w, 0.999), w.max(),
                                                  int((w > 1e-5).sum()), int((w > 1e-3).sum())))
-    assert (w > 1e-3).sum() <= w.size // 10000          # epsilon of the paper's L3 for this workload
-    assert (w > 1e-5).sum() <= w.size // 1000 and np.median(w) < 5e-7
+    assert (w > 1e-3).sum() == 0                        # epsilon of the paper's L3 for this workload
+    assert (w > 1e-5).sum() == 0 and np.median(w) < 5e-7
+    l3_report({"workload": "body, %s contact, along the reference trajectory" % FREE_RUN[solver]["name"],
+               "mode": "eps = 1e-3", "episodes": n, "env-steps": w.size, "max error": "%.1e" % w.max(),
+               "result": "every step within 1e-5 (state handed over before each step)"})
     assert np.array_equal(gd, od) and st["episodes"] == n and st["nonfinite"] == 0
 
     err = rel_err(go[:T - 1], oo[:T - 1]).max(axis=2)                  # free-running, [T-1, n]
@@ -140,8 +159,16 @@ def test_l3_body_100_episodes_epsilon():
     print("L3 body, free-running: first step beyond 1e-3 per episode: min %d, median %d, max %d; "
           "episodes within 1e-3 for all 1000 steps: %d of %d"
           % (first.min(), int(np.median(first)), first.max(), int((first == T).sum()), n))
-    assert np.median(first) >= 20
+    lo, hi = FREE_RUN[solver]["median_first"]
+    assert lo <= int(np.median(first)) <= hi
+    lo, hi = FREE_RUN[solver]["within"]
+    assert lo <= int((first == T).sum()) <= hi
     g_ret, o_ret = gr.sum(axis=0), orr.sum(axis=0)
+    l3_report({"workload": "body, %s contact, free-running" % FREE_RUN[solver]["name"], "mode": "eps = 1e-3",
+               "episodes": n, "env-steps": err.size, "max error": "%.1e" % err.max(),
+               "result": "%d of %d episodes within eps for all steps; first step beyond it: median %d; "
+                         "returns %.1f vs %.1f" % (int((first == T).sum()), n, int(np.median(first)),
+                                                   g_ret.mean(), o_ret.mean())})
     print("L3 body, episode returns: GPU mean %.2f (sd %.2f), reference mean %.2f (sd %.2f)"
           % (g_ret.mean(), g_ret.std(), o_ret.mean(), o_ret.std()))
     pooled = np.sqrt((g_ret.var(ddof=1) + o_ret.var(ddof=1)) / n)
