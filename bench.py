@@ -136,10 +136,13 @@ def bench_pong_rollout(b, torch, n, T, seed, steps, warmup, repeats=1):
     stats = b.env_stats(h)
     b.env_destroy(h)
     del obs, rew, done
+    import ctypes as C
+    b.lib().mi355env_pace_choice.argtypes = [C.c_int64]
+    pace = b.lib().mi355env_pace_choice(n)          # what the library measured for this batch size, if anything
     wall, ms = regions[0]
     mean_ms, std_ms = _mean_std(ms)
     return dict(wall=wall, mean_ms=mean_ms, std_ms=std_ms, min_ms=min(ms), max_ms=max(ms),
-                env_steps=n * T * steps, episodes=stats["episodes"],
+                env_steps=n * T * steps, episodes=stats["episodes"], pace_choice_gbs=pace,
                 runs=[dict(env_steps_per_s=n * T * steps / w, launch_ms_mean=_mean_std(m)[0]) for w, m in regions])
 
 
@@ -636,7 +639,10 @@ def main():
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
                      "kernel": "pong_rollout_kernel", "launch_ms_mean": r["mean_ms"],
                      "launch_ms_std": r["std_ms"], "launch_ms_cv": r["std_ms"] / r["mean_ms"],
-                     "algorithmic_bytes_per_launch": PONG_BYTES_PER_ENV_STEP * n * T},
+                     "algorithmic_bytes_per_launch": PONG_BYTES_PER_ENV_STEP * n * T,
+                     # the library's own one-time measurement for this batch size on this device: the write rate
+                     # its paced loop is held to (GB/s), -1 = the plain loop won, 0 = nothing measured
+                     "pace_choice_gbs": r["pace_choice_gbs"]},
         # the paper's throughput protocol (Table 2 caption): mean +- std over five runs, CV below 3 %.
         # `value` is the first of them; the other four follow it back to back.
         "runs": {"n": len(run_values), "steps_each": args.steps, "env_steps_per_s": run_values,
@@ -667,7 +673,7 @@ def main():
         for nn in (16384, 262144):
             rr = bench_pong_rollout(b, torch, nn, T, seed, max(3, args.steps // 6), 3)
             gbs = PONG_BYTES_PER_ENV_STEP * nn * T / (rr["mean_ms"] * 1e-3) / 1e9
-            extra["config2_n%d" % nn] = dict(env_steps_per_s=rr["env_steps"] / rr["wall"],
+            extra["config2_n%d" % nn] = dict(env_steps_per_s=rr["env_steps"] / rr["wall"], pace_choice_gbs=rr["pace_choice_gbs"],
                                              ms_per_launch=rr["mean_ms"], ms_min=rr["min_ms"],
                                              ms_max=rr["max_ms"], hbm_gbs=gbs, frac=gbs / HBM_PEAK_GBS)
         extra["config4_body"] = bench_body(b, torch, 8192, 1000, 4, 2)

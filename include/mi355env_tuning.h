@@ -38,11 +38,21 @@ int mi355env_tune_rollout_split(int mode);
 /* Pacing of the same loop.  gb_per_s > 0: every full wavefront runs the paced loop (two steps per
  * chunk, episode statistics brought up to date once per chunk instead of in every step) and starts
  * a chunk no sooner than 2 * N * 37 B / gb_per_s after the previous one, by the constant 100 MHz
- * clock, whatever N; 0 = chosen from N (default: paced at 6600 GB/s for N = 61440 ... 65536, at
- * 5800 GB/s up to N = 131072, at 5600 GB/s up to N = 262144, not paced elsewhere; with
- * external actions paced for N = 98305 ... 262144 only, eight steps per chunk); -1 = never paced.
+ * clock, whatever N; 0 = chosen by the library (default), -1 = never paced.  The library's choice
+ * for N = 61440 ... 262144: the first env_rollout of at least 256 steps for a batch size on a
+ * device measures, on scratch state, the plain loop against the paced loop at a few rates around
+ * a table's (6600 GB/s up to N = 65536, 5800 up to 131072, 5600 up to 262144) and keeps the fastest
+ * for the rest of the process, the paced loop only if it wins by 1 % (about 60 ms, once; that call
+ * synchronises the stream); shorter rollouts and calls under stream capture use the table; other
+ * batch sizes are never paced; with external actions only N = 98305 ... 262144 is.
  * Results are identical. */
 int mi355env_tune_rollout_pace(int gb_per_s);
+
+/* 1 (default) = measure as just described, 0 = always take the table's rate. */
+int mi355env_tune_measure_pace(int on);
+/* What the measurement found for n environments on the current device: the rate in GB/s, -1 = not
+ * paced, 0 = nothing measured yet for that batch size. */
+int mi355env_pace_choice(int64_t n);
 
 /* Pong rollout observation stores: 0 = direct (two 16-byte stores per lane), 1 = through LDS, one
  * 4 KiB page per store instruction, wherever a 256-thread workgroup is full, 2 = chosen from N

@@ -20,6 +20,8 @@ bool set_pixel_tuning(int envs_per_wave, int streaming);
 bool set_rollout_block(int threads, int xcd_remap);
 bool set_rollout_chunk(int steps);
 bool set_rollout_pace(int gb_per_s);
+bool set_measure_pace(int on);
+int pong_pace_choice(int64_t n);
 bool set_rollout_split(int mode);
 bool set_paged_stores(int mode);
 bool set_traj_mode(int mode);
@@ -41,6 +43,8 @@ struct mi355env {
   StepCounter* counter;   // device, behind stats in the same allocation
   bool device_counter;    // launches read and advance `counter` instead of taking `step` as an argument
   PixelPipe pipe;         // pixels only: second state buffer and the staging buffers of the lookahead
+  uint32_t* trial_state;  // Pong, batch sizes that may run paced: scratch for the launcher's one-time
+  DeviceStats* trial_stats;   // measurement (a second state array and statistics block), else null
   bool was_reset;
   // last device ranges that passed the residency check (avoids a driver query per step)
   struct Range { const void* p; size_t bytes; } seen[8];
@@ -244,6 +248,7 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
     p.actions = static_cast<const uint8_t*>(actions);
     p.obs = static_cast<float*>(obs); p.reward = reward; p.done = done; p.stats = e->stats;
     if (e->kind == ENV_PONG) {
+      p.trial_state = e->trial_state; p.trial_stats = e->trial_stats;
       err = launch_pong_rollout(p, e->stream);
     } else if (e->kind == ENV_CARTPOLE) {
       p.max_score = e->cfg.max_episode_steps;
@@ -301,6 +306,7 @@ int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_c
   e->stream = static_cast<hipStream_t>(hip_stream);
   e->cfg = c; e->fields = fields_of(kind); e->was_reset = false;
   e->state = nullptr; e->stats = nullptr; e->counter = nullptr; e->seen_next = 0;
+  e->trial_state = nullptr; e->trial_stats = nullptr;
   e->device_counter = c.step_counter == ENV_STEP_COUNTER_DEVICE;
   for (auto& r : e->seen) r = {nullptr, 0};
   if (hipGetDevice(&e->device) != hipSuccess) { delete e; return ENV_E_HIP; }
@@ -320,12 +326,21 @@ int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_c
     return ENV_E_ALLOC;
   }
   e->counter = reinterpret_cast<StepCounter*>(e->stats + STATS_STRIPES);
+  if (kind == ENV_PONG && n_envs >= PACED_MIN_ENVS && n_envs <= PACED_MAX_ENVS) {
+    // one allocation: the trial statistics behind the trial state
+    const size_t sb = (state_bytes + 255) & ~(size_t)255;
+    if (hipMalloc(reinterpret_cast<void**>(&e->trial_state), sb + STATS_STRIPES * sizeof(DeviceStats)) != hipSuccess) {
+      (void)hipGetLastError(); (void)hipFree(e->state); (void)hipFree(e->stats); delete e;
+      return ENV_E_ALLOC;
+    }
+    e->trial_stats = reinterpret_cast<DeviceStats*>(reinterpret_cast<char*>(e->trial_state) + sb);
+  }
   const EmptyStats z;
   if (hipMemsetAsync(e->state, 0, state_bytes, e->stream) != hipSuccess ||
       hipMemsetAsync(e->counter, 0, sizeof(StepCounter), e->stream) != hipSuccess ||
       hipMemcpyAsync(e->stats, z.stripes, sizeof z.stripes, hipMemcpyHostToDevice, e->stream) != hipSuccess ||
       hipStreamSynchronize(e->stream) != hipSuccess) {
-    (void)hipGetLastError(); (void)hipFree(e->state); (void)hipFree(e->stats);
+    (void)hipGetLastError(); (void)hipFree(e->state); (void)hipFree(e->stats); (void)hipFree(e->trial_state);
     pixel_pipe_destroy(e->pipe); delete e;
     return ENV_E_HIP;
   }
@@ -338,6 +353,7 @@ void env_destroy(env_t* e) {
   (void)hipStreamSynchronize(e->stream);
   (void)hipFree(e->state_alloc);
   (void)hipFree(e->stats);
+  (void)hipFree(e->trial_state);
   pixel_pipe_destroy(e->pipe);
   delete e;
 }
@@ -572,6 +588,13 @@ int mi355env_tune_rollout_split(int mode) { return set_rollout_split(mode) ? ENV
 // Pong rollout pacing: the write rate (GB/s) the paced loop holds the launch to; forces that loop
 // for any N.  0 = chosen from N, -1 = never paced.
 int mi355env_tune_rollout_pace(int gb_per_s) { return set_rollout_pace(gb_per_s) ? ENV_OK : ENV_E_ARG; }
+
+// 1 = whether the Pong rollout is paced, and at which rate, is measured once per device and batch
+// size (default), 0 = taken from the launcher's table.
+int mi355env_tune_measure_pace(int on) { return set_measure_pace(on) ? ENV_OK : ENV_E_ARG; }
+
+// What was measured for n environments on the current device: GB/s, -1 = not paced, 0 = nothing yet.
+int mi355env_pace_choice(int64_t n) { return pong_pace_choice(n); }
 
 // 0 = direct observation stores, 1 = paged through LDS wherever a workgroup is full, 2 = by N.
 int mi355env_tune_paged_stores(int mode) { return set_paged_stores(mode) ? ENV_OK : ENV_E_ARG; }

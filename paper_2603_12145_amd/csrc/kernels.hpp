@@ -31,7 +31,16 @@ struct PongLaunch {
   int32_t pace;           // set by the launcher (paced loop): least time between two chunks, in 1/256 of 10 ns
   int32_t normalize;      // Pong vector obs only: 1 = scale every component at the source
   float inv_score;        // 1 / max_score in float32 (used when normalize)
+  // Scratch of the handle for the launcher's one-time choice between the paced and the plain loop
+  // (null: no measurement, the launcher's table decides): a second state array [10][n] and a second
+  // statistics block, so that the timed launches touch nothing the caller can see but the output
+  // buffers, which the real launch then overwrites.
+  uint32_t* trial_state;
+  DeviceStats* trial_stats;
 };
+
+// Batch sizes for which the Pong rollout may run paced (see launch_pong_rollout)
+constexpr int64_t PACED_MIN_ENVS = 61440, PACED_MAX_ENVS = 262144;
 
 // reset launchers: counter != nullptr -> the step is read from it instead of `step`
 hipError_t launch_pong_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,

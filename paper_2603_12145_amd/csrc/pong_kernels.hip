@@ -9,6 +9,8 @@
 #include "kernels.hpp"
 #include "pong_device.hpp"
 
+#include <mutex>
+
 namespace envk {
 
 namespace {
@@ -226,7 +228,10 @@ enum RolloutVariant {
   V_NORMALIZED_PACED           // normalised observations in the paced loop
 };
 
-template <int VARIANT>
+// TRIAL changes nothing but the kernel's name: the launches with which the launcher measures, once
+// per device and batch size, whether pacing pays (see launch_pong_rollout) show up on their own
+// line in a kernel trace instead of being mixed with the launches a caller asked for.
+template <int VARIANT, bool TRIAL = false>
 __global__ __launch_bounds__(256) void pong_rollout_kernel(PongLaunch a) {
   a.step0 = launch_first_step(a.counter, a.step0, a.T, a.ticket != 0);
   const int lane = threadIdx.x & (WAVE - 1);
@@ -368,6 +373,7 @@ int g_paged_mode = 2;      // 0 never, 1 whenever possible, 2 = choose from N
 int g_xcd_remap = 1;
 int g_rollout_chunk = 0;   // 0 = choose from N
 int g_rollout_pace = 0;    // GB/s the paced variant keeps the write stream to; 0 = choose from N, -1 = never paced
+int g_measure_pace = 1;    // 1 = measure once per device and batch size whether pacing pays, 0 = the table decides
 
 }  // namespace
 
@@ -404,11 +410,160 @@ bool set_rollout_pace(int gb_per_s) {
   return true;
 }
 
+bool set_measure_pace(int on) {
+  if (on != 0 && on != 1) return false;
+  g_measure_pace = on;
+  return true;
+}
+
 bool set_rollout_block(int threads, int xcd_remap) {
   if (threads != 0 && threads != 64 && threads != 128 && threads != 256) return false;
   g_rollout_block = threads;
   g_xcd_remap = xcd_remap;
   return true;
+}
+
+namespace {
+
+// Time per chunk of the paced loops, in 1/256 of a tick of the constant clock (100 MHz on this
+// device; asked of the runtime rather than assumed).
+int32_t pace_period(int64_t n, int rate_gb_per_s, double rows) {
+  static int khz_of_device[64] = {};                       // asked once per device
+  int dev = 0, khz = 0;
+  if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); dev = -1; }
+  if (dev >= 0 && dev < 64) khz = khz_of_device[dev];
+  if (khz <= 0) {
+    if (dev < 0 || hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0) {
+      (void)hipGetLastError();
+      khz = 100000;
+    }
+    if (dev >= 0 && dev < 64) khz_of_device[dev] = khz;
+  }
+  const double q = rows * (double)n * 37.0 / ((double)rate_gb_per_s * 1e9) * ((double)khz * 1e3) * 256.0;
+  return q < 1073741824.0 ? (int32_t)q : 1073741824;       // 32-bit clock arithmetic in the kernel
+}
+
+// The launcher's table: the rate (GB/s) the paced loop is held to for a batch of n, -1 = not paced.
+int table_rate(int64_t n) {
+  return n < PACED_MIN_ENVS || n > PACED_MAX_ENVS ? -1 : n <= 65536 ? 6600 : n <= 131072 ? 5800 : 5600;
+}
+
+template <bool TRIAL>
+void dispatch_variant(int variant, dim3 g, dim3 b, hipStream_t stream, const PongLaunch& a2) {
+  switch (variant) {
+    case V_RAW_2: hipLaunchKernelGGL((pong_rollout_kernel<V_RAW_2, TRIAL>), g, b, 0, stream, a2); break;
+    case V_RAW_4: hipLaunchKernelGGL((pong_rollout_kernel<V_RAW_4, TRIAL>), g, b, 0, stream, a2); break;
+    case V_RAW_8: hipLaunchKernelGGL((pong_rollout_kernel<V_RAW_8, TRIAL>), g, b, 0, stream, a2); break;
+    case V_PACED: hipLaunchKernelGGL((pong_rollout_kernel<V_PACED, TRIAL>), g, b, 0, stream, a2); break;
+    case V_PAGED: hipLaunchKernelGGL((pong_rollout_kernel<V_PAGED, TRIAL>), g, b, 0, stream, a2); break;
+    default: break;
+  }
+}
+
+// What the measurement below found for (device, n): rate > 0 paced at that rate, -1 not paced.
+struct PaceChoice { int device; int64_t n; int rate; };
+std::mutex g_choice_mutex;
+PaceChoice g_choices[32] = {};
+int g_choices_used = 0;
+
+bool known_choice(int device, int64_t n, int* rate) {
+  std::lock_guard<std::mutex> lock(g_choice_mutex);
+  for (int k = 0; k < g_choices_used; ++k)
+    if (g_choices[k].device == device && g_choices[k].n == n) { *rate = g_choices[k].rate; return true; }
+  return false;
+}
+
+void remember_choice(int device, int64_t n, int rate) {
+  std::lock_guard<std::mutex> lock(g_choice_mutex);
+  if (g_choices_used < 32) g_choices[g_choices_used++] = {device, n, rate};
+}
+
+// Paced or not, and at which rate: measured once per device and batch size, on the handle's trial
+// state, with the loops themselves.  The table's rates were found on a few devices of one pool, a
+// rate above what the memory system of the device at hand drains is worse than no pacing at all,
+// and a launch that has fallen behind its schedule does not recover -- so the table is only the
+// starting point: the plain loop and the paced loop at the table's rate and at rates 4 and 8 %
+// below it (and 4 % above, where the loop's own pace is not the limit) each run a launch of the
+// caller's length a few times and the fastest wins; the paced loop has to beat the plain one by 1 % to be chosen.  The
+// device runs on lower clocks for some 30 ms after any idle period, during which the plain loop
+// looks better than it is, so the trials are preceded by 50 ms of the paced loop itself.  All of
+// it writes to the caller's output buffers (rows the real launch overwrites right afterwards),
+// to the trial state and the trial statistics: nothing of it is visible afterwards.  Costs 70 to
+// 120 ms, once; returns the table's rate without measuring when the launch is too short to matter,
+// when the stream is being captured, or when anything fails.
+int measured_rate(const PongLaunch& a, dim3 g, dim3 b, hipStream_t stream) {
+  const int fallback = table_rate(a.n);
+  // as long as the caller's own launch, up to 1024 steps: the plain loop's wavefronts drift apart as
+  // a launch goes on, so short trials flatter it (N = 61440: 256-step trials picked the plain loop,
+  // which then ran the caller's 1000 steps in 0.429 ms against the paced loop's 0.374)
+  constexpr int32_t TRIAL_MIN_T = 256;
+  const int32_t TRIAL_T = a.T < 1024 ? a.T : 1024;
+  if (!a.trial_state || !a.trial_stats || a.T < TRIAL_MIN_T || fallback <= 0) return fallback;
+  int device = -1;
+  if (hipGetDevice(&device) != hipSuccess) { (void)hipGetLastError(); return fallback; }
+  int rate = fallback;
+  if (known_choice(device, a.n, &rate)) return rate;
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(stream, &cs) != hipSuccess) { (void)hipGetLastError(); return fallback; }
+  if (cs != hipStreamCaptureStatusNone) return fallback;
+
+  PongLaunch t = a;
+  t.state = a.trial_state; t.stats = a.trial_stats; t.counter = nullptr; t.ticket = 0;
+  t.step0 = a.step0; t.T = TRIAL_T; t.actions = nullptr; t.normalize = 0;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  bool ok = hipMemcpyAsync(t.state, a.state, (size_t)PONG_FIELDS * (size_t)a.n * 4, hipMemcpyDeviceToDevice, stream) == hipSuccess &&
+            hipMemsetAsync(t.stats, 0, STATS_STRIPES * sizeof(DeviceStats), stream) == hipSuccess &&
+            hipEventCreate(&e0) == hipSuccess && hipEventCreate(&e1) == hipSuccess;
+  auto launch = [&](int r) {
+    PongLaunch x = t;
+    int variant = V_RAW_2;
+    x.paged = 0;
+    if (r > 0) { variant = V_PACED; x.pace = pace_period(a.n, r, 2.0); }
+    else if (a.n >= 73728 && b.x == 256) { variant = V_PAGED; x.paged = 1; }
+    dispatch_variant<true>(variant, g, b, stream, x);
+    ok = ok && hipGetLastError() == hipSuccess;
+  };
+  auto timed = [&](int r) -> float {
+    for (int k = 0; k < 2 && ok; ++k) launch(r);
+    ok = ok && hipEventRecord(e0, stream) == hipSuccess;
+    for (int k = 0; k < 6 && ok; ++k) launch(r);
+    float ms = 0.0f;
+    ok = ok && hipEventRecord(e1, stream) == hipSuccess && hipEventSynchronize(e1) == hipSuccess &&
+         hipEventElapsedTime(&ms, e0, e1) == hipSuccess;
+    return ms;
+  };
+  if (ok) {
+    // 50 ms at the table's rate: launches of TRIAL_T steps take TRIAL_T * n * 37 B / rate each
+    const double each_ms = (double)TRIAL_T * (double)a.n * 37.0 / ((double)fallback * 1e9) * 1e3;
+    const int warm = (int)(50.0 / each_ms) + 1;
+    for (int k = 0; k < warm && ok; ++k) launch(fallback);
+    const float plain = timed(-1);
+    float best_ms = 0.0f;
+    int best_rate = -1;
+    const int percent[4] = {92, 96, 100, 104};
+    for (int k = 0; k < 4 && ok; ++k) {
+      const int r = fallback * percent[k] / 100;
+      if (r > 6600 && a.n <= 65536) continue;              // there the loop's own pace is the limit already
+      const float ms = timed(r);
+      if (ok && (best_rate < 0 || ms < best_ms)) { best_ms = ms; best_rate = r; }
+    }
+    if (ok) rate = (best_rate > 0 && best_ms < 0.99f * plain) ? best_rate : -1;
+  }
+  if (e0) (void)hipEventDestroy(e0);
+  if (e1) (void)hipEventDestroy(e1);
+  if (!ok) { (void)hipGetLastError(); return fallback; }
+  remember_choice(device, a.n, rate);
+  return rate;
+}
+
+}  // namespace
+
+// For the benchmark and the tests: what was measured for (current device, n): the rate in GB/s, -1
+// for "not paced", 0 if nothing has been measured for that batch size yet.
+int pong_pace_choice(int64_t n) {
+  int device = -1, rate = 0;
+  if (hipGetDevice(&device) != hipSuccess) { (void)hipGetLastError(); return 0; }
+  return known_choice(device, n, &rate) ? rate : 0;
 }
 
 hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream) {
@@ -432,18 +587,16 @@ hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream) {
   //    (rows x N x 37 B / rate) of the constant 100 MHz clock, a rate just under what the memory
   //    system drains: N = 65536: 0.380 ms at 6.6 TB/s; N = 81920: 0.536 (unpaced 0.730, paged
   //    0.609) and N = 131072: 0.847 (1.009, 0.957) at 5.8 TB/s; N = 262144: 1.742 (2.090, 1.840)
-  //    at 5.6 TB/s.  Asking for more than the memory system drains is worse than not pacing at
-  //    all, and a launch that has fallen behind does not recover (N = 131072: 0.778 ms at
-  //    6.4 TB/s, 1.31 at 6.6; N = 262144: 1.634 at 6.0, 2.73 at 6.2; stretching the period when
-  //    chunks run late did not bring a launch back), and where the edge lies moves with the box
-  //    and with what the device did just before, hence rates 8-10 % under the edges seen.  At
-  //    N <= 65536 there is no edge: the loop's own pace (0.372 ms per 1000 steps) is the limit.
+  //    at 5.6 TB/s.  Whether it pays, and at which rate, depends on the device at hand, so it is
+  //    measured once per device and batch size (measured_rate above; the rates just quoted are
+  //    the table it starts from, and what it falls back to when it cannot measure).  At
+  //    N <= 65536 the loop's own pace (0.372 ms per 1000 steps) is the limit.
   //  * above N = 262144 the wavefronts are not all resident at once and a clock cannot align them:
   //    observation stores paged through LDS (N = 2^20: 7.4 ms per 1000 steps against 8.6 direct).
   //    Paged stores pay a barrier and an LDS round trip per step, which is exposed latency with
   //    one wavefront per SIMD (N = 65536: 0.484 ms).
   int rate = g_rollout_pace;
-  if (rate == 0) rate = a.n < 61440 || a.n > 262144 ? -1 : a.n <= 65536 ? 6600 : a.n <= 131072 ? 5800 : 5600;
+  if (rate == 0) rate = g_measure_pace ? measured_rate(a2, g, b, stream) : table_rate(a.n);
   a2.paged = g_paged_mode == 2 ? (a.n >= 73728 && rate <= 0) : g_paged_mode;
   const int chunk = g_rollout_chunk ? g_rollout_chunk : (a.n <= 53248 ? 8 : 2);
   // two wavefronts per 64 environments: in-kernel actions, raw observations, a launch of at most
@@ -467,35 +620,15 @@ hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream) {
   else if (a2.paged && block == 256) variant = V_PAGED;
   else if (rate > 0) variant = V_PACED;
   else variant = chunk == 2 ? V_RAW_2 : chunk == 8 ? V_RAW_8 : V_RAW_4;
-  // time per chunk, in 1/256 of a tick of the constant clock (100 MHz on this device; asked of the
-  // runtime rather than assumed)
-  if (variant == V_PACED || variant == V_EXTERNAL_PACED || variant == V_NORMALIZED_PACED) {
-    const double rows = variant == V_EXTERNAL_PACED ? 8.0 : 2.0;
-    static int khz_of_device[64] = {};                       // asked once per device
-    int dev = 0, khz = 0;
-    if (hipGetDevice(&dev) != hipSuccess) { (void)hipGetLastError(); dev = -1; }
-    if (dev >= 0 && dev < 64) khz = khz_of_device[dev];
-    if (khz <= 0) {
-      if (dev < 0 || hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) != hipSuccess || khz <= 0) {
-        (void)hipGetLastError();
-        khz = 100000;
-      }
-      if (dev >= 0 && dev < 64) khz_of_device[dev] = khz;
-    }
-    const double q = rows * (double)a.n * 37.0 / ((double)rate * 1e9) * ((double)khz * 1e3) * 256.0;
-    a2.pace = q < 1073741824.0 ? (int32_t)q : 1073741824;    // 32-bit clock arithmetic in the kernel
-  }
+  if (variant == V_PACED || variant == V_EXTERNAL_PACED || variant == V_NORMALIZED_PACED)
+    a2.pace = pace_period(a.n, rate, variant == V_EXTERNAL_PACED ? 8.0 : 2.0);
   switch (variant) {
-    case V_RAW_2: hipLaunchKernelGGL(pong_rollout_kernel<V_RAW_2>, g, b, 0, stream, a2); break;
-    case V_RAW_4: hipLaunchKernelGGL(pong_rollout_kernel<V_RAW_4>, g, b, 0, stream, a2); break;
-    case V_RAW_8: hipLaunchKernelGGL(pong_rollout_kernel<V_RAW_8>, g, b, 0, stream, a2); break;
-    case V_PACED: hipLaunchKernelGGL(pong_rollout_kernel<V_PACED>, g, b, 0, stream, a2); break;
-    case V_PAGED: hipLaunchKernelGGL(pong_rollout_kernel<V_PAGED>, g, b, 0, stream, a2); break;
     case V_EXTERNAL_PACED: hipLaunchKernelGGL(pong_rollout_kernel<V_EXTERNAL_PACED>, g, b, 0, stream, a2); break;
     case V_EXTERNAL: hipLaunchKernelGGL(pong_rollout_kernel<V_EXTERNAL>, g, b, 0, stream, a2); break;
     case V_NORMALIZED: hipLaunchKernelGGL(pong_rollout_kernel<V_NORMALIZED>, g, b, 0, stream, a2); break;
     case V_NORMALIZED_PACED: hipLaunchKernelGGL(pong_rollout_kernel<V_NORMALIZED_PACED>, g, b, 0, stream, a2); break;
-    default: hipLaunchKernelGGL(pong_rollout_kernel<V_NORMALIZED_EXTERNAL>, g, b, 0, stream, a2); break;
+    case V_NORMALIZED_EXTERNAL: hipLaunchKernelGGL(pong_rollout_kernel<V_NORMALIZED_EXTERNAL>, g, b, 0, stream, a2); break;
+    default: dispatch_variant<false>(variant, g, b, stream, a2); break;
   }
   const hipError_t err = hipGetLastError();
   return err != hipSuccess ? err : advance_step_counter_behind(a.counter, a.T, blocks, stream);

@@ -215,6 +215,39 @@ def test_negative_zeros_in_a_restored_state_are_stored_as_positive_zeros():
     assert_bit_equal(done.cpu().numpy(), od, "done")
 
 
+def test_the_one_time_pace_measurement_leaves_no_trace():
+    # The first long rollout of a batch size in the paced range times a few loops on scratch state
+    # and into the caller's output buffers.  Outputs, state and statistics must be those of a
+    # library that never measured, and the choice is remembered for the batch size.
+    import ctypes as C
+    L = b.lib()
+    L.mi355env_pace_choice.argtypes = [C.c_int64]
+    n, seed, T = 61440 + 64 * 3, 23, 300            # a batch size no other test uses
+    outs = []
+    for measure in (1, 0):
+        assert L.mi355env_tune_measure_pace(measure) == 0
+        assert L.mi355env_tune_rollout_pace(0 if measure else -1) == 0
+        h = b.env_create(b.ENV_PONG, n, seed, {"max_score": 1})
+        b.env_reset(h, None)
+        obs, rew, done = bufs(T, n)
+        if measure:
+            assert L.mi355env_pace_choice(n) == 0
+        b.env_rollout(h, T, None, obs, rew, done)
+        b.env_rollout(h, T, None, obs, rew, done)       # second launch: the remembered choice
+        torch.cuda.synchronize()
+        if measure:
+            choice = L.mi355env_pace_choice(n)
+            assert choice == -1 or 5000 <= choice <= 7000, choice
+        outs.append((obs.cpu().numpy(), rew.cpu().numpy(), done.cpu().numpy(), b.env_stats(h),
+                     b.env_get_state(h)))
+        b.env_destroy(h)
+    assert L.mi355env_tune_measure_pace(1) == 0 and L.mi355env_tune_rollout_pace(0) == 0
+    for k in range(3):
+        assert_bit_equal(outs[0][k], outs[1][k], "output %d with and without the measurement" % k)
+    assert outs[0][3] == outs[1][3] and outs[0][3]["episodes"] > 0
+    assert np.array_equal(outs[0][4], outs[1][4])
+
+
 def test_stats_reset_counters():
     h = b.env_create(b.ENV_PONG, 256, 3, {"max_score": 1})
     b.env_reset(h, None)
