@@ -128,11 +128,13 @@ enum { ENV_OBS_RAW = 1, ENV_OBS_NORMALIZED = 2 };
  *           env_reset read the device counter; the first two synchronise the stream.
  *           A handle with the host counter refuses env_step / env_rollout while its stream is
  *           capturing (ENV_E_STATE): replays would repeat the captured step index.
- *           ENV_PONG_PIXELS: a step is then a dynamics launch followed by a render launch that takes
- *           the ring slot from the counter (the default path computes the next step under the
- *           render of this one and alternates library buffers from the host, which a replayed
- *           graph cannot do); results are the same bit for bit, a step takes about a quarter
- *           longer (24 against 19 us at N = 16384). */
+ *           ENV_PONG_PIXELS: a step is then two launches (the default path computes the next step
+ *           under the render of this one in a single launch and alternates library buffers from
+ *           the host, which a replayed graph cannot do): with in-kernel actions a one-workgroup
+ *           launch that moves the counter, then the same fused launch with buffers and ring slot
+ *           derived from the counter; with external actions a dynamics launch, then the renderer.
+ *           Results are the same bit for bit; a step takes about a quarter longer (22.5 against
+ *           18 us at N = 16384). */
 enum { ENV_STEP_COUNTER_HOST = 1, ENV_STEP_COUNTER_DEVICE = 2 };
 
 /* Layout of the four frames of ENV_PONG_PIXELS in obs_dev of env_reset / env_step.  The first two

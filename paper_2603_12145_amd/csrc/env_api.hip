@@ -321,7 +321,9 @@ int env_create(env_t** out, int kind, int64_t n_envs, uint64_t seed, const env_c
       hipSuccess) {
     (void)hipGetLastError(); (void)hipFree(e->state); delete e; return ENV_E_ALLOC;
   }
-  if (kind == ENV_PONG_PIXELS && pixel_pipe_create(e->pipe, n_envs, c.pixel_update == ENV_PIXELS_DELTA) != hipSuccess) {
+  if (kind == ENV_PONG_PIXELS && pixel_pipe_create(e->pipe, n_envs, c.pixel_update == ENV_PIXELS_DELTA,
+                                                     c.step_counter == ENV_STEP_COUNTER_DEVICE && c.pixel_layout == ENV_PIXELS_SLOT_MAJOR &&
+                                                         c.pixel_update == ENV_PIXELS_FULL) != hipSuccess) {
     (void)hipGetLastError(); (void)hipFree(e->state); (void)hipFree(e->stats); delete e;
     return ENV_E_ALLOC;
   }
@@ -368,6 +370,7 @@ int env_reset(env_t* e, void* obs_dev) {
     err = launch_pixel_reset(e->state, e->n, e->seed, e->step, counter, static_cast<uint8_t*>(obs_dev),
                              e->cfg.pixel_layout == ENV_PIXELS_SLOT_MAJOR, e->pipe.blocks[0], e->stream);
     pixel_pipe_invalidate(e->pipe);
+    if (err == hipSuccess) err = pixel_counted_forget(e->pipe, e->stream);
     if (err == hipSuccess && e->cfg.pixel_update == ENV_PIXELS_DELTA)
       err = pixel_update_after_reset(e->pipe, e->state, e->n, e->step, counter,
                                      static_cast<const uint8_t*>(obs_dev), e->stream);
@@ -388,6 +391,7 @@ int env_reset(env_t* e, void* obs_dev) {
                             e->cfg.obs_scaling == ENV_OBS_NORMALIZED, e->stream);
     if (e->kind == ENV_PONG_PIXELS) {
       pixel_pipe_invalidate(e->pipe);
+      if (err == hipSuccess) err = pixel_counted_forget(e->pipe, e->stream);
       // new episodes, no observation buffer written: what it holds is stale
       if (err == hipSuccess) err = pixel_update_forget(e->pipe, e->stream);
     }
@@ -502,6 +506,7 @@ int env_set_state(env_t* e, const void* host_buf, size_t bytes) {
   e->was_reset = true;
   if (e->kind == ENV_PONG_PIXELS) {
     pixel_pipe_invalidate(e->pipe);
+    if (pixel_counted_forget(e->pipe, e->stream) != hipSuccess) return ENV_E_HIP;
     // the observation buffer is not part of the state: it no longer matches
     if (pixel_update_forget(e->pipe, e->stream) != hipSuccess) return ENV_E_HIP;
   }

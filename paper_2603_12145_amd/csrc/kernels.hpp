@@ -94,17 +94,26 @@ struct PixelPipe {
   uint32_t* hist = nullptr;                        // [5][3][n] cell blocks of the last five frames, entry = step mod 5
   void* book = nullptr;                            // record of what the observation buffer holds, in device memory
   unsigned long long host_book[4] = {~0ull, 0, 0, 0};   // ... and the host's copy (handles with the host step counter)
+  // Lookahead of a handle whose step counter lives in device memory (see pixel_counted_step)
+  uint32_t* stage_state[2] = {nullptr, nullptr};   // [10][n] state after the staged step, per parity of its index
+  unsigned long long* staged_for = nullptr;        // device word: index of the step the staging buffers hold, ~0 = none
 };
-hipError_t pixel_pipe_create(PixelPipe& p, int64_t n, bool delta_updates);
+hipError_t pixel_pipe_create(PixelPipe& p, int64_t n, bool delta_updates, bool device_counter);
 void pixel_pipe_destroy(PixelPipe& p);
 // One slot-major ring step.  `state` is the handle's committed-state pointer and is swapped with
 // p.state_alt.  a.pong.actions may be null (staged lookahead usable) or external.
 hipError_t pixel_pipe_step(PixelPipe& p, uint32_t*& state, const PixelLaunch& a, bool lookahead,
                            hipStream_t stream);
 inline void pixel_pipe_invalidate(PixelPipe& p) { p.staged = false; }
-// The same step for a handle whose step counter lives in device memory (a.pong.counter): two
-// launches, dynamics then page renderer, no lookahead, nothing alternated from the host.
+// The same step for a handle whose step counter lives in device memory (a.pong.counter): nothing is
+// alternated from the host, so that the call can be recorded in a graph and replayed.  In-kernel
+// actions: a one-workgroup launch that reads and advances the counter (and, only if the staging
+// buffers do not hold this step, computes it), then the fused launch with the lookahead.  External
+// actions: dynamics launch, then the page renderer.
 hipError_t pixel_counted_step(const PixelPipe& p, const PixelLaunch& a, hipStream_t stream);
+// The state changed without the step counter moving (env_reset, env_set_state): whatever is staged
+// ahead is void.
+hipError_t pixel_counted_forget(const PixelPipe& p, hipStream_t stream);
 // One step of a handle that keeps its observation buffer current by delta updates: a ring slot
 // (ordered = false; a.slot_major says which ring) or all four channels of the ordered stack.  One
 // launch; it decides by itself, from a record in device memory, whether the buffer can be repaired
