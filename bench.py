@@ -27,13 +27,13 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 PONG_BYTES_PER_ENV_STEP = 37   # 32 obs + 4 reward + 1 done
 CARTPOLE_BYTES_PER_ENV_STEP = 21   # 16 obs + 4 reward + 1 done
-CARTPOLE_VALU_PER_ENV_STEP = 209   # vector instructions in the step loop of the kernel ISA (35 of them quarter-rate integer multiplies)
+CARTPOLE_VALU_PER_ENV_STEP = 197   # SQ_INSTS_VALU per wavefront and step (profiles/cartpole_rollout_n65536_t1000.md: 196.8)
 VALU_PEAK_TINSTR = 39.3            # 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz, lane-instructions per second / 1e12
 FRAME_BYTES = 84 * 84          # one new frame per env-step
 FP32_PEAK_TFLOPS = 157.3       # MI355X vector float32, packed operations counted
 FP64_PEAK_TFLOPS = 78.6        # MI355X vector float64 (256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz)
 BODY_NEWTON_FLOP_PER_ENV_STEP = 13540   # 5 substeps x (1526 outside the Newton loop + 1.05 solves per environment x 1126), counted in the kernel ISA; a wavefront executes max-over-lanes solves (3.0 on average), which is not counted as useful work
-BODY_FLOP_PER_ENV_STEP = 9400   # 5 substeps x 1876 float64 flops (FMA = 2), counted in the substep loop of the kernel ISA
+BODY_FLOP_PER_ENV_STEP = 9400   # 5 substeps x 1876 flops (FMA = 2) of a single-lane formulation, read off the compiled substep loop; the kernel's own count is SQ_INSTS_VALU = 918 (float64) / 739 (float32) vector instructions per lane and substep, two lanes per environment (profiles/body_rollout_n8192_t1000.md)
 
 
 def _traffic(key):
@@ -285,6 +285,8 @@ def bench_pixels(b, torch, n, seed, launches, warmup=20, layout="slot_major", de
         out["roofline"] = dict(bound="hbm", achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s", frac=gbs / HBM_PEAK_GBS,
                                traffic=_traffic("pixel_fused_step_n%d" % n)
                                if layout == "slot_major" and not device_counter else None)
+        if out["roofline"]["traffic"] is None:
+            out["roofline"]["traffic_note"] = "no counter run for this variant; the full-write variants move 1.03 x the frame bytes"
     return out
 
 
@@ -393,7 +395,7 @@ def bench_body(b, torch, n, T, seed, steps, newton=False, f32=False):
                 env_steps_per_s=n * T * steps / wall, ms_per_launch=mean_ms,
                 nonfinite=st["nonfinite"], episodes=st["episodes"],
                 roofline=dict(bound="alu", achieved=flops, peak=FP64_PEAK_TFLOPS, unit="TFLOP/s",
-                              frac=flops / FP64_PEAK_TFLOPS, traffic=None))
+                              frac=flops / FP64_PEAK_TFLOPS, traffic=_traffic("body_rollout_n%d_t%d" % (n, T))))
 
 
 def bench_cartpole(b, torch, n, T, seed, steps):
@@ -593,6 +595,7 @@ def main():
               "per_step": lambda: bench_pong_per_step(b, torch, 4096, 1, args.steps),
               "sweep": lambda: {"n%d" % nn: bench_pong_rollout(b, torch, nn, 1000, 2, args.steps, 10)
                                 for nn in (16384, 131072, 262144)},
+              "sweep_large": lambda: {"n524288": bench_pong_rollout(b, torch, 524288, 250, 2, args.steps, 3)},
               "pixels_large": lambda: [bench_pixels(b, torch, 32768, 3, args.steps),
                                        bench_pixels(b, torch, 262144, 3, max(20, args.steps // 5))],
               "body": lambda: bench_body(b, torch, 8192, 1000, 4, args.steps),
@@ -675,7 +678,8 @@ def main():
             gbs = PONG_BYTES_PER_ENV_STEP * nn * T / (rr["mean_ms"] * 1e-3) / 1e9
             extra["config2_n%d" % nn] = dict(env_steps_per_s=rr["env_steps"] / rr["wall"], pace_choice_gbs=rr["pace_choice_gbs"],
                                              ms_per_launch=rr["mean_ms"], ms_min=rr["min_ms"],
-                                             ms_max=rr["max_ms"], hbm_gbs=gbs, frac=gbs / HBM_PEAK_GBS)
+                                             ms_max=rr["max_ms"], hbm_gbs=gbs, frac=gbs / HBM_PEAK_GBS,
+                                             traffic=_traffic("pong_rollout_n%d_t%d" % (nn, T)))
         extra["config4_body"] = bench_body(b, torch, 8192, 1000, 4, 2)
         extra["config4_body_n262144_t100"] = bench_body(b, torch, 262144, 100, 4, 2)
         extra["body_newton_n8192_t1000"] = bench_body(b, torch, 8192, 1000, 4, 2, newton=True)
