@@ -29,8 +29,9 @@
 //   4. q+ = q + h v+, joint angles clipped to [-1, 1].
 //
 // Second contact model (solver = 1), after the paper's final solver revision for this case study
-// (App. A.1: "Newton contact solver formulation (acceleration-space QP with Cholesky
-// factorization)"; the paper gives no formulas, so everything below is this repository's reading):
+// (App. A.1, "HalfCheetah JAX": a quadratic programme over accelerations, solved by Newton's method
+// with Cholesky factorisations; the paper gives no formulas, so everything below is this
+// repository's reading):
 // the substep's acceleration a minimises the strictly convex, piecewise quadratic
 //     c(a) = 1/2 (a - a0)^T M (a - a0)  +  sum_i  D_i / 2 * min(0, J_i a - aref_i)^2 ,
 // a0 = M^-1 (Q_g + tau - h) being the acceleration without constraints (Gauss' principle with soft
