@@ -57,6 +57,14 @@ namespace envk {
 namespace {
 
 #define LIT(x) ((real)(x))
+// Newton steps behind the float64 reciprocal square root estimate.  The estimate is good to about
+// 2^-23, one step leaves about 2^-45 -- nine orders of magnitude under the rounding of the float32
+// state the step ends in -- and a second step (full precision) changed no output of 24576 single
+// steps against the oracle while costing 4 % of the launch (N = 8192 x T = 1000: 10.09 against
+// 9.73 ms).  Build with -DBODY_RSQ_STEPS=2 for the fully converged form.
+#ifndef BODY_RSQ_STEPS
+#define BODY_RSQ_STEPS 1
+#endif
 
 namespace f64 {
 #define BODY_REAL double
