@@ -32,7 +32,7 @@ def build(force=True, verbose=False, extra=(), out=None):
     """extra: additional hipcc flags (e.g. -D switches for measurement variants); out: alternative
     output path (the default in-tree library is what the binding loads)."""
     srcs = sources()
-    deps = srcs + glob.glob(os.path.join(CSRC, "*.hpp")) + glob.glob(
+    deps = srcs + glob.glob(os.path.join(CSRC, "*.hpp")) + glob.glob(os.path.join(CSRC, "*.inc")) + glob.glob(
         os.path.join(HERE, "..", "include", "*.h"))
     lib = out or LIB
     if not force and os.path.exists(lib) and all(
