@@ -126,6 +126,75 @@ def pixel_case(rng, k):
     assert_bit_equal(got, stack, "ring after %d steps" % T)      # T >= 4: every slot rewritten
 
 
+def body_case(rng, k):
+    """Random size, length, contact model, arithmetic, action source and episode length.  A rollout
+    cut into launches at random must equal the same steps taken one launch each, bit for bit; the
+    first step must agree with the float64 oracle (1e-5 in float64, as close as float32 gets
+    otherwise); truncation times and episode counts are exact."""
+    from oracle.body_binding import Body
+    sizes = [1, 2, 31, 32, 33, 63, 64, 65, 500, 2049, 9000, 33000]      # every one is taken in turn
+    n = sizes[k % len(sizes)]
+    T = int(rng.integers(1, 40))
+    seed = int(rng.integers(0, 2 ** 62))
+    solver, f32, external, device_counter = (int(rng.integers(0, 2)) for _ in range(4))
+    limit = int(rng.integers(3, 30))
+    print("body case", k, dict(n=n, T=T, seed=seed, solver=solver, f32=f32, external=external,
+                               device_counter=device_counter, max_episode_steps=limit), flush=True)
+    cfg = {"max_episode_steps": limit}
+    if solver:
+        cfg["contact_solver"] = b.ENV_CONTACT_NEWTON
+    if f32:
+        cfg["body_arithmetic"] = b.ENV_BODY_F32
+    if device_counter:
+        cfg["step_counter"] = b.ENV_STEP_COUNTER_DEVICE
+    acts = inputs.body_actions(T, n, seed=k, scale=1.3) if external else None
+    act = None if acts is None else torch.from_numpy(acts).to(DEV)
+    outs = []
+    for per_step in (False, True):
+        h = b.env_create(b.ENV_BODY, n, seed, cfg)
+        try:
+            obs0 = torch.empty((n, 17), dtype=torch.float32, device=DEV)
+            b.env_reset(h, obs0)
+            obs, rew, done = _trajectory_buffers(T, n, 17)
+            t = 0
+            while t < T:
+                c = 1 if per_step else int(min(T - t, rng.integers(1, max(2, T // 2 + 1))))
+                b.env_rollout(h, c, None if act is None else act[t:t + c], obs[t:t + c], rew[t:t + c], done[t:t + c])
+                t += c
+            torch.cuda.synchronize()
+            outs.append((obs0.cpu().numpy(), obs.cpu().numpy(), rew.cpu().numpy(), done.cpu().numpy(),
+                         b.env_stats(h), b.env_get_state(h)))
+        finally:
+            b.env_destroy(h)
+    for j, name in enumerate(("reset obs", "obs", "reward", "done")):
+        assert_bit_equal(outs[0][j], outs[1][j], "body case %d %s: fused vs one launch per step" % (k, name))
+    # the statistics add float32 returns up per lane and launch before the float64 atomics: the sum
+    # depends on how the rollout was cut (in the ninth digit), everything else does not
+    for key in ("episodes", "length_sum", "nonfinite", "return_min", "return_max"):
+        assert outs[0][4][key] == outs[1][4][key], key
+    assert abs(outs[0][4]["return_sum"] - outs[1][4]["return_sum"]) <= 1e-6 * max(1.0, abs(outs[1][4]["return_sum"]))
+    assert np.array_equal(outs[0][5], outs[1][5])
+    o = Body(n, seed, np.float64, max_episode_steps=limit, solver=solver)
+    o0 = o.reset()
+    oo, orr, od = o.rollout(T, actions=None if acts is None else acts.astype(np.float64), nthreads=8)
+    g0, go, gr, gd, st, _ = outs[0]
+    assert np.abs(g0 - o0).max() < 5e-7                           # Box-Muller through float32 log / cos / sin
+    assert np.array_equal(gd, od), "truncation times"
+    assert st["episodes"] == int(od.sum()) == n * (T // limit) and st["nonfinite"] == 0
+    # first step: same physics from (nearly) the same initial state
+    err = np.abs(go[0].astype(np.float64) - oo[0]) / np.maximum(np.abs(oo[0]), 1.0)
+    live = od[0] == 0
+    tol = 2e-3 if f32 else 2e-5          # v0 itself differs by up to 5e-7; float32: see test_gpu_body_f32.py
+    assert err[live].max() < tol if live.any() else True, err.max()
+    assert np.isfinite(go).all() and np.isfinite(gr).all()
+
+
+def test_random_body_cases():
+    rng = np.random.default_rng(45678)
+    for k in range(14):
+        body_case(rng, k)
+
+
 def test_random_pong_cases():
     rng = np.random.default_rng(12345)
     try:
