@@ -412,6 +412,8 @@ def bench_cartpole(b, torch, n, T, seed, steps):
     gbs = CARTPOLE_BYTES_PER_ENV_STEP * n * T / (mean_ms * 1e-3) / 1e9
     tinstr = CARTPOLE_VALU_PER_ENV_STEP * n * T / (mean_ms * 1e-3) / 1e12
     # bound by vector-instruction issue, not by its 21 B per env-step: the roofline is the issue rate
+    # (197 = the instructions one wavefront per 64 environments needs per step; batches up to 65536 run
+    # two wavefronts per 64 environments, which issue a few more between them and share a SIMD better)
     return dict(workload="cart-pole N=%d x T=%d fused rollout, in-kernel Philox actions" % (n, T), dtype="f32",
                 env_steps_per_s=n * T * steps / wall, ms_per_launch=mean_ms, episodes=st["episodes"],
                 hbm_gbs=gbs, hbm_frac=gbs / HBM_PEAK_GBS,

@@ -35,6 +35,12 @@ int mi355env_tune_rollout_chunk(int steps);
  * hands them over through LDS), 1 = never, 2 = for any N and T.  Results are identical. */
 int mi355env_tune_rollout_split(int mode);
 
+/* Cart-pole rollout, batches of at most one wavefront per SIMD: 0 = default (for N <= 65536 and
+ * T >= 32 with in-kernel actions, every 64 environments get a second wavefront that draws their
+ * Philox blocks and hands them over through LDS), 1 = never, 2 = for any N and T.  Results are
+ * identical. */
+int mi355env_tune_cartpole_split(int mode);
+
 /* Pacing of the same loop.  gb_per_s > 0: every full wavefront runs the paced loop (two steps per
  * chunk, episode statistics brought up to date once per chunk instead of in every step) and starts
  * a chunk no sooner than 2 * N * 37 B / gb_per_s after the previous one, by the constant 100 MHz

@@ -21,6 +21,7 @@ bool set_rollout_block(int threads, int xcd_remap);
 bool set_rollout_chunk(int steps);
 bool set_rollout_pace(int gb_per_s);
 bool set_measure_pace(int on);
+bool set_cartpole_split(int mode);
 int pong_pace_choice(int64_t n);
 bool set_rollout_split(int mode);
 bool set_paged_stores(int mode);
@@ -600,6 +601,10 @@ int mi355env_tune_measure_pace(int on) { return set_measure_pace(on) ? ENV_OK : 
 
 // What was measured for n environments on the current device: GB/s, -1 = not paced, 0 = nothing yet.
 int mi355env_pace_choice(int64_t n) { return pong_pace_choice(n); }
+
+// Cart-pole rollout with a second wavefront per 64 environments drawing the Philox blocks: 0 = chosen
+// from N and T, 1 = never, 2 = whenever the launch has in-kernel actions.
+int mi355env_tune_cartpole_split(int mode) { return set_cartpole_split(mode) ? ENV_OK : ENV_E_ARG; }
 
 // 0 = direct observation stores, 1 = paged through LDS wherever a workgroup is full, 2 = by N.
 int mi355env_tune_paged_stores(int mode) { return set_paged_stores(mode) ? ENV_OK : ENV_E_ARG; }

@@ -164,3 +164,19 @@ def test_full_size_sampled_against_oracle():
     assert gs["return_min"] == st["length_min"] and gs["return_max"] == st["length_max"]
     assert_bit_equal(last, o_obs[-1], "final obs")
     assert_bit_equal(col, o_obs[:, 12345], "env 12345 trajectory")
+
+
+@pytest.mark.parametrize("mode", [1, 2], ids=["one wavefront per 64 environments", "producer and consumer wavefront"])
+@pytest.mark.parametrize("n,T", [(1, 5), (63, 40), (64, 33), (130, 7), (1000, 100), (4096, 41)])
+def test_both_rollout_loops_match_the_oracle(n, T, mode):
+    # batches of up to 65536 environments normally take the loop with a second wavefront per 64
+    # environments that draws the Philox blocks (from T = 32 on); here each loop is forced for
+    # every size and length, ragged wavefronts and partial last rounds included
+    assert b.lib().mi355env_tune_cartpole_split(mode) == 0
+    try:
+        seed = 700 + n
+        g = gpu_rollout(n, seed, T, max_steps=9, chunks=[T // 2, T - T // 2] if T > 1 else None)
+    finally:
+        assert b.lib().mi355env_tune_cartpole_split(0) == 0
+    compare(g, oracle_rollout(n, seed, T, max_steps=9), n, "cart-pole loop %d" % mode)
+    assert g["stats"]["episodes"] >= n * (T // 9)
