@@ -76,7 +76,10 @@ namespace f64 {
 
 namespace f32 {
 #define BODY_REAL float
-#define BODY_OCCUPANCY __attribute__((amdgpu_waves_per_eu(4, 4)))
+#ifndef BODY_F32_WAVES
+#define BODY_F32_WAVES 4
+#endif
+#define BODY_OCCUPANCY __attribute__((amdgpu_waves_per_eu(BODY_F32_WAVES, BODY_F32_WAVES)))
 #include "body_impl.inc"
 #undef BODY_REAL
 #undef BODY_OCCUPANCY
