@@ -35,6 +35,10 @@ int mi355env_tune_rollout_chunk(int steps);
  * hands them over through LDS), 1 = never, 2 = for any N and T.  Results are identical. */
 int mi355env_tune_rollout_split(int mode);
 
+/* Pong env_step (and env_rollout with T = 1): 1 = default, a kernel that holds the step and nothing
+ * else; 0 = the rollout kernel's T = 1 path.  Results are identical. */
+int mi355env_tune_step_kernel(int on);
+
 /* Cart-pole rollout, batches of at most one wavefront per SIMD: 0 = default (for N <= 65536 and
  * T >= 32 with in-kernel actions, every 64 environments get a second wavefront that draws their
  * Philox blocks and hands them over through LDS), 1 = never, 2 = for any N and T.  Results are

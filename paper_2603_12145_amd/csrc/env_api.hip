@@ -21,6 +21,7 @@ bool set_rollout_block(int threads, int xcd_remap);
 bool set_rollout_chunk(int steps);
 bool set_rollout_pace(int gb_per_s);
 bool set_measure_pace(int on);
+bool set_step_kernel(int on);
 bool set_cartpole_split(int mode);
 int pong_pace_choice(int64_t n);
 bool set_rollout_split(int mode);
@@ -601,6 +602,9 @@ int mi355env_tune_measure_pace(int on) { return set_measure_pace(on) ? ENV_OK : 
 
 // What was measured for n environments on the current device: GB/s, -1 = not paced, 0 = nothing yet.
 int mi355env_pace_choice(int64_t n) { return pong_pace_choice(n); }
+
+// Pong env_step: 1 = the dedicated step kernel (default), 0 = the rollout kernel with T = 1.
+int mi355env_tune_step_kernel(int on) { return set_step_kernel(on) ? ENV_OK : ENV_E_ARG; }
 
 // Cart-pole rollout with a second wavefront per 64 environments drawing the Philox blocks: 0 = chosen
 // from N and T, 1 = never, 2 = whenever the launch has in-kernel actions.

@@ -274,6 +274,39 @@ __global__ __launch_bounds__(256) void pong_rollout_kernel(PongLaunch a) {
   flush_wave_stats<false>(a.stats, le);
 }
 
+// env_step (T = 1) as a kernel of its own.  A per-step launch is bound by what a dependent launch
+// costs (1.5 us for an empty kernel, 3.0 us for any kernel that stores, whatever its size), and
+// on top of that by the latency of its own critical path: the rollout kernel's T = 1 path sits
+// behind that kernel's prologue and is fetched from a code object of several thousand
+// instructions; this one is the step and nothing else.
+template <bool EXTERNAL_ACTIONS, bool NORMALIZE>
+__global__ __launch_bounds__(256) void pong_step_kernel(PongLaunch a) {
+  a.step0 = launch_first_step(a.counter, a.step0, 1, a.ticket != 0);
+  const int64_t n = a.n;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const bool live = i < n;
+  const int64_t ic = live ? i : n - 1;                          // idle lanes shadow the last environment
+  // the draw does not depend on the state: its multiply chain runs under the state's loads
+  const Draw4 d = philox_draw(a.seed, (uint32_t)ic, a.step0, 0u);
+  PongLane s = pong_load(a.state, n, ic);
+  const float move = EXTERNAL_ACTIONS ? pong_move_of_action((int)a.actions[ic]) : pong_move_of_word(d.w0);
+  const PongEvent ev = pong_transition_move(s, move, d.w1, d.w2, a.max_score);
+  const bool done = live && ev.done;
+  LaneEpisodes le;
+  if (done) { le.count = 1; le.length_sum = ev.fin_len; le.ret_sum_i = ev.fin_ret; le.min_key = ev.fin_ret; le.max_key = ev.fin_ret; }
+  if (live) {
+    float4 lo, hi;
+    pong_observe<NORMALIZE>(s, a.inv_score, lo, hi);
+    float4* o = reinterpret_cast<float4*>(a.obs + i * PONG_OBS);
+    o[0] = lo;
+    o[1] = hi;
+    a.reward[i] = ev.reward;
+    a.done[i] = done ? 1 : 0;
+    pong_store(a.state, n, i, s);
+  }
+  flush_wave_stats<false>(a.stats, le);
+}
+
 // Small batches (fewer wavefronts than SIMDs): two wavefronts per 64 environments.  A launch of
 // 16384 environments occupies a quarter of the device's SIMDs.  The Philox draws do not depend on
 // the state, so a second wavefront (on another SIMD of the same CU) draws them, SPLIT_STEPS steps
@@ -373,6 +406,7 @@ int g_paged_mode = 2;      // 0 never, 1 whenever possible, 2 = choose from N
 int g_xcd_remap = 1;
 int g_rollout_chunk = 0;   // 0 = choose from N
 int g_rollout_pace = 0;    // GB/s the paced variant keeps the write stream to; 0 = choose from N, -1 = never paced
+int g_step_kernel = 1;     // 1 = T = 1 launches take the dedicated step kernel, 0 = the rollout kernel's T = 1 path
 int g_measure_pace = 1;    // 1 = measure once per device and batch size whether pacing pays, 0 = the table decides
 
 }  // namespace
@@ -407,6 +441,12 @@ bool set_rollout_split(int mode) {
 bool set_rollout_pace(int gb_per_s) {
   if (gb_per_s < -1 || gb_per_s > 8000) return false;
   g_rollout_pace = gb_per_s;
+  return true;
+}
+
+bool set_step_kernel(int on) {
+  if (on != 0 && on != 1) return false;
+  g_step_kernel = on;
   return true;
 }
 
@@ -574,6 +614,17 @@ hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream) {
   PongLaunch a2 = a;
   a2.ticket = blocks <= TICKET_MAX_BLOCKS;
   a2.xcd_remap = g_xcd_remap;
+  if (a.T == 1 && g_step_kernel) {
+    const unsigned groups = (unsigned)((a.n + 255) / 256);
+    a2.ticket = groups <= TICKET_MAX_BLOCKS;
+    const dim3 sg(groups), sb(256);
+    if (a.actions && a.normalize) hipLaunchKernelGGL((pong_step_kernel<true, true>), sg, sb, 0, stream, a2);
+    else if (a.actions) hipLaunchKernelGGL((pong_step_kernel<true, false>), sg, sb, 0, stream, a2);
+    else if (a.normalize) hipLaunchKernelGGL((pong_step_kernel<false, true>), sg, sb, 0, stream, a2);
+    else hipLaunchKernelGGL((pong_step_kernel<false, false>), sg, sb, 0, stream, a2);
+    const hipError_t e = hipGetLastError();
+    return e != hipSuccess ? e : advance_step_counter_behind(a.counter, 1, groups, stream);
+  }
   // Which loop runs the in-kernel-action, raw-observation rollout (ms per launch at T = 1000, one
   // box, same process):
   //  * N <= 53248 (fewer wavefronts than SIMDs, latency bound): 8 steps per chunk -- long chunks

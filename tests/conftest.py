@@ -28,6 +28,7 @@ def _default_tuning(request):
     L.mi355env_tune_rollout_pace(0)
     L.mi355env_tune_measure_pace(1)
     L.mi355env_tune_cartpole_split(0)
+    L.mi355env_tune_step_kernel(1)
     L.mi355env_tune_paged_stores(2)
     L.mi355env_tune_pixels(0, 0)
     L.mi355env_tune_frame_trajectory(2)

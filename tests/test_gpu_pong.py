@@ -527,3 +527,20 @@ def test_step_counter_crosses_2_to_the_32(device_counter):
         step, got = split_state(blob, n, 10)
         assert step == start + T
         assert_bit_equal(got, pong_state_fields(p.envs()), "state")
+
+
+@pytest.mark.parametrize("step_kernel", [1, 0], ids=["step kernel", "rollout kernel with T = 1"])
+@pytest.mark.parametrize("external", [False, True])
+@pytest.mark.parametrize("n", [1, 255, 257, 700])
+def test_both_ways_to_take_a_single_step(n, external, step_kernel):
+    # env_step normally takes a kernel that holds one step and nothing else; the rollout kernel's
+    # T = 1 path computes the same thing.  Each is forced here, one launch per step, ragged sizes.
+    T, seed = 60, 300 + n
+    acts = inputs.pong_actions(T, n, seed=5) if external else None
+    assert b.lib().mi355env_tune_step_kernel(step_kernel) == 0
+    try:
+        g = gpu_rollout(n, seed, T, max_score=1, actions=acts, per_step=True)
+    finally:
+        assert b.lib().mi355env_tune_step_kernel(1) == 0
+    compare(g, oracle_rollout(n, seed, T, max_score=1, actions=acts), n, "single steps")
+    assert g["stats"]["episodes"] > 0 or n < 10
