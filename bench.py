@@ -153,24 +153,34 @@ def bench_pong_per_step(b, torch, n, seed, launches):
     rew = torch.empty(n, dtype=torch.float32, device=dev)
     done = torch.empty(n, dtype=torch.uint8, device=dev)
     b.env_reset(h, None)
-    preroll(lambda: b.env_step(h, None, obs, rew, done))
-    t0 = time.perf_counter()
-    for _ in range(launches):
-        b.env_step(h, None, obs, rew, done)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
+    L = b.lib()
+
+    def loop(fn):
+        preroll(fn)
+        t0 = time.perf_counter()
+        for _ in range(launches):
+            fn()
+        t1 = time.perf_counter()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, t1 - t0
+
+    # the binding call as a user makes it, same buffers every step: launched without kernel arguments
+    # from the second call on, so the host's share (marshalling included) hides behind the device
+    wall, host_enqueue = loop(lambda: b.env_step(h, None, obs, rew, done))
+    # the same with the arguments marshalled once
+    wall_prepared, _ = loop(b.PreparedStep(h, None, obs, rew, done))
+    # and with the step kernel that takes its descriptor as a kernel argument: bound by the host's
+    # launch path
+    assert L.mi355env_tune_step_kernel(2) == 0
+    wall_args, host_args = loop(lambda: b.env_step(h, None, obs, rew, done))
+    wall_args_prepared, _ = loop(b.PreparedStep(h, None, obs, rew, done))
+    assert L.mi355env_tune_step_kernel(1) == 0
     b.env_destroy(h)
     # the same loop with an empty kernel: what a launch costs from this process on this stream
     import ctypes as C
-    L = b.lib()
     L.mi355env_bench_empty.argtypes = [C.c_void_p]
     s = torch.cuda.current_stream().cuda_stream
-    preroll(lambda: L.mi355env_bench_empty(s))
-    t0 = time.perf_counter()
-    for _ in range(launches):
-        L.mi355env_bench_empty(s)
-    torch.cuda.synchronize()
-    empty = time.perf_counter() - t0
+    empty, _ = loop(lambda: L.mi355env_bench_empty(s))
     # the same launches recorded once in a HIP graph (device-resident step counter) and replayed
     per_graph = 100
     st = torch.cuda.Stream()
@@ -200,6 +210,11 @@ def bench_pong_per_step(b, torch, n, seed, launches):
                 graph_replay_us_per_launch=graph_us, graph_env_steps_per_s=n / (graph_us * 1e-6),
                 graph_launches_per_graph=per_graph,
                 us_per_launch=1e6 * wall / launches, env_steps_per_s=n * launches / wall,
+                us_per_launch_host_enqueue=1e6 * host_enqueue / launches,
+                us_per_launch_prepared_call=1e6 * wall_prepared / launches,
+                with_kernel_arguments=dict(us_per_launch=1e6 * wall_args / launches,
+                                           us_per_launch_host_enqueue=1e6 * host_args / launches,
+                                           us_per_launch_prepared_call=1e6 * wall_args_prepared / launches),
                 bound="dispatch latency", launches=launches,
                 empty_kernel_us_per_launch=1e6 * empty / launches, ratio_to_empty_launch=wall / empty,
                 hbm_gbs=n * 101 / (wall / launches) / 1e9)

@@ -36,8 +36,14 @@ int mi355env_tune_rollout_chunk(int steps);
 int mi355env_tune_rollout_split(int mode);
 
 /* Pong env_step (and env_rollout with T = 1): 1 = default, a kernel that holds the step and nothing
- * else; 0 = the rollout kernel's T = 1 path.  Results are identical. */
+ * else, launched without kernel arguments (its launch descriptor kept in device memory) from the
+ * second call in a row that passes the same buffers, for handles with the host step counter and
+ * N <= 16384, at most four handles per device at a time; 2 = that kernel, always launched with
+ * arguments; 0 = the rollout kernel's T = 1 path.  Results are identical. */
 int mi355env_tune_step_kernel(int on);
+/* How many env_step calls of this process have been launched without kernel arguments so far
+ * (for tests that have to know which of the two launches they exercised). */
+unsigned long long mi355env_resident_step_launches(void);
 
 /* Cart-pole rollout, batches of at most one wavefront per SIMD: 0 = default (for N <= 65536 and
  * T >= 32 with in-kernel actions, every 64 environments get a second wavefront that draws their

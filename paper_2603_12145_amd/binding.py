@@ -130,6 +130,24 @@ def env_step(h, actions, obs, reward, done):
            "env_step")
 
 
+class PreparedStep:
+    """env_step with its arguments marshalled once, for loops that call it with the same buffers
+    every step: `step = PreparedStep(h, actions, obs, reward, done); step()`.  Taking the four device
+    addresses out of tensors costs about 0.6 us of host time per call, which matters wherever the
+    host's share of a call is what bounds the loop (small batches launched with kernel arguments).
+    The tensors are kept alive by the object."""
+
+    def __init__(self, h, actions, obs, reward, done):
+        self._keep = (actions, obs, reward, done)
+        self._call = lib().env_step
+        self._args = (h, _dev_ptr(actions), _dev_ptr(obs), _dev_ptr(reward), _dev_ptr(done))
+
+    def __call__(self):
+        code = self._call(*self._args)
+        if code != ENV_OK:
+            raise EnvError(code, "env_step")
+
+
 def env_rollout(h, T, actions, obs, reward, done):
     _check(lib().env_rollout(h, int(T), _dev_ptr(actions), _dev_ptr(obs), _dev_ptr(reward),
                              _dev_ptr(done)), "env_rollout")

@@ -22,6 +22,7 @@ bool set_rollout_chunk(int steps);
 bool set_rollout_pace(int gb_per_s);
 bool set_measure_pace(int on);
 bool set_step_kernel(int on);
+unsigned long long resident_step_launches();
 bool set_cartpole_split(int mode);
 int pong_pace_choice(int64_t n);
 bool set_rollout_split(int mode);
@@ -47,6 +48,7 @@ struct mi355env {
   PixelPipe pipe;         // pixels only: second state buffer and the staging buffers of the lookahead
   uint32_t* trial_state;  // Pong, batch sizes that may run paced: scratch for the launcher's one-time
   DeviceStats* trial_stats;   // measurement (a second state array and statistics block), else null
+  StepResident resident;  // Pong: what the per-step launches keep in device memory between calls
   bool was_reset;
   // last device ranges that passed the residency check (avoids a driver query per step)
   struct Range { const void* p; size_t bytes; } seen[8];
@@ -251,7 +253,7 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
     p.obs = static_cast<float*>(obs); p.reward = reward; p.done = done; p.stats = e->stats;
     if (e->kind == ENV_PONG) {
       p.trial_state = e->trial_state; p.trial_stats = e->trial_stats;
-      err = launch_pong_rollout(p, e->stream);
+      err = launch_pong_rollout(p, e->stream, &e->resident);
     } else if (e->kind == ENV_CARTPOLE) {
       p.max_score = e->cfg.max_episode_steps;
       err = launch_cartpole_rollout(p, e->stream);
@@ -358,6 +360,7 @@ void env_destroy(env_t* e) {
   (void)hipFree(e->state_alloc);
   (void)hipFree(e->stats);
   (void)hipFree(e->trial_state);
+  step_resident_release(e->resident);
   pixel_pipe_destroy(e->pipe);
   delete e;
 }
@@ -605,6 +608,7 @@ int mi355env_pace_choice(int64_t n) { return pong_pace_choice(n); }
 
 // Pong env_step: 1 = the dedicated step kernel (default), 0 = the rollout kernel with T = 1.
 int mi355env_tune_step_kernel(int on) { return set_step_kernel(on) ? ENV_OK : ENV_E_ARG; }
+unsigned long long mi355env_resident_step_launches(void) { return resident_step_launches(); }
 
 // Cart-pole rollout with a second wavefront per 64 environments drawing the Philox blocks: 0 = chosen
 // from N and T, 1 = never, 2 = whenever the launch has in-kernel actions.

@@ -45,7 +45,20 @@ constexpr int64_t PACED_MIN_ENVS = 61440, PACED_MAX_ENVS = 262144;
 // reset launchers: counter != nullptr -> the step is read from it instead of `step`
 hipError_t launch_pong_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
                              const StepCounter* counter, float* obs, bool normalize, hipStream_t stream);
-hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream);
+// What a handle remembers of its per-step launches (host side; see launch_pong_rollout): the launch
+// record it owns in device memory, what that record holds, and what the last call asked for.
+struct StepResident {
+  int device = -1, slot = -1;    // slot < 0: no record owned (not asked for yet, or none was free)
+  bool asked = false;
+  bool on_device = false;        // the record in device memory equals `rec` and counts `next_step`
+  bool have_last = false;
+  PongLaunch rec{}, last{};
+  hipStream_t rec_stream = nullptr, last_stream = nullptr;
+  uint64_t next_step = 0;
+};
+void step_resident_release(StepResident& r);
+// resident: the calling handle's StepResident (Pong with the host step counter), or null
+hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream, StepResident* resident = nullptr);
 
 // CartPole: same launch descriptor (max_score carries max_episode_steps; obs is [T,n,4]).
 constexpr int CARTPOLE_FIELDS = 6;   // x xdot theta thetadot | ep_ret ep_len

@@ -9,7 +9,9 @@
 #include "kernels.hpp"
 #include "pong_device.hpp"
 
+#include <atomic>
 #include <mutex>
+#include <vector>
 
 namespace envk {
 
@@ -274,20 +276,31 @@ __global__ __launch_bounds__(256) void pong_rollout_kernel(PongLaunch a) {
   flush_wave_stats<false>(a.stats, le);
 }
 
-// env_step (T = 1) as a kernel of its own.  A per-step launch is bound by what a dependent launch
-// costs (1.5 us for an empty kernel, 3.0 us for any kernel that stores, whatever its size), and
-// on top of that by the latency of its own critical path: the rollout kernel's T = 1 path sits
-// behind that kernel's prologue and is fetched from a code object of several thousand
-// instructions; this one is the step and nothing else.
+// env_step (T = 1) as a kernel of its own: the step and nothing else.  What bounds a loop of such
+// launches on this runtime (one stream, N = 4096, launches back to back from C++):
+//  * the device, for a kernel without a kernel-argument segment: 1.5 us per launch if it is empty,
+//    2.1 us if 16 workgroups store 16 KiB and take a ticket at the end; the host needs 0.6-0.7 us to
+//    enqueue one;
+//  * the host, for a kernel with a kernel-argument segment of any size (explicit arguments, or
+//    only the hidden ones behind gridDim / blockDim): 2.4 us per launch whatever the kernel does,
+//    20 bytes of arguments or 160, an empty body or a 1 MiB store.
+// A caller that steps in a loop passes the same buffers every time, so all that changes between
+// two launches is the step index.  Hence the resident form below: the launch descriptor lives in
+// device memory (one record per handle, STEP_RECORD_SLOTS handles per device), with step
+// counters of its own that the launch advances, and the kernel takes no argument and asks for
+// neither gridDim nor blockDim.  The host rewrites the
+// record (a one-thread launch that carries it as its argument) only when a call differs from the
+// record: other buffers, another stream, a step index that did not come from the last resident
+// launch (reset, rollout or set_state in between).  Results are those of pong_step_kernel, bit for
+// bit: both run pong_single_step.
 template <bool EXTERNAL_ACTIONS, bool NORMALIZE>
-__global__ __launch_bounds__(256) void pong_step_kernel(PongLaunch a) {
-  a.step0 = launch_first_step(a.counter, a.step0, 1, a.ticket != 0);
+__device__ __forceinline__ void pong_single_step(const PongLaunch& a, const uint64_t step) {
   const int64_t n = a.n;
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const bool live = i < n;
   const int64_t ic = live ? i : n - 1;                          // idle lanes shadow the last environment
   // the draw does not depend on the state: its multiply chain runs under the state's loads
-  const Draw4 d = philox_draw(a.seed, (uint32_t)ic, a.step0, 0u);
+  const Draw4 d = philox_draw(a.seed, (uint32_t)ic, step, 0u);
   PongLane s = pong_load(a.state, n, ic);
   const float move = EXTERNAL_ACTIONS ? pong_move_of_action((int)a.actions[ic]) : pong_move_of_word(d.w0);
   const PongEvent ev = pong_transition_move(s, move, d.w1, d.w2, a.max_score);
@@ -304,8 +317,63 @@ __global__ __launch_bounds__(256) void pong_step_kernel(PongLaunch a) {
     a.done[i] = done ? 1 : 0;
     pong_store(a.state, n, i, s);
   }
-  flush_wave_stats<false>(a.stats, le);
+  flush_wave_stats<false, 4>(a.stats, le);
 }
+
+template <bool EXTERNAL_ACTIONS, bool NORMALIZE>
+__global__ __launch_bounds__(256) void pong_step_kernel(PongLaunch a) {
+  const uint64_t step = first_step_of_launch(a.counter, a.step0);
+  pong_single_step<EXTERNAL_ACTIONS, NORMALIZE>(a, step);
+  if (a.counter && a.ticket) finish_launch_steps(a.counter, step, 1, gridDim.x);
+}
+
+constexpr int STEP_RECORD_SLOTS = 4;
+constexpr unsigned STEP_RECORD_MAX_GROUPS = 64;    // 16384 environments; larger batches are not launch-bound
+struct StepRecord {
+  PongLaunch a;        // step0, counter and ticket are not used
+};
+__device__ StepRecord g_step_records[STEP_RECORD_SLOTS];
+// The record's step index, one copy per wavefront of the launch: a wavefront reads its own copy
+// at the start and writes copy + 1 at the end, so no wavefront waits for another and nothing is
+// atomic.  Every copy moves by one per launch; the host rewrites them all when it rewrites the record.
+__device__ unsigned long long g_step_record_steps[STEP_RECORD_SLOTS][STEP_RECORD_MAX_GROUPS * 4];
+
+// A pointer read from memory is a generic one to the compiler (flat loads and stores); kernel
+// arguments are known to point to global memory.  Say the same of the record's pointers.
+template <class T>
+__device__ __forceinline__ T* known_global(T* p) {
+  return (T*)(__attribute__((address_space(1))) T*)(uintptr_t)p;   // by way of the integer: a cast pair is folded away
+}
+
+template <int SLOT>
+__global__ __launch_bounds__(256) void pong_step_resident_kernel() {
+  PongLaunch a = g_step_records[SLOT].a;
+  a.state = known_global(a.state);
+  a.actions = known_global(a.actions);
+  a.obs = known_global(a.obs);
+  a.reward = known_global(a.reward);
+  a.done = known_global(a.done);
+  a.stats = known_global(a.stats);
+  unsigned long long* const mine = &g_step_record_steps[SLOT][blockIdx.x * 4u + (threadIdx.x >> 6)];
+  const unsigned long long s = *mine;
+  const uint64_t step = ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(s >> 32)) << 32) |
+                        __builtin_amdgcn_readfirstlane((uint32_t)s);
+  if (a.actions) {
+    if (a.normalize) pong_single_step<true, true>(a, step);
+    else pong_single_step<true, false>(a, step);
+  } else {
+    if (a.normalize) pong_single_step<false, true>(a, step);
+    else pong_single_step<false, false>(a, step);
+  }
+  if ((threadIdx.x & 63u) == 0u) *mine = step + 1;
+}
+
+// One workgroup of 256 threads: the record, and every wavefront's copy of the step index.
+__global__ __launch_bounds__(256) void step_record_write_kernel(int slot, PongLaunch a, unsigned long long step) {
+  if (threadIdx.x == 0) g_step_records[slot].a = a;
+  g_step_record_steps[slot][threadIdx.x] = step;
+}
+static_assert(STEP_RECORD_MAX_GROUPS * 4 == 256, "step_record_write_kernel writes one copy per thread");
 
 // Small batches (fewer wavefronts than SIMDs): two wavefronts per 64 environments.  A launch of
 // 16384 environments occupies a quarter of the device's SIMDs.  The Philox draws do not depend on
@@ -406,7 +474,7 @@ int g_paged_mode = 2;      // 0 never, 1 whenever possible, 2 = choose from N
 int g_xcd_remap = 1;
 int g_rollout_chunk = 0;   // 0 = choose from N
 int g_rollout_pace = 0;    // GB/s the paced variant keeps the write stream to; 0 = choose from N, -1 = never paced
-int g_step_kernel = 1;     // 1 = T = 1 launches take the dedicated step kernel, 0 = the rollout kernel's T = 1 path
+int g_step_kernel = 1;     // T = 1 launches: 1 = the step kernel, resident form where it applies; 2 = the step kernel with arguments; 0 = the rollout kernel's T = 1 path
 int g_measure_pace = 1;    // 1 = measure once per device and batch size whether pacing pays, 0 = the table decides
 
 }  // namespace
@@ -445,7 +513,7 @@ bool set_rollout_pace(int gb_per_s) {
 }
 
 bool set_step_kernel(int on) {
-  if (on != 0 && on != 1) return false;
+  if (on < 0 || on > 2) return false;
   g_step_kernel = on;
   return true;
 }
@@ -606,7 +674,58 @@ int pong_pace_choice(int64_t n) {
   return known_choice(device, n, &rate) ? rate : 0;
 }
 
-hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream) {
+namespace {
+
+std::atomic<unsigned long long> g_resident_launches{0};
+
+// Ownership of the launch records, per device (host side).
+std::mutex g_step_slot_mutex;
+struct StepSlots { int device; bool taken[STEP_RECORD_SLOTS]; };
+std::vector<StepSlots> g_step_slots;
+
+int step_slot_acquire(int device) {
+  std::lock_guard<std::mutex> lock(g_step_slot_mutex);
+  StepSlots* d = nullptr;
+  for (auto& x : g_step_slots)
+    if (x.device == device) d = &x;
+  if (!d) {
+    g_step_slots.push_back(StepSlots{device, {}});
+    d = &g_step_slots.back();
+  }
+  for (int k = 0; k < STEP_RECORD_SLOTS; ++k)
+    if (!d->taken[k]) {
+      d->taken[k] = true;
+      return k;
+    }
+  return -1;
+}
+
+// What a resident launch depends on: everything the step reads from its descriptor.
+bool same_step_request(const PongLaunch& x, const PongLaunch& y) {
+  return x.state == y.state && x.n == y.n && x.seed == y.seed && x.max_score == y.max_score &&
+         x.actions == y.actions && x.obs == y.obs && x.reward == y.reward && x.done == y.done &&
+         x.stats == y.stats && x.normalize == y.normalize && x.inv_score == y.inv_score;
+}
+
+template <int SLOT>
+void launch_resident(unsigned groups, hipStream_t stream) {
+  hipLaunchKernelGGL(pong_step_resident_kernel<SLOT>, dim3(groups), dim3(256), 0, stream);
+}
+
+}  // namespace
+
+unsigned long long resident_step_launches() { return g_resident_launches.load(std::memory_order_relaxed); }
+
+void step_resident_release(StepResident& r) {
+  if (r.slot < 0) return;
+  std::lock_guard<std::mutex> lock(g_step_slot_mutex);
+  for (auto& x : g_step_slots)
+    if (x.device == r.device) x.taken[r.slot] = false;
+  r.slot = -1;
+  r.on_device = false;
+}
+
+hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream, StepResident* resident) {
   const int block = g_rollout_block ? g_rollout_block : ROLLOUT_BLOCK;
   unsigned blocks = (unsigned)((a.n + block - 1) / block);
   blocks = (blocks + 7u) & ~7u;   // multiple of the XCD count; surplus workgroups exit at once
@@ -616,6 +735,45 @@ hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream) {
   a2.xcd_remap = g_xcd_remap;
   if (a.T == 1 && g_step_kernel) {
     const unsigned groups = (unsigned)((a.n + 255) / 256);
+    // The resident form: for a handle with the host step counter (so the call is never part of a
+    // stream capture), at most STEP_RECORD_MAX_GROUPS workgroups, and a call that asks for what
+    // the call before it asked for.  A caller that alternates between buffers never takes it and never
+    // pays for a rewrite of the record; a steady loop takes it from its second call on.
+    if (resident && !a.counter && g_step_kernel == 1 && groups <= STEP_RECORD_MAX_GROUPS) {
+      StepResident& r = *resident;
+      const bool repeat = r.have_last && r.last_stream == stream && same_step_request(r.last, a);
+      r.last = a;
+      r.last_stream = stream;
+      r.have_last = true;
+      if (repeat && !r.asked) {
+        r.asked = true;
+        if (hipGetDevice(&r.device) == hipSuccess) r.slot = step_slot_acquire(r.device);
+        else (void)hipGetLastError();
+      }
+      if (repeat && r.slot >= 0) {
+        if (!(r.on_device && r.rec_stream == stream && r.next_step == a.step0 && same_step_request(r.rec, a))) {
+          hipLaunchKernelGGL(step_record_write_kernel, dim3(1), dim3(256), 0, stream, r.slot, a,
+                             (unsigned long long)a.step0);
+          const hipError_t e = hipGetLastError();
+          if (e != hipSuccess) return e;
+          r.rec = a;
+          r.rec_stream = stream;
+          r.on_device = true;
+        }
+        switch (r.slot) {
+          case 0: launch_resident<0>(groups, stream); break;
+          case 1: launch_resident<1>(groups, stream); break;
+          case 2: launch_resident<2>(groups, stream); break;
+          default: launch_resident<3>(groups, stream); break;
+        }
+        static_assert(STEP_RECORD_SLOTS == 4, "one case per record");
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) r.on_device = false;
+        r.next_step = a.step0 + 1;
+        g_resident_launches.fetch_add(1, std::memory_order_relaxed);
+        return e;
+      }
+    }
     a2.ticket = groups <= TICKET_MAX_BLOCKS;
     const dim3 sg(groups), sb(256);
     if (a.actions && a.normalize) hipLaunchKernelGGL((pong_step_kernel<true, true>), sg, sb, 0, stream, a2);

@@ -58,10 +58,13 @@ struct LaneEpisodes {
 };
 
 // Must be called by all 64 lanes of the wavefront (inactive environments pass empty accumulators).
-template <bool FLOAT_RETURNS>
+// WAVES_PER_GROUP: the workgroup's size in wavefronts where the kernel knows it (a kernel launched
+// without arguments must not ask for blockDim); 0 = ask.
+template <bool FLOAT_RETURNS, int WAVES_PER_GROUP = 0>
 __device__ __forceinline__ void flush_wave_stats(DeviceStats* __restrict__ stripes, const LaneEpisodes& le) {
   if (__ballot(le.count > 0 || le.nonfinite > 0) == 0ull) return;   // wave-uniform
-  DeviceStats* st = stripes + ((blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6)) & (STATS_STRIPES - 1));
+  const unsigned waves = WAVES_PER_GROUP ? (unsigned)WAVES_PER_GROUP : (blockDim.x >> 6);
+  DeviceStats* st = stripes + ((blockIdx.x * waves + (threadIdx.x >> 6)) & (STATS_STRIPES - 1));
   const long long cnt = wave_sum((long long)le.count);
   const long long len = wave_sum((long long)le.length_sum);
   const long long bad = wave_sum((long long)le.nonfinite);

@@ -54,6 +54,37 @@ __device__ __forceinline__ uint64_t launch_first_step(StepCounter* counter, uint
   return ((uint64_t)hi << 32) | lo;
 }
 
+// The same small-grid protocol with the ticket at the end of the launch instead of in front of its
+// work, for kernels in which every thread reaches the end: first_step_of_launch at the start (a
+// plain load that runs beside the launch's other loads), finish_launch_steps after the last store.
+// By the barrier every wavefront of the workgroup has used its copy of the counter (the loads have
+// returned), so the ticket can be a relaxed atomic: what it orders is only "this workgroup has
+// read", and the count itself tells the last workgroup that all have.  (Release / acquire at
+// device scope would make every workgroup write back and invalidate its L2 slice, which costs
+// more than the step.)  The workgroup that takes the last ticket writes first + T; the next
+// launch on the stream reads it behind the kernel boundary.
+__device__ __forceinline__ uint64_t first_step_of_launch(const StepCounter* counter, uint64_t host_step0) {
+  if (!counter) return host_step0;
+  const unsigned long long s = __hip_atomic_load(&counter->step, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)s);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(s >> 32));
+  return ((uint64_t)hi << 32) | lo;
+}
+
+__device__ __forceinline__ void finish_launch_steps(StepCounter* counter, uint64_t first, int32_t T,
+                                                    unsigned blocks) {
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned int t =
+        __hip_atomic_fetch_add(&counter->ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (t == blocks - 1u) {
+      __hip_atomic_store(&counter->ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&counter->step, (unsigned long long)first + (unsigned long long)T, __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+}
+
 // For kernels that only read the counter (reset): no ticket, no write.
 __device__ __forceinline__ uint64_t read_step(const StepCounter* counter, uint64_t host_step) {
   return counter ? __hip_atomic_load(&counter->step, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : host_step;

@@ -544,3 +544,170 @@ def test_both_ways_to_take_a_single_step(n, external, step_kernel):
         assert b.lib().mi355env_tune_step_kernel(1) == 0
     compare(g, oracle_rollout(n, seed, T, max_score=1, actions=acts), n, "single steps")
     assert g["stats"]["episodes"] > 0 or n < 10
+
+
+def test_a_prepared_step_repeated_is_the_rollout():
+    # binding.PreparedStep marshals env_step's arguments once; every call after that is the C entry
+    # point alone.  T calls into the same buffers leave the oracle's state after T steps, its
+    # statistics, and the outputs of the last step.
+    n, seed, T = 1000, 77, 90
+    h = b.env_create(b.ENV_PONG, n, seed, {"max_score": 1})
+    try:
+        b.env_reset(h, None)
+        obs, rew, done = (x[0] for x in bufs(1, n))
+        step = b.PreparedStep(h, None, obs, rew, done)
+        for _ in range(T):
+            step()
+        torch.cuda.synchronize()
+        o = oracle_rollout(n, seed, T, max_score=1)
+        assert_bit_equal(obs.cpu().numpy(), o["obs"][T - 1], "prepared step obs")
+        assert_bit_equal(rew.cpu().numpy(), o["rew"][T - 1], "prepared step reward")
+        assert_bit_equal(done.cpu().numpy(), o["done"][T - 1], "prepared step done")
+        count, fields = split_state(b.env_get_state(h), n, 10)
+        assert count == T == b.env_step_count(h)
+        assert_bit_equal(fields, o["state"], "prepared step state")
+        assert b.env_stats(h)["episodes"] == o["stats"]["episodes"] > 0
+    finally:
+        b.env_destroy(h)
+
+
+def _resident_launches():
+    f = b.lib().mi355env_resident_step_launches
+    f.restype = C.c_ulonglong
+    return int(f())
+
+
+class _Mirror:
+    """One handle and its oracle twin, stepped through the same calls; every step's outputs compared."""
+
+    def __init__(self, n, seed, external, scaled):
+        cfg = {"max_score": 1}
+        if scaled:
+            cfg["obs_scaling"] = b.ENV_OBS_NORMALIZED
+        self.n, self.external = n, external
+        self.h = b.env_create(b.ENV_PONG, n, seed, cfg)
+        self.o = orc.Pong(n, seed, max_score=1, normalize=scaled)
+        self.bufs = [tuple(x[0] for x in bufs(1, n)) for _ in range(2)]
+        self.act = torch.empty(n, dtype=torch.uint8, device=DEV) if external else None
+        self.seen = []      # (obs, reward, done) of every step, device copies taken on the stream
+        self.want = []
+        self.k = 0
+
+    def reset(self):
+        b.env_reset(self.h, None)
+        self.o.reset()
+
+    def steps(self, count, which=0):
+        obs, rew, done = self.bufs[which]
+        for _ in range(count):
+            a = None
+            if self.external:
+                a = inputs.pong_actions(1, self.n, seed=1000 + self.k)[0]
+                self.act.copy_(torch.from_numpy(a))
+            self.k += 1
+            b.env_step(self.h, self.act, obs, rew, done)
+            self.seen.append((obs.clone(), rew.clone(), done.clone()))
+            self.want.append(tuple(x[0] for x in self.o.rollout(1, actions=None if a is None else a[None])))
+
+    def rollout(self, T):
+        assert not self.external
+        obs, rew, done = bufs(T, self.n)
+        b.env_rollout(self.h, T, None, obs, rew, done)
+        oo, orr, od = self.o.rollout(T)
+        self.seen.append((obs[-1].clone(), rew[-1].clone(), done[-1].clone()))
+        self.want.append((oo[-1], orr[-1], od[-1]))
+
+    def check(self, what):
+        torch.cuda.synchronize()
+        assert len(self.seen) == len(self.want)
+        for t, (g, w) in enumerate(zip(self.seen, self.want)):
+            for gx, wx, name in zip(g, w, ("obs", "reward", "done")):
+                assert_bit_equal(gx.cpu().numpy(), wx, "%s: %s of call %d" % (what, name, t))
+        count, fields = split_state(b.env_get_state(self.h), self.n, 10)
+        assert count == self.o.step_count == b.env_step_count(self.h)
+        assert_bit_equal(fields, pong_state_fields(self.o.envs()), what + ": state")
+        gs, ws = b.env_stats(self.h), self.o.stats()
+        assert gs["episodes"] == ws["episodes"] and gs["return_sum"] == ws["return_sum"]
+        assert gs["length_sum"] == ws["length_sum"]
+
+    def close(self):
+        b.env_destroy(self.h)
+
+
+@pytest.mark.parametrize("external,scaled", [(False, False), (True, False), (False, True), (True, True)])
+@pytest.mark.parametrize("n", [1, 700, 4096, 16384])
+def test_steps_launched_from_the_resident_record(n, external, scaled):
+    # From the second call in a row with the same buffers, env_step launches a kernel that takes no
+    # argument and reads its descriptor, and the step index, from device memory.  Whatever else moves
+    # the step index or the state in between (reset, a rollout, set_state, a call with other buffers)
+    # has to show in the next step.
+    m = _Mirror(n, 40 + n, external, scaled)
+    resident_before = _resident_launches()
+    try:
+        m.reset()
+        m.steps(12)
+        if not external:
+            m.rollout(7)
+        m.steps(6)
+        m.reset()
+        m.steps(5)
+        b.env_set_state(m.h, b.env_get_state(m.h))
+        m.steps(5)
+        m.steps(2, which=1)
+        m.steps(40)
+        m.check("resident steps, n = %d" % n)
+        assert b.env_stats(m.h)["episodes"] > 0 or n == 1
+        # of the 70 steps, the first of every run with new buffers goes with arguments: 12 + 6 + 5 + 5
+        # (+ 2 in the second set of buffers) + 40, less one per run
+        assert _resident_launches() - resident_before == 11 + 6 + 5 + 5 + 1 + 39
+    finally:
+        m.close()
+
+
+def test_more_stepping_handles_than_resident_records():
+    # Four handles per device own a launch record; a fifth and sixth step with arguments.  All of
+    # them interleaved, then two destroyed and two new ones created (which take over their records).
+    ms = [_Mirror(300 + 7 * k, 900 + k, False, False) for k in range(6)]
+    resident_before = _resident_launches()
+    try:
+        for m in ms:
+            m.reset()
+        for _ in range(10):
+            for m in ms:
+                m.steps(3)
+        for m in ms:
+            m.check("handle of %d" % m.n)
+        # four handles went resident from their second step on, the other two never
+        assert _resident_launches() - resident_before == 4 * 29
+        for m in ms[:2]:
+            m.close()
+        ms = ms[2:] + [_Mirror(5000 + k, 950 + k, False, False) for k in range(2)]
+        for m in ms[-2:]:
+            m.reset()
+        for _ in range(6):
+            for m in ms:
+                m.steps(4)
+        for m in ms:
+            m.check("handle of %d, second round" % m.n)
+    finally:
+        for m in ms:
+            m.close()
+
+
+def test_resident_steps_follow_the_handle_to_another_stream():
+    n = 2000
+    m = _Mirror(n, 5, False, False)
+    side = torch.cuda.Stream()
+    try:
+        m.reset()
+        m.steps(8)
+        torch.cuda.synchronize()
+        b.env_set_stream(m.h, side.cuda_stream)
+        with torch.cuda.stream(side):
+            m.steps(8)
+        torch.cuda.synchronize()
+        b.env_set_stream(m.h, torch.cuda.current_stream().cuda_stream)
+        m.steps(8)
+        m.check("steps across streams")
+    finally:
+        m.close()
