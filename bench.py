@@ -220,6 +220,27 @@ def bench_pong_per_step(b, torch, n, seed, launches):
                 hbm_gbs=n * 101 / (wall / launches) / 1e9)
 
 
+def bench_launch_costs(b, torch, launches=20000):
+    """What a launch costs on this runtime, loops enqueued from C++ (mi355env_bench_launch_loop): an
+    empty kernel, a 16 KiB store whose descriptor travels as kernel arguments, and the same store
+    by a kernel without a kernel-argument segment.  Host time to enqueue and time until drained."""
+    import ctypes as C
+    f = b.lib().mi355env_bench_launch_loop
+    f.argtypes = [C.c_int, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    dst = torch.empty(16384, dtype=torch.uint8, device="cuda:0")
+    st = torch.cuda.current_stream().cuda_stream
+    out = {}
+    for _ in range(2):                                   # the first round warms the device up
+        for kind, name in ((0, "empty"), (1, "store_16k_with_arguments"), (2, "store_16k_no_argument_segment")):
+            host, total = C.c_double(), C.c_double()
+            rc = f(kind, launches, dst.data_ptr(), dst.numel(), st, C.byref(host), C.byref(total))
+            if rc != 0:
+                raise RuntimeError("mi355env_bench_launch_loop -> %d" % rc)
+            out[name] = dict(host_us_per_launch=host.value, us_per_launch=total.value)
+    out["launches"] = launches
+    return out
+
+
 def bench_pixels(b, torch, n, seed, launches, warmup=20, layout="slot_major", device_counter=False,
                  delta=False):
     dev = "cuda:0"
@@ -610,6 +631,7 @@ def main():
                                        bench_pixels(b, torch, 16384, 3, args.steps, layout="ordered",
                                                     device_counter=True)],
               "per_step": lambda: bench_pong_per_step(b, torch, 4096, 1, args.steps),
+              "launch_costs": lambda: bench_launch_costs(b, torch),
               "sweep": lambda: {"n%d" % nn: bench_pong_rollout(b, torch, nn, 1000, 2, args.steps, 10)
                                 for nn in (16384, 131072, 262144)},
               "sweep_large": lambda: {"n524288": bench_pong_rollout(b, torch, 524288, 250, 2, args.steps, 3)},
@@ -683,6 +705,7 @@ def main():
         floor["rollout_vs_unpaced_stores"] = floor["ms_per_launch"] / r["mean_ms"]
         floor["rollout_vs_best_paced_stores"] = floor["best_paced_ms"] / r["mean_ms"]
         extra["config1_per_step"] = bench_pong_per_step(b, torch, 4096, 1, 10000)
+        extra["launch_costs"] = bench_launch_costs(b, torch)
         extra["config3_pixels"] = bench_pixels(b, torch, 16384, 3, 500)
         for nn, st in ((32768, 300), (262144, 60)):      # the same step on larger batches (context, not the target)
             extra["pixels_n%d" % nn] = bench_pixels(b, torch, nn, 3, st)

@@ -103,6 +103,15 @@ int mi355env_bench_fill(void *dst_dev, size_t bytes, uint32_t value, void *hip_s
 int mi355env_bench_fill_pages(void *dst_dev, size_t bytes, uint32_t value, void *hip_stream);
 int mi355env_bench_copy(void *dst_dev, const void *src_dev, size_t bytes, void *hip_stream);
 int mi355env_bench_empty(void *hip_stream);
+/* A loop of `launches` launches enqueued from C++ with nothing in between, to tell the host's share
+ * of a launch from the device's.  kind 0: an empty kernel; 1: workgroups of 256 threads store
+ * bytes / 4 words, descriptor passed as kernel arguments; 2: the same store, descriptor read from
+ * device memory by a kernel without a kernel-argument segment.  dst_dev: device memory of `bytes`
+ * bytes (a multiple of 1024, at most 1 MiB; ignored for kind 0).  *host_us_out: host time per
+ * launch until the last one is enqueued; *total_us_out: per launch until the stream has drained.
+ * Synchronises the stream before and after.  Returns 0, -1 (arguments) or -3 (HIP error). */
+int mi355env_bench_launch_loop(int kind, int launches, void *dst_dev, size_t bytes, void *hip_stream,
+                               double *host_us_out, double *total_us_out);
 /* The trajectory stores of the fused Pong rollout without any computation: constant values into
  * obs_dev float32[T][n][8] (16-byte aligned), reward_dev float32[T][n], done_dev uint8[T][n], in the
  * rollout's launch shape.  Its duration is the floor the memory system sets for that layout. */

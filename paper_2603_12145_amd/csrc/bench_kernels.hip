@@ -2,6 +2,7 @@
 // copy with 16-byte accesses.  They calibrate the HBM counters (known bytes per launch) and give
 // the write / copy bandwidth a trivial kernel reaches on the same device.
 #include <hip/hip_runtime.h>
+#include <chrono>
 #include <stdint.h>
 
 namespace {
@@ -55,6 +56,29 @@ __global__ __launch_bounds__(256) void trajectory_stores_kernel(float* __restric
 }
 
 __global__ void empty_kernel() {}
+
+// What a launch costs with and without a kernel-argument segment: the same 4-byte-per-thread store,
+// once with its descriptor as kernel arguments, once read from a record in device memory by a
+// kernel that takes no argument and asks for neither gridDim nor blockDim.
+struct StoreRecord { uint32_t* dst; uint32_t words; uint32_t value; };
+__device__ StoreRecord g_store_record;
+
+__global__ __launch_bounds__(256) void store_with_arguments_kernel(uint32_t* dst, uint32_t words, uint32_t value) {
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (i < words) dst[i] = value;
+}
+
+__global__ __launch_bounds__(256) void store_from_record_kernel() {
+  const StoreRecord r = g_store_record;
+  const uint32_t i = blockIdx.x * 256u + threadIdx.x;
+  if (i < r.words) r.dst[i] = r.value;
+}
+
+__global__ void store_record_write_kernel(StoreRecord r) { g_store_record = r; }
+
+double seconds_now() {
+  return std::chrono::duration<double>(std::chrono::steady_clock::now().time_since_epoch()).count();
+}
 
 unsigned grid_for(size_t chunks) {
   const size_t want = (chunks + 255) / 256;
@@ -123,6 +147,38 @@ int mi355env_bench_trajectory_stores(void* obs_dev, void* reward_dev, void* done
 int mi355env_bench_empty(void* hip_stream) {
   hipLaunchKernelGGL(empty_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(hip_stream));
   return hipGetLastError() == hipSuccess ? 0 : -3;
+}
+
+// A loop of `launches` launches on hip_stream, enqueued from C++ with nothing in between.
+// kind 0: an empty kernel; 1: 256-thread workgroups store bytes / 4 words, descriptor passed as
+// kernel arguments; 2: the same store, descriptor read from device memory, no kernel-argument
+// segment.  dst_dev: device memory of `bytes` bytes (a multiple of 1024, at most 1 MiB; unused for
+// kind 0).  *host_us_out: host time per launch until the last one is enqueued; *total_us_out: per
+// launch until the stream has drained.  Synchronises the stream before and after.
+int mi355env_bench_launch_loop(int kind, int launches, void* dst_dev, size_t bytes, void* hip_stream,
+                               double* host_us_out, double* total_us_out) {
+  if (kind < 0 || kind > 2 || launches <= 0 || launches > 10000000 || !host_us_out || !total_us_out) return -1;
+  if (kind != 0 && (!dst_dev || bytes == 0 || (bytes & 1023) || bytes > (size_t(1) << 20) ||
+                    (reinterpret_cast<uintptr_t>(dst_dev) & 3)))
+    return -1;
+  hipStream_t st = static_cast<hipStream_t>(hip_stream);
+  uint32_t* dst = static_cast<uint32_t*>(dst_dev);
+  const uint32_t words = (uint32_t)(bytes / 4);
+  const dim3 g(kind == 0 ? 1u : words / 256u), b(kind == 0 ? 64u : 256u);
+  if (kind == 2) hipLaunchKernelGGL(store_record_write_kernel, dim3(1), dim3(1), 0, st, StoreRecord{dst, words, 1u});
+  if (hipStreamSynchronize(st) != hipSuccess) return -3;
+  const double t0 = seconds_now();
+  for (int k = 0; k < launches; ++k) {
+    if (kind == 0) hipLaunchKernelGGL(empty_kernel, g, b, 0, st);
+    else if (kind == 1) hipLaunchKernelGGL(store_with_arguments_kernel, g, b, 0, st, dst, words, 1u);
+    else hipLaunchKernelGGL(store_from_record_kernel, g, b, 0, st);
+  }
+  const double t1 = seconds_now();
+  if (hipStreamSynchronize(st) != hipSuccess || hipGetLastError() != hipSuccess) return -3;
+  const double t2 = seconds_now();
+  *host_us_out = (t1 - t0) / launches * 1e6;
+  *total_us_out = (t2 - t0) / launches * 1e6;
+  return 0;
 }
 
 int mi355env_bench_copy(void* dst_dev, const void* src_dev, size_t bytes, void* hip_stream) {
