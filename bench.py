@@ -146,10 +146,12 @@ def bench_pong_rollout(b, torch, n, T, seed, steps, warmup, repeats=1):
                 runs=[dict(env_steps_per_s=n * T * steps / w, launch_ms_mean=_mean_std(m)[0]) for w, m in regions])
 
 
-def bench_pong_per_step(b, torch, n, seed, launches):
+def bench_pong_per_step(b, torch, n, seed, launches, kind="pong"):
+    """One env_step launch per step, the same buffers every step (kind: "pong" or "cartpole")."""
     dev = "cuda:0"
-    h = b.env_create(b.ENV_PONG, n, seed, None)
-    obs = torch.empty((n, 8), dtype=torch.float32, device=dev)
+    env_kind, obs_dim, step_bytes = {"pong": (b.ENV_PONG, 8, 101), "cartpole": (b.ENV_CARTPOLE, 4, 61)}[kind]
+    h = b.env_create(env_kind, n, seed, None)
+    obs = torch.empty((n, obs_dim), dtype=torch.float32, device=dev)
     rew = torch.empty(n, dtype=torch.float32, device=dev)
     done = torch.empty(n, dtype=torch.uint8, device=dev)
     b.env_reset(h, None)
@@ -185,7 +187,7 @@ def bench_pong_per_step(b, torch, n, seed, launches):
     per_graph = 100
     st = torch.cuda.Stream()
     with torch.cuda.stream(st):
-        hg = b.env_create(b.ENV_PONG, n, seed, {"step_counter": b.ENV_STEP_COUNTER_DEVICE}, stream=st)
+        hg = b.env_create(env_kind, n, seed, {"step_counter": b.ENV_STEP_COUNTER_DEVICE}, stream=st)
         b.env_reset(hg, None)
         b.env_step(hg, None, obs, rew, done)
         st.synchronize()
@@ -206,7 +208,7 @@ def bench_pong_per_step(b, torch, n, seed, launches):
         b.env_destroy(hg)
     assert graph_steps == 1 + per_graph * (warm + reps), graph_steps   # the capture itself runs nothing
     graph_us = 1e6 * graph_wall / (reps * per_graph)
-    return dict(workload="pong vector obs N=%d, one env_step launch per step" % n,
+    return dict(workload="%s N=%d, one env_step launch per step" % ("pong vector obs" if kind == "pong" else kind, n),
                 graph_replay_us_per_launch=graph_us, graph_env_steps_per_s=n / (graph_us * 1e-6),
                 graph_launches_per_graph=per_graph,
                 us_per_launch=1e6 * wall / launches, env_steps_per_s=n * launches / wall,
@@ -217,7 +219,7 @@ def bench_pong_per_step(b, torch, n, seed, launches):
                                            us_per_launch_prepared_call=1e6 * wall_args_prepared / launches),
                 bound="dispatch latency", launches=launches,
                 empty_kernel_us_per_launch=1e6 * empty / launches, ratio_to_empty_launch=wall / empty,
-                hbm_gbs=n * 101 / (wall / launches) / 1e9)
+                hbm_gbs=n * step_bytes / (wall / launches) / 1e9)   # state read and written, obs, reward, done
 
 
 def bench_launch_costs(b, torch, launches=20000):
@@ -632,6 +634,7 @@ def main():
                                                     device_counter=True)],
               "per_step": lambda: bench_pong_per_step(b, torch, 4096, 1, args.steps),
               "launch_costs": lambda: bench_launch_costs(b, torch),
+              "cartpole_per_step": lambda: bench_pong_per_step(b, torch, 4096, 1, args.steps, kind="cartpole"),
               "sweep": lambda: {"n%d" % nn: bench_pong_rollout(b, torch, nn, 1000, 2, args.steps, 10)
                                 for nn in (16384, 131072, 262144)},
               "sweep_large": lambda: {"n524288": bench_pong_rollout(b, torch, 524288, 250, 2, args.steps, 3)},
@@ -706,6 +709,7 @@ def main():
         floor["rollout_vs_best_paced_stores"] = floor["best_paced_ms"] / r["mean_ms"]
         extra["config1_per_step"] = bench_pong_per_step(b, torch, 4096, 1, 10000)
         extra["launch_costs"] = bench_launch_costs(b, torch)
+        extra["cartpole_per_step_n4096"] = bench_pong_per_step(b, torch, 4096, 1, 10000, kind="cartpole")
         extra["config3_pixels"] = bench_pixels(b, torch, 16384, 3, 500)
         for nn, st in ((32768, 300), (262144, 60)):      # the same step on larger batches (context, not the target)
             extra["pixels_n%d" % nn] = bench_pixels(b, torch, nn, 3, st)

@@ -187,6 +187,72 @@ __global__ __launch_bounds__(256) void cartpole_rollout_kernel(PongLaunch a) {
   flush_wave_stats<false>(a.stats, le);
 }
 
+// env_step (T = 1) as a kernel of its own, launched with its descriptor as a kernel argument or,
+// in a steady loop, without any argument (see kernels.hpp).  Same arithmetic on the same words as
+// the rollout loops.
+template <bool EXTERNAL_ACTIONS>
+__device__ __forceinline__ void cart_single_step(const PongLaunch& a, const uint64_t step) {
+  const int64_t n = a.n;
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const bool live = i < n;
+  const int64_t ic = live ? i : n - 1;                          // idle lanes shadow the last environment
+  const uint32_t word = EXTERNAL_ACTIONS ? 0u : philox_draw(a.seed, (uint32_t)ic, step, 0u).w0;
+  CartLane s = cart_load(a.state, n, ic);
+  const int action = EXTERNAL_ACTIONS ? (live ? (int)a.actions[ic] : 0) : (int)(word >> 31);
+  int fin_len;
+  const bool ended = cart_transition(s, action, a.max_score, a.seed, (uint32_t)ic, step, fin_len);
+  const bool done = live && ended;
+  LaneEpisodes le;
+  if (done) { le.count = 1; le.length_sum = fin_len; le.ret_sum_i = fin_len; le.min_key = fin_len; le.max_key = fin_len; }
+  if (live) {
+    reinterpret_cast<float4*>(a.obs)[i] = make_float4(s.x, s.xd, s.th, s.thd);
+    a.reward[i] = 1.0f;
+    a.done[i] = done ? 1 : 0;
+    cart_store(a.state, n, i, s);
+  }
+  flush_wave_stats<false, 4>(a.stats, le);
+}
+
+template <bool EXTERNAL_ACTIONS>
+__global__ __launch_bounds__(256) void cartpole_step_kernel(PongLaunch a) {
+  const uint64_t step = first_step_of_launch(a.counter, a.step0);
+  cart_single_step<EXTERNAL_ACTIONS>(a, step);
+  if (a.counter && a.ticket) finish_launch_steps(a.counter, step, 1, gridDim.x);
+}
+
+__device__ PongLaunch g_cart_step_records[STEP_RECORD_SLOTS];
+__device__ unsigned long long g_cart_step_record_steps[STEP_RECORD_SLOTS][STEP_RECORD_MAX_GROUPS * 4];
+
+template <int SLOT>
+__global__ __launch_bounds__(256) void cartpole_step_resident_kernel() {
+  PongLaunch a = g_cart_step_records[SLOT];
+  a.state = known_global(a.state);
+  a.actions = known_global(a.actions);
+  a.obs = known_global(a.obs);
+  a.reward = known_global(a.reward);
+  a.done = known_global(a.done);
+  a.stats = known_global(a.stats);
+  unsigned long long* const mine = &g_cart_step_record_steps[SLOT][blockIdx.x * 4u + (threadIdx.x >> 6)];
+  const unsigned long long s = *mine;
+  const uint64_t step = ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(s >> 32)) << 32) |
+                        __builtin_amdgcn_readfirstlane((uint32_t)s);
+  if (a.actions) cart_single_step<true>(a, step);
+  else cart_single_step<false>(a, step);
+  if ((threadIdx.x & 63u) == 0u) *mine = step + 1;
+}
+
+// One workgroup of 256 threads: the record, and every wavefront's copy of the step index.
+__global__ __launch_bounds__(256) void cart_step_record_write_kernel(int slot, PongLaunch a, unsigned long long step) {
+  if (threadIdx.x == 0) g_cart_step_records[slot] = a;
+  g_cart_step_record_steps[slot][threadIdx.x] = step;
+}
+static_assert(STEP_RECORD_MAX_GROUPS * 4 == 256, "cart_step_record_write_kernel writes one copy per thread");
+
+template <int SLOT>
+void launch_cart_resident(unsigned groups, hipStream_t stream) {
+  hipLaunchKernelGGL(cartpole_step_resident_kernel<SLOT>, dim3(groups), dim3(256), 0, stream);
+}
+
 // Batches of at most one wavefront per SIMD (N <= 65536) with in-kernel actions: two wavefronts per
 // 64 environments.  A lone wavefront on a SIMD issues an instruction every 5.4 cycles, two of them
 // share the SIMD's issue slots at close to one every 4 (the same loop takes 0.438 ms per 1000
@@ -297,10 +363,34 @@ hipError_t launch_cartpole_reset(uint32_t* state, int64_t n, uint64_t seed, uint
 }
 
 // a.max_score carries max_episode_steps
-hipError_t launch_cartpole_rollout(const PongLaunch& a, hipStream_t stream) {
+hipError_t launch_cartpole_rollout(const PongLaunch& a, hipStream_t stream, StepResident* resident) {
   unsigned blocks = (unsigned)((a.n + 255) / 256);
-  blocks = (blocks + 7u) & ~7u;
   PongLaunch a2 = a;
+  if (a.T == 1 && step_kernel_mode() != 0) {
+    hipError_t re = hipSuccess;
+    if (resident_step_try(
+            resident, a, blocks, stream,
+            [&](int slot, const PongLaunch& rec, unsigned long long step) {
+              hipLaunchKernelGGL(cart_step_record_write_kernel, dim3(1), dim3(256), 0, stream, slot, rec, step);
+            },
+            [&](int slot, unsigned groups) {
+              switch (slot) {
+                case 0: launch_cart_resident<0>(groups, stream); break;
+                case 1: launch_cart_resident<1>(groups, stream); break;
+                case 2: launch_cart_resident<2>(groups, stream); break;
+                default: launch_cart_resident<3>(groups, stream); break;
+              }
+              static_assert(STEP_RECORD_SLOTS == 4, "one case per record");
+            },
+            &re))
+      return re;
+    a2.ticket = blocks <= TICKET_MAX_BLOCKS;
+    if (a.actions) hipLaunchKernelGGL(cartpole_step_kernel<true>, dim3(blocks), dim3(256), 0, stream, a2);
+    else hipLaunchKernelGGL(cartpole_step_kernel<false>, dim3(blocks), dim3(256), 0, stream, a2);
+    const hipError_t e = hipGetLastError();
+    return e != hipSuccess ? e : advance_step_counter_behind(a.counter, 1, blocks, stream);
+  }
+  blocks = (blocks + 7u) & ~7u;
   const bool split = !a.actions && (g_cartpole_split == 2 ||
                                     (g_cartpole_split == 0 && a.n <= 65536 && a.T >= 4 * CART_SPLIT_STEPS));
   if (split) {

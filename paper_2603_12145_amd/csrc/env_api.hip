@@ -48,7 +48,7 @@ struct mi355env {
   PixelPipe pipe;         // pixels only: second state buffer and the staging buffers of the lookahead
   uint32_t* trial_state;  // Pong, batch sizes that may run paced: scratch for the launcher's one-time
   DeviceStats* trial_stats;   // measurement (a second state array and statistics block), else null
-  StepResident resident;  // Pong: what the per-step launches keep in device memory between calls
+  StepResident resident;  // Pong, CartPole: what the per-step launches keep in device memory between calls
   bool was_reset;
   // last device ranges that passed the residency check (avoids a driver query per step)
   struct Range { const void* p; size_t bytes; } seen[8];
@@ -256,7 +256,7 @@ int run(env_t* e, int32_t T, bool ring_mode, const void* actions, void* obs, flo
       err = launch_pong_rollout(p, e->stream, &e->resident);
     } else if (e->kind == ENV_CARTPOLE) {
       p.max_score = e->cfg.max_episode_steps;
-      err = launch_cartpole_rollout(p, e->stream);
+      err = launch_cartpole_rollout(p, e->stream, &e->resident);
     } else {
       PixelLaunch x{};
       x.pong = p; x.pong.obs = nullptr;

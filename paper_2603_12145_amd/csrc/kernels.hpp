@@ -45,8 +45,23 @@ constexpr int64_t PACED_MIN_ENVS = 61440, PACED_MAX_ENVS = 262144;
 // reset launchers: counter != nullptr -> the step is read from it instead of `step`
 hipError_t launch_pong_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
                              const StepCounter* counter, float* obs, bool normalize, hipStream_t stream);
-// What a handle remembers of its per-step launches (host side; see launch_pong_rollout): the launch
-// record it owns in device memory, what that record holds, and what the last call asked for.
+// Per-step launches without kernel arguments (Pong with vector observations, CartPole).
+// On this runtime a loop of small launches is bound by the host's launch path whenever the kernel
+// has a kernel-argument segment (2.4 us per launch, whatever the kernel does) and by the device
+// (1.5-2.1 us) when it has none.  A caller that steps in a loop passes the same buffers every time,
+// so all that changes between two launches is the step index: the launch descriptor is kept in
+// device memory (one record per handle, STEP_RECORD_SLOTS handles per device; further handles
+// launch with arguments), the step index with it, one copy per wavefront of the launch -- a
+// wavefront reads its copy at the start and writes copy + 1 at the end, so nothing is atomic and
+// no wavefront waits for another -- and the step kernel takes no argument and asks for neither
+// gridDim nor blockDim.  The host rewrites the record (a one-workgroup launch that carries it as
+// its argument) only when a call differs from it: other buffers, another stream, a step index
+// that did not come from the last resident launch (reset, rollout or set_state in between).
+constexpr int STEP_RECORD_SLOTS = 4;
+constexpr unsigned STEP_RECORD_MAX_GROUPS = 64;    // workgroups of 256: 16384 environments; larger batches are not launch-bound
+
+// What a handle remembers of its per-step launches (host side): the launch record it owns in
+// device memory, what that record holds, and what the last call asked for.
 struct StepResident {
   int device = -1, slot = -1;    // slot < 0: no record owned (not asked for yet, or none was free)
   bool asked = false;
@@ -56,8 +71,57 @@ struct StepResident {
   hipStream_t rec_stream = nullptr, last_stream = nullptr;
   uint64_t next_step = 0;
 };
+int step_slot_acquire(int device);          // -1: all records of the device are taken
 void step_resident_release(StepResident& r);
-// resident: the calling handle's StepResident (Pong with the host step counter), or null
+void count_resident_step_launch();
+int step_kernel_mode();                     // mi355env_tune_step_kernel's value
+
+// What a resident launch depends on: everything a step reads from its descriptor.
+inline bool same_step_request(const PongLaunch& x, const PongLaunch& y) {
+  return x.state == y.state && x.n == y.n && x.seed == y.seed && x.max_score == y.max_score &&
+         x.actions == y.actions && x.obs == y.obs && x.reward == y.reward && x.done == y.done &&
+         x.stats == y.stats && x.normalize == y.normalize && x.inv_score == y.inv_score;
+}
+
+// The host side of a T = 1 launch that may go without arguments: for a handle with the host step
+// counter (so the call is never part of a stream capture), at most STEP_RECORD_MAX_GROUPS
+// workgroups, and a call that asks for what the call before it asked for.  A caller that
+// alternates between buffers never takes the path and never pays for a rewrite of the record; a
+// steady loop takes it from its second call on.  write(slot, a, step) launches the kernel that
+// rewrites record `slot`, launch(slot, groups) the step kernel that reads it.  Returns false if
+// the call is to be launched with arguments instead.
+template <class Write, class Launch>
+bool resident_step_try(StepResident* resident, const PongLaunch& a, unsigned groups, hipStream_t stream,
+                       Write write, Launch launch, hipError_t* err) {
+  if (!resident || a.counter || step_kernel_mode() != 1 || groups > STEP_RECORD_MAX_GROUPS) return false;
+  StepResident& r = *resident;
+  const bool repeat = r.have_last && r.last_stream == stream && same_step_request(r.last, a);
+  r.last = a;
+  r.last_stream = stream;
+  r.have_last = true;
+  if (repeat && !r.asked) {
+    r.asked = true;
+    if (hipGetDevice(&r.device) == hipSuccess) r.slot = step_slot_acquire(r.device);
+    else (void)hipGetLastError();
+  }
+  if (!repeat || r.slot < 0) return false;
+  if (!(r.on_device && r.rec_stream == stream && r.next_step == a.step0 && same_step_request(r.rec, a))) {
+    write(r.slot, a, (unsigned long long)a.step0);
+    *err = hipGetLastError();
+    if (*err != hipSuccess) return true;
+    r.rec = a;
+    r.rec_stream = stream;
+    r.on_device = true;
+  }
+  launch(r.slot, groups);
+  *err = hipGetLastError();
+  if (*err != hipSuccess) r.on_device = false;
+  r.next_step = a.step0 + 1;
+  count_resident_step_launch();
+  return true;
+}
+
+// resident: the calling handle's StepResident, or null
 hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream, StepResident* resident = nullptr);
 
 // CartPole: same launch descriptor (max_score carries max_episode_steps; obs is [T,n,4]).
@@ -65,7 +129,7 @@ constexpr int CARTPOLE_FIELDS = 6;   // x xdot theta thetadot | ep_ret ep_len
 constexpr int CARTPOLE_OBS = 4;
 hipError_t launch_cartpole_reset(uint32_t* state, int64_t n, uint64_t seed, uint64_t step,
                                  const StepCounter* counter, float* obs, hipStream_t stream);
-hipError_t launch_cartpole_rollout(const PongLaunch& a, hipStream_t stream);
+hipError_t launch_cartpole_rollout(const PongLaunch& a, hipStream_t stream, StepResident* resident = nullptr);
 
 // Pixel observations.  ring != nullptr: frame after step s goes to ring[i][s & 3] (T must be 1 or
 // the ring is rewritten in place T times); frames != nullptr: frame t of the launch goes to

@@ -276,23 +276,11 @@ __global__ __launch_bounds__(256) void pong_rollout_kernel(PongLaunch a) {
   flush_wave_stats<false>(a.stats, le);
 }
 
-// env_step (T = 1) as a kernel of its own: the step and nothing else.  What bounds a loop of such
-// launches on this runtime (one stream, N = 4096, launches back to back from C++):
-//  * the device, for a kernel without a kernel-argument segment: 1.5 us per launch if it is empty,
-//    2.1 us if 16 workgroups store 16 KiB and take a ticket at the end; the host needs 0.6-0.7 us to
-//    enqueue one;
-//  * the host, for a kernel with a kernel-argument segment of any size (explicit arguments, or
-//    only the hidden ones behind gridDim / blockDim): 2.4 us per launch whatever the kernel does,
-//    20 bytes of arguments or 160, an empty body or a 1 MiB store.
-// A caller that steps in a loop passes the same buffers every time, so all that changes between
-// two launches is the step index.  Hence the resident form below: the launch descriptor lives in
-// device memory (one record per handle, STEP_RECORD_SLOTS handles per device), with step
-// counters of its own that the launch advances, and the kernel takes no argument and asks for
-// neither gridDim nor blockDim.  The host rewrites the
-// record (a one-thread launch that carries it as its argument) only when a call differs from the
-// record: other buffers, another stream, a step index that did not come from the last resident
-// launch (reset, rollout or set_state in between).  Results are those of pong_step_kernel, bit for
-// bit: both run pong_single_step.
+// env_step (T = 1) as a kernel of its own: the step and nothing else, launched with its
+// descriptor as a kernel argument (pong_step_kernel) or, in a steady loop, without any argument
+// (pong_step_resident_kernel; see kernels.hpp for why and when).  Both run pong_single_step: same
+// results, bit for bit.  N = 4096: 3.1 us per step without arguments (device-bound), 3.8-4.6 us
+// with (host-bound).
 template <bool EXTERNAL_ACTIONS, bool NORMALIZE>
 __device__ __forceinline__ void pong_single_step(const PongLaunch& a, const uint64_t step) {
   const int64_t n = a.n;
@@ -327,8 +315,6 @@ __global__ __launch_bounds__(256) void pong_step_kernel(PongLaunch a) {
   if (a.counter && a.ticket) finish_launch_steps(a.counter, step, 1, gridDim.x);
 }
 
-constexpr int STEP_RECORD_SLOTS = 4;
-constexpr unsigned STEP_RECORD_MAX_GROUPS = 64;    // 16384 environments; larger batches are not launch-bound
 struct StepRecord {
   PongLaunch a;        // step0, counter and ticket are not used
 };
@@ -337,13 +323,6 @@ __device__ StepRecord g_step_records[STEP_RECORD_SLOTS];
 // at the start and writes copy + 1 at the end, so no wavefront waits for another and nothing is
 // atomic.  Every copy moves by one per launch; the host rewrites them all when it rewrites the record.
 __device__ unsigned long long g_step_record_steps[STEP_RECORD_SLOTS][STEP_RECORD_MAX_GROUPS * 4];
-
-// A pointer read from memory is a generic one to the compiler (flat loads and stores); kernel
-// arguments are known to point to global memory.  Say the same of the record's pointers.
-template <class T>
-__device__ __forceinline__ T* known_global(T* p) {
-  return (T*)(__attribute__((address_space(1))) T*)(uintptr_t)p;   // by way of the integer: a cast pair is folded away
-}
 
 template <int SLOT>
 __global__ __launch_bounds__(256) void pong_step_resident_kernel() {
@@ -683,6 +662,17 @@ std::mutex g_step_slot_mutex;
 struct StepSlots { int device; bool taken[STEP_RECORD_SLOTS]; };
 std::vector<StepSlots> g_step_slots;
 
+template <int SLOT>
+void launch_resident(unsigned groups, hipStream_t stream) {
+  hipLaunchKernelGGL(pong_step_resident_kernel<SLOT>, dim3(groups), dim3(256), 0, stream);
+}
+
+}  // namespace
+
+unsigned long long resident_step_launches() { return g_resident_launches.load(std::memory_order_relaxed); }
+void count_resident_step_launch() { g_resident_launches.fetch_add(1, std::memory_order_relaxed); }
+int step_kernel_mode() { return g_step_kernel; }
+
 int step_slot_acquire(int device) {
   std::lock_guard<std::mutex> lock(g_step_slot_mutex);
   StepSlots* d = nullptr;
@@ -699,22 +689,6 @@ int step_slot_acquire(int device) {
     }
   return -1;
 }
-
-// What a resident launch depends on: everything the step reads from its descriptor.
-bool same_step_request(const PongLaunch& x, const PongLaunch& y) {
-  return x.state == y.state && x.n == y.n && x.seed == y.seed && x.max_score == y.max_score &&
-         x.actions == y.actions && x.obs == y.obs && x.reward == y.reward && x.done == y.done &&
-         x.stats == y.stats && x.normalize == y.normalize && x.inv_score == y.inv_score;
-}
-
-template <int SLOT>
-void launch_resident(unsigned groups, hipStream_t stream) {
-  hipLaunchKernelGGL(pong_step_resident_kernel<SLOT>, dim3(groups), dim3(256), 0, stream);
-}
-
-}  // namespace
-
-unsigned long long resident_step_launches() { return g_resident_launches.load(std::memory_order_relaxed); }
 
 void step_resident_release(StepResident& r) {
   if (r.slot < 0) return;
@@ -735,45 +709,23 @@ hipError_t launch_pong_rollout(const PongLaunch& a, hipStream_t stream, StepResi
   a2.xcd_remap = g_xcd_remap;
   if (a.T == 1 && g_step_kernel) {
     const unsigned groups = (unsigned)((a.n + 255) / 256);
-    // The resident form: for a handle with the host step counter (so the call is never part of a
-    // stream capture), at most STEP_RECORD_MAX_GROUPS workgroups, and a call that asks for what
-    // the call before it asked for.  A caller that alternates between buffers never takes it and never
-    // pays for a rewrite of the record; a steady loop takes it from its second call on.
-    if (resident && !a.counter && g_step_kernel == 1 && groups <= STEP_RECORD_MAX_GROUPS) {
-      StepResident& r = *resident;
-      const bool repeat = r.have_last && r.last_stream == stream && same_step_request(r.last, a);
-      r.last = a;
-      r.last_stream = stream;
-      r.have_last = true;
-      if (repeat && !r.asked) {
-        r.asked = true;
-        if (hipGetDevice(&r.device) == hipSuccess) r.slot = step_slot_acquire(r.device);
-        else (void)hipGetLastError();
-      }
-      if (repeat && r.slot >= 0) {
-        if (!(r.on_device && r.rec_stream == stream && r.next_step == a.step0 && same_step_request(r.rec, a))) {
-          hipLaunchKernelGGL(step_record_write_kernel, dim3(1), dim3(256), 0, stream, r.slot, a,
-                             (unsigned long long)a.step0);
-          const hipError_t e = hipGetLastError();
-          if (e != hipSuccess) return e;
-          r.rec = a;
-          r.rec_stream = stream;
-          r.on_device = true;
-        }
-        switch (r.slot) {
-          case 0: launch_resident<0>(groups, stream); break;
-          case 1: launch_resident<1>(groups, stream); break;
-          case 2: launch_resident<2>(groups, stream); break;
-          default: launch_resident<3>(groups, stream); break;
-        }
-        static_assert(STEP_RECORD_SLOTS == 4, "one case per record");
-        const hipError_t e = hipGetLastError();
-        if (e != hipSuccess) r.on_device = false;
-        r.next_step = a.step0 + 1;
-        g_resident_launches.fetch_add(1, std::memory_order_relaxed);
-        return e;
-      }
-    }
+    hipError_t re = hipSuccess;
+    if (resident_step_try(
+            resident, a, groups, stream,
+            [&](int slot, const PongLaunch& rec, unsigned long long step) {
+              hipLaunchKernelGGL(step_record_write_kernel, dim3(1), dim3(256), 0, stream, slot, rec, step);
+            },
+            [&](int slot, unsigned g2) {
+              switch (slot) {
+                case 0: launch_resident<0>(g2, stream); break;
+                case 1: launch_resident<1>(g2, stream); break;
+                case 2: launch_resident<2>(g2, stream); break;
+                default: launch_resident<3>(g2, stream); break;
+              }
+              static_assert(STEP_RECORD_SLOTS == 4, "one case per record");
+            },
+            &re))
+      return re;
     a2.ticket = groups <= TICKET_MAX_BLOCKS;
     const dim3 sg(groups), sb(256);
     if (a.actions && a.normalize) hipLaunchKernelGGL((pong_step_kernel<true, true>), sg, sb, 0, stream, a2);

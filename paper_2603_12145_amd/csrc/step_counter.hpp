@@ -85,6 +85,15 @@ __device__ __forceinline__ void finish_launch_steps(StepCounter* counter, uint64
   }
 }
 
+// For kernels that read their launch descriptor from device memory: a pointer read from memory is
+// a generic one to the compiler (flat loads and stores), while kernel arguments are known to point
+// to global memory.  Says the same of such a pointer.  By way of the integer: a generic -> global ->
+// generic cast pair is folded away.
+template <class T>
+__device__ __forceinline__ T* known_global(T* p) {
+  return (T*)(__attribute__((address_space(1))) T*)(uintptr_t)p;
+}
+
 // For kernels that only read the counter (reset): no ticket, no write.
 __device__ __forceinline__ uint64_t read_step(const StepCounter* counter, uint64_t host_step) {
   return counter ? __hip_atomic_load(&counter->step, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : host_step;

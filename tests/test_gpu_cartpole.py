@@ -180,3 +180,85 @@ def test_both_rollout_loops_match_the_oracle(n, T, mode):
         assert b.lib().mi355env_tune_cartpole_split(0) == 0
     compare(g, oracle_rollout(n, seed, T, max_steps=9), n, "cart-pole loop %d" % mode)
     assert g["stats"]["episodes"] >= n * (T // 9)
+
+
+def _resident_launches():
+    import ctypes
+    f = b.lib().mi355env_resident_step_launches
+    f.restype = ctypes.c_ulonglong
+    return int(f())
+
+
+@pytest.mark.parametrize("step_kernel", [0, 1, 2], ids=["rollout kernel with T = 1", "step kernel", "step kernel, always with arguments"])
+@pytest.mark.parametrize("external", [False, True])
+@pytest.mark.parametrize("n", [1, 65, 1000, 4096])
+def test_single_steps_into_a_trajectory(n, external, step_kernel):
+    # one launch per step, each step into its own row of the trajectory buffers (so the launch
+    # always carries its arguments); the rollout kernel's T = 1 path computes the same thing
+    T, seed = 70, 900 + n
+    acts = inputs.cartpole_actions(T, n, seed=3) if external else None
+    assert b.lib().mi355env_tune_step_kernel(step_kernel) == 0
+    try:
+        g = gpu_rollout(n, seed, T, max_steps=30, actions=acts, per_step=True)
+    finally:
+        assert b.lib().mi355env_tune_step_kernel(1) == 0
+    compare(g, oracle_rollout(n, seed, T, max_steps=30, actions=acts), n, "single steps")
+    assert g["stats"]["episodes"] > 0
+
+
+@pytest.mark.parametrize("external", [False, True])
+@pytest.mark.parametrize("n", [1, 700, 4096, 16384])
+def test_steps_launched_from_the_resident_record(n, external):
+    # The same buffers step after step: from the second call on the launch takes no arguments and
+    # reads its descriptor and step index from device memory.  A rollout, a reset and a restored
+    # state in between have to show in the next step.
+    seed, max_steps = 77 + n, 25
+    h = b.env_create(b.ENV_CARTPOLE, n, seed, {"max_episode_steps": max_steps})
+    o = CartPole(n, seed, max_steps=max_steps)
+    obs = torch.empty((n, 4), dtype=torch.float32, device=DEV)
+    rew = torch.empty(n, dtype=torch.float32, device=DEV)
+    done = torch.empty(n, dtype=torch.uint8, device=DEV)
+    act = torch.empty(n, dtype=torch.uint8, device=DEV) if external else None
+    seen, want, k = [], [], [0]
+
+    def steps(count):
+        for _ in range(count):
+            a = None
+            if external:
+                a = inputs.cartpole_actions(1, n, seed=5000 + k[0])
+                act.copy_(torch.from_numpy(a[0]))
+            k[0] += 1
+            b.env_step(h, act, obs, rew, done)
+            seen.append((obs.clone(), done.clone()))
+            oo, _, od = o.rollout(1, actions=a)
+            want.append((oo[0], od[0]))
+
+    before = _resident_launches()
+    try:
+        b.env_reset(h, None)
+        o.reset()
+        steps(15)
+        if not external:
+            big = [torch.empty((9, n, 4), dtype=torch.float32, device=DEV), torch.empty((9, n), dtype=torch.float32, device=DEV),
+                   torch.empty((9, n), dtype=torch.uint8, device=DEV)]
+            b.env_rollout(h, 9, None, *big)
+            o.rollout(9)
+        steps(10)
+        b.env_reset(h, None)
+        o.reset()
+        steps(10)
+        b.env_set_state(h, b.env_get_state(h))
+        steps(20)
+        torch.cuda.synchronize()
+        for t, ((go, gd), (wo, wd)) in enumerate(zip(seen, want)):
+            assert_bit_equal(go.cpu().numpy(), wo, "obs of step %d" % t)
+            assert_bit_equal(gd.cpu().numpy(), wd, "done of step %d" % t)
+        assert _resident_launches() - before == 14 + 10 + 10 + 20
+        gs, ws = b.env_stats(h), o.stats()
+        assert gs["episodes"] == ws["episodes"] > 0 and gs["length_sum"] == ws["length_sum"]
+        count, f = split_state(b.env_get_state(h), n, 6)
+        assert count == o.step_count
+        assert_bit_equal(f[0], np.ascontiguousarray(o.envs()["x"]).view(np.uint32), "state x")
+        assert_bit_equal(f[5], np.ascontiguousarray(o.envs()["ep_len"]).view(np.uint32), "state ep_len")
+    finally:
+        b.env_destroy(h)
