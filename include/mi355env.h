@@ -213,7 +213,11 @@ int env_reset(env_t *e, void *obs_dev);
  * obs_dev: Pong float32[N,8]; body float32[N,17]; cart-pole float32[N,4]; pixels: the ring — the frame after the step
  * with index s (s = steps taken before this call) is written to slot s mod 4, the other three
  * slots are left as they are.  reward_dev float32[N], done_dev uint8[N].
- * obs_dev must be 16-byte aligned (body: 4-byte), reward_dev 4-byte aligned.  None may be NULL. */
+ * obs_dev must be 16-byte aligned (body: 4-byte), reward_dev 4-byte aligned.  None may be NULL.
+ * Pong and cart-pole handles with the host step counter and N <= 16384: a call that passes the
+ * buffers of the call before it is launched without kernel arguments, from a record of the call
+ * that the library keeps in device memory (four such handles per device; others launch with
+ * arguments); same results, and nothing for the caller to do or to avoid. */
 int env_step(env_t *e, const void *actions_dev, void *obs_dev, float *reward_dev, uint8_t *done_dev);
 
 /* Paper App. B.1 item 5 (the rollout loop fused into one kernel, no per-step dispatch) and App. A.1
