@@ -96,3 +96,19 @@ def test_binding_struct_layout_matches_header():
     st = re.search(r"typedef struct env_stats_t \{(.*?)\} env_stats_t;", hdr, re.S).group(1)
     st = re.sub(r"/\*.*?\*/", "", st, flags=re.S)
     assert re.findall(r"\b(\w+)\s*;", st) == [n for n, _ in b.env_stats_t._fields_]
+
+
+def test_the_headers_are_plain_c(tmp_path):
+    # the boundary is a C ABI: both headers compile as C99 (and as C++11) on their own
+    import shutil
+    import subprocess
+    if not shutil.which("gcc"):
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_headers.c"
+    src.write_text('#include "mi355env.h"\n#include "mi355env_tuning.h"\n'
+                   "int main(void) { env_config_t c; env_stats_t s; (void)c; (void)s; return ENV_OK; }\n")
+    inc = os.path.join(ROOT, "include")
+    for cmd in (["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only"],
+                ["g++", "-std=c++11", "-pedantic", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c++"]):
+        if shutil.which(cmd[0]):
+            subprocess.run(cmd + ["-I", inc, str(src)], check=True)
