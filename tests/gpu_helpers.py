@@ -35,3 +35,11 @@ def pong_state_fields(envs):
 def pong_blob(step, fields_u32):
     return np.concatenate([np.array([step], np.uint64).view(np.uint8),
                            np.ascontiguousarray(fields_u32).view(np.uint8).ravel()])
+
+
+def tost_p(diff, se, margin):
+    """p-value of the two one-sided tests for |true difference| < margin (the equivalence procedure
+    of the paper's section 4.3, "Cross-backend policy transfer"), normal approximation (thousands
+    of samples per side): the larger of the two one-sided p-values."""
+    from scipy.stats import norm
+    return float(max(norm.sf((diff + margin) / se), norm.sf((margin - diff) / se)))
