@@ -244,7 +244,9 @@ __global__ __launch_bounds__(256) void pixel_dynamics_kernel(PongLaunch a, const
 template <bool EXTERNAL>
 __global__ __launch_bounds__(256) void pixel_traj_dynamics_kernel(PongLaunch a, uint32_t* __restrict__ blocks,
                                                                   int64_t frames) {
-  a.step0 = launch_first_step(a.counter, a.step0, a.T, a.ticket != 0);
+  // every thread reaches the end of this kernel: the counter is read with a plain load here and
+  // the ticket taken behind the last store (see step_counter.hpp)
+  a.step0 = first_step_of_launch(a.counter, a.step0);
   const int64_t n = a.n;
   const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
   const bool live = i < n;
@@ -311,6 +313,7 @@ __global__ __launch_bounds__(256) void pixel_traj_dynamics_kernel(PongLaunch a, 
   }
   if (live) pong_store(a.state, n, i, s);
   flush_wave_stats<false>(a.stats, le);
+  if (a.counter && a.ticket) finish_launch_steps(a.counter, a.step0, a.T, gridDim.x);
 }
 
 constexpr int PAGE = 4096;
@@ -986,10 +989,11 @@ hipError_t pixel_counted_step(const PixelPipe& p, const PixelLaunch& a, hipStrea
     // Step s = the counter's value: (1) one workgroup makes sure the staging buffers of parity s & 1
     // hold step s and moves the counter on; (2) the fused launch hands step s to the caller, commits
     // its state, renders its plane and stages step s + 1 under the render.  N = 16384: 22.5 us per
-    // step against 23.7 for dynamics launch + renderer and 18.0 for the host-counter path, which
-    // needs no launch in front: a dependent launch costs 4.4 us on this runtime however little it
-    // does (1024 or 256 threads: no difference), and only a kernel boundary tells that every
-    // workgroup has read the counter before it moves.
+    // step against 23.0 for dynamics launch + renderer and 18.0 for the host-counter path, which
+    // needs no launch in front: that launch's loads and store queue behind the plane the previous
+    // launch is still writing back (1.2 us at best, 4.6 us on average in the kernel trace, 1024 or
+    // 256 threads alike), and only a kernel boundary tells that every workgroup has read the
+    // counter before it moves.
     CountedStep c{};
     c.pong = a.pong;
     c.pong.T = 1;
