@@ -342,3 +342,29 @@ def test_config4_n8192_t1000_return_statistics():
     oo, _, _ = o1.rollout(1, nthreads=16)
     first = rel_err(obs[0].cpu().numpy(), oo[0]).max(axis=1)
     assert unexplained(first, o1_state0, lambda e: o1.draw_actions(e, 0)) == []
+
+
+def test_a_million_environments_first_step():
+    # a batch far beyond the configuration: 2^20 + 3 environments (environment indices above 2^20 in
+    # the Philox counters of reset and action draws, a ragged last wavefront), the first step after
+    # reset against the float64 oracle, every component of every environment
+    n, seed = (1 << 20) + 3, 31
+    o = Body(n, seed, np.float64); o.reset()
+    s0 = o.get_state()
+    oobs, orew, odone = o.rollout(1, nthreads=16)
+    h = b.env_create(b.ENV_BODY, n, seed, None)
+    try:
+        obs0 = torch.empty((n, 17), dtype=torch.float32, device=DEV)
+        b.env_reset(h, obs0)
+        obs, rew, done = bufs(1, n)
+        b.env_step(h, None, obs[0], rew[0], done[0])
+        torch.cuda.synchronize()
+    finally:
+        b.env_destroy(h)
+    # reset: float32 draws on both sides
+    assert np.abs(obs0.cpu().numpy().astype(np.float64) - np.concatenate([s0[:, 1:9], s0[:, 9:18]], axis=1)).max() < 1e-6
+    worst = np.maximum(rel_err(obs[0].cpu().numpy(), oobs[0]).max(axis=1), rel_err(rew[0].cpu().numpy(), orew[0]))
+    print("2^20 + 3 environments, first step: median err %.2e, max %.2e, beyond 1e-5: %d"
+          % (np.median(worst), worst.max(), int((worst > TOL).sum())))
+    assert unexplained(worst, s0.astype(np.float32).astype(np.float64), lambda e: o.draw_actions(e, 0)) == []
+    assert np.array_equal(done[0].cpu().numpy(), odone[0])

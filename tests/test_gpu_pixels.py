@@ -524,3 +524,50 @@ def test_ordered_stack_at_config3_size_and_beyond():
                 assert torch.equal(stack[:, 3 - k], ring[(T - 1 - k) & 3]), (n, k)
         finally:
             b.env_destroy(hr); b.env_destroy(ho)
+
+
+def test_ring_planes_longer_than_two_gigabytes():
+    """N = 400001: a plane of the slot-major ring is 2.8 GB, so byte offsets inside a plane pass
+    2^31 and the ring is 11.3 GB.  Seven steps through env_step (the fused launch with four pages
+    per render workgroup); rewards and done flags compared in full, the four ring slots at sampled
+    environments against frames the oracle renders from its own state after each of the last four
+    steps, and the total number of lit pixels of one plane against the oracle's rectangles."""
+    n, seed, T = 400001, 23, 7
+    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"max_score": 1})
+    try:
+        ring = torch.zeros((4, n, F, F), dtype=torch.uint8, device=DEV)
+        rew = torch.empty((T, n), dtype=torch.float32, device=DEV)
+        done = torch.empty((T, n), dtype=torch.uint8, device=DEV)
+        b.env_reset(h, ring)
+        for t in range(T):
+            b.env_step(h, None, ring, rew[t], done[t])
+        torch.cuda.synchronize()
+        state = b.env_get_state(h)
+    finally:
+        b.env_destroy(h)
+    p = orc.Pong(n, seed, max_score=1)
+    p.reset()
+    oobs, orew, odone = p.rollout(T, nthreads=16)
+    assert_bit_equal(rew.cpu().numpy(), orew, "reward")
+    assert_bit_equal(done.cpu().numpy(), odone, "done")
+    _, fields = split_state(state, n, 10)
+    assert_bit_equal(fields, pong_state_fields(p.envs()), "final state")
+    rng = np.random.default_rng(5)
+    es = np.concatenate([rng.integers(0, n, 200), [0, 1, n - 2, n - 1, 304358, 304359]])   # 304358.6 frames = 2^31 bytes
+    for t in range(T - 4, T):
+        got = ring[t & 3][torch.from_numpy(es).to(DEV)].cpu().numpy()
+        for k, e in enumerate(es):
+            o = oobs[t, e]
+            st = dict(bx=float(o[0]), by=float(o[1]), vx=0.0, vy=0.0, pa=float(o[4]), po=float(o[5]), sa=0, so=0,
+                      ep_ret=0, ep_len=0)
+            assert_bit_equal(got[k], orc.pong_render_one(st), "slot %d env %d" % (t & 3, e))
+    # every environment's frame of the last step: as many lit pixels as the oracle's frames have,
+    # counted per environment on the device and compared with the oracle's count for the sampled ones
+    t = T - 1
+    lit = (ring[t & 3] != 0).sum(dim=(1, 2)).cpu().numpy()
+    assert lit.min() >= 20 and lit.max() <= 54          # two paddles and a ball on the 84 x 84 grid: at most 54 cells
+    for e in es[:50]:
+        o = oobs[t, e]
+        st = dict(bx=float(o[0]), by=float(o[1]), vx=0.0, vy=0.0, pa=float(o[4]), po=float(o[5]), sa=0, so=0,
+                  ep_ret=0, ep_len=0)
+        assert lit[e] == int((orc.pong_render_one(st) != 0).sum())

@@ -711,3 +711,16 @@ def test_resident_steps_follow_the_handle_to_another_stream():
         m.check("steps across streams")
     finally:
         m.close()
+
+
+def test_sixteen_million_environments():
+    # a batch far beyond the configurations (2^24 + 5 environments, 671 MB of state): environment
+    # indices above 2^24 in the Philox counter, offsets above 2^31 bytes into the trajectory buffers,
+    # the paged-store loop that large batches take, and a ragged last wavefront
+    n, seed, T = (1 << 24) + 5, 99, 3
+    g = gpu_rollout(n, seed, T)
+    o = oracle_rollout(n, seed, T, nthreads=16)
+    compare(g, o, n, "2^24 + 5 environments")
+    # ... and the same batch one launch per step
+    g = gpu_rollout(n, seed, T, per_step=True)
+    compare(g, o, n, "2^24 + 5 environments, one launch per step")
