@@ -262,3 +262,12 @@ def test_steps_launched_from_the_resident_record(n, external):
         assert_bit_equal(f[5], np.ascontiguousarray(o.envs()["ep_len"]).view(np.uint32), "state ep_len")
     finally:
         b.env_destroy(h)
+
+
+def test_four_million_environments():
+    # far beyond the sizes above: environment indices above 2^22 in the Philox counters, a ragged
+    # last wavefront, fused and one launch per step
+    n, seed, T = (1 << 22) + 1, 8, 4
+    o = oracle_rollout(n, seed, T, max_steps=3, nthreads=16)
+    compare(gpu_rollout(n, seed, T, max_steps=3), o, n, "2^22 + 1 environments")
+    compare(gpu_rollout(n, seed, T, max_steps=3, per_step=True), o, n, "2^22 + 1 environments, one launch per step")
