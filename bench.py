@@ -244,7 +244,9 @@ def bench_launch_costs(b, torch, launches=20000):
 
 
 def bench_pixels(b, torch, n, seed, launches, warmup=20, layout="slot_major", device_counter=False,
-                 delta=False):
+                 delta=False, external=False):
+    """external: the actions come from a device buffer, as they do behind a policy (nothing to look
+    ahead to: the step is a dynamics launch and the renderer)."""
     dev = "cuda:0"
     code = {"slot_major": b.ENV_PIXELS_SLOT_MAJOR, "env_major": b.ENV_PIXELS_ENV_MAJOR,
             "ordered": b.ENV_PIXELS_ORDERED}[layout]
@@ -260,9 +262,10 @@ def bench_pixels(b, torch, n, seed, launches, warmup=20, layout="slot_major", de
     rew = torch.empty(n, dtype=torch.float32, device=dev)
     done = torch.empty(n, dtype=torch.uint8, device=dev)
     b.env_reset(h, ring)
-    preroll(lambda: b.env_step(h, None, ring, rew, done))
+    act = torch.randint(0, 3, (n,), dtype=torch.uint8, device=dev) if external else None
+    preroll(lambda: b.env_step(h, act, ring, rew, done))
     for _ in range(warmup):
-        b.env_step(h, None, ring, rew, done)
+        b.env_step(h, act, ring, rew, done)
     torch.cuda.synchronize()
     # a step is one or two small launches: time blocks of 50 steps between one pair of events, so
     # that the event records do not sit between the launches they measure
@@ -274,7 +277,7 @@ def bench_pixels(b, torch, n, seed, launches, warmup=20, layout="slot_major", de
         s, e = _events(2)
         s.record()
         for _ in range(k):
-            b.env_step(h, None, ring, rew, done)
+            b.env_step(h, act, ring, rew, done)
         e.record()
         blocks_ms.append((s, e, k))
         done_steps += k
@@ -290,7 +293,7 @@ def bench_pixels(b, torch, n, seed, launches, warmup=20, layout="slot_major", de
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g, stream=st):
                 for _ in range(per_graph):
-                    b.env_step(h, None, ring, rew, done)
+                    b.env_step(h, act, ring, rew, done)
             preroll(g.replay)
             st.synchronize()
             reps = max(1, launches // per_graph)
@@ -309,7 +312,8 @@ def bench_pixels(b, torch, n, seed, launches, warmup=20, layout="slot_major", de
              "ordered": "an ordered stack (u8[N,4,84,84], newest frame last, all four channels kept current)"}[layout]
     out = dict(workload="pong pixels N=%d, 84x84 u8 frame into %s, one env_step "
                         "call per step%s" % (n, shape,
-                                            (", step counter in device memory" if device_counter else "")
+                                            (", actions from a device buffer" if external else "")
+                                            + (", step counter in device memory" if device_counter else "")
                                             + (", delta updates of the slot" if delta else "")),
                **graph,
                env_steps_per_s=n * launches / wall, us_per_step_events=mean_ms * 1e3,
@@ -322,7 +326,7 @@ def bench_pixels(b, torch, n, seed, launches, warmup=20, layout="slot_major", de
     else:
         out["roofline"] = dict(bound="hbm", achieved=gbs, peak=HBM_PEAK_GBS, unit="GB/s", frac=gbs / HBM_PEAK_GBS,
                                traffic=_traffic("pixel_fused_step_n%d" % n)
-                               if layout == "slot_major" and not device_counter else None)
+                               if layout == "slot_major" and not device_counter and not external else None)
         if out["roofline"]["traffic"] is None:
             out["roofline"]["traffic_note"] = "no counter run for this variant; the full-write variants move 1.03 x the frame bytes"
     return out
@@ -626,6 +630,8 @@ def main():
     if args.only:
         fn = {"pixels": lambda: bench_pixels(b, torch, 16384, 3, args.steps),
               "pixels_device_counter": lambda: bench_pixels(b, torch, 16384, 3, args.steps, device_counter=True),
+              "pixels_external": lambda: [bench_pixels(b, torch, 16384, 3, args.steps, external=True),
+                                          bench_pixels(b, torch, 16384, 3, args.steps, external=True, device_counter=True)],
               "pixels_delta": lambda: [bench_pixels(b, torch, 16384, 3, args.steps, delta=True),
                                        bench_pixels(b, torch, 16384, 3, args.steps, delta=True, layout="env_major"),
                                        bench_pixels(b, torch, 16384, 3, args.steps, layout="ordered"),
@@ -711,6 +717,9 @@ def main():
         extra["launch_costs"] = bench_launch_costs(b, torch)
         extra["cartpole_per_step_n4096"] = bench_pong_per_step(b, torch, 4096, 1, 10000, kind="cartpole")
         extra["config3_pixels"] = bench_pixels(b, torch, 16384, 3, 500)
+        extra["config3_pixels_external_actions"] = bench_pixels(b, torch, 16384, 3, 500, external=True)
+        extra["config3_pixels_external_actions_device_counter"] = bench_pixels(b, torch, 16384, 3, 500, external=True,
+                                                                               device_counter=True)
         for nn, st in ((32768, 300), (262144, 60)):      # the same step on larger batches (context, not the target)
             extra["pixels_n%d" % nn] = bench_pixels(b, torch, nn, 3, st)
         extra["config3_pixels_env_major"] = bench_pixels(b, torch, 16384, 3, 500, layout="env_major")
