@@ -571,3 +571,39 @@ def test_ring_planes_longer_than_two_gigabytes():
         st = dict(bx=float(o[0]), by=float(o[1]), vx=0.0, vy=0.0, pa=float(o[4]), po=float(o[5]), sa=0, so=0,
                   ep_ret=0, ep_len=0)
         assert lit[e] == int((orc.pong_render_one(st) != 0).sum())
+
+
+@pytest.mark.parametrize("n,T", [(1, 40), (3, 90), (700, 130), (4097, 64), (40003, 12)])
+def test_ring_steps_with_the_callers_actions(n, T):
+    """The slot-major ring step with actions from a device buffer (a policy in the loop): a dynamics
+    launch in front of the renderer.  Episodes end (max_score 1) and re-serve inside the run,
+    N = 40003 takes four pages per render workgroup; whole ring, rewards, done flags, statistics
+    and final state against the oracle."""
+    seed = 50 + n
+    acts = inputs.pong_actions(T, n, seed=4)
+    h = b.env_create(b.ENV_PONG_PIXELS, n, seed, {"max_score": 1})
+    try:
+        ring = new_ring(n, "slot_major")
+        rew = torch.empty((T, n), dtype=torch.float32, device=DEV)
+        done = torch.empty((T, n), dtype=torch.uint8, device=DEV)
+        dacts = torch.from_numpy(acts).to(DEV)
+        b.env_reset(h, ring)
+        for t in range(T):
+            b.env_step(h, dacts[t], ring, rew[t], done[t])
+        torch.cuda.synchronize()
+        stats, state = b.env_stats(h), b.env_get_state(h)
+    finally:
+        b.env_destroy(h)
+    p = orc.Pong(n, seed, max_score=1); p.reset()
+    stack = np.zeros((n, 4, F, F), np.uint8); p.fill_stack(stack)
+    orew = np.zeros((T, n), np.float32); odone = np.zeros((T, n), np.uint8)
+    for t in range(T):
+        _, orew[t], odone[t] = p.step(actions=acts[t], stack=stack)
+    assert_bit_equal(ring_as_env_major(ring, "slot_major"), stack, "ring")
+    assert_bit_equal(rew.cpu().numpy(), orew, "reward")
+    assert_bit_equal(done.cpu().numpy(), odone, "done")
+    want = p.stats()
+    assert stats["episodes"] == want["episodes"] and stats["return_sum"] == want["return_sum"]
+    assert stats["episodes"] > 0 or n < 700 or T < 30
+    _, fields = split_state(state, n, 10)
+    assert_bit_equal(fields, pong_state_fields(p.envs()), "final state")
