@@ -68,11 +68,28 @@ namespace {
 
 namespace f64 {
 #define BODY_REAL double
-#define BODY_OCCUPANCY __attribute__((amdgpu_waves_per_eu(2, 2)))
+#ifndef BODY_F64_WAVES
+#define BODY_F64_WAVES 2
+#endif
+#define BODY_OCCUPANCY __attribute__((amdgpu_waves_per_eu(BODY_F64_WAVES, BODY_F64_WAVES)))
 #include "body_impl.inc"
 #undef BODY_REAL
 #undef BODY_OCCUPANCY
 }  // namespace f64
+
+// The float64 text once more for launches of at most one wavefront per SIMD (1024 wavefronts): no
+// register cap.  The Newton model then keeps its loop invariants in registers (313) instead of
+// 244 bytes of scratch per lane, which is worth 6 % of a fused launch at N = 8192 (18.6 -> 17.5 ms
+// per 1000 steps) and 15 % of a single step (30.7 -> 26.3 us: the spills and reloads of the
+// prologue are paid at every launch).  With two wavefronts per SIMD the capped build wins
+// (N = 262144 x T = 100: 14.7 against 17.1 ms).  Same arithmetic in the same order: same bits.
+namespace f64_alone {
+#define BODY_REAL double
+#define BODY_OCCUPANCY __attribute__((amdgpu_waves_per_eu(1, 1)))
+#include "body_impl.inc"
+#undef BODY_REAL
+#undef BODY_OCCUPANCY
+}  // namespace f64_alone
 
 namespace f32 {
 #define BODY_REAL float
@@ -112,6 +129,9 @@ hipError_t launch_body_rollout(const BodyLaunch& a, hipStream_t stream) {
     if (a.newton && a.n >= 32768) hipLaunchKernelGGL((f32::body_rollout_kernel<true, true>), grid, block, 0, stream, a2);
     else if (a.newton) hipLaunchKernelGGL((f32::body_rollout_kernel<true, false>), grid, block, 0, stream, a2);
     else hipLaunchKernelGGL((f32::body_rollout_kernel<false, false>), grid, block, 0, stream, a2);
+  } else if (a.newton && grid.x <= 1024u) {          // at most one wavefront per SIMD
+    if (a.n >= 32768) hipLaunchKernelGGL((f64_alone::body_rollout_kernel<true, true>), grid, block, 0, stream, a2);
+    else hipLaunchKernelGGL((f64_alone::body_rollout_kernel<true, false>), grid, block, 0, stream, a2);
   } else {
     if (a.newton && a.n >= 32768) hipLaunchKernelGGL((f64::body_rollout_kernel<true, true>), grid, block, 0, stream, a2);
     else if (a.newton) hipLaunchKernelGGL((f64::body_rollout_kernel<true, false>), grid, block, 0, stream, a2);
