@@ -2,8 +2,8 @@
 // replayed: a kernel argument is frozen at capture time, so the index of the launch's first step
 // (which keys every Philox draw) is read from memory instead, and the launch advances it itself.
 //
-// Small grids advance it themselves: thread 0 of every workgroup reads the counter, then takes a
-// ticket; the workgroup that takes the last ticket knows every other workgroup has already read,
+// Small grids advance it themselves: thread 0 of every workgroup reads the counter, then (once the
+// value has arrived) takes a ticket; the workgroup that takes the last ticket knows every other workgroup has already read,
 // so it alone writes counter + T and clears the tickets.  The tickets are one atomic on one
 // address, about 45 ns each back to back, so above TICKET_MAX_BLOCKS workgroups (a per-step launch
 // of 262144 Pong environments has 1024: 37 us of tickets around 6 us of work) the launch only reads
@@ -38,13 +38,20 @@ __device__ __forceinline__ uint64_t launch_first_step(StepCounter* counter, uint
   }
   __shared__ unsigned long long shared_step;
   if (threadIdx.x == 0) {
-    const unsigned long long s = __hip_atomic_load(&counter->step, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_AGENT);
+    // The ticket has to be taken after the counter's value has arrived, and that is all it has to
+    // wait for: relaxed atomics with a workgroup-scope fence between them (which waits for the
+    // load and touches no cache), not acquire / release at device scope, each of which writes
+    // back and invalidates an L2 slice on this multi-die part.  The last ticket is known only
+    // once its atomic has returned, so the write of counter + T comes after every other
+    // workgroup's read; the next launch on the stream reads it behind the kernel boundary.
+    const unsigned long long s = __hip_atomic_load(&counter->step, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     shared_step = s;
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
     const unsigned int t =
-        __hip_atomic_fetch_add(&counter->ticket, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_fetch_add(&counter->ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (t == gridDim.x - 1u) {
       __hip_atomic_store(&counter->ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      __hip_atomic_store(&counter->step, s + (unsigned long long)T, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+      __hip_atomic_store(&counter->step, s + (unsigned long long)T, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
   __syncthreads();
