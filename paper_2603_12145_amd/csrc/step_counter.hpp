@@ -3,12 +3,13 @@
 // (which keys every Philox draw) is read from memory instead, and the launch advances it itself.
 //
 // Small grids advance it themselves: thread 0 of every workgroup reads the counter, then (once the
-// value has arrived) takes a ticket; the workgroup that takes the last ticket knows every other workgroup has already read,
-// so it alone writes counter + T and clears the tickets.  The tickets are one atomic on one
-// address, about 45 ns each back to back, so above TICKET_MAX_BLOCKS workgroups (a per-step launch
-// of 262144 Pong environments has 1024: 37 us of tickets around 6 us of work) the launch only reads
-// and a one-thread launch behind it does the adding.  Either way the next launch on the stream
-// starts after the counter has moved.  Two launches that use one counter must not overlap.
+// value has arrived) takes a ticket; the workgroup that takes the last ticket knows every other
+// workgroup has already read, so it alone writes counter + T and clears the tickets.  The
+// tickets are one atomic on one address, about 45 ns each back to back, so above
+// TICKET_MAX_BLOCKS workgroups (a per-step launch of 262144 Pong environments has 1024: 37 us of
+// tickets around 6 us of work) the launch only reads and a one-thread launch behind it does the
+// adding.  Either way the next launch on the stream starts after the counter has moved.  Two
+// launches that use one counter must not overlap.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
